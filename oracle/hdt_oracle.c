@@ -1,0 +1,271 @@
+/*
+ * CPU oracle for hierarchical document attention (HDT, arXiv 2407.08330).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, fp64 statement of what the
+ * method computes; it exists so that the HIP library can be checked against
+ * something written independently of it.  Only the tests, the smoke check and
+ * the benchmark's cpu_baseline leg may call it.  It shares no code, header or
+ * table with the HIP library.
+ *
+ * What is implemented, and the passage each part follows:
+ *   - the attention mask, pair by pair from explicit parent pointers: a position
+ *     sees its parent, its siblings (itself included) and its children
+ *     (Sec. 3.2 "Hierarchical Attention", Eqs. for M^DOC / M^SEC / M^SENT and
+ *     their OR; Fig. 2 caption);
+ *   - masked softmax attention by its definition, two-pass softmax, no tiling
+ *     and no online rescaling (Sec. 3.2, the equation S = softmax(A (.) 1_M),
+ *     A = Q K^T / sqrt(d_k), O = S V; -inf where M = 0);
+ *   - its gradient, by differentiating that definition (the paper does not
+ *     describe a backward pass);
+ *   - the key order "sorted by hierarchy level" and the block partition with
+ *     the skip-empty-blocks rule (Sec. 3.2 last paragraphs; App. A.1, Alg. 1
+ *     steps "Sort K, V", "Partition", "If non-zero values in M"), by brute force
+ *     over all pairs of every block.
+ *
+ * Readings where the paper is silent (each also listed in the design notes):
+ *   - a position attends to itself (M^SENT_ii = 1);
+ *   - the root has no siblings: two positions with parent -1 are not siblings;
+ *   - pad positions (level < 0) see nothing and are seen by nothing; their
+ *     output row is 0, their log-sum-exp is -inf, their gradients are 0;
+ *   - ties inside a level keep document order (stable sort); pads go last;
+ *   - the log-sum-exp returned is natural-log: lse_i = ln sum_j exp(s_ij).
+ *
+ * Every function has pins in tests/ that do not come from this file: masks
+ * enumerated by hand, the paper's three mask equations on index vectors, dense
+ * softmax attention for a one-group document, closed-form row counts, closed
+ * forms for Q = 0, central finite differences for the gradients.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- mask: parent / siblings / children, pair by pair ------------------- */
+
+/* 1 iff position i may attend to position j. */
+int oracle_allowed(const int32_t *level, const int32_t *parent, int64_t i, int64_t j)
+{
+    if (level[i] < 0 || level[j] < 0) return 0;        /* pads */
+    if (i == j) return 1;                               /* itself (a sibling of itself) */
+    if (parent[i] >= 0 && parent[i] == parent[j]) return 1; /* siblings: same parent */
+    if (parent[i] == j) return 1;                       /* j is i's parent */
+    if (parent[j] == i) return 1;                       /* j is i's child */
+    return 0;
+}
+
+/* Dense mask M[n][n] (row i, column j in document order). */
+void oracle_mask(const int32_t *level, const int32_t *parent, int64_t n, uint8_t *M)
+{
+    for (int64_t i = 0; i < n; i++)
+        for (int64_t j = 0; j < n; j++)
+            M[i * n + j] = (uint8_t)oracle_allowed(level, parent, i, j);
+}
+
+/* Number of allowed keys of every row (rowcount[n]); returns their total. */
+int64_t oracle_row_counts(const int32_t *level, const int32_t *parent, int64_t n, int64_t *rowcount)
+{
+    int64_t total = 0;
+#pragma omp parallel for schedule(dynamic, 64) reduction(+ : total)
+    for (int64_t i = 0; i < n; i++) {
+        int64_t c = 0;
+        for (int64_t j = 0; j < n; j++) c += oracle_allowed(level, parent, i, j);
+        rowcount[i] = c;
+        total += c;
+    }
+    return total;
+}
+
+/* The mask as per-row lists of allowed columns, ascending: rowptr[n+1] must hold the
+ * exclusive prefix sum of oracle_row_counts; cols[rowptr[n]] is filled.  (A cache of
+ * the pairwise test, so that it is not repeated for every head.) */
+void oracle_row_lists(const int32_t *level, const int32_t *parent, int64_t n,
+                      const int64_t *rowptr, int32_t *cols)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n; i++) {
+        int64_t w = rowptr[i];
+        for (int64_t j = 0; j < n; j++)
+            if (oracle_allowed(level, parent, i, j)) cols[w++] = (int32_t)j;
+    }
+}
+
+/* ---- forward: masked softmax attention by definition -------------------- */
+
+/* One sample, `heads` heads.  q,k,v,o: [heads][n][d] fp64; lse: [heads][n].
+ * rowptr/cols: the mask lists of this sample. */
+void oracle_attn_fwd(const double *q, const double *k, const double *v, int64_t heads, int64_t n,
+                     int64_t d, double scale, const int64_t *rowptr, const int32_t *cols,
+                     double *o, double *lse)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic, 16)
+    for (int64_t h = 0; h < heads; h++) {
+        for (int64_t i = 0; i < n; i++) {
+            const double *qi = q + (h * n + i) * d;
+            double *oi = o + (h * n + i) * d;
+            int64_t cnt = rowptr[i + 1] - rowptr[i];
+            for (int64_t c = 0; c < d; c++) oi[c] = 0.0;
+            if (cnt == 0) { lse[h * n + i] = -INFINITY; continue; }
+            double *s = (double *)malloc((size_t)cnt * sizeof(double));
+            double m = -INFINITY;
+            for (int64_t t = 0; t < cnt; t++) {
+                const double *kj = k + (h * n + cols[rowptr[i] + t]) * d;
+                double acc = 0.0;
+                for (int64_t c = 0; c < d; c++) acc += qi[c] * kj[c];
+                s[t] = scale * acc;
+                if (s[t] > m) m = s[t];
+            }
+            double z = 0.0;
+            for (int64_t t = 0; t < cnt; t++) z += exp(s[t] - m);
+            double l = m + log(z);
+            lse[h * n + i] = l;
+            for (int64_t t = 0; t < cnt; t++) {
+                double p = exp(s[t] - l);
+                const double *vj = v + (h * n + cols[rowptr[i] + t]) * d;
+                for (int64_t c = 0; c < d; c++) oi[c] += p * vj[c];
+            }
+            free(s);
+        }
+    }
+}
+
+/* ---- backward: gradient of the definition ------------------------------- */
+
+/* Given dO, with p_ij = exp(s_ij - lse_i), o_i = sum_j p_ij v_j:
+ *   D_i   = sum_c dO_ic o_ic
+ *   dV_j  = sum_i p_ij dO_i
+ *   dp_ij = sum_c dO_ic v_jc
+ *   ds_ij = p_ij (dp_ij - D_i)
+ *   dQ_i  = scale sum_j ds_ij k_j,   dK_j = scale sum_i ds_ij q_i
+ * Recomputes the forward quantities itself; uses neither O nor LSE from outside. */
+void oracle_attn_bwd(const double *q, const double *k, const double *v, const double *d_o,
+                     int64_t heads, int64_t n, int64_t d, double scale, const int64_t *rowptr,
+                     const int32_t *cols, double *dq, double *dk, double *dv)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t h = 0; h < heads; h++) {
+        const double *qh = q + h * n * d, *kh = k + h * n * d, *vh = v + h * n * d;
+        const double *doh = d_o + h * n * d;
+        double *dqh = dq + h * n * d, *dkh = dk + h * n * d, *dvh = dv + h * n * d;
+        memset(dqh, 0, (size_t)(n * d) * sizeof(double));
+        memset(dkh, 0, (size_t)(n * d) * sizeof(double));
+        memset(dvh, 0, (size_t)(n * d) * sizeof(double));
+        double *oi = (double *)malloc((size_t)d * sizeof(double));
+        for (int64_t i = 0; i < n; i++) {
+            int64_t cnt = rowptr[i + 1] - rowptr[i];
+            if (cnt == 0) continue;
+            const int32_t *ci = cols + rowptr[i];
+            double *p = (double *)malloc((size_t)cnt * sizeof(double));
+            double m = -INFINITY;
+            for (int64_t t = 0; t < cnt; t++) {
+                double acc = 0.0;
+                for (int64_t c = 0; c < d; c++) acc += qh[i * d + c] * kh[(int64_t)ci[t] * d + c];
+                p[t] = scale * acc;
+                if (p[t] > m) m = p[t];
+            }
+            double z = 0.0;
+            for (int64_t t = 0; t < cnt; t++) z += exp(p[t] - m);
+            double l = m + log(z);
+            for (int64_t c = 0; c < d; c++) oi[c] = 0.0;
+            for (int64_t t = 0; t < cnt; t++) {
+                p[t] = exp(p[t] - l);
+                for (int64_t c = 0; c < d; c++) oi[c] += p[t] * vh[(int64_t)ci[t] * d + c];
+            }
+            double D = 0.0;
+            for (int64_t c = 0; c < d; c++) D += doh[i * d + c] * oi[c];
+            for (int64_t t = 0; t < cnt; t++) {
+                int64_t j = ci[t];
+                double dp = 0.0;
+                for (int64_t c = 0; c < d; c++) dp += doh[i * d + c] * vh[j * d + c];
+                double ds = p[t] * (dp - D);
+                for (int64_t c = 0; c < d; c++) {
+                    dvh[j * d + c] += p[t] * doh[i * d + c];
+                    dqh[i * d + c] += scale * ds * kh[j * d + c];
+                    dkh[j * d + c] += scale * ds * qh[i * d + c];
+                }
+            }
+            free(p);
+        }
+        free(oi);
+    }
+}
+
+/* ---- key order and block schedule --------------------------------------- */
+
+/* kperm[s] = document position held by sorted slot s: positions ordered by level
+ * (0, 1, 2, ... ; pads last), ties in document order. */
+void oracle_kperm(const int32_t *level, int64_t n, int32_t *kperm)
+{
+    int32_t maxl = -1;
+    for (int64_t i = 0; i < n; i++) if (level[i] > maxl) maxl = level[i];
+    int64_t s = 0;
+    for (int32_t l = 0; l <= maxl; l++)
+        for (int64_t i = 0; i < n; i++) if (level[i] == l) kperm[s++] = (int32_t)i;
+    for (int64_t i = 0; i < n; i++) if (level[i] < 0) kperm[s++] = (int32_t)i;
+}
+
+/* Block (I, J) covers query rows [I*bm, (I+1)*bm) in document order and key slots
+ * [J*bn, (J+1)*bn) in sorted order (both cut off at n).  For every block this writes
+ *   count[I*tc + J] = number of allowed (row, slot) pairs in it,
+ * and, if bits != NULL, the block's bitmap at bits + (I*tc + J) * bm * (bn/32) words:
+ * word r*(bn/32) + c/32, bit c%32  <=>  row I*bm + r may attend to slot J*bn + c.
+ * tr = ceil(n/bm), tc = ceil(n/bn); bn must be a multiple of 32. */
+void oracle_block_scan(const int32_t *level, const int32_t *parent, const int32_t *kperm,
+                       int64_t n, int64_t bm, int64_t bn, int32_t *count, uint32_t *bits)
+{
+    int64_t tr = (n + bm - 1) / bm, tc = (n + bn - 1) / bn, wpr = bn / 32;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t I = 0; I < tr; I++) {
+        for (int64_t J = 0; J < tc; J++) {
+            int32_t cnt = 0;
+            uint32_t *bw = bits ? bits + (I * tc + J) * bm * wpr : NULL;
+            if (bw) memset(bw, 0, (size_t)(bm * wpr) * sizeof(uint32_t));
+            for (int64_t r = 0; r < bm; r++) {
+                int64_t i = I * bm + r;
+                if (i >= n) break;
+                for (int64_t c = 0; c < bn; c++) {
+                    int64_t s = J * bn + c;
+                    if (s >= n) break;
+                    if (oracle_allowed(level, parent, i, kperm[s])) {
+                        cnt++;
+                        if (bw) bw[r * wpr + c / 32] |= (uint32_t)1 << (c % 32);
+                    }
+                }
+            }
+            count[I * tc + J] = cnt;
+        }
+    }
+}
+
+/* Bitmaps of the listed blocks only: block b = (bi[b], bj[b]); layout of each bitmap as in
+ * oracle_block_scan, written at bits + b * bm * (bn/32). */
+void oracle_block_bitmaps(const int32_t *level, const int32_t *parent, const int32_t *kperm,
+                          int64_t n, int64_t bm, int64_t bn, int64_t n_blocks, const int32_t *bi,
+                          const int32_t *bj, uint32_t *bits)
+{
+    int64_t wpr = bn / 32;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t b = 0; b < n_blocks; b++) {
+        uint32_t *bw = bits + b * bm * wpr;
+        memset(bw, 0, (size_t)(bm * wpr) * sizeof(uint32_t));
+        for (int64_t r = 0; r < bm; r++) {
+            int64_t i = (int64_t)bi[b] * bm + r;
+            if (i >= n) break;
+            for (int64_t c = 0; c < bn; c++) {
+                int64_t s = (int64_t)bj[b] * bn + c;
+                if (s >= n) break;
+                if (oracle_allowed(level, parent, i, kperm[s]))
+                    bw[r * wpr + c / 32] |= (uint32_t)1 << (c % 32);
+            }
+        }
+    }
+}
+
+int oracle_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    n = omp_get_max_threads();
+#endif
+    return n;
+}

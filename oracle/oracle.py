@@ -1,0 +1,224 @@
+"""Python face of the CPU oracle (test infrastructure only).
+
+Thin ctypes glue over ``hdt_oracle.c`` plus the few steps that are clearer in numpy
+(assembling block lists from per-block counts).  Nothing here is imported by the product
+path, and nothing here imports the product package.
+
+Paper passages followed are cited in ``hdt_oracle.c``; the block schedule follows
+App. A.1, Alg. 1 (sort keys by level, partition into M x N blocks, skip blocks whose mask
+is all zero).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hdt_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (fp64, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        i64 = ctypes.c_int64
+        lib.oracle_allowed.argtypes = [i32p, i32p, i64, i64]
+        lib.oracle_allowed.restype = ctypes.c_int
+        lib.oracle_mask.argtypes = [i32p, i32p, i64, ctypes.POINTER(ctypes.c_uint8)]
+        lib.oracle_mask.restype = None
+        lib.oracle_row_counts.argtypes = [i32p, i32p, i64, i64p]
+        lib.oracle_row_counts.restype = i64
+        lib.oracle_row_lists.argtypes = [i32p, i32p, i64, i64p, i32p]
+        lib.oracle_row_lists.restype = None
+        lib.oracle_attn_fwd.argtypes = [f64p, f64p, f64p, i64, i64, i64, ctypes.c_double, i64p, i32p, f64p, f64p]
+        lib.oracle_attn_fwd.restype = None
+        lib.oracle_attn_bwd.argtypes = [f64p, f64p, f64p, f64p, i64, i64, i64, ctypes.c_double, i64p, i32p,
+                                        f64p, f64p, f64p]
+        lib.oracle_attn_bwd.restype = None
+        lib.oracle_kperm.argtypes = [i32p, i64, i32p]
+        lib.oracle_kperm.restype = None
+        lib.oracle_block_scan.argtypes = [i32p, i32p, i32p, i64, i64, i64, i32p, u32p]
+        lib.oracle_block_scan.restype = None
+        lib.oracle_block_bitmaps.argtypes = [i32p, i32p, i32p, i64, i64, i64, i64, i32p, i32p, u32p]
+        lib.oracle_block_bitmaps.restype = None
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def allowed(level, parent, i: int, j: int) -> bool:
+    level, parent = _i32(level), _i32(parent)
+    return bool(_load().oracle_allowed(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), i, j))
+
+
+def mask(level, parent) -> np.ndarray:
+    """Dense 0/1 mask [n][n] of one sample."""
+    level, parent = _i32(level), _i32(parent)
+    n = level.shape[0]
+    M = np.zeros((n, n), dtype=np.uint8)
+    _load().oracle_mask(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), n, _p(M, ctypes.c_uint8))
+    return M
+
+
+def row_lists(level, parent):
+    """(rowptr int64[n+1], cols int32[nnz]) of one sample's mask, by pairwise enumeration."""
+    level, parent = _i32(level), _i32(parent)
+    n = level.shape[0]
+    counts = np.zeros(n, dtype=np.int64)
+    lib = _load()
+    total = lib.oracle_row_counts(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), n, _p(counts, ctypes.c_int64))
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    assert rowptr[-1] == total
+    cols = np.zeros(max(int(total), 1), dtype=np.int32)
+    lib.oracle_row_lists(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), n, _p(rowptr, ctypes.c_int64),
+                         _p(cols, ctypes.c_int32))
+    return rowptr, cols[: int(total)]
+
+
+def attn_fwd(q, k, v, level, parent, scale: float):
+    """Masked softmax attention by definition.  q,k,v: [B][H][N][d] (any float dtype, widened to
+    fp64); level,parent: [B][N].  Returns (o fp64 [B][H][N][d], lse fp64 [B][H][N])."""
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    k = np.ascontiguousarray(k, dtype=np.float64)
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    B, H, N, d = q.shape
+    o = np.zeros_like(q)
+    lse = np.zeros((B, H, N), dtype=np.float64)
+    lib = _load()
+    for b in range(B):
+        rowptr, cols = row_lists(level[b], parent[b])
+        cols_c = np.ascontiguousarray(cols if cols.size else np.zeros(1, np.int32))
+        lib.oracle_attn_fwd(_p(q[b], ctypes.c_double), _p(k[b], ctypes.c_double), _p(v[b], ctypes.c_double),
+                            H, N, d, float(scale), _p(rowptr, ctypes.c_int64), _p(cols_c, ctypes.c_int32),
+                            _p(o[b], ctypes.c_double), _p(lse[b], ctypes.c_double))
+    return o, lse
+
+
+def attn_bwd(q, k, v, d_o, level, parent, scale: float):
+    """Gradients (dq, dk, dv), fp64 [B][H][N][d], of sum(O * dO) w.r.t. q, k, v."""
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    k = np.ascontiguousarray(k, dtype=np.float64)
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    d_o = np.ascontiguousarray(d_o, dtype=np.float64)
+    B, H, N, d = q.shape
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(q), np.zeros_like(q)
+    lib = _load()
+    for b in range(B):
+        rowptr, cols = row_lists(level[b], parent[b])
+        cols_c = np.ascontiguousarray(cols if cols.size else np.zeros(1, np.int32))
+        lib.oracle_attn_bwd(_p(q[b], ctypes.c_double), _p(k[b], ctypes.c_double), _p(v[b], ctypes.c_double),
+                            _p(d_o[b], ctypes.c_double), H, N, d, float(scale), _p(rowptr, ctypes.c_int64),
+                            _p(cols_c, ctypes.c_int32), _p(dq[b], ctypes.c_double), _p(dk[b], ctypes.c_double),
+                            _p(dv[b], ctypes.c_double))
+    return dq, dk, dv
+
+
+def kperm(level) -> np.ndarray:
+    """Sorted slot -> document position, keys ordered by level, ties in document order, pads last."""
+    level = _i32(level)
+    n = level.shape[0]
+    out = np.zeros(max(n, 1), dtype=np.int32)
+    _load().oracle_kperm(_p(level, ctypes.c_int32), n, _p(out, ctypes.c_int32))
+    return out[:n]
+
+
+@dataclass
+class BlockSchedule:
+    """Surviving blocks of one sample.  q_* lists blocks by query-block row (columns ascending);
+    k_* is the exact transpose (rows ascending).  ``sub`` packs, for the 32x32 sub-blocks of a
+    block (sub-block (r, c) -> bit r*(bn/32)+c): bits 0..15 = holds an allowed pair, bits 16..31 =
+    every pair allowed.  ``full`` = every one of the bm*bn pairs is allowed.  ``bits`` is the
+    row-major bitmap, uint32 [n_blocks][bm][bn/32]."""
+    bm: int
+    bn: int
+    kperm: np.ndarray
+    q_rowptr: np.ndarray
+    q_cols: np.ndarray
+    q_full: np.ndarray
+    q_sub: np.ndarray
+    bits: np.ndarray
+    k_colptr: np.ndarray
+    k_rows: np.ndarray
+    k_tile: np.ndarray  # index into the q-ordered block list of each transposed entry
+    nnz: int
+
+
+def block_schedule(level, parent, bm: int, bn: int, use_sort: bool = True, force_dense: bool = False) -> BlockSchedule:
+    """Brute-force block schedule of one sample (App. A.1, Alg. 1: sort, partition, skip empty)."""
+    level, parent = _i32(level), _i32(parent)
+    n = level.shape[0]
+    assert bm % 32 == 0 and bn % 32 == 0
+    kp = kperm(level) if use_sort else np.arange(n, dtype=np.int32)
+    tr, tc = -(-n // bm), -(-n // bn)
+    count = np.zeros(max(tr * tc, 1), dtype=np.int32)
+    lib = _load()
+    kp_c = np.ascontiguousarray(kp if n else np.zeros(1, np.int32))
+    if n:
+        lib.oracle_block_scan(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), _p(kp_c, ctypes.c_int32),
+                              n, bm, bn, _p(count, ctypes.c_int32), None)
+    count = count[: tr * tc].reshape(tr, tc)
+    alive = np.ones_like(count, dtype=bool) if force_dense else count > 0
+    bi, bj = np.nonzero(alive)  # row-major: rows ascending, columns ascending inside a row
+    bi = bi.astype(np.int32)
+    bj = bj.astype(np.int32)
+    nb = bi.shape[0]
+    wpr = bn // 32
+    bits = np.zeros((max(nb, 1), bm, wpr), dtype=np.uint32)
+    if nb:
+        lib.oracle_block_bitmaps(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), _p(kp_c, ctypes.c_int32),
+                                 n, bm, bn, nb, _p(np.ascontiguousarray(bi), ctypes.c_int32),
+                                 _p(np.ascontiguousarray(bj), ctypes.c_int32), _p(bits, ctypes.c_uint32))
+    bits = bits[:nb]
+    q_rowptr = np.zeros(tr + 1, dtype=np.int32)
+    np.cumsum(alive.sum(axis=1), out=q_rowptr[1:])
+    q_full = (count[bi, bj] == bm * bn).astype(np.uint8) if nb else np.zeros(0, np.uint8)
+    # 32x32 sub-block summaries from the bitmaps
+    q_sub = np.zeros(nb, dtype=np.uint32)
+    for r in range(bm // 32):
+        for c in range(wpr):
+            words = bits[:, r * 32:(r + 1) * 32, c] if nb else np.zeros((0, 32), np.uint32)
+            any_ = (words != 0).any(axis=1)
+            all_ = (words == 0xFFFFFFFF).all(axis=1)
+            q_sub |= (any_.astype(np.uint32) << np.uint32(r * wpr + c))
+            q_sub |= (all_.astype(np.uint32) << np.uint32(16 + r * wpr + c))
+    # transpose: by column, rows ascending
+    order = np.lexsort((bi, bj)) if nb else np.zeros(0, np.int64)
+    k_rows = bi[order].astype(np.int32)
+    k_colptr = np.zeros(tc + 1, dtype=np.int32)
+    np.cumsum(alive.sum(axis=0), out=k_colptr[1:])
+    return BlockSchedule(bm=bm, bn=bn, kperm=kp, q_rowptr=q_rowptr, q_cols=bj, q_full=q_full, q_sub=q_sub,
+                         bits=bits, k_colptr=k_colptr, k_rows=k_rows, k_tile=order.astype(np.int32),
+                         nnz=int(count.sum()))

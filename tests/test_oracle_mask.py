@@ -1,0 +1,101 @@
+"""Pins for the oracle's mask: hand-enumerated masks, the paper's three mask equations on
+index vectors, invariants and closed-form row counts (Sec. 3.2 "Hierarchical Attention")."""
+import numpy as np
+import pytest
+
+from paper_2407_08330_amd import inputs
+from helpers import mask_from_equations, read_golden_mask
+
+
+@pytest.mark.parametrize("name", ["mask_doc16.txt", "mask_tree10.txt"])
+def test_hand_enumerated_masks(oracle, name):
+    level, parent, _, M = read_golden_mask(name)
+    got = oracle.mask(level, parent)
+    assert got.shape == M.shape
+    np.testing.assert_array_equal(got, M)
+
+
+def test_fig2_tokens_of_different_sentences_are_not_connected(oracle):
+    # Fig. 2 caption: T1 and T3 (different sentences) interact only via anchors.
+    level, parent, _, _ = read_golden_mask("mask_doc16.txt")
+    assert not oracle.allowed(level, parent, 3, 6)      # tokens of sentences 1.1 and 1.2
+    assert not oracle.allowed(level, parent, 6, 9)      # different sections
+    assert oracle.allowed(level, parent, 3, 4)          # same sentence
+    assert oracle.allowed(level, parent, 3, 2) and oracle.allowed(level, parent, 2, 3)  # token <-> its [SENT]
+    assert oracle.allowed(level, parent, 2, 5)          # sibling [SENT] anchors
+    assert not oracle.allowed(level, parent, 2, 8)      # [SENT] anchors of different sections
+    assert not oracle.allowed(level, parent, 3, 1)      # token does not see its grandparent
+    assert not oracle.allowed(level, parent, 0, 2)      # [DOC] does not see a [SENT]
+
+
+@pytest.mark.parametrize("config,sample", [(1, 0), (2, 0), (2, 3)])
+def test_mask_equals_paper_equations(oracle, config, sample):
+    wl = inputs.make_workload(config, batch=sample + 1)
+    n = min(wl.n_pos, 1536)  # a prefix keeps the dense comparison small; masks are prefix-closed
+    M_eq = mask_from_equations(wl.sections[sample], wl.n_pos)[:n, :n]
+    # restrict the hierarchy to the prefix: parents always precede children in pre-order
+    got = oracle.mask(wl.level[sample][:n], wl.parent[sample][:n])
+    np.testing.assert_array_equal(got, M_eq)
+
+
+def test_mask_equations_random_documents(oracle):
+    rng = np.random.default_rng(7)
+    for _ in range(20):
+        sections = [[int(rng.integers(0, 7)) for _ in range(int(rng.integers(1, 5)))]
+                    for _ in range(int(rng.integers(1, 5)))]
+        need = 1 + sum(1 + sum(1 + l for l in s) for s in sections)
+        n = need + int(rng.integers(0, 5))
+        level, parent = inputs.document_from_sections(sections, n)
+        np.testing.assert_array_equal(oracle.mask(level, parent), mask_from_equations(sections, n))
+
+
+def test_invariants_and_closed_form_row_counts(oracle):
+    wl = inputs.make_workload(2, batch=1)
+    level, parent, sections = wl.level[0], wl.parent[0], wl.sections[0]
+    rowptr, cols = oracle.row_lists(level, parent)
+    counts = np.diff(rowptr)
+    # closed form: token in a sentence of l tokens: l+1; [SENT] (l tokens, k sentences in its
+    # section): l+k+1; [SEC] (k sentences, S sections): k+S+1; [DOC]: S+1; pad: 0
+    S = len(sections)
+    expect = [S + 1]
+    for sec in sections:
+        k = len(sec)
+        expect.append(k + S + 1)
+        for l in sec:
+            expect.append(l + k + 1)
+            expect.extend([l + 1] * l)
+    expect = np.array(expect + [0] * (wl.n_pos - len(expect)))
+    np.testing.assert_array_equal(counts, expect)
+    nnz = sum(l * (l + 1) + l + len(sec) + 1 for sec in sections for l in sec) \
+        + sum(len(sec) + S + 1 for sec in sections) + S + 1
+    assert rowptr[-1] == nnz
+    # O(n*s): every row holds at most s + 1 + (largest group of anchors) keys
+    s_max = max(max(sec) for sec in sections)
+    k_max = max(len(sec) for sec in sections)
+    assert counts.max() <= s_max + 1 + max(k_max, S) + 1
+    # symmetric, unit diagonal on non-pads, empty rows/columns on pads (checked on a prefix)
+    n = 1024
+    M = oracle.mask(level[:n], parent[:n])
+    np.testing.assert_array_equal(M, M.T)
+    assert (np.diag(M) == (level[:n] >= 0)).all()
+    lv_tail, pr_tail = level[-64:].copy(), parent[-64:].copy()
+    pr_tail[pr_tail >= 0] -= (wl.n_pos - 64)
+    pr_tail[pr_tail < 0] = -1
+    Mt = oracle.mask(lv_tail, pr_tail)
+    pads = lv_tail < 0
+    assert pads.any()
+    assert Mt[pads].sum() == 0 and Mt[:, pads].sum() == 0
+
+
+def test_row_lists_match_dense_mask(oracle):
+    level, parent, _, M = read_golden_mask("mask_doc16.txt")
+    rowptr, cols = oracle.row_lists(level, parent)
+    for i in range(16):
+        np.testing.assert_array_equal(cols[rowptr[i]:rowptr[i + 1]], np.nonzero(M[i])[0])
+
+
+def test_two_roots_are_not_siblings(oracle):
+    level = np.array([0, 1, 0, 1], dtype=np.int32)
+    parent = np.array([-1, 0, -1, 2], dtype=np.int32)
+    M = oracle.mask(level, parent)
+    np.testing.assert_array_equal(M, np.array([[1, 1, 0, 0], [1, 1, 0, 0], [0, 0, 1, 1], [0, 0, 1, 1]]))
