@@ -1,0 +1,197 @@
+/*
+ * hdt.h -- C ABI of the hierarchical document attention library for AMD MI355X (gfx950).
+ *
+ * The library computes the sparse attention of the Hierarchical Document Transformer
+ * (arXiv 2407.08330, Sec. 3.2 "Hierarchical Attention" and App. A.1, Alg. 1):
+ *
+ *     A = Q K^T * softmax_scale,   S = softmax(A masked by M),   O = S V
+ *
+ * where every position of a document is a regular token or an auxiliary anchor
+ * ([DOC], [SEC], [SENT], or any deeper hierarchy) and M lets a position attend only to
+ * its parent, its siblings (itself included) and its children.  M differs per sample and is
+ * shared by all heads.  M is never materialised: hdt_build_layout turns the per-position
+ * `level` and `parent` ids into a block-sparse tile schedule, and the attention calls walk
+ * that schedule.
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* and all tensor pointers are DEVICE pointers owned by the caller;
+ *     pointers named h_* are HOST pointers.  The library never takes ownership of them.
+ *   - Tensors are dense and contiguous: Q, K, V, O, dO, dQ, dK, dV are [batch][heads][n_pos]
+ *     [head_dim]; LSE is [batch][heads][n_pos] float; level, parent are [batch][n_pos] int32.
+ *     Tensor base pointers must be 16-byte aligned.  Outputs must not alias inputs.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Attention calls
+ *     only enqueue work on it; they never synchronise and never allocate.
+ *   - Every function returns an hdt_status_t; nothing aborts or throws across the boundary.
+ *     hdt_last_error() gives a thread-local text for the last non-OK status.
+ *   - Values at pad positions and at masked pairs are never used as logits, but K/V/dO rows of
+ *     a tile are multiplied by zero weights: all inputs must be finite everywhere.
+ */
+#ifndef HDT_H
+#define HDT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HDT_OK = 0,
+    HDT_ERR_INVALID_ARG = 1, /* NULL pointer, negative size, non-positive or non-finite scale */
+    HDT_ERR_SHAPE = 2,       /* sizes inconsistent with the layout or out of the supported range */
+    HDT_ERR_HIERARCHY = 3,   /* level/parent arrays do not describe a valid hierarchy */
+    HDT_ERR_UNSUPPORTED = 4, /* head_dim, dtype or tile shape without a kernel */
+    HDT_ERR_OOM = 5,         /* device or host allocation failed */
+    HDT_ERR_HIP = 6          /* a HIP runtime call failed (text in hdt_last_error) */
+} hdt_status_t;
+
+typedef enum {
+    HDT_BF16 = 0, /* bf16 tensors, fp32 accumulation, MFMA kernels                */
+    HDT_F32 = 1   /* fp32 tensors, plain fp32 arithmetic: the slow debugging path */
+} hdt_dtype_t;
+
+/* Level id of a pad position; anchors and tokens carry levels 0 .. HDT_MAX_LEVELS-1
+ * (0 = the root, e.g. [DOC]=0, [SEC]=1, [SENT]=2, token=3). */
+#define HDT_LEVEL_PAD (-1)
+#define HDT_MAX_LEVELS 32
+
+typedef struct hdt_layout hdt_layout_t; /* opaque; owns its device buffers */
+
+typedef struct {
+    int32_t tile_m;      /* query rows per tile,  0 = default (128); multiple of 32, <= 128   */
+    int32_t tile_n;      /* key slots per tile,   0 = default (64);  multiple of 32, <= 128   */
+    int32_t force_dense; /* 1: issue every tile (dense masked-attention baseline)             */
+    int32_t no_sort;     /* 1: keep keys in document order (block-sparse baseline w/o sort)   */
+} hdt_layout_opts_t;
+
+typedef struct {
+    int32_t batch, n_pos, tile_m, tile_n;
+    int32_t q_tiles, k_tiles; /* per sample: ceil(n_pos/tile_m), ceil(n_pos/tile_n)  */
+    int64_t n_tiles;          /* surviving tiles, summed over the batch              */
+    int64_t nnz;              /* allowed (query, key) pairs, summed over the batch   */
+    int64_t device_bytes;     /* device memory held by the layout                    */
+} hdt_layout_info_t;
+
+/*
+ * hdt_build_layout -- level/parent ids -> block-sparse tile schedule, built on the device.
+ * (Sec. 3.2: mask definition; App. A.1, Alg. 1: "sort K, V according to the hierarchy level",
+ * partition into blocks, process only blocks with a non-zero mask entry.)
+ *
+ *   d_level  [batch][n_pos] int32, device: hierarchy level of each position, HDT_LEVEL_PAD for pads
+ *   d_parent [batch][n_pos] int32, device: index (inside the same sample) of the parent position,
+ *            -1 for a root and for pads.  Any forest is accepted; positions need not be in
+ *            pre-order (documents laid out with anchors prepended give the fewest tiles).
+ *   opts     host, may be NULL (all defaults)
+ *   out      receives the layout; destroy it with hdt_layout_destroy
+ *
+ * The schedule, per sample:
+ *   kperm    key order: positions sorted by level (0, 1, 2, ...; pads last), ties in document order;
+ *   tile (I, J) = query rows [I*tile_m, (I+1)*tile_m) in document order x key slots
+ *            [J*tile_n, (J+1)*tile_n) in kperm order; it survives iff some pair in it is allowed:
+ *            allowed(i, j) = both non-pad and (i == j, or parent[i] == parent[j] >= 0,
+ *                            or parent[i] == j, or parent[j] == i);
+ *   per surviving tile: its column, a bitmap of the allowed pairs and a summary of its 32x32
+ *            sub-blocks; lists by query tile (columns ascending) and the transpose by key tile.
+ *
+ * Enqueues kernels on `stream`, synchronises the stream once (to size the tile arrays and to
+ * report hierarchy errors) and allocates the layout's device memory.  batch == 0 or n_pos == 0
+ * gives an empty layout on which the attention calls are no-ops.
+ *
+ * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (n_pos > 2^22),
+ * HDT_ERR_UNSUPPORTED (tile shape), HDT_ERR_HIERARCHY (level outside [-1, HDT_MAX_LEVELS),
+ * parent outside [-1, n_pos), parent[i] == i, a pad with a parent, a parent that is a pad),
+ * HDT_ERR_OOM, HDT_ERR_HIP.  On error *out is NULL.
+ */
+hdt_status_t hdt_build_layout(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
+                              const hdt_layout_opts_t *opts, void *stream, hdt_layout_t **out);
+
+/* Sizes of a layout (host struct).  Cheap; no device work. */
+hdt_status_t hdt_layout_info(const hdt_layout_t *layout, hdt_layout_info_t *h_info);
+
+/* Surviving tiles and allowed pairs of one sample. */
+hdt_status_t hdt_layout_sample_info(const hdt_layout_t *layout, int32_t sample, int64_t *h_n_tiles,
+                                    int64_t *h_nnz);
+
+/*
+ * hdt_layout_export -- copy one sample's schedule to host arrays (for inspection and tests).
+ * Any output pointer may be NULL.  Sizes, with T = the sample's n_tiles:
+ *   h_kperm    int32  [n_pos]        sorted slot -> position
+ *   h_q_rowptr int32  [q_tiles + 1]  tiles of query tile I are entries [q_rowptr[I], q_rowptr[I+1])
+ *   h_q_cols   int32  [T]            key tile of each entry, ascending inside a query tile
+ *   h_q_sub    uint32 [T]            32x32 sub-block (r, c) -> bit r*(tile_n/32)+c: bits 0..15 set iff the
+ *                                    sub-block holds an allowed pair, bits 16..31 iff all its pairs are allowed
+ *   h_bits     uint32 [T][tile_m][tile_n/32]  bitmap, word r*(tile_n/32)+c/32, bit c%32 <=> row r, slot c allowed
+ *   h_k_colptr int32  [k_tiles + 1]  transpose: entries of key tile J
+ *   h_k_rows   int32  [T]            query tile of each transposed entry, ascending inside a key tile
+ *   h_k_tile   int32  [T]            index (into the q-ordered entries) of each transposed entry
+ * `tile_capacity` is the number of entries the T-sized arrays can hold; HDT_ERR_SHAPE if too small.
+ * Synchronises the device.
+ */
+hdt_status_t hdt_layout_export(const hdt_layout_t *layout, int32_t sample, int32_t *h_kperm,
+                               int32_t *h_q_rowptr, int32_t *h_q_cols, uint32_t *h_q_sub, uint32_t *h_bits,
+                               int32_t *h_k_colptr, int32_t *h_k_rows, int32_t *h_k_tile,
+                               int64_t tile_capacity);
+
+/* Frees the layout and its device memory.  NULL is accepted.  The caller must make sure no
+ * attention call that uses the layout is still running. */
+hdt_status_t hdt_layout_destroy(hdt_layout_t *layout);
+
+/*
+ * hdt_attn_fwd -- forward pass over the surviving tiles (App. A.1, Alg. 1: per query tile, loop
+ * over its key tiles, mask, online softmax, accumulate P V; O and the softmax statistics are
+ * written once at the end instead of once per key tile).
+ *
+ *   q, k, v  device, [batch][heads][n_pos][head_dim], dtype `dt`
+ *   o        device, same shape and dtype: O = softmax(mask(Q K^T * softmax_scale)) V; 0 on pad rows
+ *   lse      device, [batch][heads][n_pos] float: natural-log sum of exp of the masked, scaled logits
+ *            of each row; -inf on pad rows
+ *   head_dim 64 or 128;  softmax_scale > 0 (the paper uses 1/sqrt(head_dim))
+ *
+ * HDT_BF16 needs a layout with tiles 128 x 64; HDT_F32 takes any layout.  batch and n_pos come from
+ * the layout.  Errors: INVALID_ARG, UNSUPPORTED (head_dim, dtype, tile shape), HDT_ERR_HIP (launch).
+ */
+hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v, void *o,
+                          float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
+                          void *stream);
+
+/* Bytes of device workspace hdt_attn_bwd needs (0 on bad arguments). */
+size_t hdt_attn_bwd_workspace_bytes(const hdt_layout_t *layout, int32_t heads, int32_t head_dim,
+                                    hdt_dtype_t dt);
+
+/*
+ * hdt_attn_bwd -- gradients of the forward pass (the paper gives no backward; this is the
+ * gradient of the definition in Sec. 3.2, evaluated over the same surviving tiles):
+ *   D_i = sum_c dO_ic O_ic,  P = exp(S - LSE),  dV = P^T dO,  dP = dO V^T,  dS = P o (dP - D),
+ *   dQ = scale dS K,  dK = scale dS^T Q.
+ *
+ *   q, k, v, o, d_o   device, [batch][heads][n_pos][head_dim], dtype `dt` (o, lse from hdt_attn_fwd)
+ *   lse               device, [batch][heads][n_pos] float
+ *   dq, dk, dv        device, outputs, same shape and dtype; rows of pad positions are written as 0
+ *   workspace         device, at least hdt_attn_bwd_workspace_bytes() bytes, 16-byte aligned; scratch only
+ */
+hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
+                          const void *o, const float *lse, const void *d_o, void *dq, void *dk, void *dv,
+                          int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Text of a status code / of the last error on this thread (never NULL). */
+const char *hdt_status_string(hdt_status_t status);
+const char *hdt_last_error(void);
+
+/*
+ * Per-kernel timing for benchmarks.  With timing enabled every kernel launch of the library is
+ * bracketed by HIP events on the stream it is launched on.  hdt_timing_read synchronises those
+ * events and returns, for up to `capacity` kernels, the kernel name (pointer to a static string),
+ * the number of launches and the summed duration in milliseconds since the last hdt_timing_reset;
+ * it returns the number of distinct kernels seen.  Not thread-safe; meant for single-threaded
+ * benchmark loops.
+ */
+hdt_status_t hdt_timing_enable(int32_t enable);
+hdt_status_t hdt_timing_reset(void);
+int32_t hdt_timing_read(const char **h_names, int64_t *h_launches, double *h_total_ms, int32_t capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HDT_H */

@@ -1,0 +1,16 @@
+"""Hierarchical document attention (HDT, arXiv 2407.08330) for AMD MI355X: hand-written HIP
+kernels behind a C ABI (``include/hdt.h``), with a thin ctypes binding.  PyTorch is only used for
+device memory and streams."""
+from .binding import (  # noqa: F401
+    HdtError,
+    Layout,
+    hdt_attn_bwd,
+    hdt_attn_bwd_workspace_bytes,
+    hdt_attn_fwd,
+    hdt_build_layout,
+    hdt_timing_enable,
+    hdt_timing_read,
+    hdt_timing_reset,
+    library_path,
+    load_library,
+)

@@ -1,0 +1,249 @@
+"""ctypes binding of libhdt.so: argument marshalling only.  Every step of the method runs in the
+HIP kernels behind the C ABI declared in ``include/hdt.h``; there is no fallback path, and a
+missing library is an error."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libhdt.so")
+_lib = None
+
+HDT_BF16, HDT_F32 = 0, 1
+
+EXPORTED_SYMBOLS = [
+    "hdt_build_layout", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
+    "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
+    "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read",
+]
+
+
+class HdtError(RuntimeError):
+    def __init__(self, status: int, name: str, text: str):
+        super().__init__(f"{name} ({status}): {text}")
+        self.status = status
+        self.name = name
+
+
+class _Opts(ctypes.Structure):
+    _fields_ = [("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32), ("force_dense", ctypes.c_int32),
+                ("no_sort", ctypes.c_int32)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_pos", ctypes.c_int32), ("tile_m", ctypes.c_int32),
+                ("tile_n", ctypes.c_int32), ("q_tiles", ctypes.c_int32), ("k_tiles", ctypes.c_int32),
+                ("n_tiles", ctypes.c_int64), ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libhdt.so built in-tree (``python -m paper_2407_08330_amd.build`` or
+    ``__graft_entry__.build()``).  Raises if it is missing: there is no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} not built; run __graft_entry__.build() first")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    lib.hdt_build_layout.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_Opts), vp, ctypes.POINTER(vp)]
+    lib.hdt_build_layout.restype = ctypes.c_int
+    lib.hdt_layout_info.argtypes = [vp, ctypes.POINTER(_Info)]
+    lib.hdt_layout_info.restype = ctypes.c_int
+    lib.hdt_layout_sample_info.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.hdt_layout_sample_info.restype = ctypes.c_int
+    lib.hdt_layout_export.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64]
+    lib.hdt_layout_export.restype = ctypes.c_int
+    lib.hdt_layout_destroy.argtypes = [vp]
+    lib.hdt_layout_destroy.restype = ctypes.c_int
+    lib.hdt_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp]
+    lib.hdt_attn_fwd.restype = ctypes.c_int
+    lib.hdt_attn_bwd_workspace_bytes.argtypes = [vp, i32, i32, ctypes.c_int]
+    lib.hdt_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.hdt_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp,
+                                 ctypes.c_size_t, vp]
+    lib.hdt_attn_bwd.restype = ctypes.c_int
+    lib.hdt_status_string.argtypes = [ctypes.c_int]
+    lib.hdt_status_string.restype = ctypes.c_char_p
+    lib.hdt_last_error.argtypes = []
+    lib.hdt_last_error.restype = ctypes.c_char_p
+    lib.hdt_timing_enable.argtypes = [i32]
+    lib.hdt_timing_enable.restype = ctypes.c_int
+    lib.hdt_timing_reset.argtypes = []
+    lib.hdt_timing_reset.restype = ctypes.c_int
+    lib.hdt_timing_read.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64),
+                                    ctypes.POINTER(ctypes.c_double), i32]
+    lib.hdt_timing_read.restype = i32
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        lib = load_library()
+        raise HdtError(status, lib.hdt_status_string(status).decode(), lib.hdt_last_error().decode())
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+class Layout:
+    """Owns an ``hdt_layout_t``."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def info(self) -> dict:
+        info = _Info()
+        _check(load_library().hdt_layout_info(self._h, ctypes.byref(info)))
+        return {f: getattr(info, f) for f, _ in _Info._fields_}
+
+    def sample_info(self, sample: int):
+        a, b = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(load_library().hdt_layout_sample_info(self._h, sample, ctypes.byref(a), ctypes.byref(b)))
+        return a.value, b.value
+
+    def export(self, sample: int) -> dict:
+        """Host copies of one sample's schedule (numpy arrays, shapes as in hdt_layout_export)."""
+        inf = self.info()
+        T, _ = self.sample_info(sample)
+        n, tr, tc, bm, bn = inf["n_pos"], inf["q_tiles"], inf["k_tiles"], inf["tile_m"], inf["tile_n"]
+        out = dict(
+            kperm=np.zeros(max(n, 1), np.int32), q_rowptr=np.zeros(tr + 1, np.int32),
+            q_cols=np.zeros(max(T, 1), np.int32), q_sub=np.zeros(max(T, 1), np.uint32),
+            bits=np.zeros((max(T, 1), bm, bn // 32), np.uint32), k_colptr=np.zeros(tc + 1, np.int32),
+            k_rows=np.zeros(max(T, 1), np.int32), k_tile=np.zeros(max(T, 1), np.int32))
+        p = {k: ctypes.c_void_p(v.ctypes.data) for k, v in out.items()}
+        _check(load_library().hdt_layout_export(self._h, sample, p["kperm"], p["q_rowptr"], p["q_cols"], p["q_sub"],
+                                                p["bits"], p["k_colptr"], p["k_rows"], p["k_tile"], max(T, 1)))
+        out["kperm"] = out["kperm"][:n]
+        for key in ("q_cols", "q_sub", "bits", "k_rows", "k_tile"):
+            out[key] = out[key][:T]
+        return out
+
+    def destroy(self):
+        if self._h is not None and self._h.value:
+            _check(load_library().hdt_layout_destroy(self._h))
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dense: bool = False,
+                     no_sort: bool = False, stream=None) -> Layout:
+    """level, parent: int32 device tensors [batch][n_pos]."""
+    import torch
+    if level.dtype != torch.int32 or parent.dtype != torch.int32:
+        raise TypeError("level and parent must be int32")
+    if level.dim() != 2 or level.shape != parent.shape:
+        raise ValueError("level and parent must both be [batch][n_pos]")
+    if not (level.is_cuda and parent.is_cuda and level.is_contiguous() and parent.is_contiguous()):
+        raise ValueError("level and parent must be contiguous device tensors")
+    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort))
+    h = ctypes.c_void_p(0)
+    B, N = level.shape
+    _check(load_library().hdt_build_layout(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,
+                                           ctypes.byref(opts), _stream_ptr(stream), ctypes.byref(h)))
+    return Layout(h.value)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return HDT_BF16
+    if t.dtype == torch.float32:
+        return HDT_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check_tensors(ts, shape=None):
+    for t in ts:
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+        if shape is not None and tuple(t.shape) != tuple(shape):
+            raise ValueError(f"tensor shape {tuple(t.shape)} != {tuple(shape)}")
+
+
+def hdt_attn_fwd(layout: Layout, q, k, v, softmax_scale: float, o=None, lse=None, stream=None):
+    """q, k, v: [batch][heads][n_pos][head_dim] device tensors (bf16 or fp32).  Returns (o, lse)."""
+    import torch
+    _check_tensors((q, k, v), q.shape)
+    B, H, N, D = q.shape
+    inf = layout.info()
+    if (B, N) != (inf["batch"], inf["n_pos"]):
+        raise ValueError("q shape does not match the layout")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    _check(load_library().hdt_attn_fwd(layout.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), H, D,
+                                       _dtype_code(q), float(softmax_scale), _stream_ptr(stream)))
+    return o, lse
+
+
+def hdt_attn_bwd_workspace_bytes(layout: Layout, heads: int, head_dim: int, dtype_code: int) -> int:
+    return int(load_library().hdt_attn_bwd_workspace_bytes(layout.handle, heads, head_dim, dtype_code))
+
+
+def hdt_attn_bwd(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq=None, dk=None, dv=None,
+                 workspace=None, stream=None):
+    """Returns (dq, dk, dv)."""
+    import torch
+    _check_tensors((q, k, v, o, d_o), q.shape)
+    B, H, N, D = q.shape
+    inf = layout.info()
+    if (B, N) != (inf["batch"], inf["n_pos"]):
+        raise ValueError("q shape does not match the layout")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(q) if dk is None else dk
+    dv = torch.empty_like(q) if dv is None else dv
+    need = hdt_attn_bwd_workspace_bytes(layout, H, D, _dtype_code(q))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(load_library().hdt_attn_bwd(layout.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                       _ptr(dq), _ptr(dk), _ptr(dv), H, D, _dtype_code(q), float(softmax_scale),
+                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                       _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def hdt_timing_enable(enable: bool):
+    _check(load_library().hdt_timing_enable(int(enable)))
+
+
+def hdt_timing_reset():
+    _check(load_library().hdt_timing_reset())
+
+
+def hdt_timing_read() -> dict:
+    """{kernel name: (launches, total milliseconds)} since the last reset."""
+    cap = 64
+    names = (ctypes.c_char_p * cap)()
+    launches = (ctypes.c_int64 * cap)()
+    ms = (ctypes.c_double * cap)()
+    n = load_library().hdt_timing_read(names, launches, ms, cap)
+    return {names[i].decode(): (int(launches[i]), float(ms[i])) for i in range(min(n, cap))}

@@ -1,0 +1,329 @@
+// C-ABI entry points: argument checking, error text, layout lifetime and export, dispatch to the
+// kernel launchers.  No arithmetic of the method lives here.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "hdt_internal.h"
+
+// ---------------------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+
+hdt_status_t hdt_fail(hdt_status_t st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+extern "C" __attribute__((visibility("default"))) const char *hdt_last_error(void) { return g_err; }
+
+extern "C" __attribute__((visibility("default"))) const char *hdt_status_string(hdt_status_t s)
+{
+    switch (s) {
+    case HDT_OK: return "HDT_OK";
+    case HDT_ERR_INVALID_ARG: return "HDT_ERR_INVALID_ARG";
+    case HDT_ERR_SHAPE: return "HDT_ERR_SHAPE";
+    case HDT_ERR_HIERARCHY: return "HDT_ERR_HIERARCHY";
+    case HDT_ERR_UNSUPPORTED: return "HDT_ERR_UNSUPPORTED";
+    case HDT_ERR_OOM: return "HDT_ERR_OOM";
+    case HDT_ERR_HIP: return "HDT_ERR_HIP";
+    }
+    return "HDT_ERR_UNKNOWN";
+}
+
+bool hdt_layout_ok(const hdt_layout_t *l) { return l != nullptr && l->magic == HDT_LAYOUT_MAGIC; }
+
+// ---------------------------------------------------------------------------- timing
+namespace {
+struct TimedLaunch {
+    const char *name;
+    hipEvent_t start, stop;
+};
+bool g_timing = false;
+std::vector<TimedLaunch> g_launches;        // since the last reset
+std::vector<hipEvent_t> g_event_pool;       // events free for reuse
+const size_t kMaxTimedLaunches = 1 << 16;
+
+hipEvent_t take_event()
+{
+    if (!g_event_pool.empty()) {
+        hipEvent_t e = g_event_pool.back();
+        g_event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+}  // namespace
+
+HdtTimer::HdtTimer(const char *name, hipStream_t st) : slot(-1), stream(st)
+{
+    if (!g_timing || g_launches.size() >= kMaxTimedLaunches) return;
+    TimedLaunch t{name, take_event(), take_event()};
+    if (!t.start || !t.stop) return;
+    (void)hipEventRecord(t.start, stream);
+    slot = (int)g_launches.size();
+    g_launches.push_back(t);
+}
+
+HdtTimer::~HdtTimer()
+{
+    if (slot >= 0) (void)hipEventRecord(g_launches[slot].stop, stream);
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_timing_enable(int32_t enable)
+{
+    g_timing = enable != 0;
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_timing_reset(void)
+{
+    for (auto &t : g_launches) {
+        (void)hipEventSynchronize(t.stop);
+        g_event_pool.push_back(t.start);
+        g_event_pool.push_back(t.stop);
+    }
+    g_launches.clear();
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) int32_t hdt_timing_read(const char **names, int64_t *launches, double *total_ms, int32_t capacity)
+{
+    std::vector<const char *> seen;
+    std::vector<int64_t> cnt;
+    std::vector<double> ms;
+    for (auto &t : g_launches) {
+        if (hipEventSynchronize(t.stop) != hipSuccess) continue;
+        float dt = 0.f;
+        if (hipEventElapsedTime(&dt, t.start, t.stop) != hipSuccess) continue;
+        size_t i = 0;
+        for (; i < seen.size(); i++)
+            if (seen[i] == t.name || strcmp(seen[i], t.name) == 0) break;
+        if (i == seen.size()) {
+            seen.push_back(t.name);
+            cnt.push_back(0);
+            ms.push_back(0.0);
+        }
+        cnt[i] += 1;
+        ms[i] += dt;
+    }
+    for (size_t i = 0; i < seen.size() && (int32_t)i < capacity; i++) {
+        if (names) names[i] = seen[i];
+        if (launches) launches[i] = cnt[i];
+        if (total_ms) total_ms[i] = ms[i];
+    }
+    return (int32_t)seen.size();
+}
+
+// ---------------------------------------------------------------------------- layout queries
+static hdt_status_t fetch_stats(hdt_layout_t *l)
+{
+    if (l->stats_cached) return HDT_OK;
+    l->h_stats.assign((size_t)l->s.batch * 2, 0);
+    if (l->s.batch > 0 && l->d_stats) {
+        HDT_HIP_TRY(hipDeviceSynchronize());
+        HDT_HIP_TRY(hipMemcpy(l->h_stats.data(), l->d_stats, sizeof(int64_t) * 2 * l->s.batch,
+                              hipMemcpyDeviceToHost));
+    }
+    l->stats_cached = true;
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(const hdt_layout_t *layout, hdt_layout_info_t *info)
+{
+    if (!hdt_layout_ok(layout) || !info) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_info: NULL or invalid layout");
+    hdt_layout_t *l = const_cast<hdt_layout_t *>(layout);
+    hdt_status_t st = fetch_stats(l);
+    if (st != HDT_OK) return st;
+    info->batch = l->s.batch;
+    info->n_pos = l->s.n_pos;
+    info->tile_m = l->s.bm;
+    info->tile_n = l->s.bn;
+    info->q_tiles = l->s.tr;
+    info->k_tiles = l->s.tc;
+    info->n_tiles = 0;
+    info->nnz = 0;
+    for (int b = 0; b < l->s.batch; b++) {
+        info->n_tiles += l->h_stats[2 * b];
+        info->nnz += l->h_stats[2 * b + 1];
+    }
+    info->device_bytes = l->device_bytes;
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_sample_info(const hdt_layout_t *layout, int32_t sample, int64_t *n_tiles,
+                                               int64_t *nnz)
+{
+    if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_sample_info: invalid layout");
+    if (sample < 0 || sample >= layout->s.batch)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_sample_info: sample %d outside [0, %d)", sample, layout->s.batch);
+    hdt_layout_t *l = const_cast<hdt_layout_t *>(layout);
+    hdt_status_t st = fetch_stats(l);
+    if (st != HDT_OK) return st;
+    if (n_tiles) *n_tiles = l->h_stats[2 * sample];
+    if (nnz) *nnz = l->h_stats[2 * sample + 1];
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export(const hdt_layout_t *layout, int32_t sample, int32_t *kperm,
+                                          int32_t *q_rowptr, int32_t *q_cols, uint32_t *q_sub, uint32_t *bits,
+                                          int32_t *k_colptr, int32_t *k_rows, int32_t *k_tile,
+                                          int64_t tile_capacity)
+{
+    if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_export: invalid layout");
+    const HdtSchedule &s = layout->s;
+    if (sample < 0 || sample >= s.batch)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: sample %d outside [0, %d)", sample, s.batch);
+    hdt_layout_t *l = const_cast<hdt_layout_t *>(layout);
+    hdt_status_t st = fetch_stats(l);
+    if (st != HDT_OK) return st;
+    const int64_t T = l->h_stats[2 * sample];
+    const bool want_tiles = q_cols || q_sub || bits || k_rows || k_tile;
+    if (want_tiles && tile_capacity < T)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: capacity %lld < %lld tiles", (long long)tile_capacity,
+                        (long long)T);
+    HDT_HIP_TRY(hipDeviceSynchronize());
+    if (kperm && s.n_pos > 0)
+        HDT_HIP_TRY(hipMemcpy(kperm, s.kperm + (size_t)sample * s.n_slots, sizeof(int32_t) * s.n_pos,
+                              hipMemcpyDeviceToHost));
+    std::vector<int32_t> rp((size_t)s.tr + 1, 0), cp((size_t)s.tc + 1, 0);
+    if (s.tr > 0) {
+        HDT_HIP_TRY(hipMemcpy(rp.data(), s.q_rowptr + (size_t)sample * s.tr, sizeof(int32_t) * (s.tr + 1),
+                              hipMemcpyDeviceToHost));
+        HDT_HIP_TRY(hipMemcpy(cp.data(), s.k_colptr + (size_t)sample * s.tc, sizeof(int32_t) * (s.tc + 1),
+                              hipMemcpyDeviceToHost));
+    }
+    const int32_t base = rp[0], kbase = cp[0];
+    if ((int64_t)rp[s.tr] - base != T || (int64_t)cp[s.tc] - kbase != T || base != kbase)
+        return hdt_fail(HDT_ERR_HIP, "hdt_layout_export: inconsistent tile counts (%d..%d, %d..%d, %lld)", base,
+                        rp[s.tr], kbase, cp[s.tc], (long long)T);
+    if (q_rowptr)
+        for (int i = 0; i <= s.tr; i++) q_rowptr[i] = rp[i] - base;
+    if (k_colptr)
+        for (int i = 0; i <= s.tc; i++) k_colptr[i] = cp[i] - kbase;
+    if (T > 0) {
+        if (q_cols) HDT_HIP_TRY(hipMemcpy(q_cols, s.q_cols + base, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
+        if (q_sub) HDT_HIP_TRY(hipMemcpy(q_sub, s.q_sub + base, sizeof(uint32_t) * T, hipMemcpyDeviceToHost));
+        if (k_rows) HDT_HIP_TRY(hipMemcpy(k_rows, s.k_rows + kbase, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
+        if (k_tile) {
+            HDT_HIP_TRY(hipMemcpy(k_tile, s.k_tile + kbase, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
+            for (int64_t t = 0; t < T; t++) k_tile[t] -= base;
+        }
+        if (bits) {
+            std::vector<int32_t> bidx((size_t)T);
+            HDT_HIP_TRY(hipMemcpy(bidx.data(), s.q_bidx + base, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
+            const size_t words = (size_t)s.bm * s.wpr;
+            for (int64_t t = 0; t < T; t++)
+                HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + (size_t)bidx[t] * words,
+                                      sizeof(uint32_t) * words, hipMemcpyDeviceToHost));
+        }
+    }
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destroy(hdt_layout_t *layout)
+{
+    if (!layout) return HDT_OK;
+    if (layout->magic != HDT_LAYOUT_MAGIC) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_destroy: not a layout");
+    layout->magic = 0;
+    hipError_t e = hipSuccess;
+    if (layout->arena) e = hipFree(layout->arena);
+    if (layout->arena2) {
+        hipError_t e2 = hipFree(layout->arena2);
+        if (e == hipSuccess) e = e2;
+    }
+    delete layout;
+    if (e != hipSuccess) return hdt_fail(HDT_ERR_HIP, "hipFree: %s", hipGetErrorString(e));
+    return HDT_OK;
+}
+
+// ---------------------------------------------------------------------------- attention
+static hdt_status_t check_attn_args(const char *fn, const hdt_layout_t *layout, int32_t heads, int32_t head_dim,
+                                    hdt_dtype_t dt, float scale)
+{
+    if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "%s: NULL or invalid layout", fn);
+    if (heads < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "%s: heads = %d", fn, heads);
+    if (!(scale > 0.f) || !isfinite(scale))
+        return hdt_fail(HDT_ERR_INVALID_ARG, "%s: softmax_scale must be positive and finite", fn);
+    if (dt != HDT_BF16 && dt != HDT_F32) return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, (int)dt);
+    if (head_dim != 64 && head_dim != 128)
+        return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: head_dim %d (supported: 64, 128)", fn, head_dim);
+    if (dt == HDT_BF16 && (layout->s.bm != 128 || layout->s.bn != 64))
+        return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: bf16 kernels need 128x64 tiles, layout has %dx%d", fn,
+                        layout->s.bm, layout->s.bn);
+    return HDT_OK;
+}
+
+static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
+                                     void *o, float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt,
+                                     float scale, void *stream)
+{
+    hdt_status_t st = check_attn_args("hdt_attn_fwd", layout, heads, head_dim, dt, scale);
+    if (st != HDT_OK) return st;
+    const HdtSchedule &s = layout->s;
+    if (s.batch == 0 || s.n_pos == 0 || heads == 0) return HDT_OK;
+    if (!q || !k || !v || !o || !lse) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_fwd: NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || ((uintptr_t)lse & 3u))
+        return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_fwd: tensor pointers must be 16-byte aligned");
+    if (o == q || o == k || o == v) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_fwd: output aliases an input");
+    if ((int64_t)s.batch * heads * s.tr > 0x7fffffffLL)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_fwd: batch*heads*q_tiles exceeds the grid limit");
+    hipStream_t hs = (hipStream_t)stream;
+    if (dt == HDT_BF16) return hdt_launch_fwd_bf16(s, q, k, v, o, lse, heads, head_dim, scale, hs);
+    return hdt_launch_fwd_f32(s, (const float *)q, (const float *)k, (const float *)v, (float *)o, lse, heads,
+                              head_dim, scale, hs);
+}
+
+extern "C" __attribute__((visibility("default"))) size_t hdt_attn_bwd_workspace_bytes(const hdt_layout_t *layout, int32_t heads, int32_t head_dim,
+                                               hdt_dtype_t dt)
+{
+    (void)head_dim;
+    (void)dt;
+    if (!hdt_layout_ok(layout) || heads < 0) return 0;
+    // D_i = sum_c dO_ic O_ic, one float per (batch, head, position)
+    size_t n = (size_t)layout->s.batch * (size_t)heads * (size_t)layout->s.n_pos * sizeof(float);
+    return (n + 255) & ~(size_t)255;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
+                                     const void *o, const float *lse, const void *d_o, void *dq, void *dk,
+                                     void *dv, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float scale,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    hdt_status_t st = check_attn_args("hdt_attn_bwd", layout, heads, head_dim, dt, scale);
+    if (st != HDT_OK) return st;
+    const HdtSchedule &s = layout->s;
+    if (s.batch == 0 || s.n_pos == 0 || heads == 0) return HDT_OK;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv)
+        return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: NULL tensor pointer");
+    const void *ptrs[] = {q, k, v, o, d_o, dq, dk, dv, workspace};
+    for (const void *p : ptrs)
+        if (misaligned(p)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: pointers must be 16-byte aligned");
+    const void *ins[] = {q, k, v, o, d_o};
+    void *outs[] = {dq, dk, dv};
+    for (void *w : outs) {
+        for (const void *r : ins)
+            if (w == r) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: output aliases an input");
+    }
+    if (dq == dk || dq == dv || dk == dv) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: outputs alias each other");
+    size_t need = hdt_attn_bwd_workspace_bytes(layout, heads, head_dim, dt);
+    if (!workspace || workspace_bytes < need)
+        return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: workspace of %zu bytes needed, %zu given", need,
+                        workspace_bytes);
+    if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) > 0x7fffffffLL)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
+    hipStream_t hs = (hipStream_t)stream;
+    if (dt == HDT_BF16)
+        return hdt_launch_bwd_bf16(s, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, (float *)workspace, hs);
+    return hdt_launch_bwd_f32(s, (const float *)q, (const float *)k, (const float *)v, (const float *)o, lse,
+                              (const float *)d_o, (float *)dq, (float *)dk, (float *)dv, heads, head_dim, scale,
+                              (float *)workspace, hs);
+}

@@ -1,0 +1,78 @@
+// Internal declarations shared by the translation units of libhdt (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "hdt.h"
+
+#define HDT_LAYOUT_MAGIC 0x4844544cu  // "HDTL"
+
+// Device-side view of a tile schedule, passed by value to the attention kernels.
+struct HdtSchedule {
+    int32_t batch, n_pos;
+    int32_t bm, bn;        // tile shape (query rows x key slots)
+    int32_t tr, tc;        // tiles per sample along queries / keys
+    int32_t n_slots;       // tc * bn: length of one sample's padded key order
+    int32_t wpr;           // bitmap words per tile row = bn / 32
+    const int32_t *kperm;  // [batch][n_slots] sorted slot -> position, -1 beyond n_pos
+    const int32_t *q_rowptr;  // [batch*tr + 1] entries of query tile (b, I), global numbering
+    const int32_t *q_cols;    // [n_tiles] key tile of each entry
+    const uint32_t *q_sub;    // [n_tiles] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
+    const int32_t *q_bidx;    // [n_tiles] index of the entry's bitmap in `bits`
+    const uint32_t *bits;     // [capacity][bm][wpr]   row r, word c/32, bit c%32
+    const uint32_t *bits_t;   // [capacity][bn][bm/32] the same bitmap by column: col c, word r/32, bit r%32
+    const int32_t *k_colptr;  // [batch*tc + 1] transposed entries of key tile (b, J)
+    const int32_t *k_rows;    // [n_tiles] query tile of each transposed entry
+    const int32_t *k_tile;    // [n_tiles] index of the entry in the q-ordered arrays
+};
+
+struct hdt_layout {
+    uint32_t magic;
+    HdtSchedule s;       // pointers into `arena`
+    int32_t device;      // device the buffers live on
+    int64_t capacity;    // entries the tile arrays can hold (= candidates found)
+    int64_t device_bytes;
+    void *arena;         // key order, lists' pointers, scratch of the build
+    void *arena2;        // per-tile arrays, sized once the number of candidate tiles is known
+    int64_t *d_stats;    // [batch][2] = (n_tiles, nnz) per sample, inside the arena
+    bool stats_cached;
+    std::vector<int64_t> h_stats;
+};
+
+// --- error reporting (hdt_api.hip) ---
+hdt_status_t hdt_fail(hdt_status_t st, const char *fmt, ...);
+#define HDT_HIP_TRY(expr)                                                                     \
+    do {                                                                                      \
+        hipError_t _e = (expr);                                                               \
+        if (_e != hipSuccess)                                                                 \
+            return hdt_fail(_e == hipErrorOutOfMemory ? HDT_ERR_OOM : HDT_ERR_HIP, "%s: %s", \
+                            #expr, hipGetErrorString(_e));                                    \
+    } while (0)
+
+bool hdt_layout_ok(const hdt_layout_t *l);
+
+// --- per-kernel timing (hdt_api.hip) ---
+struct HdtTimer {  // brackets one kernel launch with events when timing is enabled
+    HdtTimer(const char *name, hipStream_t stream);
+    ~HdtTimer();
+    int slot;
+    hipStream_t stream;
+};
+
+// --- kernels' host launchers (each validates nothing; callers have done it) ---
+hdt_status_t hdt_launch_fwd_bf16(const HdtSchedule &s, const void *q, const void *k, const void *v, void *o,
+                                 float *lse, int heads, int head_dim, float scale, hipStream_t st);
+hdt_status_t hdt_launch_fwd_f32(const HdtSchedule &s, const float *q, const float *k, const float *v, float *o,
+                                float *lse, int heads, int head_dim, float scale, hipStream_t st);
+hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const void *q, const void *k, const void *v,
+                                 const void *o, const float *lse, const void *d_o, void *dq, void *dk,
+                                 void *dv, int heads, int head_dim, float scale, float *ws_delta,
+                                 hipStream_t st);
+hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const float *q, const float *k, const float *v,
+                                const float *o, const float *lse, const float *d_o, float *dq, float *dk,
+                                float *dv, int heads, int head_dim, float scale, float *ws_delta,
+                                hipStream_t st);

@@ -1,0 +1,69 @@
+"""Helpers for the GPU parity tests: move seeded inputs to the device, call the C ABI through the
+binding, bring results back as numpy."""
+import sys
+
+import numpy as np
+
+from paper_2407_08330_amd import inputs
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def to_dev_i32(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def to_dev_bf16(x32):
+    """float32 numpy values that are already bf16-representable -> bf16 device tensor."""
+    import torch
+    bits = inputs.bf16_bits(x32)
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def from_dev(t):
+    """device tensor (bf16 or fp32) -> float32 numpy"""
+    import torch
+    if t.dtype == torch.bfloat16:
+        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return inputs.bf16_bits_to_f32(bits)
+    return t.float().cpu().numpy()
+
+
+def make_inputs(B, H, N, D, seed, dtype, n_tensors=3):
+    """Seeded N(0,1) tensors; for bf16 they are rounded first so that both sides see the same values."""
+    xs = inputs.make_qkv(B, H, N, D, seed, n_tensors)
+    if dtype == "bf16":
+        xs = [inputs.round_to_bf16(x) for x in xs]
+        dev = [to_dev_bf16(x) for x in xs]
+    else:
+        import torch
+        dev = [torch.from_numpy(x).cuda() for x in xs]
+    return xs, dev
+
+
+def compare_layout(oracle, layout, level, parent, bm, bn, **kw):
+    """Bit-exact comparison of every exported array of every sample with the oracle's schedule."""
+    B = level.shape[0]
+    total_tiles = total_nnz = 0
+    for b in range(B):
+        ref = oracle.block_schedule(level[b], parent[b], bm, bn, **kw)
+        got = layout.export(b)
+        np.testing.assert_array_equal(got["kperm"], ref.kperm, err_msg=f"kperm sample {b}")
+        np.testing.assert_array_equal(got["q_rowptr"], ref.q_rowptr, err_msg=f"q_rowptr sample {b}")
+        np.testing.assert_array_equal(got["q_cols"], ref.q_cols, err_msg=f"q_cols sample {b}")
+        np.testing.assert_array_equal(got["q_sub"], ref.q_sub, err_msg=f"q_sub sample {b}")
+        np.testing.assert_array_equal(got["bits"], ref.bits, err_msg=f"bits sample {b}")
+        np.testing.assert_array_equal(got["k_colptr"], ref.k_colptr, err_msg=f"k_colptr sample {b}")
+        np.testing.assert_array_equal(got["k_rows"], ref.k_rows, err_msg=f"k_rows sample {b}")
+        np.testing.assert_array_equal(got["k_tile"], ref.k_tile, err_msg=f"k_tile sample {b}")
+        n_tiles, nnz = layout.sample_info(b)
+        assert n_tiles == ref.q_cols.shape[0] and nnz == ref.nnz
+        total_tiles += n_tiles
+        total_nnz += nnz
+    info = layout.info()
+    assert info["n_tiles"] == total_tiles and info["nnz"] == total_nnz
+    return total_tiles, total_nnz

@@ -1,0 +1,117 @@
+"""GPU parity: hdt_build_layout against the oracle's brute-force block schedule, bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2407_08330_amd import inputs
+from gpu_common import compare_layout, say, to_dev_i32
+
+pytestmark = pytest.mark.gpu
+
+
+def _build(level, parent, **kw):
+    import paper_2407_08330_amd as hdt
+    return hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), **kw)
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 5])
+def test_layout_matches_oracle_on_benchmark_configs(oracle, config):
+    wl = inputs.make_workload(config)
+    say(f"[layout] config {config} B={wl.batch} N={wl.n_pos}")
+    lay = _build(wl.level, wl.parent)
+    tiles, nnz = compare_layout(oracle, lay, wl.level, wl.parent, 128, 64)
+    say(f"[layout] config {config}: {tiles} tiles, nnz {nnz}")
+    lay.destroy()
+
+
+@pytest.mark.parametrize("bm,bn", [(64, 32), (32, 32), (128, 128), (96, 64)])
+def test_layout_other_tile_shapes(oracle, bm, bn):
+    wl = inputs.make_workload(2, batch=2)
+    say(f"[layout] tile {bm}x{bn}")
+    lay = _build(wl.level, wl.parent, tile_m=bm, tile_n=bn)
+    compare_layout(oracle, lay, wl.level, wl.parent, bm, bn)
+
+
+@pytest.mark.parametrize("n", [1, 31, 100, 129, 1000, 4097])
+def test_layout_ragged_lengths(oracle, n):
+    rng = np.random.default_rng(n)
+    level, parent = inputs.tree_document([(1, 6), (0, 7), (0, 20)], rng, max_nodes=n)
+    level = np.concatenate([level, np.full(n - level.shape[0], -1, np.int32)])[None]
+    parent = np.concatenate([parent, np.full(n - parent.shape[0], -1, np.int32)])[None]
+    say(f"[layout] ragged n={n} real={(level >= 0).sum()}")
+    lay = _build(level, parent)
+    compare_layout(oracle, lay, level, parent, 128, 64)
+
+
+def test_layout_deep_trees_and_all_pad_sample(oracle):
+    rng = np.random.default_rng(11)
+    n = 768
+    lv, pr = [], []
+    for s in range(3):
+        l, p = inputs.tree_document([(1, 4)] * 7 + [(0, 5)], rng, n_pos=None, max_nodes=n)
+        lv.append(np.concatenate([l, np.full(n - l.shape[0], -1, np.int32)]))
+        pr.append(np.concatenate([p, np.full(n - p.shape[0], -1, np.int32)]))
+    lv.append(np.full(n, -1, np.int32))   # an empty document: all pads
+    pr.append(np.full(n, -1, np.int32))
+    level, parent = np.stack(lv), np.stack(pr)
+    say("[layout] deep trees + all-pad sample")
+    lay = _build(level, parent)
+    compare_layout(oracle, lay, level, parent, 128, 64)
+    assert lay.sample_info(3) == (0, 0)
+
+
+def test_layout_positions_not_in_preorder(oracle):
+    # a shuffled document: sibling groups are scattered, candidate ranges over-approximate and the
+    # exact per-tile evaluation has to drop the empty ones
+    wl = inputs.make_workload(1)
+    rng = np.random.default_rng(5)
+    n = wl.n_pos
+    perm = rng.permutation(n)              # new position of old position i is perm[i]
+    level = np.empty(n, np.int32)
+    parent = np.empty(n, np.int32)
+    level[perm] = wl.level[0]
+    old_parent = wl.parent[0]
+    parent[perm] = np.where(old_parent >= 0, perm[np.maximum(old_parent, 0)], -1)
+    say("[layout] shuffled positions")
+    lay = _build(level[None], parent[None])
+    compare_layout(oracle, lay, level[None], parent[None], 128, 64)
+
+
+def test_layout_force_dense_and_no_sort(oracle):
+    wl = inputs.make_workload(1)
+    say("[layout] force_dense / no_sort")
+    lay = _build(wl.level, wl.parent, force_dense=True)
+    tiles, _ = compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, force_dense=True)
+    assert tiles == 4 * 8
+    lay = _build(wl.level, wl.parent, no_sort=True)
+    compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, use_sort=False)
+
+
+def test_layout_rejects_bad_hierarchies():
+    import paper_2407_08330_amd as hdt
+    good_l = np.array([[0, 1, 2, 3, -1, -1]], np.int32)
+    good_p = np.array([[-1, 0, 1, 2, -1, -1]], np.int32)
+    _build(good_l, good_p)
+    cases = {
+        "self parent": (good_l, np.array([[-1, 1, 1, 2, -1, -1]], np.int32)),
+        "parent out of range": (good_l, np.array([[-1, 0, 1, 6, -1, -1]], np.int32)),
+        "parent below -1": (good_l, np.array([[-2, 0, 1, 2, -1, -1]], np.int32)),
+        "pad with parent": (good_l, np.array([[-1, 0, 1, 2, 0, -1]], np.int32)),
+        "pad parent": (good_l, np.array([[-1, 0, 1, 4, -1, -1]], np.int32)),
+        "level too large": (np.array([[0, 1, 2, 32, -1, -1]], np.int32), good_p),
+        "level below -1": (np.array([[0, 1, 2, 3, -2, -1]], np.int32), good_p),
+    }
+    for name, (l, p) in cases.items():
+        say(f"[layout] reject: {name}")
+        with pytest.raises(hdt.HdtError) as e:
+            _build(l, p)
+        assert e.value.name == "HDT_ERR_HIERARCHY", name
+
+
+def test_layout_empty_inputs():
+    import torch
+    import paper_2407_08330_amd as hdt
+    for shape in [(0, 128), (3, 0), (0, 0)]:
+        z = torch.zeros(shape, dtype=torch.int32, device="cuda")
+        lay = hdt.hdt_build_layout(z, z.clone())
+        info = lay.info()
+        assert info["n_tiles"] == 0 and info["nnz"] == 0 and info["batch"] == shape[0]
