@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the hierarchical-attention hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch: hdt_build_layout (level/parent ids ->
+tile schedule), hdt_attn_fwd and hdt_attn_bwd, all through the C ABI, inputs resident in HBM.
+Workload = the training step at 8192 positions (batch 4, 12 heads, head_dim 64, bf16), the
+configuration the headline metric is quoted on.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def algorithmic_bytes_per_unit(kernel: str, d: int) -> int:
+    """Compulsory HBM bytes per (position, head) of one launch of `kernel` (bf16 tensors, fp32 LSE/D):
+    forward reads Q,K,V and writes O,LSE; the dQ pass reads Q,K,V,O,dO,LSE and writes dQ,D; the
+    dK/dV pass reads Q,K,V,dO,LSE,D and writes dK,dV."""
+    row = 2 * d
+    if kernel.startswith("hdt_fwd"):
+        return 4 * row + 4
+    if kernel.startswith("hdt_bwd_dq"):
+        return 6 * row + 8
+    if kernel.startswith("hdt_bwd_dkv"):
+        return 6 * row + 8
+    raise KeyError(kernel)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, choices=[2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="do not bracket kernels with events (for external profilers)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (batch and heads shard without any exchange; "
+              "no multi-GPU path is part of it). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2407_08330_amd as hdt
+    from paper_2407_08330_amd import inputs
+
+    wl = inputs.make_workload(args.config)
+    B, H, N, D = wl.batch, wl.heads, wl.n_pos, wl.head_dim
+    scale = wl.softmax_scale
+    do_bwd = wl.backward
+    dev = torch.device("cuda:0")
+    level = torch.from_numpy(wl.level).to(dev)
+    parent = torch.from_numpy(wl.parent).to(dev)
+
+    # several independent buffer sets so that successive steps do not find their inputs in the
+    # 256 MB last-level cache
+    n_sets = 3
+    sets = []
+    for i in range(n_sets):
+        xs = inputs.make_qkv(B, H, N, D, inputs.sample_seed(args.config, 70 + i), 4 if do_bwd else 3)
+        t = [torch.from_numpy(inputs.bf16_bits(inputs.round_to_bf16(x)).view(np.int16)).to(dev).view(torch.bfloat16)
+             for x in xs]
+        outs = dict(o=torch.empty_like(t[0]), lse=torch.empty((B, H, N), dtype=torch.float32, device=dev))
+        if do_bwd:
+            outs.update(dq=torch.empty_like(t[0]), dk=torch.empty_like(t[0]), dv=torch.empty_like(t[0]))
+        sets.append((t, outs))
+    del xs
+    probe = hdt.hdt_build_layout(level, parent)
+    info = probe.info()
+    ws_bytes = hdt.hdt_attn_bwd_workspace_bytes(probe, H, D, 0)
+    workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    probe.destroy()
+
+    layouts = []
+
+    def step(i):
+        t, outs = sets[i % n_sets]
+        lay = hdt.hdt_build_layout(level, parent)
+        hdt.hdt_attn_fwd(lay, t[0], t[1], t[2], scale, o=outs["o"], lse=outs["lse"])
+        if do_bwd:
+            hdt.hdt_attn_bwd(lay, t[0], t[1], t[2], outs["o"], outs["lse"], t[3], scale, dq=outs["dq"],
+                             dk=outs["dk"], dv=outs["dv"], workspace=workspace)
+        layouts.append(lay)   # freed after the timed region: hipFree synchronises the device
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    for lay in layouts:
+        lay.destroy()
+    layouts.clear()
+
+    if not args.no_kernel_timing:
+        hdt.hdt_timing_enable(True)
+        hdt.hdt_timing_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kernels = {} if args.no_kernel_timing else hdt.hdt_timing_read()
+    hdt.hdt_timing_enable(False)
+    for lay in layouts:
+        lay.destroy()
+    layouts.clear()
+
+    tokens = B * N
+    value = tokens / (ms_per_step * 1e-3)
+    nnz, n_tiles = info["nnz"], info["n_tiles"]
+    useful_flop = (4 + (10 if do_bwd else 0)) * nnz * D * H
+    issued_fwd_flop = 4 * n_tiles * 128 * 64 * D * H
+
+    per_kernel = {name: {"launches": c, "avg_us": 1e3 * ms / c} for name, (c, ms) in kernels.items() if c}
+    phase_us = {"layout": 0.0, "fwd": 0.0, "bwd": 0.0}
+    for name, kv in per_kernel.items():
+        per_step = kv["avg_us"] * kv["launches"] / args.steps
+        if name.startswith("hdt_layout"):
+            phase_us["layout"] += per_step
+        elif name.startswith("hdt_fwd"):
+            phase_us["fwd"] += per_step
+        else:
+            phase_us["bwd"] += per_step
+
+    roofline = None
+    attn = {n: kv for n, kv in per_kernel.items() if not n.startswith("hdt_layout")}
+    if attn:
+        dom = max(attn, key=lambda n: attn[n]["avg_us"] * attn[n]["launches"])
+        units = B * H * N
+        alg_bytes = algorithmic_bytes_per_unit(dom, D) * units
+        achieved = alg_bytes / (attn[dom]["avg_us"] * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(attn[dom]["avg_us"], 2)}
+
+    out = {
+        "metric": "hier-attn fwd+bwd tokens/s at 8192 tok (layout build + forward + backward per step)"
+        if do_bwd else "hier-attn fwd tokens/s (layout build + forward per step)",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{wl.name}", "batch": B, "heads": H, "head_dim": D,
+                   "n_pos": N, "real_positions": wl.n_real, "tile": "128x64", "n_tiles": n_tiles, "nnz": nnz},
+        "useful_tflops": round(useful_flop / (ms_per_step * 1e-3) / 1e12, 3),
+        "phase_us_per_step": {k: round(v, 2) for k, v in phase_us.items()},
+        "kernels": {n: {"launches": kv["launches"], "avg_us": round(kv["avg_us"], 2)} for n, kv in per_kernel.items()},
+        "roofline": roofline,
+    }
+    fwd_name = next((n for n in per_kernel if n.startswith("hdt_fwd")), None)
+    if fwd_name:
+        fwd_us = per_kernel[fwd_name]["avg_us"]
+        out["fwd"] = {
+            "tokens_per_s": round(tokens / (fwd_us * 1e-6), 1),
+            "useful_tflops": round(4 * nnz * D * H / (fwd_us * 1e-6) / 1e12, 3),
+            "issued_tile_tflops": round(issued_fwd_flop / (fwd_us * 1e-6) / 1e12, 2),
+            "mfma_frac_on_issued_tiles": round(issued_fwd_flop / (fwd_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "hbm_gbs_algorithmic": round(algorithmic_bytes_per_unit(fwd_name, D) * B * H * N / (fwd_us * 1e-6) / 1e9, 1),
+        }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on the host cores: mask enumeration + forward (+ backward) of the
+        # same batch with fresh seeded inputs, once
+        from oracle import oracle
+        xs = [inputs.round_to_bf16(x) for x in inputs.make_qkv(B, H, N, D, inputs.sample_seed(args.config, 70),
+                                                               4 if do_bwd else 3)]
+        c0 = time.perf_counter()
+        oracle.attn_fwd(xs[0], xs[1], xs[2], wl.level, wl.parent, scale)
+        if do_bwd:
+            oracle.attn_bwd(xs[0], xs[1], xs[2], xs[3], wl.level, wl.parent, scale)
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": round(tokens / (c1 - c0), 1), "unit": "tokens/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"the whole batch once ({tokens} positions, {H} heads): pairwise mask "
+                                         f"enumeration + fp64 forward{' + backward' if do_bwd else ''}, "
+                                         f"{c1 - c0:.2f} s wall"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

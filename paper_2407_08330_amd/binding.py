@@ -52,6 +52,9 @@ def load_library():
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(f"{_LIB_PATH} not built; run __graft_entry__.build() first")
+    # PyTorch-ROCm ships its own HIP runtime.  Import it first so that libhdt binds to that same
+    # copy: two HIP runtimes in one process do not see each other's device state.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
     lib.hdt_build_layout.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_Opts), vp, ctypes.POINTER(vp)]
