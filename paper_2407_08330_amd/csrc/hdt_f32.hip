@@ -113,9 +113,9 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
     const size_t col = (size_t)b * s.tc + J;
     for (int en = s.k_colptr[col]; en < s.k_colptr[col + 1]; en++) {
         const int I = s.k_rows[en], t = s.k_tile[en];
-        const uint32_t *bw = s.bits_t + ((size_t)s.q_bidx[t] * s.bn + c) * (s.bm >> 5);  // column c
+        const uint32_t *bw = s.bits + (size_t)s.q_bidx[t] * s.bm * s.wpr;
         for (int r = 0; r < s.bm; r++) {
-            if (!((bw[r >> 5] >> (r & 31)) & 1u)) continue;
+            if (!((bw[r * s.wpr + (c >> 5)] >> (c & 31)) & 1u)) continue;
             const int i = I * s.bm + r;
             const float *qi = q + base + (size_t)i * D;
             const float *doi = d_o + base + (size_t)i * D;

@@ -24,7 +24,9 @@ struct HdtSchedule {
     const uint32_t *q_sub;    // [n_tiles] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
     const int32_t *q_bidx;    // [n_tiles] index of the entry's bitmap in `bits`
     const uint32_t *bits;     // [capacity][bm][wpr]   row r, word c/32, bit c%32
-    const uint32_t *bits_t;   // [capacity][bn][bm/32] the same bitmap by column: col c, word r/32, bit r%32
+    // [capacity][(bm/32)*(bn/32)][16] per 32x32 sub-block (r, c) = index r*(bn/32)+c: bit l of word e <=>
+    // row 32r + l%32, column 32c + (l/32)*4 + 8*(e/4) + e%4 allowed: the lane mask of MFMA accumulator register e
+    const unsigned long long *bits_rm;
     const int32_t *k_colptr;  // [batch*tc + 1] transposed entries of key tile (b, J)
     const int32_t *k_rows;    // [n_tiles] query tile of each transposed entry
     const int32_t *k_tile;    // [n_tiles] index of the entry in the q-ordered arrays

@@ -240,112 +240,138 @@ __global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restri
 }
 
 // ---- 4. exact evaluation of every candidate tile ---------------------------------------------
+// 4a: one wave per query tile lists its candidates: c_row[c] = query tile (global), c_col[c] = key tile
+__global__ __launch_bounds__(64) void k_expand_candidates(const uint32_t *__restrict__ cand,
+                                                          const int32_t *__restrict__ cand_ptr, int tr, int wc,
+                                                          int64_t capacity, int32_t *c_row, int32_t *c_col)
+{
+    const int I = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const size_t row = (size_t)b * tr + I;
+    const int cbase = cand_ptr[row];
+    int n_cand = 0;
+    for (int w0 = 0; w0 < wc; w0 += 2) {
+        const int w = w0 + (lane >> 5), bit = lane & 31;
+        const uint32_t word = w < wc ? cand[row * wc + w] : 0u;
+        const bool is_cand = (word >> bit) & 1u;
+        const unsigned long long cm = __ballot(is_cand);
+        const int64_t c = (int64_t)cbase + n_cand + __popcll(cm & lanemask_lt());
+        if (is_cand && c < capacity) {
+            c_row[c] = (int32_t)row;
+            c_col[c] = (w << 5) + bit;
+        }
+        n_cand += __popcll(cm);
+    }
+}
+
+// 4b: one workgroup per candidate tile: pair-by-pair bitmap (row-major words for export and the
+// fp32 path, and per 32x32 sub-block the 16 x 64-bit lane masks the MFMA kernels apply to their
+// accumulator registers), pair count and sub-block summary.
 __global__ __launch_bounds__(256) void k_tile_bitmaps(const int32_t *__restrict__ level,
                                                       const int32_t *__restrict__ parent,
                                                       const int32_t *__restrict__ kperm,
-                                                      const uint32_t *__restrict__ cand,
-                                                      const int32_t *__restrict__ cand_ptr, int n, int n_slots,
-                                                      int bm, int bn, int tr, int wc, int force_dense,
-                                                      int64_t capacity, uint32_t *bits, uint32_t *bits_t, int32_t *c_col,
-                                                      int32_t *c_cnt, uint32_t *c_sub, int32_t *row_cnt,
-                                                      unsigned long long *stats)
+                                                      const int32_t *__restrict__ c_row,
+                                                      const int32_t *__restrict__ c_col, int n, int n_slots,
+                                                      int bm, int bn, int tr, uint32_t *bits,
+                                                      unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
 {
     __shared__ int s_kpos[128], s_kpar[128];
-    __shared__ int s_qpar[128];  // parent of each query row of this tile, INT_MIN for pad / out of range
+    __shared__ uint32_t s_words[128 * 4];
     __shared__ int s_cnt;
     __shared__ unsigned int s_any, s_all;
-    const int I = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int64_t c = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int row = c_row[c], J = c_col[c];
+    const int b = row / tr, I = row - b * tr;
     const size_t o = (size_t)b * n;
-    const size_t row = (size_t)b * tr + I;
     const int wpr = bn >> 5;
     const int words = bm * wpr;
-    const int cbase = cand_ptr[row];
-    int nth = 0, n_alive = 0;
-    long long nnz = 0;
-    const int wq_n = bm >> 5;
-    if (tid < bm) {
-        const int i = I * bm + tid;
-        s_qpar[tid] = (i < n && level[o + i] >= 0) ? parent[o + i] : INT_MIN;
-    }
-    for (int w = 0; w < wc; w++) {
-        uint32_t word = cand[row * wc + w];
-        while (word) {
-            const int J = (w << 5) + __ffs((int)word) - 1;
-            word &= word - 1;
-            const int64_t c = (int64_t)cbase + nth;
-            nth++;
-            if (c >= capacity) continue;  // cannot happen: capacity is the candidate total
-            __syncthreads();
-            if (tid < bn) {
-                const int s = J * bn + tid;
-                int pos = s < n_slots ? kperm[(size_t)b * n_slots + s] : -1;
-                int par = -1;
-                if (pos >= 0 && pos < n && level[o + pos] >= 0)
-                    par = parent[o + pos];
-                else
-                    pos = -1;
-                s_kpos[tid] = pos;
-                s_kpar[tid] = par;
-            }
-            if (tid == 0) {
-                s_cnt = 0;
-                s_any = 0;
-                s_all = 0xffffu;
-            }
-            __syncthreads();
-            for (int idx = tid; idx < words; idx += 256) {
-                const int r = idx / wpr, wd = idx - r * wpr;
-                const int i = I * bm + r;
-                uint32_t out = 0;
-                if (i < n && level[o + i] >= 0) {
-                    const int pi = parent[o + i];
-                    for (int cc = 0; cc < 32; cc++) {
-                        const int kj = s_kpos[wd * 32 + cc], kp = s_kpar[wd * 32 + cc];
-                        const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kp) || pi == kj || kp == i);
-                        out |= (uint32_t)ok << cc;
-                    }
-                }
-                bits[(size_t)c * words + idx] = out;
-                const int sub = (r >> 5) * wpr + wd;
-                if (out) {
-                    atomicAdd(&s_cnt, __popc(out));
-                    atomicOr(&s_any, 1u << sub);
-                }
-                if (out != 0xffffffffu) atomicAnd(&s_all, ~(1u << sub));
-            }
-            // the same pairs once more, gathered by column for the key-major backward pass
-            for (int idx = tid; idx < bn * wq_n; idx += 256) {
-                const int cc = idx / wq_n, wq = idx - cc * wq_n;
-                const int kj = s_kpos[cc], kp = s_kpar[cc];
-                uint32_t out = 0;
-                if (kj >= 0) {
-                    for (int r = 0; r < 32; r++) {
-                        const int pi = s_qpar[wq * 32 + r];
-                        const int i = I * bm + wq * 32 + r;
-                        const bool ok = pi != INT_MIN && (kj == i || (pi >= 0 && pi == kp) || pi == kj || kp == i);
-                        out |= (uint32_t)ok << r;
-                    }
-                }
-                bits_t[(size_t)c * words + idx] = out;
-            }
-            __syncthreads();
-            if (tid == 0) {
-                const int nsub = (bm >> 5) * wpr;
-                const unsigned int all = s_all & ((1u << nsub) - 1u);
-                c_col[c] = J;
-                c_cnt[c] = s_cnt;
-                c_sub[c] = s_any | (all << 16);
-                if (s_cnt > 0 || force_dense) {
-                    n_alive++;
-                    nnz += s_cnt;
-                }
-            }
-        }
+    const int nsub = (bm >> 5) * wpr;
+    if (tid < bn) {
+        const int s = J * bn + tid;
+        int pos = s < n_slots ? kperm[(size_t)b * n_slots + s] : -1;
+        int par = -1;
+        if (pos >= 0 && pos < n && level[o + pos] >= 0)
+            par = parent[o + pos];
+        else
+            pos = -1;
+        s_kpos[tid] = pos;
+        s_kpar[tid] = par;
     }
     if (tid == 0) {
-        row_cnt[row] = n_alive;
-        atomicAdd(&stats[2 * b], (unsigned long long)n_alive);
-        atomicAdd(&stats[2 * b + 1], (unsigned long long)nnz);
+        s_cnt = 0;
+        s_any = 0;
+        s_all = 0xffffu;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < words; idx += 256) {
+        const int r = idx / wpr, wd = idx - r * wpr;
+        const int i = I * bm + r;
+        uint32_t out = 0;
+        if (i < n && level[o + i] >= 0) {
+            const int pi = parent[o + i];
+            for (int cc = 0; cc < 32; cc++) {
+                const int kj = s_kpos[wd * 32 + cc], kp = s_kpar[wd * 32 + cc];
+                const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kp) || pi == kj || kp == i);
+                out |= (uint32_t)ok << cc;
+            }
+        }
+        bits[(size_t)c * words + idx] = out;
+        s_words[idx] = out;
+        const int sub = (r >> 5) * wpr + wd;
+        if (out) {
+            atomicAdd(&s_cnt, __popc(out));
+            atomicOr(&s_any, 1u << sub);
+        }
+        if (out != 0xffffffffu) atomicAnd(&s_all, ~(1u << sub));
+    }
+    __syncthreads();
+    // register-major masks: sub-block sb = rblk*wpr + cblk, accumulator register e, lane l:
+    // row rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
+    for (int idx = tid; idx < nsub * 16; idx += 256) {
+        const int sb = idx >> 4, e = idx & 15;
+        const int rblk = sb / wpr, cblk = sb - rblk * wpr;
+        unsigned long long m = 0;
+        for (int l = 0; l < 64; l++) {
+            const uint32_t w = s_words[(rblk * 32 + (l & 31)) * wpr + cblk];
+            const int bit = (l >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+            m |= (unsigned long long)((w >> bit) & 1u) << l;
+        }
+        bits_rm[(size_t)c * nsub * 16 + idx] = m;
+    }
+    if (tid == 0) {
+        const unsigned int all = s_all & ((1u << nsub) - 1u);
+        c_cnt[c] = s_cnt;
+        c_sub[c] = s_any | (all << 16);
+    }
+}
+
+// 4c: surviving tiles per query tile, and the per-sample totals
+__global__ __launch_bounds__(64) void k_row_counts(const int32_t *__restrict__ cand_ptr,
+                                                   const int32_t *__restrict__ c_cnt, int tr, int force_dense,
+                                                   int64_t capacity, int32_t *row_cnt, unsigned long long *stats)
+{
+    const int I = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const size_t row = (size_t)b * tr + I;
+    const int c0 = cand_ptr[row], c1 = cand_ptr[row + 1];
+    int alive = 0;
+    long long nnz = 0;
+    for (int c = c0 + lane; c < c1 && c < capacity; c += 64) {
+        const int cnt = c_cnt[c];
+        if (cnt > 0 || force_dense) {
+            alive++;
+            nnz += cnt;
+        }
+    }
+    for (int d = 32; d > 0; d >>= 1) {
+        alive += __shfl_xor(alive, d);
+        nnz += __shfl_xor(nnz, d);
+    }
+    if (lane == 0) {
+        row_cnt[row] = alive;
+        if (alive) {
+            atomicAdd(&stats[2 * b], (unsigned long long)alive);
+            atomicAdd(&stats[2 * b + 1], (unsigned long long)nnz);
+        }
     }
 }
 
@@ -576,7 +602,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
             int32_t *k_rows = c2.take<int32_t>((size_t)cap);
             int32_t *k_tile = c2.take<int32_t>((size_t)cap);
             uint32_t *bits = c2.take<uint32_t>((size_t)cap * words);
-            uint32_t *bits_t = c2.take<uint32_t>((size_t)cap * words);
+            unsigned long long *bits_rm = c2.take<unsigned long long>((size_t)cap * (bm / 32) * s.wpr * 16);
+            int32_t *c_row = c2.take<int32_t>((size_t)cap);
             if (pass == 0) {
                 if (cap > 0) BUILD_TRY(hipMalloc(&L->arena2, c2.off));
                 c2.base = (char *)L->arena2;
@@ -589,16 +616,25 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
             s.q_sub = q_sub;
             s.q_bidx = q_bidx;
             s.bits = bits;
-            s.bits_t = bits_t;
+            s.bits_rm = bits_rm;
             s.k_colptr = p.k_colptr;
             s.k_rows = k_rows;
             s.k_tile = k_tile;
             L->d_stats = p.stats;
             {
+                HdtTimer t("hdt_layout_expand", st);
+                hipLaunchKernelGGL(k_expand_candidates, dim3(tr, B), dim3(64), 0, st, p.cand, p.cand_ptr, tr, wc, cap,
+                                   c_row, c_col);
+            }
+            if (cap > 0) {
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
-                hipLaunchKernelGGL(k_tile_bitmaps, dim3(tr, B), dim3(256), 0, st, d_level, d_parent, p.kperm, p.cand,
-                                   p.cand_ptr, n, s.n_slots, bm, bn, tr, wc, force_dense, cap, bits, bits_t, c_col, c_cnt,
-                                   c_sub, p.row_cnt, (unsigned long long *)p.stats);
+                hipLaunchKernelGGL(k_tile_bitmaps, dim3((unsigned)cap), dim3(256), 0, st, d_level, d_parent, p.kperm,
+                                   c_row, c_col, n, s.n_slots, bm, bn, tr, bits, bits_rm, c_cnt, c_sub);
+            }
+            {
+                HdtTimer t("hdt_layout_row_counts", st);
+                hipLaunchKernelGGL(k_row_counts, dim3(tr, B), dim3(64), 0, st, p.cand_ptr, c_cnt, tr, force_dense, cap,
+                                   p.row_cnt, (unsigned long long *)p.stats);
             }
             {
                 HdtTimer t("hdt_layout_scan", st);
