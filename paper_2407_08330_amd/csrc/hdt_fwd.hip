@@ -6,8 +6,8 @@
 //
 // Work split: one workgroup (4 waves) per (sample, head, query tile of 128 rows); wave w owns
 // query rows 32w .. 32w+31.  A key tile is 64 slots of the level-sorted key order, gathered row
-// by row through kperm into LDS (coalesced 16-byte loads, one full 128/256-byte row per 8/16
-// lanes).  Inside a tile a wave works on 32x32 sub-blocks and skips those the layout marks empty.
+// by row through kperm straight into LDS (hdt_tile.h).  Inside a tile a wave works on 32x32
+// sub-blocks and skips those the layout marks empty.
 //
 // The scores are computed transposed, S^T = K Q^T (keys along the MFMA rows, queries along the
 // columns): then every lane owns ONE query (column l%32) and 16 of the 32 keys, so the row max and
@@ -28,15 +28,20 @@ namespace {
 using namespace hdt_tile;
 
 template <int D>
-__global__ __launch_bounds__(THREADS, 2) void k_fwd_bf16(HdtSchedule s, const __bf16 *__restrict__ q,
-                                                         const __bf16 *__restrict__ k,
-                                                         const __bf16 *__restrict__ v, __bf16 *__restrict__ o,
-                                                         float *__restrict__ lse, int heads, float scale_log2)
+struct FwdCfg {
+    static constexpr int S = (D == 64) ? 3 : 2;      // ring stages (LDS: 52 KB / 68 KB per workgroup)
+    static constexpr int WAVES = (D == 64) ? 3 : 2;  // waves per SIMD the register budget allows
+};
+
+template <int D>
+__global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
+    HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
+    __bf16 *__restrict__ o, float *__restrict__ lse, int heads, float scale_log2)
 {
-    using G = Geom<D>;
-    constexpr int K_STRIDE = G::ROW_STRIDE, V_STRIDE = G::TR_STRIDE;
-    __shared__ __attribute__((aligned(16))) char smem[BN * (K_STRIDE + V_STRIDE)];
-    char *sK = smem, *sV = smem + BN * K_STRIDE;
+    using P = Pipe<D, FwdCfg<D>::S, false>;
+    using R = Ring<P>;
+    constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
+    __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -44,64 +49,70 @@ __global__ __launch_bounds__(THREADS, 2) void k_fwd_bf16(HdtSchedule s, const __
     const unsigned lb = logical_block(blockIdx.x, gridDim.x);
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     const size_t base = (size_t)bh * s.n_pos * D;
-    const int32_t *kperm = s.kperm + (size_t)b * s.n_slots;
 
     const size_t row = (size_t)b * s.tr + I;
-    const int t0 = s.q_rowptr[row], t1 = s.q_rowptr[row + 1];
-    Entry e0 = load_entry(s, t0, t1), e1 = load_entry(s, t0 + 1, t1), e2 = load_entry(s, t0 + 2, t1);
+    const cptr_i32 rowptr = as_const(s.q_rowptr);
+    const int t0 = rowptr[row], n = rowptr[row + 1] - t0;
+    const cptr_i32 cols = as_const(s.q_cols) + t0;
+    const cptr_u32 subs = as_const(s.q_sub) + t0;
+    const cptr_i32 bidxs = as_const(s.q_bidx) + t0;
 
     // this lane's query row (clamped for loads; rows past n_pos are never stored)
     const int qrow = I * BM + wave * 32 + qn;
     const int qrow_ld = min(qrow, s.n_pos - 1);
-    bf16x8 qf[G::KSTEPS];
+    bf16x8 qf[KSTEPS];
 #pragma unroll
-    for (int st = 0; st < G::KSTEPS; st++)
+    for (int st = 0; st < KSTEPS; st++)
         qf[st] = *reinterpret_cast<const bf16x8 *>(q + base + (size_t)qrow_ld * D + st * 16 + hf * 8);
-
-    f32x16 oacc[G::DBLK];
+    // make the compiler wait for these loads here, before the hand-scheduled loads start
 #pragma unroll
-    for (int i = 0; i < G::DBLK; i++)
+    for (int st = 0; st < KSTEPS; st++) asm volatile("" ::"v"(qf[st]));
+
+    P pipe;
+    pipe.smem = smem;
+    pipe.smem_addr = lds_addr(smem);
+    pipe.wave = wave;
+    pipe.lane = lane;
+    pipe.kperm = s.kperm + (size_t)b * s.n_slots;
+    pipe.a = k + base;
+    pipe.b = v + base;
+    pipe.aux0 = pipe.aux1 = nullptr;
+    R::prologue(pipe, n, [&](int j) { return cols[j]; });
+
+    f32x16 oacc[DBLK];
+#pragma unroll
+    for (int i = 0; i < DBLK; i++)
 #pragma unroll
         for (int e = 0; e < 16; e++) oacc[i][e] = 0.f;
     float m_ref = -INFINITY, l_part = 0.f;
+    const RowLane rl = row_lane(lane);
+    const TrLane tl = tr_lane(lane);
 
-    const int ld_row = tid / G::CPR, ld_ch = tid % G::CPR;
-    int pos1[G::NLD], pos2[G::NLD];
-    u32x4 kreg[G::NLD], vreg[G::NLD];
-#pragma unroll
-    for (int p = 0; p < G::NLD; p++) pos1[p] = pos2[p] = 0;
-    if (t0 < t1) {
-        load_positions<D>(kperm, e0.col, ld_row, pos1);
-        if (t0 + 1 < t1) load_positions<D>(kperm, e1.col, ld_row, pos2);
-        gather_rows<D>(k, v, base, pos1, ld_ch, kreg, vreg);
-#pragma unroll
-        for (int p = 0; p < G::NLD; p++) pos1[p] = pos2[p];
-    }
-    const int vtr = tr_offset(lane, V_STRIDE);
-
-    for (int t = t0; t < t1; t++) {
-        __syncthreads();
-        stage_rows<D, K_STRIDE, V_STRIDE>(sK, sV, ld_row, ld_ch, kreg, vreg);
-        __syncthreads();
-        if (t + 1 < t1) gather_rows<D>(k, v, base, pos1, ld_ch, kreg, vreg);   // tile t+1
-        if (t + 2 < t1) load_positions<D>(kperm, e2.col, ld_row, pos1);        // tile t+2
-        const Entry e3 = load_entry(s, t + 3, t1);                            // tile t+3
+    int col_ahead = (S < n) ? cols[S] : 0;  // column of tile i+S
+    for (int i = 0; i < n; i++) {
+        const uint32_t sub = subs[i];
+        const int bidx = bidxs[i];
+        R::top(i, n);
+        wg_barrier();
+        R::advance(pipe, i, n, col_ahead);
+        col_ahead = (i + 1 + S < n) ? cols[i + 1 + S] : 0;
+        const char *sK = pipe.tile_a(i % S), *sV = pipe.tile_b(i % S);
 
 #pragma unroll
         for (int kb = 0; kb < 2; kb++) {
             const int sb = wave * 2 + kb;
-            if (!((e0.sub >> sb) & 1u)) continue;  // empty 32x32 sub-block (wave-uniform)
+            if (!((sub >> sb) & 1u)) continue;  // empty 32x32 sub-block (wave-uniform)
 
             // S^T sub-block = K[kb*32 .. +32) . Q^T
             f32x16 sacc;
 #pragma unroll
             for (int e = 0; e < 16; e++) sacc[e] = 0.f;
-            const char *krow = sK + (kb * 32 + qn) * K_STRIDE + hf * 16;
 #pragma unroll
-            for (int st = 0; st < G::KSTEPS; st++) sacc = mfma_32x32x16(lds_read_8(krow + st * 32), qf[st], sacc);
+            for (int st = 0; st < KSTEPS; st++)
+                sacc = mfma_32x32x16(read_row<ROWB>(sK, rl, kb * 32, st), qf[st], sacc);
 
-            if (!((e0.sub >> (16 + sb)) & 1u))  // not all pairs allowed: apply the bitmap
-                apply_mask(sacc, s.bits_rm + ((size_t)e0.bidx * 8 + sb) * 16, -INFINITY);
+            if (!((sub >> (16 + sb)) & 1u))  // not all pairs allowed: apply the bitmap
+                apply_mask(sacc, s.bits_rm + ((size_t)bidx * 8 + sb) * 16, -INFINITY);
 
             // online softmax for this lane's query over its 16 keys (+ the other half-wave's 16)
             float mx = fmaxf(sacc[0], sacc[1]);
@@ -114,9 +125,9 @@ __global__ __launch_bounds__(THREADS, 2) void k_fwd_bf16(HdtSchedule s, const __
                 m_ref = m_new;
                 l_part *= alpha;
 #pragma unroll
-                for (int i = 0; i < G::DBLK; i++)
+                for (int j = 0; j < DBLK; j++)
 #pragma unroll
-                    for (int e = 0; e < 16; e++) oacc[i][e] *= alpha;
+                    for (int e = 0; e < 16; e++) oacc[j][e] *= alpha;
             }
             const float m_sub = (m_ref == -INFINITY) ? 0.f : m_ref;  // row without any allowed key so far
             float psum = 0.f;
@@ -129,17 +140,12 @@ __global__ __launch_bounds__(THREADS, 2) void k_fwd_bf16(HdtSchedule s, const __
 
             // O^T += V^T P^T
             const bf16x8 pb0 = pack_bf16x8(sacc, 0), pb1 = pack_bf16x8(sacc, 8);
-            const char *vbase = sV + kb * 32 * V_STRIDE + vtr;
 #pragma unroll
-            for (int i = 0; i < G::DBLK; i++) {
-                const char *vp = vbase + i * 64;
-                oacc[i] = mfma_32x32x16(lds_read_tr_8(vp, vp + 8 * V_STRIDE), pb0, oacc[i]);
-                oacc[i] = mfma_32x32x16(lds_read_tr_8(vp + 16 * V_STRIDE, vp + 24 * V_STRIDE), pb1, oacc[i]);
+            for (int j = 0; j < DBLK; j++) {
+                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, kb * 32, j), pb0, oacc[j]);
+                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, kb * 32 + 16, j), pb1, oacc[j]);
             }
         }
-        e0 = e1;
-        e1 = e2;
-        e2 = e3;
     }
 
     // epilogue: O = acc / l, LSE = ln(sum exp) = ln2 * (m_ref + log2 l)
@@ -148,13 +154,13 @@ __global__ __launch_bounds__(THREADS, 2) void k_fwd_bf16(HdtSchedule s, const __
     if (qrow < s.n_pos) {
         __bf16 *orow = o + base + (size_t)qrow * D;
 #pragma unroll
-        for (int i = 0; i < G::DBLK; i++)
+        for (int j = 0; j < DBLK; j++)
 #pragma unroll
             for (int gq = 0; gq < 4; gq++) {
                 bf16x4 w;
 #pragma unroll
-                for (int e = 0; e < 4; e++) w[e] = (__bf16)(oacc[i][gq * 4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(orow + i * 32 + hf * 4 + gq * 8) = w;
+                for (int e = 0; e < 4; e++) w[e] = (__bf16)(oacc[j][gq * 4 + e] * inv);
+                *reinterpret_cast<bf16x4 *>(orow + j * 32 + hf * 4 + gq * 8) = w;
             }
         if (hf == 0)
             lse[(size_t)bh * s.n_pos + qrow] =

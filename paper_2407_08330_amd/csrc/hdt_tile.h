@@ -2,8 +2,20 @@
 // skeleton: a workgroup of 4 waves owns 128 consecutive rows of the schedule (wave w the rows
 // 32w..32w+31, whose operands stay in registers as MFMA B fragments), walks the row tile's list of
 // column tiles, and for each column tile gathers 64 rows of two [n_pos][D] tensors through kperm into
-// LDS.  Global loads run one tile ahead of the compute, the kperm look-ups two tiles ahead and the
-// list entries three tiles ahead, so that no iteration waits on a chain of dependent loads.
+// LDS.
+//
+// The gather uses the CDNA direct-to-LDS loads (global_load_lds_*: every lane supplies a global
+// address, the 64 results land in LDS at M0 + lane*size) into a ring of S stages, so that several
+// tiles are in flight per workgroup without holding them in registers:
+//   iteration t:  wait until tile t has landed -> barrier -> start tile t+S-1 -> compute tile t.
+// The key order kperm is read the same way, one tile further ahead than the rows it addresses, and
+// the list entries are read with scalar loads, so no iteration waits on a chain of dependent loads.
+// The only vector-memory instructions inside the loop are those issued here with inline asm, which
+// is what makes the hand-counted s_waitcnt vmcnt(N) exact.
+//
+// A wave-level load writes 1024 contiguous bytes, so LDS rows cannot be padded; bank conflicts are
+// avoided with an XOR swizzle of the 16-byte chunks of a row instead (applied to the global address
+// of each lane on the way in, and to the LDS address on the way out).
 #pragma once
 
 #include "hdt_internal.h"
@@ -15,23 +27,14 @@ constexpr int BM = 128, BN = 64, THREADS = 256;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// One list entry: column tile, 32x32 sub-block summary, index of its bitmaps.
-struct Entry {
-    int col;
-    uint32_t sub;
-    int bidx;
-};
-
-__device__ __forceinline__ Entry load_entry(const HdtSchedule &s, int t, int t_end)
-{
-    Entry e{0, 0u, 0};
-    if (t < t_end) {
-        e.col = s.q_cols[t];
-        e.sub = s.q_sub[t];
-        e.bidx = s.q_bidx[t];
-    }
-    return e;
-}
+// Read-only schedule arrays are read through the constant address space: with a wave-uniform index
+// the compiler then uses scalar loads (lgkmcnt), which keeps them out of the vector-memory queue
+// whose in-order counter the hand-scheduled loads rely on.
+#define HDT_CONST __attribute__((address_space(4)))
+typedef const int32_t HDT_CONST *cptr_i32;
+typedef const uint32_t HDT_CONST *cptr_u32;
+__device__ __forceinline__ cptr_i32 as_const(const int32_t *p) { return (cptr_i32)(uintptr_t)p; }
+__device__ __forceinline__ cptr_u32 as_const(const uint32_t *p) { return (cptr_u32)(uintptr_t)p; }
 
 // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical
 // work items so that the row tiles of one (sample, head) share an L2.
@@ -41,51 +44,209 @@ __device__ __forceinline__ unsigned logical_block(unsigned bid, unsigned grid)
     return (bid % 8u) * (grid / 8u) + bid / 8u;
 }
 
-template <int D>
-struct Geom {
-    static constexpr int KSTEPS = D / 16;              // MFMA steps over the head dimension
-    static constexpr int DBLK = D / 32;                // 32-wide blocks of the head dimension
-    static constexpr int CPR = D / 8;                  // 16-byte chunks per row
-    static constexpr int NLD = BN * CPR / THREADS;     // chunks per thread per gathered tile
-    static constexpr int RPP = THREADS / CPR;          // rows covered by one load pass
-    static constexpr int ROW_STRIDE = D * 2 + 16;      // LDS row stride for tiles read by rows
-    static constexpr int TR_STRIDE = D * 2 + 32;       // ... for tiles (also) read transposed
+// chunk swizzle of row r: 8 consecutive rows get 8 different values (conflict-free 16-byte reads
+// of one logical chunk down a column) and 4 consecutive aligned rows differ in the upper two bits
+// (conflict-free transposing reads, which touch 4 rows x 2 adjacent chunks)
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+
+__device__ __forceinline__ uint32_t lds_addr(const void *p)
+{
+    return (uint32_t)(uintptr_t)(HDT_LDS const char *)p;
+}
+
+// direct-to-LDS loads: lane l's 16 (4) bytes at `g` land at lds_base + 16*l (4*l)
+__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(const void *g, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds_base)
+                 : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// workgroup barrier without the fence __syncthreads() carries: LDS traffic of this wave is drained
+// by the lgkmcnt wait, the direct-to-LDS loads by the explicit vmcnt waits of the callers
+__device__ __forceinline__ void wg_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int D, int S_, bool AUX>
+struct Pipe {
+    static constexpr int S = S_;                      // data stages in the ring
+    static constexpr int PS = 4;                      // position stages
+    static constexpr int KSTEPS = D / 16;             // MFMA steps over the head dimension
+    static constexpr int DBLK = D / 32;               // 32-wide blocks of the head dimension
+    static constexpr int ROWB = D * 2;                // bytes per LDS row (unpadded)
+    static constexpr int CPR = D / 8;                 // 16-byte chunks per row
+    static constexpr int TILE = BN * ROWB;            // bytes of one gathered tile of one tensor
+    static constexpr int RPI = 1024 / ROWB;           // rows per wave-level load
+    static constexpr int NI = 16 / RPI;               // wave-level loads per tensor per tile per wave
+    static constexpr int NDMA = 2 * NI + (AUX ? 1 : 0);  // vector-memory instructions per tile per wave
+    static constexpr int DATA_BYTES = S * 2 * TILE;
+    static constexpr int POS_BYTES = PS * 4 * BN * 4;
+    static constexpr int AUX_BYTES = AUX ? S * 4 * BN * 4 : 0;
+    static constexpr int SMEM_BYTES = DATA_BYTES + POS_BYTES + AUX_BYTES;
+
+    char *smem;
+    uint32_t smem_addr;
+    int wave, lane;
+    const int32_t *kperm;      // this sample's key order
+    const __bf16 *a, *b;       // the two gathered tensors, already offset to this (sample, head)
+    const float *aux0, *aux1;  // per-position floats gathered with the rows (AUX only), same offset
+
+    __device__ __forceinline__ const char *tile_a(int stage) const { return smem + (stage * 2 + 0) * TILE; }
+    __device__ __forceinline__ const char *tile_b(int stage) const { return smem + (stage * 2 + 1) * TILE; }
+    __device__ __forceinline__ const int *pos_buf(int ps) const
+    {
+        return reinterpret_cast<const int *>(smem + DATA_BYTES) + (ps * 4 + wave) * BN;
+    }
+    // aux values of the 64 slots: array 0 is written by wave 0, array 1 by wave 1
+    __device__ __forceinline__ const float *aux_buf(int stage, int which) const
+    {
+        return reinterpret_cast<const float *>(smem + DATA_BYTES + POS_BYTES) + (stage * 4 + which) * BN;
+    }
+
+    // start loading the positions of column tile `col` (every wave keeps its own copy)
+    __device__ __forceinline__ void issue_pos(int col, int ps) const
+    {
+        dma4(kperm + col * BN + lane, smem_addr + DATA_BYTES + ((ps * 4 + wave) * BN) * 4);
+    }
+
+    // start gathering the rows of a column tile whose positions sit in position stage ps
+    __device__ __forceinline__ void issue_data(int stage, int ps) const
+    {
+        const int *pb = pos_buf(ps);
+        const int lr = lane / CPR, c = lane % CPR;  // row inside the wave-level load, chunk slot
+#pragma unroll
+        for (int i = 0; i < NI; i++) {
+            const int r = wave * 16 + i * RPI + lr;
+            const int pos = max(pb[r], 0);  // slots past n_pos: any readable row, the bitmap masks them
+            const size_t off = (size_t)pos * D + (size_t)((c ^ swz(r & 7)) * 8);
+            const uint32_t dst = (uint32_t)((wave * 16 + i * RPI) * ROWB);
+            dma16(a + off, smem_addr + (stage * 2 + 0) * TILE + dst);
+            dma16(b + off, smem_addr + (stage * 2 + 1) * TILE + dst);
+        }
+        if (AUX) {
+            const int pos = max(pb[lane], 0);
+            const float *src = (wave & 1) ? aux1 : aux0;
+            dma4(src + pos, smem_addr + DATA_BYTES + POS_BYTES + ((stage * 4 + wave) * BN) * 4);
+        }
+    }
 };
 
-// gather positions of column tile `col` for this thread's rows
-template <int D>
-__device__ __forceinline__ void load_positions(const int32_t *kperm, int col, int ld_row, int (&pos)[Geom<D>::NLD])
+// vmcnt wait with a run-time count out of a small set (the immediate must be a constant)
+// k tiles were started after the one waited for: k*NDMA row loads and k-1 position loads
+template <int NDMA>
+__device__ __forceinline__ void wait_vmcnt_tail(int k)
 {
-#pragma unroll
-    for (int p = 0; p < Geom<D>::NLD; p++) {
-        const int v = kperm[col * BN + ld_row + p * Geom<D>::RPP];
-        pos[p] = v < 0 ? 0 : v;  // slots past n_pos: any readable row, the bitmap masks them
-    }
+    if (k <= 0)
+        wait_vmcnt<0>();
+    else if (k == 1)
+        wait_vmcnt<NDMA>();
+    else if (k == 2)
+        wait_vmcnt<2 * NDMA + 1>();
+    else
+        wait_vmcnt<3 * NDMA + 2>();  // also safe (stricter) for k > 3
 }
 
-template <int D>
-__device__ __forceinline__ void gather_rows(const __bf16 *__restrict__ a, const __bf16 *__restrict__ b, size_t base,
-                                            const int (&pos)[Geom<D>::NLD], int ld_ch, u32x4 (&ra)[Geom<D>::NLD],
-                                            u32x4 (&rb)[Geom<D>::NLD])
-{
+// Ring schedule (positions run one tile ahead of their rows).  Per wave the vector-memory
+// instructions are issued in the order  pos(0), pos(1), data(0), pos(2), data(1), ..., pos(j+1), data(j), ...
+// where data(j) is NDMA instructions and pos(j) one.
+//   prologue(n, cols): starts pos(0..S-1) and data(0..S-2) as far as they exist
+//   top(i, n):         call at the top of iteration i: returns when data(i) and pos(i+S-1) have landed
+//                      in LDS for this wave; the caller then executes a workgroup barrier
+//   advance(i, n, col_next): after the barrier: starts pos(i+S) (column col_next) and data(i+S-1)
+template <typename P>
+struct Ring {
+    static constexpr int S = P::S, NDMA = P::NDMA, PS = P::PS;
+
+    template <typename ColFn>
+    static __device__ __forceinline__ void prologue(const P &p, int n, ColFn col_of)
+    {
+        if (n > 0) p.issue_pos(col_of(0), 0);
 #pragma unroll
-    for (int p = 0; p < Geom<D>::NLD; p++) {
-        const size_t off = base + (size_t)pos[p] * D + ld_ch * 8;
-        ra[p] = *reinterpret_cast<const u32x4 *>(a + off);
-        rb[p] = *reinterpret_cast<const u32x4 *>(b + off);
+        for (int j = 0; j < S - 1; j++) {
+            if (j + 1 < n) p.issue_pos(col_of(j + 1), (j + 1) % PS);
+            if (j < n) {
+                // pos(j) must have landed; issued after it: [data(j-1)], [pos(j+1)]
+                if (j == 0) {
+                    if (1 < n) wait_vmcnt<1>(); else wait_vmcnt<0>();
+                } else {
+                    if (j + 1 < n) wait_vmcnt<NDMA + 1>(); else wait_vmcnt<NDMA>();
+                }
+                p.issue_data(j % S, j % PS);
+            }
+        }
     }
+
+    static __device__ __forceinline__ void top(int i, int n)
+    {
+        if (i + S - 1 < n) {
+            // the last instructions issued were pos(i+S-1), data(i+S-2): with S >= 3 the latter may stay
+            // in flight, with S == 2 it is data(i) itself
+            wait_vmcnt<(S >= 3) ? NDMA : 0>();
+        } else {
+            // nothing more to start: data(i+1 .. n-1) and the position loads between them may be in flight
+            wait_vmcnt_tail<NDMA>(n - 1 - i);
+        }
+    }
+
+    static __device__ __forceinline__ void advance(const P &p, int i, int n, int col_next)
+    {
+        if (i + S < n) p.issue_pos(col_next, (i + S) % PS);
+        if (i + S - 1 < n) p.issue_data((i + S - 1) % S, (i + S - 1) % PS);
+    }
+};
+
+// Per-lane constants for reading MFMA A operands by rows out of a swizzled tile: the lane's row
+// inside a 32-row block and its swizzle term; 16-byte chunk 2*st + hf of that row sits at
+// ((2*st) ^ x) * 16.
+struct RowLane {
+    int row;  // l % 32
+    int x;    // hf ^ swz(row & 7)
+};
+__device__ __forceinline__ RowLane row_lane(int lane)
+{
+    RowLane r;
+    r.row = lane & 31;
+    r.x = (lane >> 5) ^ swz(r.row & 7);
+    return r;
+}
+template <int ROWB>
+__device__ __forceinline__ bf16x8 read_row(const char *tile, const RowLane &r, int r0, int st)
+{
+    return lds_read_8(tile + (r0 + r.row) * ROWB + ((((st << 1) ^ r.x)) << 4));
 }
 
-template <int D, int STRIDE_A, int STRIDE_B>
-__device__ __forceinline__ void stage_rows(char *sa, char *sb, int ld_row, int ld_ch,
-                                           const u32x4 (&ra)[Geom<D>::NLD], const u32x4 (&rb)[Geom<D>::NLD])
+// Per-lane constants of the transposing reads of a 32(k) x 32(n) operand block out of a swizzled
+// row-major tile: row of the first read and the swizzle term; the chunk of n-block i is (4i) ^ y.
+struct TrLane {
+    int row;   // (g>>1)*4 + (tl>>2)
+    int y;     // ((g&1)*2 + ((tl&3)>>1)) ^ swz(row & 7)
+    int half;  // (tl & 1) * 8 bytes inside the chunk
+};
+__device__ __forceinline__ TrLane tr_lane(int lane)
 {
-#pragma unroll
-    for (int p = 0; p < Geom<D>::NLD; p++) {
-        const int r = ld_row + p * Geom<D>::RPP;
-        *reinterpret_cast<u32x4 *>(sa + r * STRIDE_A + ld_ch * 16) = ra[p];
-        *reinterpret_cast<u32x4 *>(sb + r * STRIDE_B + ld_ch * 16) = rb[p];
-    }
+    const int g = lane >> 4, tl = lane & 15;
+    TrLane t;
+    t.row = (g >> 1) * 4 + (tl >> 2);
+    t.y = (((g & 1) << 1) | ((tl & 3) >> 1)) ^ swz(t.row & 7);
+    t.half = (tl & 1) * 8;
+    return t;
+}
+// the 8 contraction values {k0 + hf*4 + 0..3} and {k0 + 8 + hf*4 + 0..3} at n = 32*i + l%32
+template <int ROWB>
+__device__ __forceinline__ bf16x8 read_tr(const char *tile, const TrLane &t, int k0, int i)
+{
+    const char *p = tile + (k0 + t.row) * ROWB + ((((i << 2) ^ t.y)) << 4) + t.half;
+    return lds_read_tr_8(p, p + 8 * ROWB);
 }
 
 // Apply a 32x32 sub-block's bitmap to a C fragment: element e of lane l is kept iff bit l of
@@ -101,17 +262,9 @@ __device__ __forceinline__ void apply_mask(f32x16 &x, const unsigned long long *
     for (int e = 0; e < 16; e++) {
         const unsigned long long m = cm[e];
         float r;
-        asm volatile("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(fill), "v"(x[e]), "s"(m));
+        asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(fill), "v"(x[e]), "s"(m));
         x[e] = r;
     }
-}
-
-// byte offset, inside a row-major LDS tile with the given row stride, of this lane's first
-// transposing read for the 32(k) x 32(n) operand block whose first k-row is k0 and first n is n0
-__device__ __forceinline__ int tr_offset(int lane, int stride)
-{
-    const int g = lane >> 4, tl = lane & 15;
-    return ((g >> 1) * 4 + (tl >> 2)) * stride + ((g & 1) * 16 + (tl & 3) * 4) * 2;
 }
 
 }  // namespace hdt_tile
