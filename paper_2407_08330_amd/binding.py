@@ -10,7 +10,8 @@ from typing import Optional
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libhdt.so")
+# HDT_LIBRARY_PATH selects another build of the same library (kernel tuning variants)
+_LIB_PATH = os.environ.get("HDT_LIBRARY_PATH") or os.path.join(_PKG, "libhdt.so")
 _lib = None
 
 HDT_BF16, HDT_F32 = 0, 1

@@ -27,9 +27,23 @@ using namespace hdt_tile;
 
 template <int D>
 struct BwdCfg {
-    static constexpr int S = (D == 64) ? 3 : 2;
-    static constexpr int WAVES_DQ = (D == 64) ? 3 : 2;
-    static constexpr int WAVES_DKV = (D == 64) ? 2 : 1;
+#ifndef HDT_DQ_S64
+#define HDT_DQ_S64 3
+#endif
+#ifndef HDT_DQ_W64
+#define HDT_DQ_W64 3
+#endif
+#ifndef HDT_DKV_S64
+#define HDT_DKV_S64 2
+#endif
+#ifndef HDT_DKV_W64
+#define HDT_DKV_W64 3
+#endif
+    // ring stages and waves per SIMD (register budget) of the two passes
+    static constexpr int S_DQ = (D == 64) ? HDT_DQ_S64 : 2;
+    static constexpr int S_DKV = (D == 64) ? HDT_DKV_S64 : 2;
+    static constexpr int WAVES_DQ = (D == 64) ? HDT_DQ_W64 : 2;
+    static constexpr int WAVES_DKV = (D == 64) ? HDT_DKV_W64 : 1;
 };
 
 // ------------------------------------------------------------------------------------------- dQ
@@ -39,7 +53,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     const __bf16 *__restrict__ o, const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
     __bf16 *__restrict__ dq, float *__restrict__ delta, int heads, float scale)
 {
-    using P = Pipe<D, BwdCfg<D>::S, false>;
+    using P = Pipe<D, BwdCfg<D>::S_DQ, false>;
     using R = Ring<P>;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
     __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
@@ -59,28 +73,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     const cptr_u32 subs = as_const(s.q_sub) + t0;
     const cptr_i32 bidxs = as_const(s.q_bidx) + t0;
 
-    const int qrow = I * BM + wave * 32 + qn;
-    const int qrow_ld = min(qrow, s.n_pos - 1);
-    bf16x8 qf[KSTEPS], dof[KSTEPS];
-    float Di = 0.f;
-#pragma unroll
-    for (int st = 0; st < KSTEPS; st++) {
-        const size_t off = base + (size_t)qrow_ld * D + st * 16 + hf * 8;
-        qf[st] = *reinterpret_cast<const bf16x8 *>(q + off);
-        dof[st] = *reinterpret_cast<const bf16x8 *>(d_o + off);
-        const bf16x8 of = *reinterpret_cast<const bf16x8 *>(o + off);
-#pragma unroll
-        for (int e = 0; e < 8; e++) Di += (float)dof[st][e] * (float)of[e];
-    }
-    Di += __shfl_xor(Di, 32);
-    if (qrow < s.n_pos && hf == 0) delta[(size_t)bh * s.n_pos + qrow] = Di;
-    float lse2 = lse[(size_t)bh * s.n_pos + qrow_ld];
-    lse2 = (lse2 == -INFINITY) ? 0.f : lse2 * LOG2E;  // pad rows are masked by the bitmap anyway
-    // the compiler must finish its own loads before the hand-scheduled ones start
-    asm volatile("" ::"v"(Di), "v"(lse2));
-#pragma unroll
-    for (int st = 0; st < KSTEPS; st++) asm volatile("" ::"v"(qf[st]), "v"(dof[st]));
-
     P pipe;
     pipe.smem = smem;
     pipe.smem_addr = lds_addr(smem);
@@ -90,20 +82,71 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     pipe.a = k + base;
     pipe.b = v + base;
     pipe.aux0 = pipe.aux1 = nullptr;
-    R::prologue(pipe, n, [&](int j) { return cols[j]; });
+    const int qrow = I * BM + wave * 32 + qn;
+    const RowLane rl = row_lane(lane);
+    const TrLane tl = tr_lane(lane);
+
+    // Q and dO rows of this wave go through the two highest ring stages (full-row loads into LDS);
+    // the B fragments are read back from there.  The ring may only take those stages over after a
+    // barrier, so the prologue is issued in two pieces.
+    constexpr uint32_t STG_Q = (uint32_t)(S - 1) * 2 * P::TILE, STG_DO = (uint32_t)(S - 2) * 2 * P::TILE;
+    __shared__ float sDi[BM];
+    stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, STG_Q);
+    stage_own_rows(pipe, d_o + base, I * BM, s.n_pos, D, STG_DO);
+    R::start(pipe, n, [&](int j) { return cols[j]; });
+    R::template prologue<0, S - 2>(pipe, n, [&](int j) { return cols[j]; });
+    if (S == 2 || n == 0) wait_vmcnt<0>();  // otherwise the prologue's first wait covered the staged rows
+
+    // D_i = sum_c dO_ic O_ic from full-row reads: lane (row l/CPR, chunk l%CPR) multiplies 8 values of O
+    // (global, coalesced) with the staged dO chunk, the CPR lanes of a row are then added up
+    {
+        const int lr = lane / P::CPR, c = lane % P::CPR;
+#pragma unroll
+        for (int i = 0; i < 32 / P::RPI; i++) {
+            const int r = wave * 32 + i * P::RPI + lr;
+            const int g = min(I * BM + r, s.n_pos - 1);
+            const bf16x8 ov = *reinterpret_cast<const bf16x8 *>(o + base + (size_t)g * D + c * 8);
+            const bf16x8 dv8 = lds_read_8(smem + STG_DO + r * ROWB + ((c ^ swz(r & 7)) << 4));
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) part += (float)ov[e] * (float)dv8[e];
+#pragma unroll
+            for (int m = 1; m < P::CPR; m <<= 1) part += __shfl_xor(part, m);
+            if (c == 0) sDi[r] = part;
+        }
+    }
+    bf16x8 qf[KSTEPS], dof[KSTEPS];
+#pragma unroll
+    for (int st = 0; st < KSTEPS; st++) {
+        qf[st] = read_row<ROWB>(smem + STG_Q, rl, wave * 32, st);
+        dof[st] = read_row<ROWB>(smem + STG_DO, rl, wave * 32, st);
+    }
+    const int qrow_ld = min(qrow, s.n_pos - 1);
+    float lse2 = lse[(size_t)bh * s.n_pos + qrow_ld];
+    lse2 = (lse2 == -INFINITY) ? 0.f : lse2 * LOG2E;  // pad rows are masked by the bitmap anyway
+    const float Di = sDi[wave * 32 + qn];  // written by this wave
+    if (qrow < s.n_pos && hf == 0) delta[(size_t)bh * s.n_pos + qrow] = Di;
+    // the compiler must finish its own loads before the hand-scheduled ones continue
+    asm volatile("" ::"v"(Di), "v"(lse2));
+    wg_barrier();  // every wave has read its fragments: the ring may use all stages
+    R::template prologue<S - 2, S - 1>(pipe, n, [&](int j) { return cols[j]; });
 
     f32x16 dqacc[DBLK];
 #pragma unroll
     for (int i = 0; i < DBLK; i++)
 #pragma unroll
         for (int e = 0; e < 16; e++) dqacc[i][e] = 0.f;
-    const RowLane rl = row_lane(lane);
-    const TrLane tl = tr_lane(lane);
 
     int col_ahead = (S < n) ? cols[S] : 0;
+    uint32_t sub_next = n > 0 ? subs[0] : 0u;
+    int bidx_next = n > 0 ? bidxs[0] : 0;
     for (int i = 0; i < n; i++) {
-        const uint32_t sub = subs[i];
-        const int bidx = bidxs[i];
+        const uint32_t sub = sub_next;
+        const int bidx = bidx_next;
+        if (i + 1 < n) {
+            sub_next = subs[i + 1];
+            bidx_next = bidxs[i + 1];
+        }
         R::top(i, n);
         wg_barrier();
         R::advance(pipe, i, n, col_ahead);
@@ -137,17 +180,11 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
         }
     }
 
-    if (qrow < s.n_pos) {
-        __bf16 *orow = dq + base + (size_t)qrow * D;
-#pragma unroll
-        for (int j = 0; j < DBLK; j++)
-#pragma unroll
-            for (int gq = 0; gq < 4; gq++) {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; e++) w[e] = (__bf16)(dqacc[j][gq * 4 + e] * scale);
-                *reinterpret_cast<bf16x4 *>(orow + j * 32 + hf * 4 + gq * 8) = w;
-            }
+    wg_barrier();  // every wave is done reading the ring
+    {
+        const int wrow0 = I * BM + wave * 32;
+        store_rows_via_lds<P, D>(smem + wave * 32 * ROWB, lane, dqacc, scale, dq + base + (size_t)wrow0 * D,
+                                 s.n_pos - wrow0);
     }
 }
 
@@ -158,7 +195,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     const float *__restrict__ lse, const __bf16 *__restrict__ d_o, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int heads, float scale)
 {
-    using P = Pipe<D, BwdCfg<D>::S, true>;
+    using P = Pipe<D, BwdCfg<D>::S_DKV, true>;
     using R = Ring<P>;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
     __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
@@ -178,19 +215,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     const cptr_u32 subs = as_const(s.q_sub) + t0;
     const cptr_i32 bidxs = as_const(s.q_bidx) + t0;
 
-    // this lane's key row, document order
-    const int krow = I * BM + wave * 32 + kn;
-    const int krow_ld = min(krow, s.n_pos - 1);
-    bf16x8 kf[KSTEPS], vf[KSTEPS];
-#pragma unroll
-    for (int st = 0; st < KSTEPS; st++) {
-        const size_t off = base + (size_t)krow_ld * D + st * 16 + hf * 8;
-        kf[st] = *reinterpret_cast<const bf16x8 *>(k + off);
-        vf[st] = *reinterpret_cast<const bf16x8 *>(v + off);
-    }
-#pragma unroll
-    for (int st = 0; st < KSTEPS; st++) asm volatile("" ::"v"(kf[st]), "v"(vf[st]));
-
     P pipe;
     pipe.smem = smem;
     pipe.smem_addr = lds_addr(smem);
@@ -201,20 +225,43 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     pipe.b = d_o + base;
     pipe.aux0 = lse + (size_t)bh * s.n_pos;
     pipe.aux1 = delta + (size_t)bh * s.n_pos;
-    R::prologue(pipe, n, [&](int j) { return cols[j]; });
+    // this lane's key row, document order
+    const int krow = I * BM + wave * 32 + kn;
+    const RowLane rl = row_lane(lane);
+    const TrLane tl = tr_lane(lane);
+
+    // K and V rows of this wave: through the two highest ring stages, as Q and dO in the dQ pass
+    constexpr uint32_t STG_K = (uint32_t)(S - 1) * 2 * P::TILE, STG_V = (uint32_t)(S - 2) * 2 * P::TILE;
+    stage_own_rows(pipe, k + base, I * BM, s.n_pos, D, STG_K);
+    stage_own_rows(pipe, v + base, I * BM, s.n_pos, D, STG_V);
+    R::start(pipe, n, [&](int j) { return cols[j]; });
+    R::template prologue<0, S - 2>(pipe, n, [&](int j) { return cols[j]; });
+    if (S == 2 || n == 0) wait_vmcnt<0>();
+    bf16x8 kf[KSTEPS], vf[KSTEPS];
+#pragma unroll
+    for (int st = 0; st < KSTEPS; st++) {
+        kf[st] = read_row<ROWB>(smem + STG_K, rl, wave * 32, st);
+        vf[st] = read_row<ROWB>(smem + STG_V, rl, wave * 32, st);
+    }
+    wg_barrier();
+    R::template prologue<S - 2, S - 1>(pipe, n, [&](int j) { return cols[j]; });
 
     f32x16 dkacc[DBLK], dvacc[DBLK];
 #pragma unroll
     for (int i = 0; i < DBLK; i++)
 #pragma unroll
         for (int e = 0; e < 16; e++) dkacc[i][e] = dvacc[i][e] = 0.f;
-    const RowLane rl = row_lane(lane);
-    const TrLane tl = tr_lane(lane);
 
     int col_ahead = (S < n) ? cols[S] : 0;
+    uint32_t sub_next = n > 0 ? subs[0] : 0u;
+    int bidx_next = n > 0 ? bidxs[0] : 0;
     for (int i = 0; i < n; i++) {
-        const uint32_t sub = subs[i];
-        const int bidx = bidxs[i];
+        const uint32_t sub = sub_next;
+        const int bidx = bidx_next;
+        if (i + 1 < n) {
+            sub_next = subs[i + 1];
+            bidx_next = bidxs[i + 1];
+        }
         R::top(i, n);
         wg_barrier();
         R::advance(pipe, i, n, col_ahead);
@@ -263,22 +310,12 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
         }
     }
 
-    if (krow < s.n_pos) {
-        __bf16 *dkrow = dk + base + (size_t)krow * D;
-        __bf16 *dvrow = dv + base + (size_t)krow * D;
-#pragma unroll
-        for (int j = 0; j < DBLK; j++)
-#pragma unroll
-            for (int gq = 0; gq < 4; gq++) {
-                bf16x4 wk, wv;
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    wk[e] = (__bf16)(dkacc[j][gq * 4 + e] * scale);
-                    wv[e] = (__bf16)dvacc[j][gq * 4 + e];
-                }
-                *reinterpret_cast<bf16x4 *>(dkrow + j * 32 + hf * 4 + gq * 8) = wk;
-                *reinterpret_cast<bf16x4 *>(dvrow + j * 32 + hf * 4 + gq * 8) = wv;
-            }
+    wg_barrier();  // every wave is done reading the ring
+    {
+        const int wrow0 = I * BM + wave * 32;
+        char *wl = smem + wave * 32 * ROWB;
+        store_rows_via_lds<P, D>(wl, lane, dkacc, scale, dk + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+        store_rows_via_lds<P, D>(wl, lane, dvacc, 1.f, dv + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     }
 }
 

@@ -29,8 +29,14 @@ using namespace hdt_tile;
 
 template <int D>
 struct FwdCfg {
-    static constexpr int S = (D == 64) ? 3 : 2;      // ring stages (LDS: 52 KB / 68 KB per workgroup)
-    static constexpr int WAVES = (D == 64) ? 3 : 2;  // waves per SIMD the register budget allows
+#ifndef HDT_FWD_S64
+#define HDT_FWD_S64 2
+#endif
+#ifndef HDT_FWD_W64
+#define HDT_FWD_W64 4
+#endif
+    static constexpr int S = (D == 64) ? HDT_FWD_S64 : 2;      // ring stages (LDS: 36 KB / 68 KB per workgroup)
+    static constexpr int WAVES = (D == 64) ? HDT_FWD_W64 : 2;  // waves per SIMD the register budget allows
 };
 
 template <int D>
@@ -57,17 +63,6 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const cptr_u32 subs = as_const(s.q_sub) + t0;
     const cptr_i32 bidxs = as_const(s.q_bidx) + t0;
 
-    // this lane's query row (clamped for loads; rows past n_pos are never stored)
-    const int qrow = I * BM + wave * 32 + qn;
-    const int qrow_ld = min(qrow, s.n_pos - 1);
-    bf16x8 qf[KSTEPS];
-#pragma unroll
-    for (int st = 0; st < KSTEPS; st++)
-        qf[st] = *reinterpret_cast<const bf16x8 *>(q + base + (size_t)qrow_ld * D + st * 16 + hf * 8);
-    // make the compiler wait for these loads here, before the hand-scheduled loads start
-#pragma unroll
-    for (int st = 0; st < KSTEPS; st++) asm volatile("" ::"v"(qf[st]));
-
     P pipe;
     pipe.smem = smem;
     pipe.smem_addr = lds_addr(smem);
@@ -77,7 +72,22 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     pipe.a = k + base;
     pipe.b = v + base;
     pipe.aux0 = pipe.aux1 = nullptr;
-    R::prologue(pipe, n, [&](int j) { return cols[j]; });
+    // this lane's query row; rows past n_pos are computed on a clamped copy and never stored
+    const int qrow = I * BM + wave * 32 + qn;
+    const RowLane rl = row_lane(lane);
+    const TrLane tl = tr_lane(lane);
+
+    // Q rows of this wave go through the ring stage the prologue leaves free (S-1): full-row loads
+    // into LDS, then the B fragments (query l%32, 8 head-dim values per step) are read back
+    constexpr uint32_t Q_STAGE = (uint32_t)(S - 1) * 2 * P::TILE;
+    bf16x8 qf[KSTEPS];
+    if (n > 0) {
+        stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, Q_STAGE);
+        R::start(pipe, n, [&](int j) { return cols[j]; });
+        R::template prologue<0, S - 1>(pipe, n, [&](int j) { return cols[j]; });  // its first wait covers the Q rows
+#pragma unroll
+        for (int st = 0; st < KSTEPS; st++) qf[st] = read_row<ROWB>(smem + Q_STAGE, rl, wave * 32, st);
+    }
 
     f32x16 oacc[DBLK];
 #pragma unroll
@@ -85,87 +95,112 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
 #pragma unroll
         for (int e = 0; e < 16; e++) oacc[i][e] = 0.f;
     float m_ref = -INFINITY, l_part = 0.f;
-    const RowLane rl = row_lane(lane);
-    const TrLane tl = tr_lane(lane);
+    const int xlane = (lane ^ 32) << 2;  // ds_bpermute address of the partner lane in the other half-wave
 
     int col_ahead = (S < n) ? cols[S] : 0;  // column of tile i+S
+    uint32_t sub_next = n > 0 ? subs[0] : 0u;
+    int bidx_next = n > 0 ? bidxs[0] : 0;
     for (int i = 0; i < n; i++) {
-        const uint32_t sub = subs[i];
-        const int bidx = bidxs[i];
+        const uint32_t sub = sub_next;
+        const int bidx = bidx_next;
+        if (i + 1 < n) {
+            sub_next = subs[i + 1];
+            bidx_next = bidxs[i + 1];
+        }
         R::top(i, n);
         wg_barrier();
         R::advance(pipe, i, n, col_ahead);
         col_ahead = (i + 1 + S < n) ? cols[i + 1 + S] : 0;
         const char *sK = pipe.tile_a(i % S), *sV = pipe.tile_b(i % S);
 
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-            const int sb = wave * 2 + kb;
-            if (!((sub >> sb) & 1u)) continue;  // empty 32x32 sub-block (wave-uniform)
+        // this wave's two 32x32 sub-blocks of the tile (wave-uniform flags)
+        const bool act0 = (sub >> (wave * 2)) & 1u, act1 = (sub >> (wave * 2 + 1)) & 1u;
+        if (!(act0 || act1)) continue;
+        const unsigned long long *mk = s.bits_rm + ((size_t)bidx * 8 + wave * 2) * 16;
 
-            // S^T sub-block = K[kb*32 .. +32) . Q^T
-            f32x16 sacc;
+        // S^T sub-blocks = K[kb*32 .. +32) . Q^T, masked
+        f32x16 s0, s1;
+        float mx = -INFINITY;
+        if (act0) {
 #pragma unroll
-            for (int e = 0; e < 16; e++) sacc[e] = 0.f;
+            for (int e = 0; e < 16; e++) s0[e] = 0.f;
 #pragma unroll
-            for (int st = 0; st < KSTEPS; st++)
-                sacc = mfma_32x32x16(read_row<ROWB>(sK, rl, kb * 32, st), qf[st], sacc);
+            for (int st = 0; st < KSTEPS; st++) s0 = mfma_32x32x16(read_row<ROWB>(sK, rl, 0, st), qf[st], s0);
+        }
+        if (act1) {
+#pragma unroll
+            for (int e = 0; e < 16; e++) s1[e] = 0.f;
+#pragma unroll
+            for (int st = 0; st < KSTEPS; st++) s1 = mfma_32x32x16(read_row<ROWB>(sK, rl, 32, st), qf[st], s1);
+        }
+        if (act0) {
+            if (!((sub >> (16 + wave * 2)) & 1u)) apply_mask(s0, mk, -INFINITY);
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(s0[e], s0[e + 1]));
+        }
+        if (act1) {
+            if (!((sub >> (17 + wave * 2)) & 1u)) apply_mask(s1, mk + 16, -INFINITY);
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(s1[e], s1[e + 1]));
+        }
 
-            if (!((sub >> (16 + sb)) & 1u))  // not all pairs allowed: apply the bitmap
-                apply_mask(sacc, s.bits_rm + ((size_t)bidx * 8 + sb) * 16, -INFINITY);
+        // online softmax for this lane's query over up to 64 keys: its own registers plus those of
+        // the partner lane in the other half-wave
+        mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(xlane, __builtin_bit_cast(int, mx))));
+        mx *= scale_log2;
+        if (__any(mx > m_ref + 8.f)) {  // raise the reference and rescale (always on a row's first keys)
+            const float m_new = fmaxf(m_ref, mx);
+            const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref - m_new);
+            m_ref = m_new;
+            l_part *= alpha;
+#pragma unroll
+            for (int j = 0; j < DBLK; j++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) oacc[j][e] *= alpha;
+        }
+        const float m_sub = (m_ref == -INFINITY) ? 0.f : m_ref;  // row without any allowed key so far
 
-            // online softmax for this lane's query over its 16 keys (+ the other half-wave's 16)
-            float mx = fmaxf(sacc[0], sacc[1]);
-#pragma unroll
-            for (int e = 2; e < 16; e += 2) mx = fmaxf(mx, fmaxf(sacc[e], sacc[e + 1]));
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
-            if (__any(mx > m_ref + 8.f)) {  // raise the reference and rescale (always on a row's first keys)
-                const float m_new = fmaxf(m_ref, mx);
-                const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref - m_new);
-                m_ref = m_new;
-                l_part *= alpha;
-#pragma unroll
-                for (int j = 0; j < DBLK; j++)
-#pragma unroll
-                    for (int e = 0; e < 16; e++) oacc[j][e] *= alpha;
-            }
-            const float m_sub = (m_ref == -INFINITY) ? 0.f : m_ref;  // row without any allowed key so far
+        // P^T = exp2(S^T * scale*log2e - m_ref); O^T += V^T P^T
+        if (act0) {
             float psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; e++) {
-                sacc[e] = fast_exp2(fmaf(sacc[e], scale_log2, -m_sub));
-                psum += sacc[e];
+                s0[e] = fast_exp2(fmaf(s0[e], scale_log2, -m_sub));
+                psum += s0[e];
             }
             l_part += psum;
-
-            // O^T += V^T P^T
-            const bf16x8 pb0 = pack_bf16x8(sacc, 0), pb1 = pack_bf16x8(sacc, 8);
+            const bf16x8 pb0 = pack_bf16x8(s0, 0), pb1 = pack_bf16x8(s0, 8);
 #pragma unroll
             for (int j = 0; j < DBLK; j++) {
-                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, kb * 32, j), pb0, oacc[j]);
-                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, kb * 32 + 16, j), pb1, oacc[j]);
+                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 0, j), pb0, oacc[j]);
+                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 16, j), pb1, oacc[j]);
+            }
+        }
+        if (act1) {
+            float psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+                s1[e] = fast_exp2(fmaf(s1[e], scale_log2, -m_sub));
+                psum += s1[e];
+            }
+            l_part += psum;
+            const bf16x8 pb0 = pack_bf16x8(s1, 0), pb1 = pack_bf16x8(s1, 8);
+#pragma unroll
+            for (int j = 0; j < DBLK; j++) {
+                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 32, j), pb0, oacc[j]);
+                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 48, j), pb1, oacc[j]);
             }
         }
     }
 
-    // epilogue: O = acc / l, LSE = ln(sum exp) = ln2 * (m_ref + log2 l)
-    const float l_tot = l_part + __shfl_xor(l_part, 32);
+    // epilogue: O = acc / l, LSE = ln(sum exp) = ln2 * (m_ref + log2 l); O leaves through LDS as full rows
+    const float l_tot = l_part + __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(xlane, __builtin_bit_cast(int, l_part)));
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (qrow < s.n_pos) {
-        __bf16 *orow = o + base + (size_t)qrow * D;
-#pragma unroll
-        for (int j = 0; j < DBLK; j++)
-#pragma unroll
-            for (int gq = 0; gq < 4; gq++) {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; e++) w[e] = (__bf16)(oacc[j][gq * 4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(orow + j * 32 + hf * 4 + gq * 8) = w;
-            }
-        if (hf == 0)
-            lse[(size_t)bh * s.n_pos + qrow] =
-                l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
-    }
+    wg_barrier();  // every wave is done reading the ring
+    const int wrow0 = I * BM + wave * 32;
+    store_rows_via_lds<P, D>(smem + wave * 32 * ROWB, lane, oacc, inv, o + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+    if (qrow < s.n_pos && hf == 0)
+        lse[(size_t)bh * s.n_pos + qrow] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
 }
 
 }  // namespace

@@ -167,13 +167,23 @@ template <typename P>
 struct Ring {
     static constexpr int S = P::S, NDMA = P::NDMA, PS = P::PS;
 
+    // first half of the prologue: pos(0), pos(1).  The caller may issue its own (compiler-scheduled)
+    // loads after this and before prologue(); the compiler's wait for those also covers these two.
     template <typename ColFn>
-    static __device__ __forceinline__ void prologue(const P &p, int n, ColFn col_of)
+    static __device__ __forceinline__ void start(const P &p, int n, ColFn col_of)
     {
         if (n > 0) p.issue_pos(col_of(0), 0);
+        if (n > 1) p.issue_pos(col_of(1), 1);
+    }
+
+    // second half: pos(j+1), data(j) for j in [J0, J1) (the whole prologue is J0 = 0, J1 = S-1; it may be
+    // issued in two pieces when some ring stages are still in use, see the backward kernels)
+    template <int J0, int J1, typename ColFn>
+    static __device__ __forceinline__ void prologue(const P &p, int n, ColFn col_of)
+    {
 #pragma unroll
-        for (int j = 0; j < S - 1; j++) {
-            if (j + 1 < n) p.issue_pos(col_of(j + 1), (j + 1) % PS);
+        for (int j = J0; j < J1; j++) {
+            if (j > 0 && j + 1 < n) p.issue_pos(col_of(j + 1), (j + 1) % PS);
             if (j < n) {
                 // pos(j) must have landed; issued after it: [data(j-1)], [pos(j+1)]
                 if (j == 0) {
@@ -204,6 +214,50 @@ struct Ring {
         if (i + S - 1 < n) p.issue_data((i + S - 1) % S, (i + S - 1) % PS);
     }
 };
+
+// A wave's own 32 rows of a [n_pos][D] tensor (rows row0 + 32*wave .. +31, clamped to n_pos-1),
+// loaded straight into LDS as rows 32*wave .. of a swizzled tile at byte offset lds_off: full rows per
+// 8 or 16 lanes, so every 128-byte line is fetched once.  The MFMA B fragments of those rows are
+// then read back with read_row().  Issues 32/RPI vector-memory instructions.
+template <typename P>
+__device__ __forceinline__ void stage_own_rows(const P &p, const __bf16 *t, int row0, int n_pos, int D, uint32_t lds_off)
+{
+    const int lr = p.lane / P::CPR, c = p.lane % P::CPR;
+#pragma unroll
+    for (int i = 0; i < 32 / P::RPI; i++) {
+        const int r = p.wave * 32 + i * P::RPI + lr;
+        const int g = min(row0 + r, n_pos - 1);
+        dma16(t + (size_t)g * D + (size_t)((c ^ swz(r & 7)) * 8),
+              p.smem_addr + lds_off + (uint32_t)((p.wave * 32 + i * P::RPI) * P::ROWB));
+    }
+}
+
+// Epilogue: a wave's 32 x D accumulator block, held transposed in C fragments (lane (row l%32, hf)
+// holds columns 32j + 4hf + 8g + 0..3), is scaled, rounded to bf16, transposed through a wave-private
+// LDS area of 32*ROWB bytes and written to global memory as full rows (16 bytes per lane).
+template <typename P, int D>
+__device__ __forceinline__ void store_rows_via_lds(char *wave_lds, int lane, const f32x16 (&acc)[D / 32], float mult,
+                                                   __bf16 *dst, int rows_valid)
+{
+    const int r = lane & 31, hf = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < D / 32; j++)
+#pragma unroll
+        for (int gq = 0; gq < 4; gq++) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; e++) w[e] = (__bf16)(acc[j][gq * 4 + e] * mult);
+            const int cl = j * 4 + gq;  // 16-byte chunk holding columns 32j + 8gq .. +7
+            *reinterpret_cast<bf16x4 *>(wave_lds + r * P::ROWB + ((cl ^ (r & 7)) << 4) + hf * 8) = w;
+        }
+    const int lr = lane / P::CPR, c = lane % P::CPR;
+#pragma unroll
+    for (int i = 0; i < 32 / P::RPI; i++) {
+        const int row = i * P::RPI + lr;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(wave_lds + row * P::ROWB + ((c ^ (row & 7)) << 4));
+        if (row < rows_valid) *reinterpret_cast<u32x4 *>(dst + (size_t)row * D + c * 8) = v;
+    }
+}
 
 // Per-lane constants for reading MFMA A operands by rows out of a swizzled tile: the lane's row
 // inside a 32-row block and its swizzle term; 16-byte chunk 2*st + hf of that row sits at
