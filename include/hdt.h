@@ -94,11 +94,12 @@ typedef struct {
  *   per surviving tile: its column, a bitmap of the allowed pairs and a summary of its 32x32
  *            sub-blocks; lists by query tile (columns ascending) and the transpose by key tile.
  *
- * Enqueues kernels on `stream`, synchronises the stream once (to size the tile arrays and to
- * report hierarchy errors) and allocates the layout's device memory.  batch == 0 or n_pos == 0
+ * Enqueues kernels on `stream` and synchronises the stream once, at the end (to read back the tile
+ * counts and to report hierarchy errors).  Device memory for the layout comes from a cache of buffers
+ * of destroyed layouts (hipMalloc when the cache has nothing that fits).  batch == 0 or n_pos == 0
  * gives an empty layout on which the attention calls are no-ops.
  *
- * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (n_pos > 2^22),
+ * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (n_pos > 2^19),
  * HDT_ERR_UNSUPPORTED (tile shape), HDT_ERR_HIERARCHY (level outside [-1, HDT_MAX_LEVELS),
  * parent outside [-1, n_pos), parent[i] == i, a pad with a parent, a parent that is a pad),
  * HDT_ERR_OOM, HDT_ERR_HIP.  On error *out is NULL.
@@ -133,9 +134,14 @@ hdt_status_t hdt_layout_export(const hdt_layout_t *layout, int32_t sample, int32
                                int32_t *h_k_colptr, int32_t *h_k_rows, int32_t *h_k_tile,
                                int64_t tile_capacity);
 
-/* Frees the layout and its device memory.  NULL is accepted.  The caller must make sure no
- * attention call that uses the layout is still running. */
+/* Destroys the layout.  NULL is accepted.  Its device buffers go to a cache (at most 16 buffers /
+ * 1 GiB per process) that later hdt_build_layout calls draw from, without synchronising.  A later
+ * build may therefore overwrite them: either no attention call using this layout is still running,
+ * or every such call was enqueued on the stream the later builds use. */
 hdt_status_t hdt_layout_destroy(hdt_layout_t *layout);
+
+/* Returns the cached device buffers to the driver (hipFree). */
+hdt_status_t hdt_release_cached_memory(void);
 
 /*
  * hdt_attn_fwd -- forward pass over the surviving tiles (App. A.1, Alg. 1: per query tile, loop

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     hdt_attn_bwd_workspace_bytes,
     hdt_attn_fwd,
     hdt_build_layout,
+    hdt_release_cached_memory,
     hdt_timing_enable,
     hdt_timing_read,
     hdt_timing_reset,

@@ -19,7 +19,7 @@ HDT_BF16, HDT_F32 = 0, 1
 EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
     "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
-    "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read",
+    "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
 ]
 
 
@@ -86,6 +86,8 @@ def load_library():
     lib.hdt_timing_read.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64),
                                     ctypes.POINTER(ctypes.c_double), i32]
     lib.hdt_timing_read.restype = i32
+    lib.hdt_release_cached_memory.argtypes = []
+    lib.hdt_release_cached_memory.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -233,6 +235,10 @@ def hdt_attn_bwd(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq=
                                        _ptr(workspace), workspace.numel() * workspace.element_size(),
                                        _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def hdt_release_cached_memory():
+    _check(load_library().hdt_release_cached_memory())
 
 
 def hdt_timing_enable(enable: bool):

@@ -122,25 +122,10 @@ extern "C" __attribute__((visibility("default"))) int32_t hdt_timing_read(const 
 }
 
 // ---------------------------------------------------------------------------- layout queries
-static hdt_status_t fetch_stats(hdt_layout_t *l)
-{
-    if (l->stats_cached) return HDT_OK;
-    l->h_stats.assign((size_t)l->s.batch * 2, 0);
-    if (l->s.batch > 0 && l->d_stats) {
-        HDT_HIP_TRY(hipDeviceSynchronize());
-        HDT_HIP_TRY(hipMemcpy(l->h_stats.data(), l->d_stats, sizeof(int64_t) * 2 * l->s.batch,
-                              hipMemcpyDeviceToHost));
-    }
-    l->stats_cached = true;
-    return HDT_OK;
-}
-
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(const hdt_layout_t *layout, hdt_layout_info_t *info)
 {
     if (!hdt_layout_ok(layout) || !info) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_info: NULL or invalid layout");
-    hdt_layout_t *l = const_cast<hdt_layout_t *>(layout);
-    hdt_status_t st = fetch_stats(l);
-    if (st != HDT_OK) return st;
+    const hdt_layout_t *l = layout;
     info->batch = l->s.batch;
     info->n_pos = l->s.n_pos;
     info->tile_m = l->s.bm;
@@ -163,27 +148,21 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_sample
     if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_sample_info: invalid layout");
     if (sample < 0 || sample >= layout->s.batch)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_sample_info: sample %d outside [0, %d)", sample, layout->s.batch);
-    hdt_layout_t *l = const_cast<hdt_layout_t *>(layout);
-    hdt_status_t st = fetch_stats(l);
-    if (st != HDT_OK) return st;
+    const hdt_layout_t *l = layout;
     if (n_tiles) *n_tiles = l->h_stats[2 * sample];
     if (nnz) *nnz = l->h_stats[2 * sample + 1];
     return HDT_OK;
 }
 
-extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export(const hdt_layout_t *layout, int32_t sample, int32_t *kperm,
-                                          int32_t *q_rowptr, int32_t *q_cols, uint32_t *q_sub, uint32_t *bits,
-                                          int32_t *k_colptr, int32_t *k_rows, int32_t *k_tile,
-                                          int64_t tile_capacity)
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export(
+    const hdt_layout_t *layout, int32_t sample, int32_t *kperm, int32_t *q_rowptr, int32_t *q_cols, uint32_t *q_sub,
+    uint32_t *bits, int32_t *k_colptr, int32_t *k_rows, int32_t *k_tile, int64_t tile_capacity)
 {
     if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_export: invalid layout");
     const HdtSchedule &s = layout->s;
     if (sample < 0 || sample >= s.batch)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: sample %d outside [0, %d)", sample, s.batch);
-    hdt_layout_t *l = const_cast<hdt_layout_t *>(layout);
-    hdt_status_t st = fetch_stats(l);
-    if (st != HDT_OK) return st;
-    const int64_t T = l->h_stats[2 * sample];
+    const int64_t T = layout->h_stats[2 * (size_t)sample];
     const bool want_tiles = q_cols || q_sub || bits || k_rows || k_tile;
     if (want_tiles && tile_capacity < T)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: capacity %lld < %lld tiles", (long long)tile_capacity,
@@ -192,36 +171,55 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
     if (kperm && s.n_pos > 0)
         HDT_HIP_TRY(hipMemcpy(kperm, s.kperm + (size_t)sample * s.n_slots, sizeof(int32_t) * s.n_pos,
                               hipMemcpyDeviceToHost));
-    std::vector<int32_t> rp((size_t)s.tr + 1, 0), cp((size_t)s.tc + 1, 0);
-    if (s.tr > 0) {
-        HDT_HIP_TRY(hipMemcpy(rp.data(), s.q_rowptr + (size_t)sample * s.tr, sizeof(int32_t) * (s.tr + 1),
+    // the device lists hold every candidate tile; the exported schedule keeps those with an allowed pair
+    // (all of them for a dense layout) and is numbered from 0
+    std::vector<int32_t> rp((size_t)s.tr + 1, 0);
+    if (s.tr > 0)
+        HDT_HIP_TRY(hipMemcpy(rp.data(), s.q_rowptr + (size_t)sample * (s.tr + 1), sizeof(int32_t) * (s.tr + 1),
                               hipMemcpyDeviceToHost));
-        HDT_HIP_TRY(hipMemcpy(cp.data(), s.k_colptr + (size_t)sample * s.tc, sizeof(int32_t) * (s.tc + 1),
-                              hipMemcpyDeviceToHost));
+    const int32_t base = rp[0];
+    const int64_t E = (int64_t)rp[s.tr] - base;  // entries of this sample
+    std::vector<int32_t> cols((size_t)E), cnt((size_t)E);
+    std::vector<uint32_t> sub((size_t)E);
+    if (E > 0) {
+        HDT_HIP_TRY(hipMemcpy(cols.data(), s.q_cols + base, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
+        HDT_HIP_TRY(hipMemcpy(cnt.data(), layout->d_cnt + base, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
+        HDT_HIP_TRY(hipMemcpy(sub.data(), s.q_sub + base, sizeof(uint32_t) * E, hipMemcpyDeviceToHost));
     }
-    const int32_t base = rp[0], kbase = cp[0];
-    if ((int64_t)rp[s.tr] - base != T || (int64_t)cp[s.tc] - kbase != T || base != kbase)
-        return hdt_fail(HDT_ERR_HIP, "hdt_layout_export: inconsistent tile counts (%d..%d, %d..%d, %lld)", base,
-                        rp[s.tr], kbase, cp[s.tc], (long long)T);
-    if (q_rowptr)
-        for (int i = 0; i <= s.tr; i++) q_rowptr[i] = rp[i] - base;
-    if (k_colptr)
-        for (int i = 0; i <= s.tc; i++) k_colptr[i] = cp[i] - kbase;
-    if (T > 0) {
-        if (q_cols) HDT_HIP_TRY(hipMemcpy(q_cols, s.q_cols + base, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
-        if (q_sub) HDT_HIP_TRY(hipMemcpy(q_sub, s.q_sub + base, sizeof(uint32_t) * T, hipMemcpyDeviceToHost));
-        if (k_rows) HDT_HIP_TRY(hipMemcpy(k_rows, s.k_rows + kbase, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
-        if (k_tile) {
-            HDT_HIP_TRY(hipMemcpy(k_tile, s.k_tile + kbase, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
-            for (int64_t t = 0; t < T; t++) k_tile[t] -= base;
-        }
-        if (bits) {
-            std::vector<int32_t> bidx((size_t)T);
-            HDT_HIP_TRY(hipMemcpy(bidx.data(), s.q_bidx + base, sizeof(int32_t) * T, hipMemcpyDeviceToHost));
-            const size_t words = (size_t)s.bm * s.wpr;
-            for (int64_t t = 0; t < T; t++)
-                HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + (size_t)bidx[t] * words,
-                                      sizeof(uint32_t) * words, hipMemcpyDeviceToHost));
+    std::vector<int32_t> new_rp((size_t)s.tr + 1, 0), keep_col, keep_row, keep_entry;
+    for (int I = 0; I < s.tr; I++) {
+        for (int32_t e = rp[I] - base; e < rp[I + 1] - base; e++)
+            if (cnt[e] > 0 || layout->force_dense) {
+                keep_col.push_back(cols[e]);
+                keep_row.push_back(I);
+                keep_entry.push_back(e);
+            }
+        new_rp[I + 1] = (int32_t)keep_col.size();
+    }
+    if ((int64_t)keep_col.size() != T)
+        return hdt_fail(HDT_ERR_HIP, "hdt_layout_export: inconsistent tile counts (%zu listed, %lld counted)",
+                        keep_col.size(), (long long)T);
+    if (q_rowptr) memcpy(q_rowptr, new_rp.data(), sizeof(int32_t) * (s.tr + 1));
+    const size_t words = (size_t)s.bm * s.wpr;
+    for (int64_t t = 0; t < T; t++) {
+        if (q_cols) q_cols[t] = keep_col[t];
+        if (q_sub) q_sub[t] = sub[keep_entry[t]];
+        if (bits)
+            HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + ((size_t)base + keep_entry[t]) * words,
+                                  sizeof(uint32_t) * words, hipMemcpyDeviceToHost));
+    }
+    // transpose by key tile (query tiles ascending): the kernels do not need it (the mask is symmetric,
+    // so the backward walks the same lists); it is derived here for callers that want both views
+    if (k_colptr || k_rows || k_tile) {
+        std::vector<int32_t> cp((size_t)s.tc + 1, 0);
+        for (int64_t t = 0; t < T; t++) cp[keep_col[t] + 1]++;
+        for (int J = 0; J < s.tc; J++) cp[J + 1] += cp[J];
+        if (k_colptr) memcpy(k_colptr, cp.data(), sizeof(int32_t) * (s.tc + 1));
+        std::vector<int32_t> cur(cp.begin(), cp.end() - 1);
+        for (int64_t t = 0; t < T; t++) {  // t ascends with the query tile, so rows come out ascending
+            const int32_t e = cur[keep_col[t]]++;
+            if (k_rows) k_rows[e] = keep_row[t];
+            if (k_tile) k_tile[e] = (int32_t)t;
         }
     }
     return HDT_OK;
@@ -232,14 +230,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destro
     if (!layout) return HDT_OK;
     if (layout->magic != HDT_LAYOUT_MAGIC) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_destroy: not a layout");
     layout->magic = 0;
-    hipError_t e = hipSuccess;
-    if (layout->arena) e = hipFree(layout->arena);
-    if (layout->arena2) {
-        hipError_t e2 = hipFree(layout->arena2);
-        if (e == hipSuccess) e = e2;
-    }
+    hdt_layout_release(layout);
     delete layout;
-    if (e != hipSuccess) return hdt_fail(HDT_ERR_HIP, "hipFree: %s", hipGetErrorString(e));
     return HDT_OK;
 }
 

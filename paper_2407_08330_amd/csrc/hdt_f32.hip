@@ -1,5 +1,5 @@
 // fp32 debugging path: the same tile schedule walked with plain fp32 arithmetic, one thread per
-// query row (forward, dQ) or per key slot (dK, dV).  Slow on purpose; it exists to check the
+// query row (forward, dQ) or per key row (dK, dV).  Slow on purpose; it exists to check the
 // schedule, the mask bitmaps and the online softmax separately from the MFMA kernels.
 // Forward: App. A.1, Alg. 1 (online softmax over the surviving tiles).  Backward: gradient of
 // the definition in Sec. 3.2.
@@ -22,10 +22,10 @@ __global__ __launch_bounds__(128) void k_fwd_f32(HdtSchedule s, const float *__r
     float acc[D];
     for (int c = 0; c < D; c++) acc[c] = 0.f;
     float m = -INFINITY, l = 0.f;
-    const size_t row = (size_t)b * s.tr + I;
+    const size_t row = (size_t)b * (s.tr + 1) + I;
     for (int t = s.q_rowptr[row]; t < s.q_rowptr[row + 1]; t++) {
         const int J = s.q_cols[t];
-        const uint32_t *bw = s.bits + ((size_t)s.q_bidx[t] * s.bm + r) * s.wpr;
+        const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
             const int pos = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];
@@ -70,10 +70,10 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     const float li = lse[(size_t)bh * s.n_pos + i];
     float acc[D];
     for (int c = 0; c < D; c++) acc[c] = 0.f;
-    const size_t row = (size_t)b * s.tr + I;
+    const size_t row = (size_t)b * (s.tr + 1) + I;
     for (int t = s.q_rowptr[row]; t < s.q_rowptr[row + 1]; t++) {
         const int J = s.q_cols[t];
-        const uint32_t *bw = s.bits + ((size_t)s.q_bidx[t] * s.bm + r) * s.wpr;
+        const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
             const int pos = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];
@@ -94,6 +94,9 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     for (int c = 0; c < D; c++) dqi[c] = acc[c];
 }
 
+// dK, dV: the mask is symmetric (i may attend to j iff j may attend to i), so the list of query tile I
+// x key slots J is also the list of key rows I x query slots J with the same bitmaps.  One thread per
+// key row (document order) walks that list and gathers the query rows through kperm.
 template <int D>
 __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float *__restrict__ q,
                                                      const float *__restrict__ k, const float *__restrict__ v,
@@ -101,22 +104,23 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
                                                      const float *__restrict__ delta, float *__restrict__ dk,
                                                      float *__restrict__ dv, int heads, float scale)
 {
-    const int J = blockIdx.x, bh = blockIdx.y, b = bh / heads, c = threadIdx.x;
-    if (c >= s.bn) return;
-    const int pos = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];
-    if (pos < 0) return;
+    const int I = blockIdx.x, bh = blockIdx.y, b = bh / heads, r = threadIdx.x;
+    if (r >= s.bm) return;
+    const int j = I * s.bm + r;  // key position
+    if (j >= s.n_pos) return;
     const size_t base = (size_t)bh * s.n_pos * D;
-    const float *kj = k + base + (size_t)pos * D;
-    const float *vj = v + base + (size_t)pos * D;
+    const float *kj = k + base + (size_t)j * D;
+    const float *vj = v + base + (size_t)j * D;
     float ak[D], av[D];
     for (int e = 0; e < D; e++) ak[e] = av[e] = 0.f;
-    const size_t col = (size_t)b * s.tc + J;
-    for (int en = s.k_colptr[col]; en < s.k_colptr[col + 1]; en++) {
-        const int I = s.k_rows[en], t = s.k_tile[en];
-        const uint32_t *bw = s.bits + (size_t)s.q_bidx[t] * s.bm * s.wpr;
-        for (int r = 0; r < s.bm; r++) {
-            if (!((bw[r * s.wpr + (c >> 5)] >> (c & 31)) & 1u)) continue;
-            const int i = I * s.bm + r;
+    const size_t row = (size_t)b * (s.tr + 1) + I;
+    for (int t = s.q_rowptr[row]; t < s.q_rowptr[row + 1]; t++) {
+        const int J = s.q_cols[t];
+        const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
+        for (int c = 0; c < s.bn; c++) {
+            if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
+            const int i = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];  // query position
+            if (i < 0) continue;
             const float *qi = q + base + (size_t)i * D;
             const float *doi = d_o + base + (size_t)i * D;
             float sc = 0.f, dp = 0.f;
@@ -132,8 +136,8 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
             }
         }
     }
-    float *dkj = dk + base + (size_t)pos * D;
-    float *dvj = dv + base + (size_t)pos * D;
+    float *dkj = dk + base + (size_t)j * D;
+    float *dvj = dv + base + (size_t)j * D;
     for (int e = 0; e < D; e++) {
         dkj[e] = ak[e];
         dvj[e] = av[e];
@@ -161,7 +165,7 @@ hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const float *q, const floa
                                 float *dv, int heads, int head_dim, float scale, float *delta, hipStream_t st)
 {
     if ((int64_t)s.batch * heads > 65535) return hdt_fail(HDT_ERR_SHAPE, "fp32 path: batch*heads > 65535");
-    dim3 gq(s.tr, s.batch * heads), gk(s.tc, s.batch * heads), block(128);
+    dim3 gq(s.tr, s.batch * heads), gk(s.tr, s.batch * heads), block(128);
     {
         HdtTimer t("hdt_bwd_dq_f32", st);
         if (head_dim == 64)

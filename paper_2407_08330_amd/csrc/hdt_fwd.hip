@@ -56,12 +56,11 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     const size_t base = (size_t)bh * s.n_pos * D;
 
-    const size_t row = (size_t)b * s.tr + I;
+    const size_t row = (size_t)b * (s.tr + 1) + I;
     const cptr_i32 rowptr = as_const(s.q_rowptr);
     const int t0 = rowptr[row], n = rowptr[row + 1] - t0;
     const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
-    const cptr_i32 bidxs = as_const(s.q_bidx) + t0;
 
     P pipe;
     pipe.smem = smem;
@@ -99,13 +98,11 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
 
     int col_ahead = (S < n) ? cols[S] : 0;  // column of tile i+S
     uint32_t sub_next = n > 0 ? subs[0] : 0u;
-    int bidx_next = n > 0 ? bidxs[0] : 0;
     for (int i = 0; i < n; i++) {
         const uint32_t sub = sub_next;
-        const int bidx = bidx_next;
+        const int bidx = t0 + i;  // bitmaps are stored in list order
         if (i + 1 < n) {
             sub_next = subs[i + 1];
-            bidx_next = bidxs[i + 1];
         }
         R::top(i, n);
         wg_barrier();

@@ -12,6 +12,11 @@
 #define HDT_LAYOUT_MAGIC 0x4844544cu  // "HDTL"
 
 // Device-side view of a tile schedule, passed by value to the attention kernels.
+//
+// The lists hold the CANDIDATE tiles of every query tile, columns ascending.  Every candidate has
+// been evaluated exactly; one that turned out to hold no allowed pair keeps its place in the list with
+// an all-zero summary (q_sub == 0) and all-zero bitmaps, which makes every kernel skip it.  For
+// documents laid out in pre-order there are no such entries; hdt_layout_export filters them out.
 struct HdtSchedule {
     int32_t batch, n_pos;
     int32_t bm, bn;        // tile shape (query rows x key slots)
@@ -19,30 +24,27 @@ struct HdtSchedule {
     int32_t n_slots;       // tc * bn: length of one sample's padded key order
     int32_t wpr;           // bitmap words per tile row = bn / 32
     const int32_t *kperm;  // [batch][n_slots] sorted slot -> position, -1 beyond n_pos
-    const int32_t *q_rowptr;  // [batch*tr + 1] entries of query tile (b, I), global numbering
-    const int32_t *q_cols;    // [n_tiles] key tile of each entry
-    const uint32_t *q_sub;    // [n_tiles] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
-    const int32_t *q_bidx;    // [n_tiles] index of the entry's bitmap in `bits`
-    const uint32_t *bits;     // [capacity][bm][wpr]   row r, word c/32, bit c%32
-    // [capacity][(bm/32)*(bn/32)][16] per 32x32 sub-block (r, c) = index r*(bn/32)+c: bit l of word e <=>
+    const int32_t *q_rowptr;  // [batch][tr + 1] entries of query tile (b, I), global numbering
+    const int32_t *q_cols;    // [entries] key tile of each entry
+    const uint32_t *q_sub;    // [entries] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
+    const uint32_t *bits;     // [entries][bm][wpr]   row r, word c/32, bit c%32
+    // [entries][(bm/32)*(bn/32)][16] per 32x32 sub-block (r, c) = index r*(bn/32)+c: bit l of word e <=>
     // row 32r + l%32, column 32c + (l/32)*4 + 8*(e/4) + e%4 allowed: the lane mask of MFMA accumulator register e
     const unsigned long long *bits_rm;
-    const int32_t *k_colptr;  // [batch*tc + 1] transposed entries of key tile (b, J)
-    const int32_t *k_rows;    // [n_tiles] query tile of each transposed entry
-    const int32_t *k_tile;    // [n_tiles] index of the entry in the q-ordered arrays
 };
 
 struct hdt_layout {
     uint32_t magic;
-    HdtSchedule s;       // pointers into `arena`
+    HdtSchedule s;       // pointers into the arenas
     int32_t device;      // device the buffers live on
-    int64_t capacity;    // entries the tile arrays can hold (= candidates found)
+    int32_t force_dense; // every candidate counts as a tile, empty or not
+    int64_t capacity;    // entries the per-tile arrays can hold
     int64_t device_bytes;
-    void *arena;         // key order, lists' pointers, scratch of the build
-    void *arena2;        // per-tile arrays, sized once the number of candidate tiles is known
-    int64_t *d_stats;    // [batch][2] = (n_tiles, nnz) per sample, inside the arena
-    bool stats_cached;
-    std::vector<int64_t> h_stats;
+    void *arena;         // key order, list pointers, scratch of the build
+    void *arena2;        // per-tile arrays
+    size_t arena_bytes, arena2_bytes;
+    const int32_t *d_cnt;          // [entries] allowed pairs of each entry (device)
+    std::vector<int64_t> h_stats;  // [batch][2] = (surviving tiles, allowed pairs) per sample
 };
 
 // --- error reporting (hdt_api.hip) ---
@@ -56,6 +58,7 @@ hdt_status_t hdt_fail(hdt_status_t st, const char *fmt, ...);
     } while (0)
 
 bool hdt_layout_ok(const hdt_layout_t *l);
+void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
 
 // --- per-kernel timing (hdt_api.hip) ---
 struct HdtTimer {  // brackets one kernel launch with events when timing is enabled

@@ -2,155 +2,85 @@
 //
 // What is computed is fixed by the paper (Sec. 3.2: a position attends to parent, siblings and
 // children; App. A.1, Alg. 1: sort keys by hierarchy level, partition into blocks, process a block
-// only if its mask has a non-zero entry).  How it is computed is ours:
-//   1. key order: stable counting sort by level with wave ballots (one workgroup per sample);
-//   2. per anchor, the range of sorted slots its children occupy (integer atomic min/max);
+// only if its mask has a non-zero entry).  How it is computed is ours.  Three kernels:
+//
+//  front (one workgroup per sample)
+//   1. key order: stable counting sort by level with wave ballots;
+//   2. per anchor, the range of sorted slots its children occupy (integer atomic min/max, one
+//      pair of atomics per run of consecutive children);
 //   3. candidate tiles per query tile: every allowed key of a row lies in one of <= 2 slot ranges
 //      (its siblings = the children of its parent, and its own children) or is one of 2 single
 //      slots (itself, its parent), so a row marks O(1) ranges instead of testing n keys.  For
 //      documents laid out in pre-order the ranges are exact; for any other forest they are a
 //      superset;
-//   4. every candidate tile is then evaluated exactly, pair by pair (bitmap, pair count, 32x32
-//      sub-block summary), and empty candidates are dropped, so the result never depends on
-//      step 3 being tight;
-//   5. compaction into lists by query tile and their transpose by key tile (prefix sums; all
-//      orders are fixed by index, no ordering depends on atomics).
+//   4. prefix sum of the candidate counts, a slice of the per-tile arrays reserved with one atomic
+//      add per sample, and the key tile of every candidate written out: these ARE the tile lists;
+//  bitmaps (grid-stride over candidates)
+//   5. every candidate tile is evaluated exactly, pair by pair (bitmap, pair count, 32x32
+//      sub-block summary), so the result never depends on step 3 being tight.  A candidate without
+//      any allowed pair keeps its list entry with an all-zero summary, which every kernel skips;
+//      it is not counted as a tile and hdt_layout_export leaves it out.
+//
+// The per-tile arrays are sized before the number of candidates is known (a heuristic, raised by
+// what earlier builds needed); both kernels check the capacity, the host reads the counters back
+// once at the end and repeats the build with the exact size in the rare case the guess was too small.
+// Device memory comes from a small cache of earlier layouts' buffers.
 #include <limits.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "hdt_internal.h"
 
 namespace {
 
-constexpr int kSortThreads = 1024;
-constexpr int kSortWaves = kSortThreads / 64;
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / 64;
 constexpr int kBuckets = HDT_MAX_LEVELS + 1;  // levels 0..31, pads in the last bucket
+constexpr int kSortChunk = 8;                 // positions per lane loaded ahead of the ballot loops
 
-__device__ __forceinline__ unsigned long long lanemask_lt()
+enum { CNT_ERR = 0, CNT_CAND = 1, CNT_TILES = 2, CNT_PAD = 3 };
+
+__device__ __forceinline__ unsigned long long lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
+
+__device__ __forceinline__ int wave_sum(int x)
 {
-    return (1ull << (threadIdx.x & 63)) - 1ull;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) x += __shfl_xor(x, d);
+    return x;
 }
 
-// ---- 1. validation + stable sort of positions by level ------------------------------------
-__global__ __launch_bounds__(kSortThreads) void k_sort_by_level(const int32_t *__restrict__ level,
-                                                                 const int32_t *__restrict__ parent, int n,
-                                                                 int n_slots, int no_sort, int32_t *kperm,
-                                                                 int32_t *slot, int32_t *cmin, int32_t *cmax,
-                                                                 int32_t *err)
+// exclusive scan, in place, of data[0..n) by the whole workgroup; returns the total to every thread
+__device__ int block_scan_inplace(int32_t *data, int n, int *s_wave /*[kWaves + 1]*/)
 {
-    const int b = blockIdx.x;
-    level += (size_t)b * n;
-    parent += (size_t)b * n;
-    kperm += (size_t)b * n_slots;
-    slot += (size_t)b * n;
-    cmin += (size_t)b * n;
-    cmax += (size_t)b * n;
-
-    __shared__ volatile int s_cnt[kSortWaves][kBuckets];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-
-    for (int i = tid; i < n; i += kSortThreads) {
-        cmin[i] = INT_MAX;
-        cmax[i] = -1;
+    int carry = 0;
+    for (int base = 0; base < n; base += kThreads) {
+        const int i = base + tid;
+        const int v = i < n ? data[i] : 0;
+        int x = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(x, d);
+            if (lane >= d) x += y;
+        }
+        if (lane == 63) s_wave[wave] = x;
+        __syncthreads();
+        int off = 0, tot = 0;
+        for (int w = 0; w < kWaves; w++) {
+            const int sw = s_wave[w];
+            if (w < wave) off += sw;
+            tot += sw;
+        }
+        if (i < n) data[i] = carry + off + x - v;
+        carry += tot;
+        __syncthreads();
     }
-    for (int s = n + tid; s < n_slots; s += kSortThreads) kperm[s] = -1;
-    for (int i = tid; i < kSortWaves * kBuckets; i += kSortThreads) (&s_cnt[0][0])[i] = 0;
-    __syncthreads();
-
-    // each wave owns a contiguous segment whose length is a multiple of 64
-    const int seg = ((n + kSortWaves * 64 - 1) / (kSortWaves * 64)) * 64;
-    const int begin = min(n, wave * seg), end = min(n, begin + seg);
-
-    // pass A: validate, count positions per (wave, bucket)
-    bool bad = false;
-    for (int base = begin; base < end; base += 64) {
-        const int i = base + lane;
-        const bool in = i < end;
-        int bucket = kBuckets - 1;
-        if (in) {
-            const int lv = level[i], p = parent[i];
-            if (lv < -1 || lv >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (lv < 0 && p != -1)) bad = true;
-            if (lv >= 0 && lv < HDT_MAX_LEVELS) bucket = lv;
-        }
-        unsigned long long remaining = __ballot(in);
-        while (remaining) {
-            const int leader = __ffsll((long long)remaining) - 1;
-            const int bk = __shfl(bucket, leader);
-            const unsigned long long m = __ballot(in && bucket == bk);
-            if (lane == 0) s_cnt[wave][bk] += __popcll(m);
-            remaining &= ~m;
-        }
-    }
-    if (__ballot(bad) && lane == 0) atomicOr(&err[0], 1);
-    __syncthreads();
-
-    // exclusive prefix over (bucket major, wave minor): first slot of every (wave, bucket)
-    if (tid == 0) {
-        int off = 0;
-        for (int k = 0; k < kBuckets; k++)
-            for (int w = 0; w < kSortWaves; w++) {
-                const int c = s_cnt[w][k];
-                s_cnt[w][k] = off;
-                off += c;
-            }
-    }
-    __syncthreads();
-
-    // pass B: hand out slots in document order inside every bucket
-    for (int base = begin; base < end; base += 64) {
-        const int i = base + lane;
-        const bool in = i < end;
-        int bucket = kBuckets - 1;
-        if (in) {
-            const int lv = level[i];
-            if (lv >= 0 && lv < HDT_MAX_LEVELS) bucket = lv;
-        }
-        int my_slot = i;
-        unsigned long long remaining = __ballot(in);
-        while (remaining) {
-            const int leader = __ffsll((long long)remaining) - 1;
-            const int bk = __shfl(bucket, leader);
-            const bool mine = in && bucket == bk;
-            const unsigned long long m = __ballot(mine);
-            const int first = s_cnt[wave][bk];
-            if (mine) my_slot = first + __popcll(m & lanemask_lt());
-            __builtin_amdgcn_wave_barrier();
-            if (lane == 0) s_cnt[wave][bk] = first + __popcll(m);
-            __builtin_amdgcn_wave_barrier();
-            remaining &= ~m;
-        }
-        if (in) {
-            if (no_sort) my_slot = i;
-            slot[i] = my_slot;
-            kperm[my_slot] = i;
-        }
-    }
+    return carry;
 }
 
-// ---- 2. slot range of every node's children ---------------------------------------------------
-__global__ __launch_bounds__(256) void k_child_ranges(const int32_t *__restrict__ level,
-                                                      const int32_t *__restrict__ parent,
-                                                      const int32_t *__restrict__ slot, int n, int32_t *cmin,
-                                                      int32_t *cmax, int32_t *err)
-{
-    const int b = blockIdx.y;
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const size_t o = (size_t)b * n;
-    const int lv = level[o + i], p = parent[o + i];
-    if (lv < 0 || p < 0 || p >= n) return;
-    if (level[o + p] < 0) {  // a parent must be a real position
-        atomicOr(&err[0], 1);
-        return;
-    }
-    const int s = slot[o + i];
-    atomicMin(&cmin[o + p], s);
-    atomicMax(&cmax[o + p], s);
-}
-
-// ---- 3. candidate key tiles of every query tile -------------------------------------------------
 __device__ __forceinline__ void mark_tiles(uint32_t *bits, int tlo, int thi)
 {
     for (int w = tlo >> 5; w <= (thi >> 5); w++) {
@@ -160,285 +90,388 @@ __device__ __forceinline__ void mark_tiles(uint32_t *bits, int tlo, int thi)
     }
 }
 
-__global__ __launch_bounds__(128) void k_mark_candidates(const int32_t *__restrict__ level,
-                                                         const int32_t *__restrict__ parent,
-                                                         const int32_t *__restrict__ slot,
-                                                         const int32_t *__restrict__ cmin,
-                                                         const int32_t *__restrict__ cmax, int n, int bm, int bn,
-                                                         int tr, int tc, int wc, int force_dense, uint32_t *cand,
-                                                         int32_t *cand_cnt)
-{
-    extern __shared__ uint32_t s_bits[];
-    __shared__ int s_total;
-    const int I = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-    const size_t o = (size_t)b * n;
-    for (int w = tid; w < wc; w += 128) s_bits[w] = 0;
-    if (tid == 0) s_total = 0;
-    __syncthreads();
-    if (force_dense) {
-        if (tid == 0) mark_tiles(s_bits, 0, tc - 1);
-    } else if (tid < bm) {
-        const int i = I * bm + tid;
-        if (i < n && level[o + i] >= 0) {
-            const int si = slot[o + i] / bn;
-            mark_tiles(s_bits, si, si);  // itself
-            const int p = parent[o + i];
-            if (p >= 0 && p < n && level[o + p] >= 0) {
-                const int sp = slot[o + p] / bn;
-                mark_tiles(s_bits, sp, sp);  // its parent
-                const int lo = cmin[o + p], hi = cmax[o + p];  // its siblings: children of the parent
-                if (lo <= hi && lo >= 0 && hi < n) mark_tiles(s_bits, lo / bn, hi / bn);
-            }
-            const int lo = cmin[o + i], hi = cmax[o + i];  // its children
-            if (lo <= hi && lo >= 0 && hi < n) mark_tiles(s_bits, lo / bn, hi / bn);
-        }
-    }
-    __syncthreads();
-    int local = 0;
-    uint32_t *out = cand + ((size_t)b * tr + I) * wc;
-    for (int w = tid; w < wc; w += 128) {
-        const uint32_t v = s_bits[w];
-        out[w] = v;
-        local += __popc(v);
-    }
-    if (local) atomicAdd(&s_total, local);
-    __syncthreads();
-    if (tid == 0) cand_cnt[(size_t)b * tr + I] = s_total;
-}
+struct FrontArgs {
+    const int32_t *level, *parent;
+    int n, n_slots, bm, bn, tr, tc, wc, force_dense, no_sort;
+    int64_t capacity;
+    int32_t *kperm, *slot, *cmin, *cmax;
+    uint32_t *cand;     // [B][tr][wc]
+    int32_t *cand_ptr;  // [B][tr+1]: becomes the lists' row pointer
+    int32_t *c_row, *q_cols;
+    int32_t *counters;
+};
 
-// ---- exclusive scan of a short int array by one workgroup ------------------------------------
-__global__ __launch_bounds__(1024) void k_exclusive_scan(const int32_t *__restrict__ in, int32_t *out, int n,
-                                                         int32_t *total_out)
+// ---- front: sort, child ranges, candidates ---------------------------------------------------
+__global__ __launch_bounds__(kThreads) void k_layout_front(FrontArgs a)
 {
-    __shared__ int s_wave[16];
-    __shared__ int s_carry;
+    extern __shared__ uint32_t s_bitmaps[];  // [kWaves][wc]
+    __shared__ volatile int s_cnt[kWaves][kBuckets];
+    __shared__ int s_wave[kWaves + 1];
+    __shared__ int s_base;
+    const int b = blockIdx.x, n = a.n;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    if (tid == 0) s_carry = 0;
+    const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
+    int32_t *kperm = a.kperm + (size_t)b * a.n_slots, *slot = a.slot + (size_t)b * n;
+    int32_t *cmin = a.cmin + (size_t)b * n, *cmax = a.cmax + (size_t)b * n;
+
+    for (int i = tid; i < n; i += kThreads) {
+        cmin[i] = INT_MAX;
+        cmax[i] = -1;
+    }
+    for (int s = n + tid; s < a.n_slots; s += kThreads) kperm[s] = -1;
+    for (int i = tid; i < kWaves * kBuckets; i += kThreads) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
-    for (int base = 0; base < n; base += 1024) {
-        const int i = base + tid;
-        const int v = i < n ? in[i] : 0;
-        int x = v;  // inclusive scan inside the wave
+
+    // 1. stable sort by level.  Each wave owns a contiguous segment (a multiple of 64 positions); lane k
+    // of a wave keeps the wave's running count of bucket k in a register.
+    const int seg = ((n + kWaves * 64 - 1) / (kWaves * 64)) * 64;
+    const int begin = min(n, wave * seg), end = min(n, begin + seg);
+    bool bad = false;
+    int mycnt = 0;
+    for (int base = begin; base < end; base += 64 * kSortChunk) {  // pass A: validate and count
+        int lv[kSortChunk], pr[kSortChunk];
+#pragma unroll
+        for (int u = 0; u < kSortChunk; u++) {
+            const int i = base + u * 64 + lane;
+            lv[u] = i < end ? level[i] : -1;
+            pr[u] = i < end ? parent[i] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kSortChunk; u++) {
+            const int i = base + u * 64 + lane;
+            const bool in = i < end;
+            int bucket = kBuckets - 1;
+            if (in) {
+                const int l = lv[u], p = pr[u];
+                if (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1)) bad = true;
+                if (l >= 0 && l < HDT_MAX_LEVELS) bucket = l;
+            }
+            unsigned long long remaining = __ballot(in);
+            while (remaining) {
+                const int leader = __ffsll((long long)remaining) - 1;
+                const int bk = __builtin_amdgcn_readlane(bucket, leader);
+                const unsigned long long m = __ballot(in && bucket == bk);
+                if (lane == bk) mycnt += __popcll(m);
+                remaining &= ~m;
+            }
+        }
+    }
+    if (__ballot(bad) && lane == 0) atomicOr(&a.counters[CNT_ERR], 1);
+    if (lane < kBuckets) s_cnt[wave][lane] = mycnt;
+    __syncthreads();
+    if (wave == 0) {  // first slot of every (bucket, wave): bucket major, wave minor; lane k scans bucket k
+        int tot = 0, pre[kWaves];
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < kWaves; w++) {
+                pre[w] = tot;
+                tot += s_cnt[w][lane];
+            }
+        }
+        int incl = tot;  // inclusive scan of the bucket totals over lanes
+#pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(x, d);
-            if (lane >= d) x += y;
+            const int y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
         }
-        if (lane == 63) s_wave[wave] = x;
-        __syncthreads();
-        int wave_off = 0;
-        for (int w = 0; w < wave; w++) wave_off += s_wave[w];
-        const int carry = s_carry;
-        if (i < n) out[i] = carry + wave_off + x - v;
-        __syncthreads();
-        if (tid == 1023) s_carry = carry + wave_off + x;
-        __syncthreads();
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < kWaves; w++) s_cnt[w][lane] = incl - tot + pre[w];
+        }
     }
-    if (tid == 0) {
-        out[n] = s_carry;
-        if (total_out) *total_out = s_carry;
+    __syncthreads();
+    int mybase = lane < kBuckets ? s_cnt[wave][lane] : 0;
+    for (int base = begin; base < end; base += 64 * kSortChunk) {  // pass B: hand out slots in document order
+        int lv[kSortChunk];
+#pragma unroll
+        for (int u = 0; u < kSortChunk; u++) {
+            const int i = base + u * 64 + lane;
+            lv[u] = i < end ? level[i] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kSortChunk; u++) {
+            const int i = base + u * 64 + lane;
+            const bool in = i < end;
+            int bucket = kBuckets - 1;
+            if (in && lv[u] >= 0 && lv[u] < HDT_MAX_LEVELS) bucket = lv[u];
+            int my_slot = i;
+            unsigned long long remaining = __ballot(in);
+            while (remaining) {
+                const int leader = __ffsll((long long)remaining) - 1;
+                const int bk = __builtin_amdgcn_readlane(bucket, leader);
+                const bool mine = in && bucket == bk;
+                const unsigned long long m = __ballot(mine);
+                const int first = __builtin_amdgcn_readlane(mybase, bk);
+                if (mine) my_slot = first + __popcll(m & lanemask_lt());
+                if (lane == bk) mybase += __popcll(m);
+                remaining &= ~m;
+            }
+            if (in) {
+                if (a.no_sort) my_slot = i;
+                slot[i] = my_slot;
+                kperm[my_slot] = i;
+            }
+        }
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // 2. slot range of every node's children.  Consecutive positions with the same parent and
+    // consecutive slots (the tokens of a sentence, for one) form a run whose minimum and maximum are its
+    // first and last slot: one atomic each per run.
+    for (int base = 0; base < n; base += kThreads) {
+        const int i = base + tid;
+        int p = -1, sl = -1;
+        bool valid = false;
+        if (i < n) {
+            const int l = level[i];
+            p = parent[i];
+            valid = l >= 0 && p >= 0 && p < n;
+            if (valid && level[p] < 0) {  // a parent must be a real position
+                atomicOr(&a.counters[CNT_ERR], 1);
+                valid = false;
+            }
+            if (valid) sl = slot[i];
+        }
+        const int p_prev = __shfl_up(p, 1), s_prev = __shfl_up(sl, 1);
+        const bool v_prev = __shfl_up((int)valid, 1) != 0;
+        const bool head = lane == 0 || !v_prev || p_prev != p || s_prev + 1 != sl;
+        const bool next_head = __shfl_down((int)(head || !valid), 1) != 0;  // lane+1 starts a new run (or is invalid)
+        const bool tail = lane == 63 || next_head;
+        if (valid && head) atomicMin(&cmin[p], sl);
+        if (valid && tail) atomicMax(&cmax[p], sl);
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // 3. candidate key tiles of every query tile: one wave per query tile, a bitmap per wave in LDS
+    const int bm = a.bm, bn = a.bn, tr = a.tr, tc = a.tc, wc = a.wc;
+    uint32_t *wbits = s_bitmaps + (size_t)wave * wc;
+    int32_t *cand_ptr = a.cand_ptr + (size_t)b * (tr + 1);
+    for (int I = wave; I < tr; I += kWaves) {
+        for (int w = lane; w < wc; w += 64) wbits[w] = 0;
+        __builtin_amdgcn_wave_barrier();
+        if (a.force_dense) {
+            if (lane == 0) mark_tiles(wbits, 0, tc - 1);
+        } else {
+            // rows lane and lane + 64 of the tile; all loads of one dependency level are issued together
+            int i2[2], sl2[2], p2[2], lo_c[2], hi_c[2];
+            bool ok[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int rr = lane + 64 * u;
+                i2[u] = I * bm + rr;
+                ok[u] = rr < bm && i2[u] < n && level[min(i2[u], n - 1)] >= 0;
+                const int ii = ok[u] ? i2[u] : 0;
+                sl2[u] = slot[ii];
+                p2[u] = parent[ii];
+                lo_c[u] = cmin[ii];
+                hi_c[u] = cmax[ii];
+            }
+            int sp2[2], lo_s[2], hi_s[2];
+            bool okp[2];
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                okp[u] = ok[u] && p2[u] >= 0 && p2[u] < n;
+                const int pp = okp[u] ? p2[u] : 0;
+                okp[u] = okp[u] && level[pp] >= 0;
+                sp2[u] = slot[pp];
+                lo_s[u] = cmin[pp];
+                hi_s[u] = cmax[pp];
+            }
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                if (!ok[u]) continue;
+                mark_tiles(wbits, sl2[u] / bn, sl2[u] / bn);  // itself
+                if (okp[u]) {
+                    mark_tiles(wbits, sp2[u] / bn, sp2[u] / bn);  // its parent
+                    if (lo_s[u] <= hi_s[u] && lo_s[u] >= 0 && hi_s[u] < n)
+                        mark_tiles(wbits, lo_s[u] / bn, hi_s[u] / bn);  // its siblings: the children of its parent
+                }
+                if (lo_c[u] <= hi_c[u] && lo_c[u] >= 0 && hi_c[u] < n)
+                    mark_tiles(wbits, lo_c[u] / bn, hi_c[u] / bn);  // its children
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        int cnt = 0;
+        uint32_t *out = a.cand + ((size_t)b * tr + I) * wc;
+        for (int w = lane; w < wc; w += 64) {
+            const uint32_t v = wbits[w];
+            out[w] = v;
+            cnt += __popc(v);
+        }
+        cnt = wave_sum(cnt);
+        if (lane == 0) cand_ptr[I] = cnt;
+        __builtin_amdgcn_wave_barrier();
+    }
+    __threadfence_block();
+    __syncthreads();
+
+    // 4. prefix sum, reserve this sample's slice of the candidate arrays, list the candidates
+    const int total = block_scan_inplace(cand_ptr, tr, s_wave);
+    if (tid == 0) s_base = atomicAdd(&a.counters[CNT_CAND], total);
+    __syncthreads();
+    const int gbase = s_base;
+    for (int I = tid; I < tr; I += kThreads) cand_ptr[I] += gbase;
+    if (tid == 0) cand_ptr[tr] = gbase + total;
+    __threadfence_block();
+    __syncthreads();
+    for (int I = wave; I < tr; I += kWaves) {
+        const size_t row = (size_t)b * tr + I;
+        const int cbase = cand_ptr[I];
+        int n_cand = 0;
+        for (int w0 = 0; w0 < wc; w0 += 2) {
+            const int w = w0 + (lane >> 5), bit = lane & 31;
+            const uint32_t word = w < wc ? a.cand[row * wc + w] : 0u;
+            const bool is_cand = (word >> bit) & 1u;
+            const unsigned long long cm = __ballot(is_cand);
+            const int64_t c = (int64_t)cbase + n_cand + __popcll(cm & lanemask_lt());
+            if (is_cand && c < a.capacity) {
+                a.c_row[c] = (int32_t)row;
+                a.q_cols[c] = (w << 5) + bit;
+            }
+            n_cand += __popcll(cm);
+        }
     }
 }
 
-// ---- 4. exact evaluation of every candidate tile ---------------------------------------------
-// 4a: one wave per query tile lists its candidates: c_row[c] = query tile (global), c_col[c] = key tile
-__global__ __launch_bounds__(64) void k_expand_candidates(const uint32_t *__restrict__ cand,
-                                                          const int32_t *__restrict__ cand_ptr, int tr, int wc,
-                                                          int64_t capacity, int32_t *c_row, int32_t *c_col)
-{
-    const int I = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-    const size_t row = (size_t)b * tr + I;
-    const int cbase = cand_ptr[row];
-    int n_cand = 0;
-    for (int w0 = 0; w0 < wc; w0 += 2) {
-        const int w = w0 + (lane >> 5), bit = lane & 31;
-        const uint32_t word = w < wc ? cand[row * wc + w] : 0u;
-        const bool is_cand = (word >> bit) & 1u;
-        const unsigned long long cm = __ballot(is_cand);
-        const int64_t c = (int64_t)cbase + n_cand + __popcll(cm & lanemask_lt());
-        if (is_cand && c < capacity) {
-            c_row[c] = (int32_t)row;
-            c_col[c] = (w << 5) + bit;
-        }
-        n_cand += __popcll(cm);
-    }
-}
-
-// 4b: one workgroup per candidate tile: pair-by-pair bitmap (row-major words for export and the
+// ---- bitmaps: exact evaluation of every candidate tile ------------------------------------------
+// One candidate per workgroup iteration: pair-by-pair bitmap (row-major words for export and the
 // fp32 path, and per 32x32 sub-block the 16 x 64-bit lane masks the MFMA kernels apply to their
 // accumulator registers), pair count and sub-block summary.
 __global__ __launch_bounds__(256) void k_tile_bitmaps(const int32_t *__restrict__ level,
                                                       const int32_t *__restrict__ parent,
                                                       const int32_t *__restrict__ kperm,
                                                       const int32_t *__restrict__ c_row,
-                                                      const int32_t *__restrict__ c_col, int n, int n_slots,
-                                                      int bm, int bn, int tr, uint32_t *bits,
+                                                      const int32_t *__restrict__ c_col,
+                                                      const int32_t *__restrict__ counters, int64_t capacity,
+                                                      int n, int n_slots, int bm, int bn, int tr, uint32_t *bits,
                                                       unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
 {
     __shared__ int s_kpos[128], s_kpar[128];
     __shared__ uint32_t s_words[128 * 4];
     __shared__ int s_cnt;
     __shared__ unsigned int s_any, s_all;
-    const int64_t c = blockIdx.x;
     const int tid = threadIdx.x;
-    const int row = c_row[c], J = c_col[c];
-    const int b = row / tr, I = row - b * tr;
-    const size_t o = (size_t)b * n;
     const int wpr = bn >> 5;
     const int words = bm * wpr;
     const int nsub = (bm >> 5) * wpr;
-    if (tid < bn) {
-        const int s = J * bn + tid;
-        int pos = s < n_slots ? kperm[(size_t)b * n_slots + s] : -1;
-        int par = -1;
-        if (pos >= 0 && pos < n && level[o + pos] >= 0)
-            par = parent[o + pos];
-        else
-            pos = -1;
-        s_kpos[tid] = pos;
-        s_kpar[tid] = par;
-    }
-    if (tid == 0) {
-        s_cnt = 0;
-        s_any = 0;
-        s_all = 0xffffu;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < words; idx += 256) {
-        const int r = idx / wpr, wd = idx - r * wpr;
-        const int i = I * bm + r;
-        uint32_t out = 0;
-        if (i < n && level[o + i] >= 0) {
-            const int pi = parent[o + i];
-            for (int cc = 0; cc < 32; cc++) {
-                const int kj = s_kpos[wd * 32 + cc], kp = s_kpar[wd * 32 + cc];
-                const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kp) || pi == kj || kp == i);
-                out |= (uint32_t)ok << cc;
+    const int64_t total = min((int64_t)counters[CNT_CAND], capacity);
+    for (int64_t c = blockIdx.x; c < total; c += gridDim.x) {
+        const int row = c_row[c], J = c_col[c];
+        const int b = row / tr, I = row - b * tr;
+        const size_t o = (size_t)b * n;
+        __syncthreads();  // the previous candidate's LDS words are no longer read
+        if (tid < bn) {
+            const int s = J * bn + tid;
+            int pos = s < n_slots ? kperm[(size_t)b * n_slots + s] : -1;
+            int par = -1;
+            if (pos >= 0 && pos < n && level[o + pos] >= 0)
+                par = parent[o + pos];
+            else
+                pos = -1;
+            s_kpos[tid] = pos;
+            s_kpar[tid] = par;
+        }
+        if (tid == 0) {
+            s_cnt = 0;
+            s_any = 0;
+            s_all = 0xffffu;
+        }
+        __syncthreads();
+        for (int idx = tid; idx < words; idx += 256) {
+            const int r = idx / wpr, wd = idx - r * wpr;
+            const int i = I * bm + r;
+            uint32_t out = 0;
+            if (i < n && level[o + i] >= 0) {
+                const int pi = parent[o + i];
+                for (int cc = 0; cc < 32; cc++) {
+                    const int kj = s_kpos[wd * 32 + cc], kp = s_kpar[wd * 32 + cc];
+                    const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kp) || pi == kj || kp == i);
+                    out |= (uint32_t)ok << cc;
+                }
             }
+            bits[(size_t)c * words + idx] = out;
+            s_words[idx] = out;
+            const int sub = (r >> 5) * wpr + wd;
+            if (out) {
+                atomicAdd(&s_cnt, __popc(out));
+                atomicOr(&s_any, 1u << sub);
+            }
+            if (out != 0xffffffffu) atomicAnd(&s_all, ~(1u << sub));
         }
-        bits[(size_t)c * words + idx] = out;
-        s_words[idx] = out;
-        const int sub = (r >> 5) * wpr + wd;
-        if (out) {
-            atomicAdd(&s_cnt, __popc(out));
-            atomicOr(&s_any, 1u << sub);
+        __syncthreads();
+        // register-major masks: sub-block sb = rblk*wpr + cblk, accumulator register e, lane l:
+        // row rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
+        for (int idx = tid; idx < nsub * 16; idx += 256) {
+            const int sb = idx >> 4, e = idx & 15;
+            const int rblk = sb / wpr, cblk = sb - rblk * wpr;
+            unsigned long long m = 0;
+            for (int l = 0; l < 64; l++) {
+                const uint32_t w = s_words[(rblk * 32 + (l & 31)) * wpr + cblk];
+                const int bit = (l >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+                m |= (unsigned long long)((w >> bit) & 1u) << l;
+            }
+            bits_rm[(size_t)c * nsub * 16 + idx] = m;
         }
-        if (out != 0xffffffffu) atomicAnd(&s_all, ~(1u << sub));
-    }
-    __syncthreads();
-    // register-major masks: sub-block sb = rblk*wpr + cblk, accumulator register e, lane l:
-    // row rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
-    for (int idx = tid; idx < nsub * 16; idx += 256) {
-        const int sb = idx >> 4, e = idx & 15;
-        const int rblk = sb / wpr, cblk = sb - rblk * wpr;
-        unsigned long long m = 0;
-        for (int l = 0; l < 64; l++) {
-            const uint32_t w = s_words[(rblk * 32 + (l & 31)) * wpr + cblk];
-            const int bit = (l >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-            m |= (unsigned long long)((w >> bit) & 1u) << l;
+        if (tid == 0) {
+            const unsigned int all = s_all & ((1u << nsub) - 1u);
+            c_cnt[c] = s_cnt;
+            c_sub[c] = s_any | (all << 16);
         }
-        bits_rm[(size_t)c * nsub * 16 + idx] = m;
-    }
-    if (tid == 0) {
-        const unsigned int all = s_all & ((1u << nsub) - 1u);
-        c_cnt[c] = s_cnt;
-        c_sub[c] = s_any | (all << 16);
     }
 }
 
-// 4c: surviving tiles per query tile, and the per-sample totals
-__global__ __launch_bounds__(64) void k_row_counts(const int32_t *__restrict__ cand_ptr,
-                                                   const int32_t *__restrict__ c_cnt, int tr, int force_dense,
-                                                   int64_t capacity, int32_t *row_cnt, unsigned long long *stats)
+// ---- device memory: a small cache of buffers of destroyed layouts ------------------------------
+struct CachedBlock {
+    void *ptr;
+    size_t bytes;
+    int device;
+};
+std::mutex g_pool_mutex;
+std::vector<CachedBlock> g_pool;
+constexpr size_t kPoolMaxBlocks = 16;
+constexpr size_t kPoolMaxBytes = (size_t)1 << 30;
+int64_t g_capacity_hint = 0;  // candidates the last build needed
+
+hipError_t pool_alloc(void **out, size_t bytes, size_t *got)
 {
-    const int I = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-    const size_t row = (size_t)b * tr + I;
-    const int c0 = cand_ptr[row], c1 = cand_ptr[row + 1];
-    int alive = 0;
-    long long nnz = 0;
-    for (int c = c0 + lane; c < c1 && c < capacity; c += 64) {
-        const int cnt = c_cnt[c];
-        if (cnt > 0 || force_dense) {
-            alive++;
-            nnz += cnt;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mutex);
+        int best = -1;
+        for (size_t i = 0; i < g_pool.size(); i++)
+            if (g_pool[i].device == dev && g_pool[i].bytes >= bytes && g_pool[i].bytes <= 2 * bytes + (1 << 20) &&
+                (best < 0 || g_pool[i].bytes < g_pool[best].bytes))
+                best = (int)i;
+        if (best >= 0) {
+            *out = g_pool[best].ptr;
+            *got = g_pool[best].bytes;
+            g_pool.erase(g_pool.begin() + best);
+            return hipSuccess;
         }
     }
-    for (int d = 32; d > 0; d >>= 1) {
-        alive += __shfl_xor(alive, d);
-        nnz += __shfl_xor(nnz, d);
-    }
-    if (lane == 0) {
-        row_cnt[row] = alive;
-        if (alive) {
-            atomicAdd(&stats[2 * b], (unsigned long long)alive);
-            atomicAdd(&stats[2 * b + 1], (unsigned long long)nnz);
-        }
-    }
+    *got = bytes;
+    return hipMalloc(out, bytes);
 }
 
-// ---- 5a. lists by query tile -------------------------------------------------------------------
-// One wave per query tile.  Rewrites `cand` in place to hold only the surviving tiles and
-// fills `pre` with the number of surviving tiles in the words before each word.
-__global__ __launch_bounds__(64) void k_compact_rows(uint32_t *cand, const int32_t *__restrict__ cand_ptr,
-                                                     const int32_t *__restrict__ q_rowptr,
-                                                     const int32_t *__restrict__ c_cnt,
-                                                     const uint32_t *__restrict__ c_sub, int tr, int tc, int wc,
-                                                     int force_dense, int64_t capacity, int32_t *pre,
-                                                     int32_t *q_cols, uint32_t *q_sub, int32_t *q_bidx,
-                                                     int32_t *k_cnt)
+void pool_free(void *ptr, size_t bytes, int device)
 {
-    const int I = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
-    const size_t row = (size_t)b * tr + I;
-    const int cbase = cand_ptr[row], tbase = q_rowptr[row];
-    int n_cand = 0, n_alive = 0;
-    for (int w0 = 0; w0 < wc; w0 += 2) {
-        const int w = w0 + (lane >> 5), bit = lane & 31;
-        const uint32_t word = w < wc ? cand[row * wc + w] : 0u;
-        const bool is_cand = (word >> bit) & 1u;
-        const unsigned long long cm = __ballot(is_cand);
-        const int64_t c = (int64_t)cbase + n_cand + __popcll(cm & lanemask_lt());
-        const bool alive = is_cand && c < capacity && (force_dense || c_cnt[c] > 0);
-        const unsigned long long am = __ballot(alive);
-        const int before = n_alive + __popcll(am & lanemask_lt());
-        if (alive) {
-            const int t = tbase + before;
-            const int J = (w << 5) + bit;
-            q_cols[t] = J;
-            q_sub[t] = c_sub[c];
-            q_bidx[t] = (int32_t)c;
-            atomicAdd(&k_cnt[(size_t)b * tc + J], 1);
-        }
-        if (bit == 0 && w < wc) {
-            pre[row * wc + w] = before;
-            cand[row * wc + w] = (uint32_t)(am >> (lane & 32));
-        }
-        n_cand += __popcll(cm);
-        n_alive += __popcll(am);
-    }
-}
-
-// ---- 5b. transpose: lists by key tile, query tiles ascending --------------------------------
-__global__ __launch_bounds__(64) void k_transpose(const uint32_t *__restrict__ alive,
-                                                  const int32_t *__restrict__ pre,
-                                                  const int32_t *__restrict__ q_rowptr,
-                                                  const int32_t *__restrict__ k_colptr, int tr, int tc, int wc,
-                                                  int32_t *k_rows, int32_t *k_tile)
-{
-    const int J = blockIdx.x * 64 + threadIdx.x, b = blockIdx.y;
-    if (J >= tc) return;
-    int e = k_colptr[(size_t)b * tc + J];
-    const int w = J >> 5, bit = J & 31;
-    for (int I = 0; I < tr; I++) {
-        const size_t row = (size_t)b * tr + I;
-        const uint32_t word = alive[row * wc + w];
-        if ((word >> bit) & 1u) {
-            k_rows[e] = I;
-            k_tile[e] = q_rowptr[row] + pre[row * wc + w] + __popc(word & ((1u << bit) - 1u));
-            e++;
+    if (!ptr) return;
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mutex);
+        size_t held = 0;
+        for (auto &b : g_pool) held += b.bytes;
+        if (g_pool.size() < kPoolMaxBlocks && held + bytes <= kPoolMaxBytes) {
+            g_pool.push_back({ptr, bytes, device});
+            return;
         }
     }
+    (void)hipFree(ptr);
 }
 
-// carve `bytes` (rounded up to 256) out of an arena
+// carve buffers (each rounded up to 256 bytes) out of an arena
 struct Carver {
     char *base;
     size_t off = 0;
@@ -452,10 +485,10 @@ struct Carver {
 };
 
 struct Phase1 {
-    int32_t *kperm, *slot, *cmin, *cmax, *cand_cnt, *cand_ptr, *row_cnt, *q_rowptr, *k_cnt, *k_colptr, *pre, *err;
+    int32_t *kperm, *slot, *cmin, *cmax, *cand_ptr, *counters;
     uint32_t *cand;
     int64_t *stats;
-    size_t zero_begin, zero_end;  // byte range that must start at zero
+    size_t zero_begin, zero_end;  // byte range that must start at zero (also what the host reads back)
     size_t bytes;
 };
 
@@ -468,31 +501,72 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int tc, int w
     p.cmin = c.take<int32_t>((size_t)B * n);
     p.cmax = c.take<int32_t>((size_t)B * n);
     p.cand = c.take<uint32_t>((size_t)B * tr * wc);
-    p.pre = c.take<int32_t>((size_t)B * tr * wc);
-    p.cand_cnt = c.take<int32_t>((size_t)B * tr);
-    p.cand_ptr = c.take<int32_t>((size_t)B * tr + 1);
-    p.row_cnt = c.take<int32_t>((size_t)B * tr);
-    p.q_rowptr = c.take<int32_t>((size_t)B * tr + 1);
-    p.k_colptr = c.take<int32_t>((size_t)B * tc + 1);
+    p.cand_ptr = c.take<int32_t>((size_t)B * (tr + 1));
     p.zero_begin = c.off;
-    p.k_cnt = c.take<int32_t>((size_t)B * tc);
+    p.counters = c.take<int32_t>(64);  // 256 bytes, so that stats follows immediately
     p.stats = c.take<int64_t>((size_t)B * 2);
-    p.err = c.take<int32_t>(4);
     p.zero_end = c.off;
+    p.bytes = c.off;
+    return p;
+}
+
+struct Phase2 {
+    int32_t *q_cols, *c_row, *c_cnt;
+    uint32_t *q_sub, *bits;
+    unsigned long long *bits_rm;
+    size_t bytes;
+};
+
+Phase2 carve_phase2(char *base, int64_t cap, int bm, int bn)
+{
+    Carver c{base};
+    Phase2 p;
+    const size_t n = (size_t)cap, words = (size_t)bm * (bn / 32), nsub = (size_t)(bm / 32) * (bn / 32);
+    p.q_cols = c.take<int32_t>(n);
+    p.q_sub = c.take<uint32_t>(n);
+    p.c_row = c.take<int32_t>(n);
+    p.c_cnt = c.take<int32_t>(n);
+    p.bits = c.take<uint32_t>(n * words);
+    p.bits_rm = c.take<unsigned long long>(n * nsub * 16);
     p.bytes = c.off;
     return p;
 }
 
 }  // namespace
 
-extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(const int32_t *d_level, const int32_t *d_parent, int32_t batch,
-                                         int32_t n_pos, const hdt_layout_opts_t *opts, void *stream,
-                                         hdt_layout_t **out)
+void hdt_layout_release(hdt_layout_t *L)
+{
+    pool_free(L->arena, L->arena_bytes, L->device);
+    pool_free(L->arena2, L->arena2_bytes, L->device);
+    L->arena = L->arena2 = nullptr;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_release_cached_memory(void)
+{
+    std::vector<CachedBlock> blocks;
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mutex);
+        blocks.swap(g_pool);
+    }
+    hipError_t e = hipSuccess;
+    for (auto &b : blocks) {
+        hipError_t e2 = hipFree(b.ptr);
+        if (e == hipSuccess) e = e2;
+    }
+    if (e != hipSuccess) return hdt_fail(HDT_ERR_HIP, "hipFree: %s", hipGetErrorString(e));
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(const int32_t *d_level,
+                                                                                 const int32_t *d_parent,
+                                                                                 int32_t batch, int32_t n_pos,
+                                                                                 const hdt_layout_opts_t *opts,
+                                                                                 void *stream, hdt_layout_t **out)
 {
     if (!out) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: out is NULL");
     *out = nullptr;
     if (batch < 0 || n_pos < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: negative size");
-    if (n_pos > (1 << 22)) return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: n_pos %d > 2^22", n_pos);
+    if (n_pos > (1 << 19)) return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: n_pos %d > 2^19", n_pos);
     int bm = 128, bn = 64, force_dense = 0, no_sort = 0;
     if (opts) {
         if (opts->tile_m) bm = opts->tile_m;
@@ -509,9 +583,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     if (!L) return hdt_fail(HDT_ERR_OOM, "hdt_build_layout: host allocation failed");
     L->magic = HDT_LAYOUT_MAGIC;
     L->arena = L->arena2 = nullptr;
-    L->d_stats = nullptr;
-    L->stats_cached = false;
+    L->arena_bytes = L->arena2_bytes = 0;
     L->capacity = 0;
+    L->d_cnt = nullptr;
+    L->force_dense = force_dense;
     L->device_bytes = 0;
     L->device = 0;
     HdtSchedule &s = L->s;
@@ -524,14 +599,12 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     s.tr = empty ? 0 : (n_pos + bm - 1) / bm;
     s.tc = empty ? 0 : (n_pos + bn - 1) / bn;
     s.n_slots = s.tc * bn;
+    L->h_stats.assign((size_t)batch * 2, 0);
     if (empty) {
-        if (batch == 0) s.tr = s.tc = s.n_slots = 0;
-        L->stats_cached = true;
-        L->h_stats.assign((size_t)batch * 2, 0);
         *out = L;
         return HDT_OK;
     }
-    if ((int64_t)batch * s.tr > (1 << 24) || (int64_t)batch * n_pos > (1LL << 30)) {
+    if ((int64_t)batch * n_pos > (1LL << 30)) {
         delete L;
         return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: batch * n_pos too large");
     }
@@ -539,131 +612,109 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     hipStream_t st = (hipStream_t)stream;
     const int B = batch, n = n_pos, tr = s.tr, tc = s.tc, wc = (tc + 31) / 32;
     hdt_status_t status = HDT_OK;
-#define BUILD_TRY(expr)                                                                                  \
-    do {                                                                                                 \
-        hipError_t _e = (expr);                                                                          \
-        if (_e != hipSuccess) {                                                                          \
-            status = hdt_fail(_e == hipErrorOutOfMemory ? HDT_ERR_OOM : HDT_ERR_HIP, "%s: %s", #expr,  \
-                              hipGetErrorString(_e));                                                    \
-            goto fail;                                                                                   \
-        }                                                                                                \
+    (void)hipGetDevice(&L->device);
+#define BUILD_TRY(expr)                                                                                 \
+    do {                                                                                                \
+        hipError_t _e = (expr);                                                                         \
+        if (_e != hipSuccess) {                                                                         \
+            status = hdt_fail(_e == hipErrorOutOfMemory ? HDT_ERR_OOM : HDT_ERR_HIP, "%s: %s", #expr, \
+                              hipGetErrorString(_e));                                                   \
+            goto fail;                                                                                  \
+        }                                                                                               \
     } while (0)
 
     {
-        (void)hipGetDevice(&L->device);
         Phase1 p = carve_phase1(nullptr, B, n, s.n_slots, tr, tc, wc);
-        BUILD_TRY(hipMalloc(&L->arena, p.bytes));
+        BUILD_TRY(pool_alloc(&L->arena, p.bytes, &L->arena_bytes));
         p = carve_phase1((char *)L->arena, B, n, s.n_slots, tr, tc, wc);
-        L->device_bytes = (int64_t)p.bytes;
-        BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
+
+        // capacity of the per-tile arrays: exact for the dense baseline, else a guess
+        int64_t cap = force_dense ? (int64_t)B * tr * tc : (int64_t)B * ((int64_t)tr * 8 + 64);
         {
-            HdtTimer t("hdt_layout_sort", st);
-            hipLaunchKernelGGL(k_sort_by_level, dim3(B), dim3(kSortThreads), 0, st, d_level, d_parent, n, s.n_slots,
-                               no_sort, p.kperm, p.slot, p.cmin, p.cmax, p.err);
+            std::lock_guard<std::mutex> lk(g_pool_mutex);
+            if (!force_dense && g_capacity_hint + g_capacity_hint / 8 > cap) cap = g_capacity_hint + g_capacity_hint / 8;
         }
-        {
-            HdtTimer t("hdt_layout_child_ranges", st);
-            hipLaunchKernelGGL(k_child_ranges, dim3((n + 255) / 256, B), dim3(256), 0, st, d_level, d_parent, p.slot, n,
-                               p.cmin, p.cmax, p.err);
-        }
-        {
-            HdtTimer t("hdt_layout_mark", st);
-            hipLaunchKernelGGL(k_mark_candidates, dim3(tr, B), dim3(128), (size_t)wc * sizeof(uint32_t), st, d_level,
-                               d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, p.cand,
-                               p.cand_cnt);
-        }
-        {
-            HdtTimer t("hdt_layout_scan", st);
-            hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, p.cand_cnt, p.cand_ptr, B * tr, p.err + 1);
-        }
-        BUILD_TRY(hipGetLastError());
-        int32_t h_err[2] = {0, 0};
-        BUILD_TRY(hipMemcpyAsync(h_err, p.err, sizeof(h_err), hipMemcpyDeviceToHost, st));
-        BUILD_TRY(hipStreamSynchronize(st));
-        if (h_err[0]) {
-            status = hdt_fail(HDT_ERR_HIERARCHY,
-                              "hdt_build_layout: level/parent arrays are not a valid hierarchy (level outside "
-                              "[-1, %d), parent outside [-1, n_pos), self-parent, pad with a parent, or pad parent)",
-                              HDT_MAX_LEVELS);
-            goto fail;
-        }
-        const int64_t cap = h_err[1];
-        L->capacity = cap;
-        const size_t words = (size_t)bm * s.wpr;
-        Carver c2{nullptr};
-        for (int pass = 0; pass < 2; pass++) {
-            c2.off = 0;
-            int32_t *q_cols = c2.take<int32_t>((size_t)cap);
-            uint32_t *q_sub = c2.take<uint32_t>((size_t)cap);
-            int32_t *q_bidx = c2.take<int32_t>((size_t)cap);
-            int32_t *c_col = c2.take<int32_t>((size_t)cap);
-            int32_t *c_cnt = c2.take<int32_t>((size_t)cap);
-            uint32_t *c_sub = c2.take<uint32_t>((size_t)cap);
-            int32_t *k_rows = c2.take<int32_t>((size_t)cap);
-            int32_t *k_tile = c2.take<int32_t>((size_t)cap);
-            uint32_t *bits = c2.take<uint32_t>((size_t)cap * words);
-            unsigned long long *bits_rm = c2.take<unsigned long long>((size_t)cap * (bm / 32) * s.wpr * 16);
-            int32_t *c_row = c2.take<int32_t>((size_t)cap);
-            if (pass == 0) {
-                if (cap > 0) BUILD_TRY(hipMalloc(&L->arena2, c2.off));
-                c2.base = (char *)L->arena2;
-                L->device_bytes += cap > 0 ? (int64_t)c2.off : 0;
-                continue;
+        cap = cap > (int64_t)B * tr * tc ? (int64_t)B * tr * tc : cap;
+        std::vector<char> host(p.zero_end - p.zero_begin), host_tiles;
+        for (int attempt = 0; attempt < 2; attempt++) {
+            if (cap >= (1LL << 31)) {
+                status = hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: %lld candidate tiles", (long long)cap);
+                goto fail;
             }
-            s.kperm = p.kperm;
-            s.q_rowptr = p.q_rowptr;
-            s.q_cols = q_cols;
-            s.q_sub = q_sub;
-            s.q_bidx = q_bidx;
-            s.bits = bits;
-            s.bits_rm = bits_rm;
-            s.k_colptr = p.k_colptr;
-            s.k_rows = k_rows;
-            s.k_tile = k_tile;
-            L->d_stats = p.stats;
+            Phase2 q = carve_phase2(nullptr, cap, bm, bn);
+            BUILD_TRY(pool_alloc(&L->arena2, q.bytes, &L->arena2_bytes));
+            q = carve_phase2((char *)L->arena2, cap, bm, bn);
+            BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
             {
-                HdtTimer t("hdt_layout_expand", st);
-                hipLaunchKernelGGL(k_expand_candidates, dim3(tr, B), dim3(64), 0, st, p.cand, p.cand_ptr, tr, wc, cap,
-                                   c_row, c_col);
+                FrontArgs fa{d_level, d_parent, n, s.n_slots, bm, bn, tr, tc, wc, force_dense, no_sort, cap,
+                             p.kperm, p.slot, p.cmin, p.cmax, p.cand, p.cand_ptr, q.c_row, q.q_cols, p.counters};
+                HdtTimer t("hdt_layout_front", st);
+                hipLaunchKernelGGL(k_layout_front, dim3(B), dim3(kThreads), (size_t)kWaves * wc * sizeof(uint32_t), st,
+                                   fa);
             }
-            if (cap > 0) {
+            {
+                const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
-                hipLaunchKernelGGL(k_tile_bitmaps, dim3((unsigned)cap), dim3(256), 0, st, d_level, d_parent, p.kperm,
-                                   c_row, c_col, n, s.n_slots, bm, bn, tr, bits, bits_rm, c_cnt, c_sub);
-            }
-            {
-                HdtTimer t("hdt_layout_row_counts", st);
-                hipLaunchKernelGGL(k_row_counts, dim3(tr, B), dim3(64), 0, st, p.cand_ptr, c_cnt, tr, force_dense, cap,
-                                   p.row_cnt, (unsigned long long *)p.stats);
-            }
-            {
-                HdtTimer t("hdt_layout_scan", st);
-                hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, p.row_cnt, p.q_rowptr, B * tr,
-                                   (int32_t *)nullptr);
-            }
-            {
-                HdtTimer t("hdt_layout_compact", st);
-                hipLaunchKernelGGL(k_compact_rows, dim3(tr, B), dim3(64), 0, st, p.cand, p.cand_ptr, p.q_rowptr, c_cnt,
-                                   c_sub, tr, tc, wc, force_dense, cap, p.pre, q_cols, q_sub, q_bidx, p.k_cnt);
-            }
-            {
-                HdtTimer t("hdt_layout_scan", st);
-                hipLaunchKernelGGL(k_exclusive_scan, dim3(1), dim3(1024), 0, st, p.k_cnt, p.k_colptr, B * tc,
-                                   (int32_t *)nullptr);
-            }
-            {
-                HdtTimer t("hdt_layout_transpose", st);
-                hipLaunchKernelGGL(k_transpose, dim3((tc + 63) / 64, B), dim3(64), 0, st, p.cand, p.pre, p.q_rowptr,
-                                   p.k_colptr, tr, tc, wc, k_rows, k_tile);
+                hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(256), 0, st, d_level, d_parent, p.kperm, q.c_row,
+                                   q.q_cols, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits, q.bits_rm, q.c_cnt,
+                                   q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
+            BUILD_TRY(hipMemcpyAsync(host.data(), (char *)L->arena + p.zero_begin, host.size(), hipMemcpyDeviceToHost,
+                                     st));
+            // query tile and pair count of every candidate (adjacent arrays): the per-sample totals are
+            // summed on the host, which is cheaper than thousands of atomics on a handful of addresses
+            const size_t tail_bytes = (size_t)((char *)q.c_cnt - (char *)q.c_row) + (size_t)cap * sizeof(int32_t);
+            host_tiles.resize(tail_bytes);
+            BUILD_TRY(hipMemcpyAsync(host_tiles.data(), q.c_row, tail_bytes, hipMemcpyDeviceToHost, st));
+            BUILD_TRY(hipStreamSynchronize(st));
+            const int32_t *cnt = reinterpret_cast<const int32_t *>(host.data());
+            if (cnt[CNT_ERR]) {
+                status = hdt_fail(HDT_ERR_HIERARCHY,
+                                  "hdt_build_layout: level/parent arrays are not a valid hierarchy (level outside "
+                                  "[-1, %d), parent outside [-1, n_pos), self-parent, pad with a parent, or pad parent)",
+                                  HDT_MAX_LEVELS);
+                goto fail;
+            }
+            const int64_t need = cnt[CNT_CAND];
+            {
+                std::lock_guard<std::mutex> lk(g_pool_mutex);
+                if (!force_dense) g_capacity_hint = need;
+            }
+            if (need <= cap) {
+                const int32_t *h_row = reinterpret_cast<const int32_t *>(host_tiles.data());
+                const int32_t *h_cnt =
+                    reinterpret_cast<const int32_t *>(host_tiles.data() + ((char *)q.c_cnt - (char *)q.c_row));
+                for (int64_t c = 0; c < need; c++) {
+                    const int b = h_row[c] / tr;
+                    if (b < 0 || b >= B) continue;
+                    if (h_cnt[c] > 0 || force_dense) {
+                        L->h_stats[2 * b] += 1;
+                        L->h_stats[2 * b + 1] += h_cnt[c];
+                    }
+                }
+                L->capacity = cap;
+                s.kperm = p.kperm;
+                s.q_rowptr = p.cand_ptr;
+                s.q_cols = q.q_cols;
+                s.q_sub = q.q_sub;
+                s.bits = q.bits;
+                s.bits_rm = q.bits_rm;
+                L->d_cnt = q.c_cnt;
+                L->force_dense = force_dense;
+                L->device_bytes = (int64_t)(L->arena_bytes + L->arena2_bytes);
+                *out = L;
+                return HDT_OK;
+            }
+            // the guess was too small: once more with the exact size
+            pool_free(L->arena2, L->arena2_bytes, L->device);
+            L->arena2 = nullptr;
+            cap = need;
         }
+        status = hdt_fail(HDT_ERR_HIP, "hdt_build_layout: candidate count changed between two passes");
     }
-    *out = L;
-    return HDT_OK;
 fail:
-    if (L->arena) (void)hipFree(L->arena);
-    if (L->arena2) (void)hipFree(L->arena2);
+    hdt_layout_release(L);
     L->magic = 0;
     delete L;
     return status;
