@@ -47,6 +47,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events (for external profilers)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy 3 times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (batch and heads shard without any exchange; "
@@ -94,6 +96,14 @@ def main() -> int:
                              dk=outs["dk"], dv=outs["dv"], workspace=workspace)
         lay.destroy()   # buffers go back to the library's cache; the next build reuses them in stream order
 
+    if args.calibrate_copy:
+        # a copy kernel of known size: 256 MiB read + 256 MiB written per launch
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -135,8 +145,17 @@ def main() -> int:
         units = B * H * N
         alg_bytes = algorithmic_bytes_per_unit(dom, D) * units
         achieved = alg_bytes / (attn[dom]["avg_us"] * 1e-6) / 1e9
+        # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a copy
+        # kernel of known size); counters cannot be read from inside this process, so the figure of the
+        # last profiled run of this workload is kept under profiles/
+        traffic = None
+        try:
+            with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+                traffic = json.load(f).get(f"config{args.config}", {}).get(dom)
+        except (OSError, ValueError):
+            pass
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(attn[dom]["avg_us"], 2)}
 
     out = {
