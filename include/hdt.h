@@ -94,10 +94,13 @@ typedef struct {
  *   per surviving tile: its column, a bitmap of the allowed pairs and a summary of its 32x32
  *            sub-blocks; lists by query tile (columns ascending) and the transpose by key tile.
  *
- * Enqueues kernels on `stream` and synchronises the stream once, at the end (to read back the tile
- * counts and to report hierarchy errors).  Device memory for the layout comes from a cache of buffers
- * of destroyed layouts (hipMalloc when the cache has nothing that fits).  batch == 0 or n_pos == 0
- * gives an empty layout on which the attention calls are no-ops.
+ * Enqueues kernels on `stream` and returns as soon as the first of them has reported, through pinned
+ * host memory, that the hierarchy is valid and how many tiles the lists need: the call waits for that
+ * kernel (and for whatever was enqueued on `stream` before it), not for the stream.  The rest of the
+ * build may still be running when the call returns; work enqueued on the same stream afterwards is
+ * ordered behind it, work on other streams must wait for `stream` first.  Device memory for the
+ * layout comes from a cache of buffers of destroyed layouts (hipMalloc when the cache has nothing
+ * that fits).  batch == 0 or n_pos == 0 gives an empty layout on which the attention calls are no-ops.
  *
  * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (n_pos > 2^19),
  * HDT_ERR_UNSUPPORTED (tile shape), HDT_ERR_HIERARCHY (level outside [-1, HDT_MAX_LEVELS),
@@ -107,7 +110,9 @@ typedef struct {
 hdt_status_t hdt_build_layout(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
                               const hdt_layout_opts_t *opts, void *stream, hdt_layout_t **out);
 
-/* Sizes of a layout (host struct).  Cheap; no device work. */
+/* Sizes of a layout (host struct).  n_tiles and nnz are read back from the device by the first call
+ * of hdt_layout_info / hdt_layout_sample_info / hdt_layout_export on a layout, which synchronises
+ * the device; later calls are host-only. */
 hdt_status_t hdt_layout_info(const hdt_layout_t *layout, hdt_layout_info_t *h_info);
 
 /* Surviving tiles and allowed pairs of one sample. */

@@ -112,8 +112,9 @@ def _ptr(t):
 class Layout:
     """Owns an ``hdt_layout_t``."""
 
-    def __init__(self, handle: int):
+    def __init__(self, handle: int, batch: int, n_pos: int):
         self._h = ctypes.c_void_p(handle)
+        self.batch, self.n_pos = int(batch), int(n_pos)
 
     @property
     def handle(self):
@@ -174,7 +175,7 @@ def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dens
     B, N = level.shape
     _check(load_library().hdt_build_layout(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,
                                            ctypes.byref(opts), _stream_ptr(stream), ctypes.byref(h)))
-    return Layout(h.value)
+    return Layout(h.value, B, N)
 
 
 def _dtype_code(t):
@@ -199,8 +200,7 @@ def hdt_attn_fwd(layout: Layout, q, k, v, softmax_scale: float, o=None, lse=None
     import torch
     _check_tensors((q, k, v), q.shape)
     B, H, N, D = q.shape
-    inf = layout.info()
-    if (B, N) != (inf["batch"], inf["n_pos"]):
+    if (B, N) != (layout.batch, layout.n_pos):
         raise ValueError("q shape does not match the layout")
     if o is None:
         o = torch.empty_like(q)
@@ -221,8 +221,7 @@ def hdt_attn_bwd(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq=
     import torch
     _check_tensors((q, k, v, o, d_o), q.shape)
     B, H, N, D = q.shape
-    inf = layout.info()
-    if (B, N) != (inf["batch"], inf["n_pos"]):
+    if (B, N) != (layout.batch, layout.n_pos):
         raise ValueError("q shape does not match the layout")
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(q) if dk is None else dk

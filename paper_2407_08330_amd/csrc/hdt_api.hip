@@ -126,6 +126,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(c
 {
     if (!hdt_layout_ok(layout) || !info) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_info: NULL or invalid layout");
     const hdt_layout_t *l = layout;
+    if (hdt_status_t st = hdt_layout_stats(l)) return st;
     info->batch = l->s.batch;
     info->n_pos = l->s.n_pos;
     info->tile_m = l->s.bm;
@@ -149,6 +150,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_sample
     if (sample < 0 || sample >= layout->s.batch)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_sample_info: sample %d outside [0, %d)", sample, layout->s.batch);
     const hdt_layout_t *l = layout;
+    if (hdt_status_t st = hdt_layout_stats(l)) return st;
     if (n_tiles) *n_tiles = l->h_stats[2 * sample];
     if (nnz) *nnz = l->h_stats[2 * sample + 1];
     return HDT_OK;
@@ -162,6 +164,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
     const HdtSchedule &s = layout->s;
     if (sample < 0 || sample >= s.batch)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: sample %d outside [0, %d)", sample, s.batch);
+    if (hdt_status_t st = hdt_layout_stats(layout)) return st;
     const int64_t T = layout->h_stats[2 * (size_t)sample];
     const bool want_tiles = q_cols || q_sub || bits || k_rows || k_tile;
     if (want_tiles && tile_capacity < T)

@@ -44,7 +44,12 @@ struct hdt_layout {
     void *arena2;        // per-tile arrays
     size_t arena_bytes, arena2_bytes;
     const int32_t *d_cnt;          // [entries] allowed pairs of each entry (device)
-    std::vector<int64_t> h_stats;  // [batch][2] = (surviving tiles, allowed pairs) per sample
+    const int32_t *d_row;          // [entries] query tile (global numbering b * tr + I) of each entry (device)
+    int64_t n_entries;             // list entries of all samples
+    // [batch][2] = (surviving tiles, allowed pairs) per sample; read back from the device by the first
+    // query that needs them (hdt_layout_stats), not by the build
+    mutable std::vector<int64_t> h_stats;
+    mutable bool stats_ready;
 };
 
 // --- error reporting (hdt_api.hip) ---
@@ -58,6 +63,7 @@ hdt_status_t hdt_fail(hdt_status_t st, const char *fmt, ...);
     } while (0)
 
 bool hdt_layout_ok(const hdt_layout_t *l);
+hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (waits for the device) (hdt_layout.hip)
 void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
 
 // --- per-kernel timing (hdt_api.hip) ---

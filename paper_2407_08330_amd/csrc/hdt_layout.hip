@@ -22,12 +22,16 @@
 //      it is not counted as a tile and hdt_layout_export leaves it out.
 //
 // The per-tile arrays are sized before the number of candidates is known (a heuristic, raised by
-// what earlier builds needed); both kernels check the capacity, the host reads the counters back
-// once at the end and repeats the build with the exact size in the rare case the guess was too small.
+// what earlier builds needed); both kernels check the capacity.  The front kernel reports the count
+// (and whether the hierarchy was valid) through one word of pinned host memory as soon as it is
+// known; the host waits for that word only, not for the stream, and repeats the build with the exact
+// size in the rare case the guess was too small.
 // Device memory comes from a small cache of earlier layouts' buffers.
 #include <limits.h>
 #include <string.h>
 
+#include <algorithm>
+#include <chrono>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -41,7 +45,14 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kBuckets = HDT_MAX_LEVELS + 1;  // levels 0..31, pads in the last bucket
 constexpr int kSortChunk = 8;                 // positions per lane loaded ahead of the ballot loops
 
-enum { CNT_ERR = 0, CNT_CAND = 1, CNT_TILES = 2, CNT_PAD = 3 };
+enum { CNT_ERR = 0, CNT_CAND = 1, CNT_TILES = 2, CNT_ARRIVED = 3 };
+
+// What the front kernel reports to the host through pinned host memory: one 64-bit word
+// [63:40] ticket of the build, [39] hierarchy error, [31:0] candidate tiles needed.
+__host__ __device__ inline unsigned long long report_word(uint32_t ticket, int err, uint32_t need)
+{
+    return ((unsigned long long)(ticket & 0xffffffu) << 40) | ((unsigned long long)(err != 0) << 39) | need;
+}
 
 __device__ __forceinline__ unsigned long long lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
@@ -99,6 +110,8 @@ struct FrontArgs {
     int32_t *cand_ptr;  // [B][tr+1]: becomes the lists' row pointer
     int32_t *c_row, *q_cols;
     int32_t *counters;
+    unsigned long long *report;  // pinned host memory, written once by the last workgroup to get there
+    uint32_t ticket;
 };
 
 // ---- front: sort, child ranges, candidates ---------------------------------------------------
@@ -304,12 +317,24 @@ __global__ __launch_bounds__(kThreads) void k_layout_front(FrontArgs a)
         if (lane == 0) cand_ptr[I] = cnt;
         __builtin_amdgcn_wave_barrier();
     }
-    __threadfence_block();
+    __threadfence();  // device scope: this workgroup's error flags have reached the counters
     __syncthreads();
 
     // 4. prefix sum, reserve this sample's slice of the candidate arrays, list the candidates
     const int total = block_scan_inplace(cand_ptr, tr, s_wave);
-    if (tid == 0) s_base = atomicAdd(&a.counters[CNT_CAND], total);
+    if (tid == 0) {
+        s_base = atomicAdd(&a.counters[CNT_CAND], total);
+        // the last workgroup to get here knows the final counters: it tells the host, which is waiting
+        // for exactly this word, while the lists and the bitmaps are still being written
+        __threadfence();
+        if (atomicAdd(&a.counters[CNT_ARRIVED], 1) == (int)gridDim.x - 1) {
+            __threadfence();
+            const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int need = __hip_atomic_load(&a.counters[CNT_CAND], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)need), __ATOMIC_RELEASE,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
     __syncthreads();
     const int gbase = s_base;
     for (int I = tid; I < tr; I += kThreads) cand_ptr[I] += gbase;
@@ -532,6 +557,44 @@ Phase2 carve_phase2(char *base, int64_t cap, int bm, int bn)
     return p;
 }
 
+// ---- the build's report from the device: 64 words of pinned host memory, one per build in flight ----
+constexpr int kReportSlots = 64;
+unsigned long long *g_reports = nullptr;  // never freed: a kernel may still write to it at exit
+uint32_t g_ticket = 0;
+
+unsigned long long *report_slot(uint32_t *ticket)
+{
+    std::lock_guard<std::mutex> lk(g_pool_mutex);
+    if (!g_reports) {
+        void *ptr = nullptr;
+        if (hipHostMalloc(&ptr, kReportSlots * 64, hipHostMallocPortable | hipHostMallocMapped) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        memset(ptr, 0, kReportSlots * 64);
+        g_reports = static_cast<unsigned long long *>(ptr);
+    }
+    g_ticket = (g_ticket + 1) & 0xffffffu;
+    if (g_ticket == 0) g_ticket = 1;
+    *ticket = g_ticket;
+    return g_reports + (size_t)(g_ticket % kReportSlots) * 8;  // one 64-byte line per slot
+}
+
+// polls the word until it carries this build's ticket; false after 10 s without it
+bool wait_for_report(const unsigned long long *slot, uint32_t ticket, unsigned long long *word)
+{
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint64_t spins = 0;; spins++) {
+        const unsigned long long w = __atomic_load_n(slot, __ATOMIC_ACQUIRE);
+        if ((uint32_t)(w >> 40) == ticket) {
+            *word = w;
+            return true;
+        }
+        if ((spins & 0x3ff) == 0x3ff && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(10)) return false;
+        __builtin_ia32_pause();
+    }
+}
+
 }  // namespace
 
 void hdt_layout_release(hdt_layout_t *L)
@@ -539,6 +602,38 @@ void hdt_layout_release(hdt_layout_t *L)
     pool_free(L->arena, L->arena_bytes, L->device);
     pool_free(L->arena2, L->arena2_bytes, L->device);
     L->arena = L->arena2 = nullptr;
+}
+
+// Surviving tiles and allowed pairs per sample, summed on the host from the query tile and the pair
+// count of every list entry (two adjacent device arrays): cheaper than thousands of device atomics on
+// a handful of addresses, and only paid by callers that ask.
+hdt_status_t hdt_layout_stats(const hdt_layout_t *L)
+{
+    static std::mutex stats_mutex;
+    std::lock_guard<std::mutex> lk(stats_mutex);
+    if (L->stats_ready) return HDT_OK;
+    const int64_t E = L->n_entries;
+    std::vector<int32_t> row((size_t)E), cnt((size_t)E);
+    int dev = 0;
+    HDT_HIP_TRY(hipGetDevice(&dev));
+    if (dev != L->device) HDT_HIP_TRY(hipSetDevice(L->device));
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess && E > 0) e = hipMemcpy(row.data(), L->d_row, sizeof(int32_t) * E, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && E > 0) e = hipMemcpy(cnt.data(), L->d_cnt, sizeof(int32_t) * E, hipMemcpyDeviceToHost);
+    if (dev != L->device) (void)hipSetDevice(dev);
+    if (e != hipSuccess) return hdt_fail(HDT_ERR_HIP, "hdt_layout_stats: %s", hipGetErrorString(e));
+    std::fill(L->h_stats.begin(), L->h_stats.end(), 0);
+    const int B = L->s.batch, tr = L->s.tr;
+    for (int64_t c = 0; c < E; c++) {
+        const int b = row[c] / tr;
+        if (b < 0 || b >= B) continue;
+        if (cnt[c] > 0 || L->force_dense) {
+            L->h_stats[2 * b] += 1;
+            L->h_stats[2 * b + 1] += cnt[c];
+        }
+    }
+    L->stats_ready = true;
+    return HDT_OK;
 }
 
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_release_cached_memory(void)
@@ -586,6 +681,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     L->arena_bytes = L->arena2_bytes = 0;
     L->capacity = 0;
     L->d_cnt = nullptr;
+    L->d_row = nullptr;
+    L->n_entries = 0;
+    L->stats_ready = false;
     L->force_dense = force_dense;
     L->device_bytes = 0;
     L->device = 0;
@@ -601,10 +699,11 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     s.n_slots = s.tc * bn;
     L->h_stats.assign((size_t)batch * 2, 0);
     if (empty) {
+        L->stats_ready = true;
         *out = L;
         return HDT_OK;
     }
-    if ((int64_t)batch * n_pos > (1LL << 30)) {
+    if ((int64_t)batch * n_pos > (1LL << 30) || (int64_t)batch * s.tr * s.tc >= (1LL << 31)) {
         delete L;
         return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: batch * n_pos too large");
     }
@@ -635,7 +734,6 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
             if (!force_dense && g_capacity_hint + g_capacity_hint / 8 > cap) cap = g_capacity_hint + g_capacity_hint / 8;
         }
         cap = cap > (int64_t)B * tr * tc ? (int64_t)B * tr * tc : cap;
-        std::vector<char> host(p.zero_end - p.zero_begin), host_tiles;
         for (int attempt = 0; attempt < 2; attempt++) {
             if (cap >= (1LL << 31)) {
                 status = hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: %lld candidate tiles", (long long)cap);
@@ -644,10 +742,17 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
             Phase2 q = carve_phase2(nullptr, cap, bm, bn);
             BUILD_TRY(pool_alloc(&L->arena2, q.bytes, &L->arena2_bytes));
             q = carve_phase2((char *)L->arena2, cap, bm, bn);
+            uint32_t ticket = 0;
+            unsigned long long *report = report_slot(&ticket);
+            if (!report) {
+                status = hdt_fail(HDT_ERR_OOM, "hdt_build_layout: no pinned host memory for the build report");
+                goto fail;
+            }
             BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
             {
                 FrontArgs fa{d_level, d_parent, n, s.n_slots, bm, bn, tr, tc, wc, force_dense, no_sort, cap,
-                             p.kperm, p.slot, p.cmin, p.cmax, p.cand, p.cand_ptr, q.c_row, q.q_cols, p.counters};
+                             p.kperm, p.slot, p.cmin, p.cmax, p.cand, p.cand_ptr, q.c_row, q.q_cols, p.counters,
+                             report, ticket};
                 HdtTimer t("hdt_layout_front", st);
                 hipLaunchKernelGGL(k_layout_front, dim3(B), dim3(kThreads), (size_t)kWaves * wc * sizeof(uint32_t), st,
                                    fa);
@@ -660,40 +765,34 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                                    q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
-            BUILD_TRY(hipMemcpyAsync(host.data(), (char *)L->arena + p.zero_begin, host.size(), hipMemcpyDeviceToHost,
-                                     st));
-            // query tile and pair count of every candidate (adjacent arrays): the per-sample totals are
-            // summed on the host, which is cheaper than thousands of atomics on a handful of addresses
-            const size_t tail_bytes = (size_t)((char *)q.c_cnt - (char *)q.c_row) + (size_t)cap * sizeof(int32_t);
-            host_tiles.resize(tail_bytes);
-            BUILD_TRY(hipMemcpyAsync(host_tiles.data(), q.c_row, tail_bytes, hipMemcpyDeviceToHost, st));
-            BUILD_TRY(hipStreamSynchronize(st));
-            const int32_t *cnt = reinterpret_cast<const int32_t *>(host.data());
-            if (cnt[CNT_ERR]) {
+            // The host needs two facts before it can hand the layout out: whether the hierarchy was valid and
+            // whether the per-tile arrays were large enough.  The front kernel knows both before it writes
+            // the lists; it stores them into pinned host memory and the host polls that word instead of
+            // draining the stream, so the bitmap kernel and whatever the caller enqueues next keep the GPU busy.
+            unsigned long long word = 0;
+            if (!wait_for_report(report, ticket, &word)) {
+                // no word within the time limit: drain the stream and read the counters the slow way
+                int32_t cnt[4] = {0, 0, 0, 0};
+                BUILD_TRY(hipStreamSynchronize(st));
+                BUILD_TRY(hipMemcpy(cnt, p.counters, sizeof(cnt), hipMemcpyDeviceToHost));
+                word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);
+            }
+            if ((word >> 39) & 1u) {
+                BUILD_TRY(hipStreamSynchronize(st));  // the bitmap kernel still reads the arenas
                 status = hdt_fail(HDT_ERR_HIERARCHY,
                                   "hdt_build_layout: level/parent arrays are not a valid hierarchy (level outside "
                                   "[-1, %d), parent outside [-1, n_pos), self-parent, pad with a parent, or pad parent)",
                                   HDT_MAX_LEVELS);
                 goto fail;
             }
-            const int64_t need = cnt[CNT_CAND];
+            const int64_t need = (int64_t)(word & 0xffffffffu);
             {
                 std::lock_guard<std::mutex> lk(g_pool_mutex);
                 if (!force_dense) g_capacity_hint = need;
             }
             if (need <= cap) {
-                const int32_t *h_row = reinterpret_cast<const int32_t *>(host_tiles.data());
-                const int32_t *h_cnt =
-                    reinterpret_cast<const int32_t *>(host_tiles.data() + ((char *)q.c_cnt - (char *)q.c_row));
-                for (int64_t c = 0; c < need; c++) {
-                    const int b = h_row[c] / tr;
-                    if (b < 0 || b >= B) continue;
-                    if (h_cnt[c] > 0 || force_dense) {
-                        L->h_stats[2 * b] += 1;
-                        L->h_stats[2 * b + 1] += h_cnt[c];
-                    }
-                }
                 L->capacity = cap;
+                L->n_entries = need;
                 s.kperm = p.kperm;
                 s.q_rowptr = p.cand_ptr;
                 s.q_cols = q.q_cols;
@@ -701,11 +800,13 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 s.bits = q.bits;
                 s.bits_rm = q.bits_rm;
                 L->d_cnt = q.c_cnt;
+                L->d_row = q.c_row;
                 L->force_dense = force_dense;
                 L->device_bytes = (int64_t)(L->arena_bytes + L->arena2_bytes);
                 *out = L;
                 return HDT_OK;
             }
+            BUILD_TRY(hipStreamSynchronize(st));  // the bitmap kernel still writes the arrays about to be replaced
             // the guess was too small: once more with the exact size
             pool_free(L->arena2, L->arena2_bytes, L->device);
             L->arena2 = nullptr;
