@@ -176,22 +176,23 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
                               hipMemcpyDeviceToHost));
     // the device lists hold every candidate tile; the exported schedule keeps those with an allowed pair
     // (all of them for a dense layout) and is numbered from 0
-    std::vector<int32_t> rp((size_t)s.tr + 1, 0);
+    std::vector<int32_t> rg((size_t)s.tr * 2, 0);
     if (s.tr > 0)
-        HDT_HIP_TRY(hipMemcpy(rp.data(), s.q_rowptr + (size_t)sample * (s.tr + 1), sizeof(int32_t) * (s.tr + 1),
+        HDT_HIP_TRY(hipMemcpy(rg.data(), s.q_range + (size_t)sample * s.tr * 2, sizeof(int32_t) * s.tr * 2,
                               hipMemcpyDeviceToHost));
-    const int32_t base = rp[0];
-    const int64_t E = (int64_t)rp[s.tr] - base;  // entries of this sample
+    const int64_t E = layout->n_entries;  // entries of all samples (a query tile's entries are contiguous)
     std::vector<int32_t> cols((size_t)E), cnt((size_t)E);
     std::vector<uint32_t> sub((size_t)E);
     if (E > 0) {
-        HDT_HIP_TRY(hipMemcpy(cols.data(), s.q_cols + base, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
-        HDT_HIP_TRY(hipMemcpy(cnt.data(), layout->d_cnt + base, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
-        HDT_HIP_TRY(hipMemcpy(sub.data(), s.q_sub + base, sizeof(uint32_t) * E, hipMemcpyDeviceToHost));
+        HDT_HIP_TRY(hipMemcpy(cols.data(), s.q_cols, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
+        HDT_HIP_TRY(hipMemcpy(cnt.data(), layout->d_cnt, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
+        HDT_HIP_TRY(hipMemcpy(sub.data(), s.q_sub, sizeof(uint32_t) * E, hipMemcpyDeviceToHost));
     }
     std::vector<int32_t> new_rp((size_t)s.tr + 1, 0), keep_col, keep_row, keep_entry;
     for (int I = 0; I < s.tr; I++) {
-        for (int32_t e = rp[I] - base; e < rp[I + 1] - base; e++)
+        if (rg[2 * I] < 0 || rg[2 * I + 1] < rg[2 * I] || rg[2 * I + 1] > E)
+            return hdt_fail(HDT_ERR_HIP, "hdt_layout_export: corrupt list range of query tile %d", I);
+        for (int32_t e = rg[2 * I]; e < rg[2 * I + 1]; e++)
             if (cnt[e] > 0 || layout->force_dense) {
                 keep_col.push_back(cols[e]);
                 keep_row.push_back(I);
@@ -208,7 +209,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
         if (q_cols) q_cols[t] = keep_col[t];
         if (q_sub) q_sub[t] = sub[keep_entry[t]];
         if (bits)
-            HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + ((size_t)base + keep_entry[t]) * words,
+            HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + (size_t)keep_entry[t] * words,
                                   sizeof(uint32_t) * words, hipMemcpyDeviceToHost));
     }
     // transpose by key tile (query tiles ascending): the kernels do not need it (the mask is symmetric,

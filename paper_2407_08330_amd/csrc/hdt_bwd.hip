@@ -66,9 +66,9 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     const size_t base = (size_t)bh * s.n_pos * D;
     const float scale_log2 = scale * LOG2E;
 
-    const size_t row = (size_t)b * (s.tr + 1) + I;
-    const cptr_i32 rowptr = as_const(s.q_rowptr);
-    const int t0 = rowptr[row], n = rowptr[row + 1] - t0;
+    const size_t row = (size_t)b * s.tr + I;
+    const cptr_i32 range = as_const(s.q_range);
+    const int t0 = range[2 * row], n = range[2 * row + 1] - t0;
     const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
 
@@ -205,9 +205,9 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     const size_t base = (size_t)bh * s.n_pos * D;
     const float scale_log2 = scale * LOG2E;
 
-    const size_t row = (size_t)b * (s.tr + 1) + I;
-    const cptr_i32 rowptr = as_const(s.q_rowptr);
-    const int t0 = rowptr[row], n = rowptr[row + 1] - t0;
+    const size_t row = (size_t)b * s.tr + I;
+    const cptr_i32 range = as_const(s.q_range);
+    const int t0 = range[2 * row], n = range[2 * row + 1] - t0;
     const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
 

@@ -22,8 +22,8 @@ __global__ __launch_bounds__(128) void k_fwd_f32(HdtSchedule s, const float *__r
     float acc[D];
     for (int c = 0; c < D; c++) acc[c] = 0.f;
     float m = -INFINITY, l = 0.f;
-    const size_t row = (size_t)b * (s.tr + 1) + I;
-    for (int t = s.q_rowptr[row]; t < s.q_rowptr[row + 1]; t++) {
+    const size_t row = (size_t)b * s.tr + I;
+    for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
         const int J = s.q_cols[t];
         const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
@@ -70,8 +70,8 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     const float li = lse[(size_t)bh * s.n_pos + i];
     float acc[D];
     for (int c = 0; c < D; c++) acc[c] = 0.f;
-    const size_t row = (size_t)b * (s.tr + 1) + I;
-    for (int t = s.q_rowptr[row]; t < s.q_rowptr[row + 1]; t++) {
+    const size_t row = (size_t)b * s.tr + I;
+    for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
         const int J = s.q_cols[t];
         const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
@@ -113,8 +113,8 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
     const float *vj = v + base + (size_t)j * D;
     float ak[D], av[D];
     for (int e = 0; e < D; e++) ak[e] = av[e] = 0.f;
-    const size_t row = (size_t)b * (s.tr + 1) + I;
-    for (int t = s.q_rowptr[row]; t < s.q_rowptr[row + 1]; t++) {
+    const size_t row = (size_t)b * s.tr + I;
+    for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
         const int J = s.q_cols[t];
         const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {

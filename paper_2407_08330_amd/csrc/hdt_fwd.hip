@@ -56,9 +56,9 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     const size_t base = (size_t)bh * s.n_pos * D;
 
-    const size_t row = (size_t)b * (s.tr + 1) + I;
-    const cptr_i32 rowptr = as_const(s.q_rowptr);
-    const int t0 = rowptr[row], n = rowptr[row + 1] - t0;
+    const size_t row = (size_t)b * s.tr + I;
+    const cptr_i32 range = as_const(s.q_range);
+    const int t0 = range[2 * row], n = range[2 * row + 1] - t0;
     const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
 

@@ -24,7 +24,7 @@ struct HdtSchedule {
     int32_t n_slots;       // tc * bn: length of one sample's padded key order
     int32_t wpr;           // bitmap words per tile row = bn / 32
     const int32_t *kperm;  // [batch][n_slots] sorted slot -> position, -1 beyond n_pos
-    const int32_t *q_rowptr;  // [batch][tr + 1] entries of query tile (b, I), global numbering
+    const int32_t *q_range;   // [batch][tr][2] first and one-past-last list entry of query tile (b, I)
     const int32_t *q_cols;    // [entries] key tile of each entry
     const uint32_t *q_sub;    // [entries] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
     const uint32_t *bits;     // [entries][bm][wpr]   row r, word c/32, bit c%32

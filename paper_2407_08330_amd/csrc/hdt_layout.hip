@@ -2,27 +2,30 @@
 //
 // What is computed is fixed by the paper (Sec. 3.2: a position attends to parent, siblings and
 // children; App. A.1, Alg. 1: sort keys by hierarchy level, partition into blocks, process a block
-// only if its mask has a non-zero entry).  How it is computed is ours.  Three kernels:
+// only if its mask has a non-zero entry).  How it is computed is ours.  Four small kernels:
 //
-//  front (one workgroup per sample)
-//   1. key order: stable counting sort by level with wave ballots;
+//  sort_count / sort_scatter (one workgroup per 1024 positions)
+//   1. key order: stable counting sort by level with wave ballots; the first kernel counts the levels
+//      of every chunk, the second turns the counts into each chunk's first slot per level and hands
+//      out the slots in document order;
 //   2. per anchor, the range of sorted slots its children occupy (integer atomic min/max, one
 //      pair of atomics per run of consecutive children);
+//  candidates (one wave per query tile)
 //   3. candidate tiles per query tile: every allowed key of a row lies in one of <= 2 slot ranges
 //      (its siblings = the children of its parent, and its own children) or is one of 2 single
 //      slots (itself, its parent), so a row marks O(1) ranges instead of testing n keys.  For
 //      documents laid out in pre-order the ranges are exact; for any other forest they are a
 //      superset;
-//   4. prefix sum of the candidate counts, a slice of the per-tile arrays reserved with one atomic
-//      add per sample, and the key tile of every candidate written out: these ARE the tile lists;
-//  bitmaps (grid-stride over candidates)
+//   4. a slice of the per-tile arrays reserved with one atomic add per workgroup, and the key tile of
+//      every candidate written out: these ARE the tile lists (first/last entry per query tile);
+//  tile_bitmaps (grid-stride over candidates)
 //   5. every candidate tile is evaluated exactly, pair by pair (bitmap, pair count, 32x32
 //      sub-block summary), so the result never depends on step 3 being tight.  A candidate without
 //      any allowed pair keeps its list entry with an all-zero summary, which every kernel skips;
 //      it is not counted as a tile and hdt_layout_export leaves it out.
 //
 // The per-tile arrays are sized before the number of candidates is known (a heuristic, raised by
-// what earlier builds needed); both kernels check the capacity.  The front kernel reports the count
+// what earlier builds needed); the kernels check the capacity.  The candidate kernel reports the count
 // (and whether the hierarchy was valid) through one word of pinned host memory as soon as it is
 // known; the host waits for that word only, not for the stream, and repeats the build with the exact
 // size in the rare case the guess was too small.
@@ -43,12 +46,12 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kBuckets = HDT_MAX_LEVELS + 1;  // levels 0..31, pads in the last bucket
-constexpr int kSortChunk = 8;                 // positions per lane loaded ahead of the ballot loops
+constexpr int kChunk = kThreads;              // positions per workgroup of the two sort kernels
 
-enum { CNT_ERR = 0, CNT_CAND = 1, CNT_TILES = 2, CNT_ARRIVED = 3 };
+enum { CNT_ERR = 0, CNT_CAND = 1, CNT_ARRIVED = 2 };
 
-// What the front kernel reports to the host through pinned host memory: one 64-bit word
-// [63:40] ticket of the build, [39] hierarchy error, [31:0] candidate tiles needed.
+// What the candidate kernel reports to the host through pinned host memory: one 64-bit word
+// [63:40] ticket of the build, [39] hierarchy error, [31:0] list entries needed.
 __host__ __device__ inline unsigned long long report_word(uint32_t ticket, int err, uint32_t need)
 {
     return ((unsigned long long)(ticket & 0xffffffu) << 40) | ((unsigned long long)(err != 0) << 39) | need;
@@ -63,33 +66,22 @@ __device__ __forceinline__ int wave_sum(int x)
     return x;
 }
 
-// exclusive scan, in place, of data[0..n) by the whole workgroup; returns the total to every thread
-__device__ int block_scan_inplace(int32_t *data, int n, int *s_wave /*[kWaves + 1]*/)
+__device__ __forceinline__ int bucket_of(int level) { return (level >= 0 && level < HDT_MAX_LEVELS) ? level : kBuckets - 1; }
+
+// histogram of `bucket` over the lanes with `in`: lane k gets the number of lanes that hold bucket k
+__device__ __forceinline__ int wave_bucket_count(bool in, int bucket)
 {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    int carry = 0;
-    for (int base = 0; base < n; base += kThreads) {
-        const int i = base + tid;
-        const int v = i < n ? data[i] : 0;
-        int x = v;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(x, d);
-            if (lane >= d) x += y;
-        }
-        if (lane == 63) s_wave[wave] = x;
-        __syncthreads();
-        int off = 0, tot = 0;
-        for (int w = 0; w < kWaves; w++) {
-            const int sw = s_wave[w];
-            if (w < wave) off += sw;
-            tot += sw;
-        }
-        if (i < n) data[i] = carry + off + x - v;
-        carry += tot;
-        __syncthreads();
+    const int lane = threadIdx.x & 63;
+    int mine = 0;
+    unsigned long long remaining = __ballot(in);
+    while (remaining) {
+        const int leader = __ffsll((long long)remaining) - 1;
+        const int bk = __builtin_amdgcn_readlane(bucket, leader);
+        const unsigned long long m = __ballot(in && bucket == bk);
+        if (lane == bk) mine = __popcll(m);
+        remaining &= ~m;
     }
-    return carry;
+    return mine;
 }
 
 __device__ __forceinline__ void mark_tiles(uint32_t *bits, int tlo, int thi)
@@ -101,228 +93,221 @@ __device__ __forceinline__ void mark_tiles(uint32_t *bits, int tlo, int thi)
     }
 }
 
-struct FrontArgs {
+struct SortArgs {
     const int32_t *level, *parent;
-    int n, n_slots, bm, bn, tr, tc, wc, force_dense, no_sort;
-    int64_t capacity;
+    int n, n_slots, nchunks, no_sort;
+    int32_t *hist;  // [B][nchunks][kBuckets] positions of every level in every chunk of kChunk positions
     int32_t *kperm, *slot, *cmin, *cmax;
-    uint32_t *cand;     // [B][tr][wc]
-    int32_t *cand_ptr;  // [B][tr+1]: becomes the lists' row pointer
+    int32_t *counters;
+};
+
+// ---- sort, first half: validate, count the levels of each chunk ---------------------------------
+__global__ __launch_bounds__(kThreads) void k_sort_count(SortArgs a)
+{
+    __shared__ int s_cnt[kWaves][kBuckets];
+    const int b = blockIdx.x / a.nchunks, chunk = blockIdx.x - b * a.nchunks, n = a.n;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int i = chunk * kChunk + tid;
+    const bool in = i < n;
+    const size_t o = (size_t)b * n;
+    int l = -1, p = -1;
+    if (in) {
+        l = a.level[o + i];
+        p = a.parent[o + i];
+        a.cmin[o + i] = INT_MAX;
+        a.cmax[o + i] = -1;
+    }
+    const bool bad = in && (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1));
+    if (__ballot(bad) && lane == 0) atomicOr(&a.counters[CNT_ERR], 1);
+    if (chunk == a.nchunks - 1)
+        for (int s = n + tid; s < a.n_slots; s += kThreads) a.kperm[(size_t)b * a.n_slots + s] = -1;
+    const int mine = wave_bucket_count(in, bucket_of(l));
+    if (lane < kBuckets) s_cnt[wave][lane] = mine;
+    __syncthreads();
+    if (tid < kBuckets) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; w++) t += s_cnt[w][tid];
+        a.hist[((size_t)b * a.nchunks + chunk) * kBuckets + tid] = t;
+    }
+}
+
+// ---- sort, second half: slots in document order; slot range of every node's children ------------
+__global__ __launch_bounds__(kThreads) void k_sort_scatter(SortArgs a)
+{
+    __shared__ int s_cnt[kWaves][kBuckets], s_tot[kWaves][kBuckets], s_pre[kWaves][kBuckets];
+    const int b = blockIdx.x / a.nchunks, chunk = blockIdx.x - b * a.nchunks, n = a.n;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int i = chunk * kChunk + tid;
+    const bool in = i < n;
+    const size_t o = (size_t)b * n;
+    int l = -1, p = -1;
+    if (in) {
+        l = a.level[o + i];
+        p = a.parent[o + i];
+    }
+    // what the parent check below needs, requested before the counting so that its latency hides there
+    bool valid = in && l >= 0 && p >= 0 && p < n;
+    const int lp = valid ? a.level[o + p] : 0;
+    const int bucket = bucket_of(l);
+    const int mine = wave_bucket_count(in, bucket);
+    // lane k sums level k over the chunks this wave looks at: all of them, and those before this chunk
+    int tot = 0, pre = 0;
+    if (lane < kBuckets)
+        for (int c = wave; c < a.nchunks; c += kWaves) {
+            const int v = a.hist[((size_t)b * a.nchunks + c) * kBuckets + lane];
+            tot += v;
+            if (c < chunk) pre += v;
+        }
+    if (lane < kBuckets) {
+        s_cnt[wave][lane] = mine;
+        s_tot[wave][lane] = tot;
+        s_pre[wave][lane] = pre;
+    }
+    __syncthreads();
+    if (wave == 0) {  // first slot of every (level, wave of this chunk): level major, then chunk, then wave
+        int t = 0, pr = 0;
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < kWaves; w++) {
+                t += s_tot[w][lane];
+                pr += s_pre[w][lane];
+            }
+        }
+        int incl = t;  // inclusive scan of the level totals over lanes
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
+        }
+        int run = incl - t + pr;
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < kWaves; w++) {
+                const int c = s_cnt[w][lane];
+                s_cnt[w][lane] = run;
+                run += c;
+            }
+        }
+    }
+    __syncthreads();
+    const int mybase = lane < kBuckets ? s_cnt[wave][lane] : 0;
+    int my_slot = i;
+    {
+        unsigned long long remaining = __ballot(in);
+        while (remaining) {
+            const int leader = __ffsll((long long)remaining) - 1;
+            const int bk = __builtin_amdgcn_readlane(bucket, leader);
+            const bool is_bk = in && bucket == bk;
+            const unsigned long long m = __ballot(is_bk);
+            const int first = __builtin_amdgcn_readlane(mybase, bk);
+            if (is_bk) my_slot = first + __popcll(m & lanemask_lt());
+            remaining &= ~m;
+        }
+    }
+    if (a.no_sort) my_slot = i;
+    if (in) {
+        a.slot[o + i] = my_slot;
+        a.kperm[(size_t)b * a.n_slots + my_slot] = i;
+    }
+    // Slot range of every node's children.  Consecutive positions with the same parent and consecutive
+    // slots (the tokens of a sentence, for one) form a run whose minimum and maximum are its first and
+    // last slot: one atomic each per run.
+    if (valid && lp < 0) {  // a parent must be a real position
+        atomicOr(&a.counters[CNT_ERR], 1);
+        valid = false;
+    }
+    const int sl = valid ? my_slot : -1;
+    const int p_prev = __shfl_up(p, 1), s_prev = __shfl_up(sl, 1);
+    const bool v_prev = __shfl_up((int)valid, 1) != 0;
+    const bool head = lane == 0 || !v_prev || p_prev != p || s_prev + 1 != sl;
+    const bool next_head = __shfl_down((int)(head || !valid), 1) != 0;  // lane+1 starts a new run (or is invalid)
+    const bool tail = lane == 63 || next_head;
+    if (valid && head) atomicMin(&a.cmin[o + p], sl);
+    if (valid && tail) atomicMax(&a.cmax[o + p], sl);
+}
+
+struct CandArgs {
+    const int32_t *level, *parent, *slot, *cmin, *cmax;
+    int n, bm, bn, tr, tc, wc, force_dense;
+    int64_t capacity;
+    int32_t *q_range;  // [B][tr][2]: first and one-past-last list entry of every query tile
     int32_t *c_row, *q_cols;
     int32_t *counters;
     unsigned long long *report;  // pinned host memory, written once by the last workgroup to get there
     uint32_t ticket;
 };
 
-// ---- front: sort, child ranges, candidates ---------------------------------------------------
-__global__ __launch_bounds__(kThreads) void k_layout_front(FrontArgs a)
+// ---- candidate key tiles of every query tile: one wave per query tile, a bitmap per wave in LDS ----
+__global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
 {
     extern __shared__ uint32_t s_bitmaps[];  // [kWaves][wc]
-    __shared__ volatile int s_cnt[kWaves][kBuckets];
-    __shared__ int s_wave[kWaves + 1];
+    __shared__ int s_n[kWaves];
     __shared__ int s_base;
-    const int b = blockIdx.x, n = a.n;
+    const int groups = (a.tr + kWaves - 1) / kWaves;
+    const int b = blockIdx.x / groups, g = blockIdx.x - b * groups, n = a.n;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
-    int32_t *kperm = a.kperm + (size_t)b * a.n_slots, *slot = a.slot + (size_t)b * n;
-    int32_t *cmin = a.cmin + (size_t)b * n, *cmax = a.cmax + (size_t)b * n;
-
-    for (int i = tid; i < n; i += kThreads) {
-        cmin[i] = INT_MAX;
-        cmax[i] = -1;
-    }
-    for (int s = n + tid; s < a.n_slots; s += kThreads) kperm[s] = -1;
-    for (int i = tid; i < kWaves * kBuckets; i += kThreads) (&s_cnt[0][0])[i] = 0;
-    __syncthreads();
-
-    // 1. stable sort by level.  Each wave owns a contiguous segment (a multiple of 64 positions); lane k
-    // of a wave keeps the wave's running count of bucket k in a register.
-    const int seg = ((n + kWaves * 64 - 1) / (kWaves * 64)) * 64;
-    const int begin = min(n, wave * seg), end = min(n, begin + seg);
-    bool bad = false;
-    int mycnt = 0;
-    for (int base = begin; base < end; base += 64 * kSortChunk) {  // pass A: validate and count
-        int lv[kSortChunk], pr[kSortChunk];
-#pragma unroll
-        for (int u = 0; u < kSortChunk; u++) {
-            const int i = base + u * 64 + lane;
-            lv[u] = i < end ? level[i] : -1;
-            pr[u] = i < end ? parent[i] : -1;
-        }
-#pragma unroll
-        for (int u = 0; u < kSortChunk; u++) {
-            const int i = base + u * 64 + lane;
-            const bool in = i < end;
-            int bucket = kBuckets - 1;
-            if (in) {
-                const int l = lv[u], p = pr[u];
-                if (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1)) bad = true;
-                if (l >= 0 && l < HDT_MAX_LEVELS) bucket = l;
-            }
-            unsigned long long remaining = __ballot(in);
-            while (remaining) {
-                const int leader = __ffsll((long long)remaining) - 1;
-                const int bk = __builtin_amdgcn_readlane(bucket, leader);
-                const unsigned long long m = __ballot(in && bucket == bk);
-                if (lane == bk) mycnt += __popcll(m);
-                remaining &= ~m;
-            }
-        }
-    }
-    if (__ballot(bad) && lane == 0) atomicOr(&a.counters[CNT_ERR], 1);
-    if (lane < kBuckets) s_cnt[wave][lane] = mycnt;
-    __syncthreads();
-    if (wave == 0) {  // first slot of every (bucket, wave): bucket major, wave minor; lane k scans bucket k
-        int tot = 0, pre[kWaves];
-        if (lane < kBuckets) {
-#pragma unroll
-            for (int w = 0; w < kWaves; w++) {
-                pre[w] = tot;
-                tot += s_cnt[w][lane];
-            }
-        }
-        int incl = tot;  // inclusive scan of the bucket totals over lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(incl, d);
-            if (lane >= d) incl += y;
-        }
-        if (lane < kBuckets) {
-#pragma unroll
-            for (int w = 0; w < kWaves; w++) s_cnt[w][lane] = incl - tot + pre[w];
-        }
-    }
-    __syncthreads();
-    int mybase = lane < kBuckets ? s_cnt[wave][lane] : 0;
-    for (int base = begin; base < end; base += 64 * kSortChunk) {  // pass B: hand out slots in document order
-        int lv[kSortChunk];
-#pragma unroll
-        for (int u = 0; u < kSortChunk; u++) {
-            const int i = base + u * 64 + lane;
-            lv[u] = i < end ? level[i] : -1;
-        }
-#pragma unroll
-        for (int u = 0; u < kSortChunk; u++) {
-            const int i = base + u * 64 + lane;
-            const bool in = i < end;
-            int bucket = kBuckets - 1;
-            if (in && lv[u] >= 0 && lv[u] < HDT_MAX_LEVELS) bucket = lv[u];
-            int my_slot = i;
-            unsigned long long remaining = __ballot(in);
-            while (remaining) {
-                const int leader = __ffsll((long long)remaining) - 1;
-                const int bk = __builtin_amdgcn_readlane(bucket, leader);
-                const bool mine = in && bucket == bk;
-                const unsigned long long m = __ballot(mine);
-                const int first = __builtin_amdgcn_readlane(mybase, bk);
-                if (mine) my_slot = first + __popcll(m & lanemask_lt());
-                if (lane == bk) mybase += __popcll(m);
-                remaining &= ~m;
-            }
-            if (in) {
-                if (a.no_sort) my_slot = i;
-                slot[i] = my_slot;
-                kperm[my_slot] = i;
-            }
-        }
-    }
-    __threadfence_block();
-    __syncthreads();
-
-    // 2. slot range of every node's children.  Consecutive positions with the same parent and
-    // consecutive slots (the tokens of a sentence, for one) form a run whose minimum and maximum are its
-    // first and last slot: one atomic each per run.
-    for (int base = 0; base < n; base += kThreads) {
-        const int i = base + tid;
-        int p = -1, sl = -1;
-        bool valid = false;
-        if (i < n) {
-            const int l = level[i];
-            p = parent[i];
-            valid = l >= 0 && p >= 0 && p < n;
-            if (valid && level[p] < 0) {  // a parent must be a real position
-                atomicOr(&a.counters[CNT_ERR], 1);
-                valid = false;
-            }
-            if (valid) sl = slot[i];
-        }
-        const int p_prev = __shfl_up(p, 1), s_prev = __shfl_up(sl, 1);
-        const bool v_prev = __shfl_up((int)valid, 1) != 0;
-        const bool head = lane == 0 || !v_prev || p_prev != p || s_prev + 1 != sl;
-        const bool next_head = __shfl_down((int)(head || !valid), 1) != 0;  // lane+1 starts a new run (or is invalid)
-        const bool tail = lane == 63 || next_head;
-        if (valid && head) atomicMin(&cmin[p], sl);
-        if (valid && tail) atomicMax(&cmax[p], sl);
-    }
-    __threadfence_block();
-    __syncthreads();
-
-    // 3. candidate key tiles of every query tile: one wave per query tile, a bitmap per wave in LDS
     const int bm = a.bm, bn = a.bn, tr = a.tr, tc = a.tc, wc = a.wc;
+    const int I = g * kWaves + wave;
+    const bool active = I < tr;
+    const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
+    const int32_t *slot = a.slot + (size_t)b * n, *cmin = a.cmin + (size_t)b * n, *cmax = a.cmax + (size_t)b * n;
     uint32_t *wbits = s_bitmaps + (size_t)wave * wc;
-    int32_t *cand_ptr = a.cand_ptr + (size_t)b * (tr + 1);
-    for (int I = wave; I < tr; I += kWaves) {
-        for (int w = lane; w < wc; w += 64) wbits[w] = 0;
-        __builtin_amdgcn_wave_barrier();
-        if (a.force_dense) {
-            if (lane == 0) mark_tiles(wbits, 0, tc - 1);
-        } else {
-            // rows lane and lane + 64 of the tile; all loads of one dependency level are issued together
-            int i2[2], sl2[2], p2[2], lo_c[2], hi_c[2];
-            bool ok[2];
+    for (int w = lane; w < wc; w += 64) wbits[w] = 0;
+    __builtin_amdgcn_wave_barrier();
+    if (active && a.force_dense) {
+        if (lane == 0) mark_tiles(wbits, 0, tc - 1);
+    } else if (active) {
+        // rows lane and lane + 64 of the tile; all loads of one dependency level are issued together
+        int i2[2], sl2[2], p2[2], lo_c[2], hi_c[2];
+        bool ok[2];
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
-                const int rr = lane + 64 * u;
-                i2[u] = I * bm + rr;
-                ok[u] = rr < bm && i2[u] < n && level[min(i2[u], n - 1)] >= 0;
-                const int ii = ok[u] ? i2[u] : 0;
-                sl2[u] = slot[ii];
-                p2[u] = parent[ii];
-                lo_c[u] = cmin[ii];
-                hi_c[u] = cmax[ii];
-            }
-            int sp2[2], lo_s[2], hi_s[2];
-            bool okp[2];
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-                okp[u] = ok[u] && p2[u] >= 0 && p2[u] < n;
-                const int pp = okp[u] ? p2[u] : 0;
-                okp[u] = okp[u] && level[pp] >= 0;
-                sp2[u] = slot[pp];
-                lo_s[u] = cmin[pp];
-                hi_s[u] = cmax[pp];
-            }
-#pragma unroll
-            for (int u = 0; u < 2; u++) {
-                if (!ok[u]) continue;
-                mark_tiles(wbits, sl2[u] / bn, sl2[u] / bn);  // itself
-                if (okp[u]) {
-                    mark_tiles(wbits, sp2[u] / bn, sp2[u] / bn);  // its parent
-                    if (lo_s[u] <= hi_s[u] && lo_s[u] >= 0 && hi_s[u] < n)
-                        mark_tiles(wbits, lo_s[u] / bn, hi_s[u] / bn);  // its siblings: the children of its parent
-                }
-                if (lo_c[u] <= hi_c[u] && lo_c[u] >= 0 && hi_c[u] < n)
-                    mark_tiles(wbits, lo_c[u] / bn, hi_c[u] / bn);  // its children
-            }
+        for (int u = 0; u < 2; u++) {
+            const int rr = lane + 64 * u;
+            i2[u] = I * bm + rr;
+            ok[u] = rr < bm && i2[u] < n;
+            const int ii = ok[u] ? i2[u] : 0;
+            ok[u] = ok[u] && level[ii] >= 0;
+            sl2[u] = slot[ii];
+            p2[u] = parent[ii];
+            lo_c[u] = cmin[ii];
+            hi_c[u] = cmax[ii];
         }
-        __builtin_amdgcn_wave_barrier();
-        int cnt = 0;
-        uint32_t *out = a.cand + ((size_t)b * tr + I) * wc;
-        for (int w = lane; w < wc; w += 64) {
-            const uint32_t v = wbits[w];
-            out[w] = v;
-            cnt += __popc(v);
+        int sp2[2], lo_s[2], hi_s[2];
+        bool okp[2];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            okp[u] = ok[u] && p2[u] >= 0 && p2[u] < n;
+            const int pp = okp[u] ? p2[u] : 0;
+            okp[u] = okp[u] && level[pp] >= 0;
+            sp2[u] = slot[pp];
+            lo_s[u] = cmin[pp];
+            hi_s[u] = cmax[pp];
         }
-        cnt = wave_sum(cnt);
-        if (lane == 0) cand_ptr[I] = cnt;
-        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            if (!ok[u]) continue;
+            mark_tiles(wbits, sl2[u] / bn, sl2[u] / bn);  // itself
+            if (okp[u]) {
+                mark_tiles(wbits, sp2[u] / bn, sp2[u] / bn);  // its parent
+                if (lo_s[u] <= hi_s[u] && lo_s[u] >= 0 && hi_s[u] < n)
+                    mark_tiles(wbits, lo_s[u] / bn, hi_s[u] / bn);  // its siblings: the children of its parent
+            }
+            if (lo_c[u] <= hi_c[u] && lo_c[u] >= 0 && hi_c[u] < n)
+                mark_tiles(wbits, lo_c[u] / bn, hi_c[u] / bn);  // its children
+        }
     }
-    __threadfence();  // device scope: this workgroup's error flags have reached the counters
+    __builtin_amdgcn_wave_barrier();
+    int cnt = 0;
+    for (int w = lane; w < wc; w += 64) cnt += __popc(wbits[w]);
+    cnt = wave_sum(cnt);
+    if (lane == 0) s_n[wave] = cnt;
     __syncthreads();
-
-    // 4. prefix sum, reserve this sample's slice of the candidate arrays, list the candidates
-    const int total = block_scan_inplace(cand_ptr, tr, s_wave);
     if (tid == 0) {
+        int total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; w++) total += s_n[w];
+        // this workgroup's slice of the list arrays
         s_base = atomicAdd(&a.counters[CNT_CAND], total);
         // the last workgroup to get here knows the final counters: it tells the host, which is waiting
         // for exactly this word, while the lists and the bitmaps are still being written
@@ -336,35 +321,36 @@ __global__ __launch_bounds__(kThreads) void k_layout_front(FrontArgs a)
         }
     }
     __syncthreads();
-    const int gbase = s_base;
-    for (int I = tid; I < tr; I += kThreads) cand_ptr[I] += gbase;
-    if (tid == 0) cand_ptr[tr] = gbase + total;
-    __threadfence_block();
-    __syncthreads();
-    for (int I = wave; I < tr; I += kWaves) {
-        const size_t row = (size_t)b * tr + I;
-        const int cbase = cand_ptr[I];
-        int n_cand = 0;
-        for (int w0 = 0; w0 < wc; w0 += 2) {
-            const int w = w0 + (lane >> 5), bit = lane & 31;
-            const uint32_t word = w < wc ? a.cand[row * wc + w] : 0u;
-            const bool is_cand = (word >> bit) & 1u;
-            const unsigned long long cm = __ballot(is_cand);
-            const int64_t c = (int64_t)cbase + n_cand + __popcll(cm & lanemask_lt());
-            if (is_cand && c < a.capacity) {
-                a.c_row[c] = (int32_t)row;
-                a.q_cols[c] = (w << 5) + bit;
-            }
-            n_cand += __popcll(cm);
+    if (!active) return;
+    int cbase = s_base;
+    for (int w = 0; w < wave; w++) cbase += s_n[w];
+    const size_t row = (size_t)b * tr + I;
+    if (lane == 0) {
+        a.q_range[2 * row] = cbase;
+        a.q_range[2 * row + 1] = cbase + cnt;
+    }
+    int n_cand = 0;
+    for (int w0 = 0; w0 < wc; w0 += 2) {
+        const int w = w0 + (lane >> 5), bit = lane & 31;
+        const uint32_t word = w < wc ? wbits[w] : 0u;
+        const bool is_cand = (word >> bit) & 1u;
+        const unsigned long long cm = __ballot(is_cand);
+        const int64_t c = (int64_t)cbase + n_cand + __popcll(cm & lanemask_lt());
+        if (is_cand && c < a.capacity) {
+            a.c_row[c] = (int32_t)row;
+            a.q_cols[c] = (w << 5) + bit;
         }
+        n_cand += __popcll(cm);
     }
 }
 
 // ---- bitmaps: exact evaluation of every candidate tile ------------------------------------------
-// One candidate per workgroup iteration: pair-by-pair bitmap (row-major words for export and the
-// fp32 path, and per 32x32 sub-block the 16 x 64-bit lane masks the MFMA kernels apply to their
-// accumulator registers), pair count and sub-block summary.
-__global__ __launch_bounds__(256) void k_tile_bitmaps(const int32_t *__restrict__ level,
+// One candidate per workgroup iteration, one row per lane (two waves cover up to 128 rows).  The keys
+// of the tile sit in registers, one or two per lane, and are broadcast by lane index; each lane tests
+// its row against every key.  Outputs: the row-major bitmap (export, fp32 path), per 32x32 sub-block
+// the 16 x 64-bit lane masks the MFMA kernels apply to their accumulator registers (wave ballots), the
+// pair count and the sub-block summary.
+__global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict__ level,
                                                       const int32_t *__restrict__ parent,
                                                       const int32_t *__restrict__ kperm,
                                                       const int32_t *__restrict__ c_row,
@@ -373,76 +359,93 @@ __global__ __launch_bounds__(256) void k_tile_bitmaps(const int32_t *__restrict_
                                                       int n, int n_slots, int bm, int bn, int tr, uint32_t *bits,
                                                       unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
 {
-    __shared__ int s_kpos[128], s_kpar[128];
-    __shared__ uint32_t s_words[128 * 4];
-    __shared__ int s_cnt;
-    __shared__ unsigned int s_any, s_all;
-    const int tid = threadIdx.x;
-    const int wpr = bn >> 5;
-    const int words = bm * wpr;
-    const int nsub = (bm >> 5) * wpr;
+    __shared__ int s_cnt[2];
+    __shared__ uint32_t s_any[2], s_all[2];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
+    const size_t words = (size_t)bm * wpr;
     const int64_t total = min((int64_t)counters[CNT_CAND], capacity);
     for (int64_t c = blockIdx.x; c < total; c += gridDim.x) {
         const int row = c_row[c], J = c_col[c];
         const int b = row / tr, I = row - b * tr;
         const size_t o = (size_t)b * n;
-        __syncthreads();  // the previous candidate's LDS words are no longer read
-        if (tid < bn) {
-            const int s = J * bn + tid;
-            int pos = s < n_slots ? kperm[(size_t)b * n_slots + s] : -1;
-            int par = -1;
-            if (pos >= 0 && pos < n && level[o + pos] >= 0)
-                par = parent[o + pos];
-            else
-                pos = -1;
-            s_kpos[tid] = pos;
-            s_kpar[tid] = par;
+        // keys: lane l holds slots l and 64 + l of the tile
+        int kpos[2], kpar[2];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int si = 64 * u + lane, s = J * bn + si;
+            kpos[u] = (si < bn && s < n_slots) ? kperm[(size_t)b * n_slots + s] : -1;
         }
-        if (tid == 0) {
-            s_cnt = 0;
-            s_any = 0;
-            s_all = 0xffffu;
+        // this lane's row
+        const int r = wave * 64 + lane, i = I * bm + r;
+        bool rowok = r < bm && i < n;
+        const int ii = rowok ? i : 0;
+        const int li = level[o + ii], pi = parent[o + ii];
+        rowok = rowok && li >= 0;
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const bool okp = kpos[u] >= 0 && kpos[u] < n;
+            const int pp = okp ? kpos[u] : 0;
+            const int lv = level[o + pp], pr = parent[o + pp];
+            kpos[u] = (okp && lv >= 0) ? kpos[u] : -1;
+            kpar[u] = (okp && lv >= 0) ? pr : -1;
         }
-        __syncthreads();
-        for (int idx = tid; idx < words; idx += 256) {
-            const int r = idx / wpr, wd = idx - r * wpr;
-            const int i = I * bm + r;
-            uint32_t out = 0;
-            if (i < n && level[o + i] >= 0) {
-                const int pi = parent[o + i];
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        int cnt = 0;
+#pragma unroll
+        for (int wd = 0; wd < 4; wd++) {
+            if (wd < wpr) {
+                const int kp = kpos[wd >> 1], kq = kpar[wd >> 1];
+                uint32_t out = 0;
+#pragma unroll
                 for (int cc = 0; cc < 32; cc++) {
-                    const int kj = s_kpos[wd * 32 + cc], kp = s_kpar[wd * 32 + cc];
-                    const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kp) || pi == kj || kp == i);
+                    const int kj = __builtin_amdgcn_readlane(kp, (wd & 1) * 32 + cc);
+                    const int kr = __builtin_amdgcn_readlane(kq, (wd & 1) * 32 + cc);
+                    const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kr) || pi == kj || kr == i);
                     out |= (uint32_t)ok << cc;
                 }
+                w[wd] = rowok ? out : 0u;
+                cnt += __popc(w[wd]);
+                if (r < bm) bits[(size_t)c * words + (size_t)r * wpr + wd] = w[wd];
             }
-            bits[(size_t)c * words + idx] = out;
-            s_words[idx] = out;
-            const int sub = (r >> 5) * wpr + wd;
-            if (out) {
-                atomicAdd(&s_cnt, __popc(out));
-                atomicOr(&s_any, 1u << sub);
+        }
+        cnt = wave_sum(cnt);
+        // register-major masks of sub-block (rblk, cblk), accumulator register e: bit l <=> row
+        // rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
+        uint32_t sub_any = 0, sub_all = 0;
+#pragma unroll
+        for (int rr = 0; rr < 2; rr++) {
+            const int rblk = 2 * wave + rr;
+            if (rblk < nrb) {
+#pragma unroll
+                for (int cblk = 0; cblk < 4; cblk++) {
+                    if (cblk < wpr) {
+                        const uint32_t x = (uint32_t)__shfl((int)w[cblk], rr * 32 + (lane & 31));
+                        unsigned long long mine = 0;
+#pragma unroll
+                        for (int e = 0; e < 16; e++) {
+                            const int bit = (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+                            const unsigned long long m = __ballot((x >> bit) & 1u);
+                            if (lane == e) mine = m;
+                        }
+                        const int sb = rblk * wpr + cblk;
+                        if (lane < 16) bits_rm[((size_t)c * nsub + sb) * 16 + lane] = mine;
+                        if (__ballot(x != 0u) != 0ull) sub_any |= 1u << sb;
+                        if (__ballot(x == 0xffffffffu) == ~0ull) sub_all |= 1u << sb;
+                    }
+                }
             }
-            if (out != 0xffffffffu) atomicAnd(&s_all, ~(1u << sub));
+        }
+        __syncthreads();  // the previous candidate's partial results have been read
+        if (lane == 0) {
+            s_cnt[wave] = cnt;
+            s_any[wave] = sub_any;
+            s_all[wave] = sub_all;
         }
         __syncthreads();
-        // register-major masks: sub-block sb = rblk*wpr + cblk, accumulator register e, lane l:
-        // row rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
-        for (int idx = tid; idx < nsub * 16; idx += 256) {
-            const int sb = idx >> 4, e = idx & 15;
-            const int rblk = sb / wpr, cblk = sb - rblk * wpr;
-            unsigned long long m = 0;
-            for (int l = 0; l < 64; l++) {
-                const uint32_t w = s_words[(rblk * 32 + (l & 31)) * wpr + cblk];
-                const int bit = (l >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-                m |= (unsigned long long)((w >> bit) & 1u) << l;
-            }
-            bits_rm[(size_t)c * nsub * 16 + idx] = m;
-        }
         if (tid == 0) {
-            const unsigned int all = s_all & ((1u << nsub) - 1u);
-            c_cnt[c] = s_cnt;
-            c_sub[c] = s_any | (all << 16);
+            c_cnt[c] = s_cnt[0] + s_cnt[1];
+            c_sub[c] = (s_any[0] | s_any[1]) | ((s_all[0] | s_all[1]) << 16);
         }
     }
 }
@@ -510,14 +513,12 @@ struct Carver {
 };
 
 struct Phase1 {
-    int32_t *kperm, *slot, *cmin, *cmax, *cand_ptr, *counters;
-    uint32_t *cand;
-    int64_t *stats;
-    size_t zero_begin, zero_end;  // byte range that must start at zero (also what the host reads back)
+    int32_t *kperm, *slot, *cmin, *cmax, *hist, *q_range, *counters;
+    size_t zero_begin, zero_end;  // byte range that must start at zero
     size_t bytes;
 };
 
-Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int tc, int wc)
+Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int nchunks)
 {
     Carver c{base};
     Phase1 p;
@@ -525,11 +526,10 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int tc, int w
     p.slot = c.take<int32_t>((size_t)B * n);
     p.cmin = c.take<int32_t>((size_t)B * n);
     p.cmax = c.take<int32_t>((size_t)B * n);
-    p.cand = c.take<uint32_t>((size_t)B * tr * wc);
-    p.cand_ptr = c.take<int32_t>((size_t)B * (tr + 1));
+    p.hist = c.take<int32_t>((size_t)B * nchunks * kBuckets);
+    p.q_range = c.take<int32_t>((size_t)B * tr * 2);
     p.zero_begin = c.off;
-    p.counters = c.take<int32_t>(64);  // 256 bytes, so that stats follows immediately
-    p.stats = c.take<int64_t>((size_t)B * 2);
+    p.counters = c.take<int32_t>(64);
     p.zero_end = c.off;
     p.bytes = c.off;
     return p;
@@ -723,9 +723,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     } while (0)
 
     {
-        Phase1 p = carve_phase1(nullptr, B, n, s.n_slots, tr, tc, wc);
+        const int nchunks = (n + kChunk - 1) / kChunk, groups = (tr + kWaves - 1) / kWaves;
+        Phase1 p = carve_phase1(nullptr, B, n, s.n_slots, tr, nchunks);
         BUILD_TRY(pool_alloc(&L->arena, p.bytes, &L->arena_bytes));
-        p = carve_phase1((char *)L->arena, B, n, s.n_slots, tr, tc, wc);
+        p = carve_phase1((char *)L->arena, B, n, s.n_slots, tr, nchunks);
 
         // capacity of the per-tile arrays: exact for the dense baseline, else a guess
         int64_t cap = force_dense ? (int64_t)B * tr * tc : (int64_t)B * ((int64_t)tr * 8 + 64);
@@ -750,23 +751,32 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
             }
             BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
             {
-                FrontArgs fa{d_level, d_parent, n, s.n_slots, bm, bn, tr, tc, wc, force_dense, no_sort, cap,
-                             p.kperm, p.slot, p.cmin, p.cmax, p.cand, p.cand_ptr, q.c_row, q.q_cols, p.counters,
-                             report, ticket};
-                HdtTimer t("hdt_layout_front", st);
-                hipLaunchKernelGGL(k_layout_front, dim3(B), dim3(kThreads), (size_t)kWaves * wc * sizeof(uint32_t), st,
-                                   fa);
+                SortArgs sa{d_level, d_parent, n, s.n_slots, nchunks, no_sort, p.hist, p.kperm, p.slot, p.cmin, p.cmax,
+                            p.counters};
+                {
+                    HdtTimer t("hdt_layout_sort_count", st);
+                    hipLaunchKernelGGL(k_sort_count, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
+                }
+                {
+                    HdtTimer t("hdt_layout_sort_scatter", st);
+                    hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
+                }
+                CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, cap,
+                            p.q_range, q.c_row, q.q_cols, p.counters, report, ticket};
+                HdtTimer t("hdt_layout_candidates", st);
+                hipLaunchKernelGGL(k_candidates, dim3((unsigned)B * groups), dim3(kThreads),
+                                   (size_t)kWaves * wc * sizeof(uint32_t), st, ca);
             }
             {
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
-                hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(256), 0, st, d_level, d_parent, p.kperm, q.c_row,
+                hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(128), 0, st, d_level, d_parent, p.kperm, q.c_row,
                                    q.q_cols, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits, q.bits_rm, q.c_cnt,
                                    q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
             // The host needs two facts before it can hand the layout out: whether the hierarchy was valid and
-            // whether the per-tile arrays were large enough.  The front kernel knows both before it writes
+            // whether the per-tile arrays were large enough.  The candidate kernel knows both before it writes
             // the lists; it stores them into pinned host memory and the host polls that word instead of
             // draining the stream, so the bitmap kernel and whatever the caller enqueues next keep the GPU busy.
             unsigned long long word = 0;
@@ -794,7 +804,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 L->capacity = cap;
                 L->n_entries = need;
                 s.kperm = p.kperm;
-                s.q_rowptr = p.cand_ptr;
+                s.q_range = p.q_range;
                 s.q_cols = q.q_cols;
                 s.q_sub = q.q_sub;
                 s.bits = q.bits;
