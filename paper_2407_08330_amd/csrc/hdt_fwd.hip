@@ -39,6 +39,85 @@ struct FwdCfg {
     static constexpr int WAVES = (D == 64) ? HDT_FWD_W64 : 2;  // waves per SIMD the register budget allows
 };
 
+// One key tile for one wave: its sub-blocks A0 (keys 0..31) and A1 (keys 32..63) of the tile, as selected.
+template <int D, bool A0, bool A1>
+__device__ __forceinline__ void fwd_step(const char *sK, const char *sV, const RowLane &rl, const TrLane &tl,
+                                         const bf16x8 (&qf)[D / 16], f32x16 (&oacc)[D / 32], float &m_ref,
+                                         float &l_part, const unsigned long long *mk, int xlane, float scale_log2)
+{
+    constexpr int ROWB = 2 * D, KSTEPS = D / 16, DBLK = D / 32;
+    // S^T sub-blocks = K[kb*32 .. +32) . Q^T, masked
+    f32x16 s0, s1;
+#pragma unroll
+    for (int e = 0; e < 16; e++) s0[e] = s1[e] = 0.f;
+#pragma unroll
+    for (int st = 0; st < KSTEPS; st++) {
+        if (A0) s0 = mfma_32x32x16(read_row<ROWB>(sK, rl, 0, st), qf[st], s0);
+        if (A1) s1 = mfma_32x32x16(read_row<ROWB>(sK, rl, 32, st), qf[st], s1);
+    }
+    float mx = -INFINITY;
+    if (A0) {
+        apply_mask(s0, mk, -INFINITY);
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(s0[e], s0[e + 1]));
+    }
+    if (A1) {
+        apply_mask(s1, mk + 16, -INFINITY);
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(s1[e], s1[e + 1]));
+    }
+
+    // online softmax for this lane's query over up to 64 keys: its own registers plus those of
+    // the partner lane in the other half-wave
+    mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(xlane, __builtin_bit_cast(int, mx))));
+    mx *= scale_log2;
+    if (__any(mx > m_ref + 8.f)) {  // raise the reference and rescale (always on a row's first keys)
+        const float m_new = fmaxf(m_ref, mx);
+        const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref - m_new);
+        m_ref = m_new;
+        l_part *= alpha;
+#pragma unroll
+        for (int j = 0; j < DBLK; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) oacc[j][e] *= alpha;
+    }
+    const float m_sub = (m_ref == -INFINITY) ? 0.f : m_ref;  // row without any allowed key so far
+
+    // P^T = exp2(S^T * scale*log2e - m_ref); O^T += V^T P^T
+    float psum = 0.f;
+    bf16x8 p00, p01, p10, p11;
+    if (A0) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            s0[e] = fast_exp2(fmaf(s0[e], scale_log2, -m_sub));
+            psum += s0[e];
+        }
+        p00 = pack_bf16x8(s0, 0);
+        p01 = pack_bf16x8(s0, 8);
+    }
+    if (A1) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            s1[e] = fast_exp2(fmaf(s1[e], scale_log2, -m_sub));
+            psum += s1[e];
+        }
+        p10 = pack_bf16x8(s1, 0);
+        p11 = pack_bf16x8(s1, 8);
+    }
+    l_part += psum;
+#pragma unroll
+    for (int j = 0; j < DBLK; j++) {
+        if (A0) {
+            oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 0, j), p00, oacc[j]);
+            oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 16, j), p01, oacc[j]);
+        }
+        if (A1) {
+            oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 32, j), p10, oacc[j]);
+            oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 48, j), p11, oacc[j]);
+        }
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
@@ -110,84 +189,17 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
         col_ahead = (i + 1 + S < n) ? cols[i + 1 + S] : 0;
         const char *sK = pipe.tile_a(i % S), *sV = pipe.tile_b(i % S);
 
-        // this wave's two 32x32 sub-blocks of the tile (wave-uniform flags)
+        // this wave's two 32x32 sub-blocks of the tile (wave-uniform flags); one straight-line code path
+        // per combination, so that the two sub-blocks' loads, MFMA chains and exponentials interleave
         const bool act0 = (sub >> (wave * 2)) & 1u, act1 = (sub >> (wave * 2 + 1)) & 1u;
         if (!(act0 || act1)) continue;
         const unsigned long long *mk = s.bits_rm + ((size_t)bidx * 8 + wave * 2) * 16;
-
-        // S^T sub-blocks = K[kb*32 .. +32) . Q^T, masked
-        f32x16 s0, s1;
-        float mx = -INFINITY;
-        if (act0) {
-#pragma unroll
-            for (int e = 0; e < 16; e++) s0[e] = 0.f;
-#pragma unroll
-            for (int st = 0; st < KSTEPS; st++) s0 = mfma_32x32x16(read_row<ROWB>(sK, rl, 0, st), qf[st], s0);
-        }
-        if (act1) {
-#pragma unroll
-            for (int e = 0; e < 16; e++) s1[e] = 0.f;
-#pragma unroll
-            for (int st = 0; st < KSTEPS; st++) s1 = mfma_32x32x16(read_row<ROWB>(sK, rl, 32, st), qf[st], s1);
-        }
-        if (act0) {
-            if (!((sub >> (16 + wave * 2)) & 1u)) apply_mask(s0, mk, -INFINITY);
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(s0[e], s0[e + 1]));
-        }
-        if (act1) {
-            if (!((sub >> (17 + wave * 2)) & 1u)) apply_mask(s1, mk + 16, -INFINITY);
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) mx = fmaxf(mx, fmaxf(s1[e], s1[e + 1]));
-        }
-
-        // online softmax for this lane's query over up to 64 keys: its own registers plus those of
-        // the partner lane in the other half-wave
-        mx = fmaxf(mx, __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(xlane, __builtin_bit_cast(int, mx))));
-        mx *= scale_log2;
-        if (__any(mx > m_ref + 8.f)) {  // raise the reference and rescale (always on a row's first keys)
-            const float m_new = fmaxf(m_ref, mx);
-            const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref - m_new);
-            m_ref = m_new;
-            l_part *= alpha;
-#pragma unroll
-            for (int j = 0; j < DBLK; j++)
-#pragma unroll
-                for (int e = 0; e < 16; e++) oacc[j][e] *= alpha;
-        }
-        const float m_sub = (m_ref == -INFINITY) ? 0.f : m_ref;  // row without any allowed key so far
-
-        // P^T = exp2(S^T * scale*log2e - m_ref); O^T += V^T P^T
-        if (act0) {
-            float psum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                s0[e] = fast_exp2(fmaf(s0[e], scale_log2, -m_sub));
-                psum += s0[e];
-            }
-            l_part += psum;
-            const bf16x8 pb0 = pack_bf16x8(s0, 0), pb1 = pack_bf16x8(s0, 8);
-#pragma unroll
-            for (int j = 0; j < DBLK; j++) {
-                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 0, j), pb0, oacc[j]);
-                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 16, j), pb1, oacc[j]);
-            }
-        }
-        if (act1) {
-            float psum = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                s1[e] = fast_exp2(fmaf(s1[e], scale_log2, -m_sub));
-                psum += s1[e];
-            }
-            l_part += psum;
-            const bf16x8 pb0 = pack_bf16x8(s1, 0), pb1 = pack_bf16x8(s1, 8);
-#pragma unroll
-            for (int j = 0; j < DBLK; j++) {
-                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 32, j), pb0, oacc[j]);
-                oacc[j] = mfma_32x32x16(read_tr<ROWB>(sV, tl, 48, j), pb1, oacc[j]);
-            }
-        }
+        if (act0 && act1)
+            fwd_step<D, true, true>(sK, sV, rl, tl, qf, oacc, m_ref, l_part, mk, xlane, scale_log2);
+        else if (act0)
+            fwd_step<D, true, false>(sK, sV, rl, tl, qf, oacc, m_ref, l_part, mk, xlane, scale_log2);
+        else
+            fwd_step<D, false, true>(sK, sV, rl, tl, qf, oacc, m_ref, l_part, mk, xlane, scale_log2);
     }
 
     // epilogue: O = acc / l, LSE = ln(sum exp) = ln2 * (m_ref + log2 l); O leaves through LDS as full rows

@@ -306,19 +306,15 @@ __device__ __forceinline__ bf16x8 read_tr(const char *tile, const TrLane &t, int
 // Apply a 32x32 sub-block's bitmap to a C fragment: element e of lane l is kept iff bit l of
 // mask[e] is set (the "register-major" bitmap the layout stores per sub-block), else replaced.
 // The 16 masks are fetched with scalar loads (the address is the same for the whole wave; the
-// layout is read-only while attention kernels run) and used directly as v_cndmask lane masks.
+// layout is read-only while attention kernels run) and used directly as the lane masks of
+// v_cndmask (a wave-uniform 64-bit value turned into a per-lane condition).
 typedef const unsigned long long __attribute__((address_space(4))) hdt_cmask_t;
 
 __device__ __forceinline__ void apply_mask(f32x16 &x, const unsigned long long *mask, float fill)
 {
     hdt_cmask_t *cm = (hdt_cmask_t *)(uintptr_t)mask;
 #pragma unroll
-    for (int e = 0; e < 16; e++) {
-        const unsigned long long m = cm[e];
-        float r;
-        asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(fill), "v"(x[e]), "s"(m));
-        x[e] = r;
-    }
+    for (int e = 0; e < 16; e++) x[e] = __builtin_amdgcn_inverse_ballot_w64(cm[e]) ? x[e] : fill;
 }
 
 }  // namespace hdt_tile
