@@ -199,7 +199,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kn = lane & 31, hf = lane >> 5;
+    const int hf = lane >> 5;
     const unsigned lb = logical_block(blockIdx.x, gridDim.x);
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     const size_t base = (size_t)bh * s.n_pos * D;
@@ -221,8 +221,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     pipe.b = d_o + base;
     pipe.aux0 = lse + (size_t)bh * s.n_pos;
     pipe.aux1 = delta + (size_t)bh * s.n_pos;
-    // this lane's key row, document order
-    const int krow = I * BM + wave * 32 + kn;
     const RowLane rl = row_lane(lane);
     const TrLane tl = tr_lane(lane);
 
