@@ -20,7 +20,11 @@
  *   - the key order "sorted by hierarchy level" and the block partition with
  *     the skip-empty-blocks rule (Sec. 3.2 last paragraphs; App. A.1, Alg. 1
  *     steps "Sort K, V", "Partition", "If non-zero values in M"), by brute force
- *     over all pairs of every block.
+ *     over all pairs of every block;
+ *   - per-query-block key lists (the keys any row of the block may attend to, in
+ *     that key order, cut into entries of a fixed number of keys), again by brute
+ *     force: the library's default schedule, a refinement of the fixed windows
+ *     that the paper's closing remark of Sec. 3.2 on better permutations invites.
  *
  * Readings where the paper is silent (each also listed in the design notes):
  *   - a position attends to itself (M^SENT_ii = 1);
@@ -33,7 +37,8 @@
  * Every function has pins in tests/ that do not come from this file: masks
  * enumerated by hand, the paper's three mask equations on index vectors, dense
  * softmax attention for a one-group document, closed-form row counts, closed
- * forms for Q = 0, central finite differences for the gradients.
+ * forms for Q = 0, central finite differences for the gradients, key lists written
+ * out by hand for a 16-position document.
  */
 #include <math.h>
 #include <stdint.h>
@@ -255,6 +260,70 @@ void oracle_block_bitmaps(const int32_t *level, const int32_t *parent, const int
                 if (s >= n) break;
                 if (oracle_allowed(level, parent, i, kperm[s]))
                     bw[r * wpr + c / 32] |= (uint32_t)1 << (c % 32);
+            }
+        }
+    }
+}
+
+/* ---- key lists per query block (the library's default schedule) ----------
+ *
+ * A refinement of the block schedule above that the paper leaves open ("more advanced
+ * permutation algorithms", Sec. 3.2 last paragraph): instead of cutting the level-sorted key
+ * order into fixed windows shared by all query blocks, every query block I gets its OWN list
+ *     U_I = { j : some row i of block I may attend to j },
+ * written in key order (the order of kperm: level by level, ties in document order), and that
+ * list is cut into entries of bn keys; the last entry of a block is filled up with -1.
+ * The result of attention does not depend on this choice (softmax over a set of keys). */
+
+/* ucount[I] = |U_I| for every query block of bm rows; tr = ceil(n/bm) values. */
+void oracle_keylist_counts(const int32_t *level, const int32_t *parent, int64_t n, int64_t bm,
+                           int32_t *ucount)
+{
+    int64_t tr = (n + bm - 1) / bm;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t I = 0; I < tr; I++) {
+        int32_t u = 0;
+        for (int64_t j = 0; j < n; j++) {
+            int any = 0;
+            for (int64_t i = I * bm; i < (I + 1) * bm && i < n && !any; i++)
+                any = oracle_allowed(level, parent, i, j);
+            u += any;
+        }
+        ucount[I] = u;
+    }
+}
+
+/* entry_ptr[tr+1]: entries of block I are [entry_ptr[I], entry_ptr[I+1]), with
+ * entry_ptr[I+1] - entry_ptr[I] = ceil(ucount[I] / bn).  Writes, for every entry e,
+ *   keys[e*bn + c]  = c-th key of the entry (document position), -1 past the end of U_I,
+ *   bits[(e*bm + r)*wpr + c/32] bit c%32  <=>  row I*bm + r may attend to keys[e*bn + c]
+ *                                              (wpr = ceil(bn/32) words per row),
+ *   pairs[e]        = number of set bits of the entry. */
+void oracle_keylist_fill(const int32_t *level, const int32_t *parent, const int32_t *kperm,
+                         int64_t n, int64_t bm, int64_t bn, const int64_t *entry_ptr,
+                         int32_t *keys, uint32_t *bits, int32_t *pairs)
+{
+    int64_t tr = (n + bm - 1) / bm, wpr = (bn + 31) / 32;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t I = 0; I < tr; I++) {
+        int64_t e0 = entry_ptr[I], e1 = entry_ptr[I + 1];
+        for (int64_t t = e0 * bn; t < e1 * bn; t++) keys[t] = -1;
+        memset(bits + e0 * bm * wpr, 0, (size_t)((e1 - e0) * bm * wpr) * sizeof(uint32_t));
+        for (int64_t e = e0; e < e1; e++) pairs[e] = 0;
+        int64_t u = 0; /* keys of U_I found so far */
+        for (int64_t s = 0; s < n; s++) { /* key order */
+            int64_t j = kperm[s];
+            int any = 0;
+            for (int64_t i = I * bm; i < (I + 1) * bm && i < n; i++) {
+                if (!oracle_allowed(level, parent, i, j)) continue;
+                int64_t e = e0 + u / bn, c = u % bn, r = i - I * bm;
+                bits[(e * bm + r) * wpr + c / 32] |= (uint32_t)1 << (c % 32);
+                pairs[e]++;
+                any = 1;
+            }
+            if (any) {
+                keys[(e0 + u / bn) * bn + u % bn] = (int32_t)j;
+                u++;
             }
         }
     }

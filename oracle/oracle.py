@@ -60,6 +60,10 @@ def _load():
         lib.oracle_block_scan.restype = None
         lib.oracle_block_bitmaps.argtypes = [i32p, i32p, i32p, i64, i64, i64, i64, i32p, i32p, u32p]
         lib.oracle_block_bitmaps.restype = None
+        lib.oracle_keylist_counts.argtypes = [i32p, i32p, i64, i64, i32p]
+        lib.oracle_keylist_counts.restype = None
+        lib.oracle_keylist_fill.argtypes = [i32p, i32p, i32p, i64, i64, i64, i64p, i32p, u32p, i32p]
+        lib.oracle_keylist_fill.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -174,6 +178,7 @@ class BlockSchedule:
     k_rows: np.ndarray
     k_tile: np.ndarray  # index into the q-ordered block list of each transposed entry
     nnz: int
+    q_keys: np.ndarray = None  # int32 [n_blocks][bn]: document position behind every key slot, -1 for pads / past n
 
 
 def block_schedule(level, parent, bm: int, bn: int, use_sort: bool = True, force_dense: bool = False) -> BlockSchedule:
@@ -219,6 +224,70 @@ def block_schedule(level, parent, bm: int, bn: int, use_sort: bool = True, force
     k_rows = bi[order].astype(np.int32)
     k_colptr = np.zeros(tc + 1, dtype=np.int32)
     np.cumsum(alive.sum(axis=0), out=k_colptr[1:])
+    # the positions behind the key slots of every block (pads and slots past n: -1)
+    kp_pad = np.full(tc * bn, -1, dtype=np.int32)
+    kp_pad[:n] = np.where(level[kp] >= 0, kp, -1) if n else kp
+    q_keys = kp_pad.reshape(tc, bn)[bj] if nb else np.zeros((0, bn), np.int32)
     return BlockSchedule(bm=bm, bn=bn, kperm=kp, q_rowptr=q_rowptr, q_cols=bj, q_full=q_full, q_sub=q_sub,
                          bits=bits, k_colptr=k_colptr, k_rows=k_rows, k_tile=order.astype(np.int32),
-                         nnz=int(count.sum()))
+                         nnz=int(count.sum()), q_keys=q_keys)
+
+
+def _sub_summary(bits: np.ndarray, bm: int, bn: int) -> np.ndarray:
+    """Per entry: bit r*(bn/32)+c set iff 32x32 sub-block (r, c) of the bitmap holds a set bit; bit
+    16 + r*(bn/32)+c iff all of its bits are set."""
+    nb, wpr = bits.shape[0], bn // 32
+    sub = np.zeros(nb, dtype=np.uint32)
+    for r in range(bm // 32):
+        for c in range(wpr):
+            words = bits[:, r * 32:(r + 1) * 32, c] if nb else np.zeros((0, 32), np.uint32)
+            sub |= ((words != 0).any(axis=1).astype(np.uint32) << np.uint32(r * wpr + c))
+            sub |= ((words == 0xFFFFFFFF).all(axis=1).astype(np.uint32) << np.uint32(16 + r * wpr + c))
+    return sub
+
+
+@dataclass
+class KeyListSchedule:
+    """Per-query-block key lists of one sample (see ``oracle_keylist_fill``): entries
+    [q_rowptr[I], q_rowptr[I+1]) belong to query block I; entry e holds the keys ``q_keys[e]``
+    (document positions in key order, -1 past the end of the block's list) and the bitmap
+    ``bits[e]`` (uint32 [bm][ceil(bn/32)], bit c%32 of word c/32 <=> row r may attend to key c).
+    ``q_sub`` as in BlockSchedule (only when bm and bn are multiples of 32)."""
+    bm: int
+    bn: int
+    kperm: np.ndarray
+    q_rowptr: np.ndarray
+    q_keys: np.ndarray
+    bits: np.ndarray
+    pairs: np.ndarray
+    q_sub: np.ndarray
+    nnz: int
+
+
+def keylist_schedule(level, parent, bm: int, bn: int, use_sort: bool = True) -> KeyListSchedule:
+    """Brute-force key lists of every query block of one sample."""
+    level, parent = _i32(level), _i32(parent)
+    n = level.shape[0]
+    kp = kperm(level) if use_sort else np.arange(n, dtype=np.int32)
+    tr, wpr = -(-n // bm), -(-bn // 32)
+    lib = _load()
+    ucount = np.zeros(max(tr, 1), dtype=np.int32)
+    if n:
+        lib.oracle_keylist_counts(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), n, bm,
+                                  _p(ucount, ctypes.c_int32))
+    ucount = ucount[:tr]
+    entry_ptr = np.zeros(tr + 1, dtype=np.int64)
+    np.cumsum(-(-ucount.astype(np.int64) // bn), out=entry_ptr[1:])
+    E = int(entry_ptr[-1])
+    keys = np.zeros((max(E, 1), bn), dtype=np.int32)
+    bits = np.zeros((max(E, 1), bm, wpr), dtype=np.uint32)
+    pairs = np.zeros(max(E, 1), dtype=np.int32)
+    if n:
+        kp_c = np.ascontiguousarray(kp)
+        lib.oracle_keylist_fill(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), _p(kp_c, ctypes.c_int32),
+                                n, bm, bn, _p(entry_ptr, ctypes.c_int64), _p(keys, ctypes.c_int32),
+                                _p(bits, ctypes.c_uint32), _p(pairs, ctypes.c_int32))
+    keys, bits, pairs = keys[:E], bits[:E], pairs[:E]
+    q_sub = _sub_summary(bits, bm, bn) if (bm % 32 == 0 and bn % 32 == 0) else np.zeros(E, np.uint32)
+    return KeyListSchedule(bm=bm, bn=bn, kperm=kp, q_rowptr=entry_ptr.astype(np.int32), q_keys=keys, bits=bits,
+                           pairs=pairs, q_sub=q_sub, nnz=int(pairs.sum()))

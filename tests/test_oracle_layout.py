@@ -111,3 +111,135 @@ def test_force_dense_issues_every_block(oracle):
     sch = oracle.block_schedule(wl.level[0], wl.parent[0], 128, 64, force_dense=True)
     assert sch.q_cols.shape[0] == (512 // 128) * (512 // 64)
     assert sch.q_rowptr.tolist() == [0, 8, 16, 24, 32]
+
+
+# ---- per-query-block key lists (the library's default schedule) ---------------------------------
+
+def _read_golden_keylists(name):
+    import os
+    from helpers import GOLDEN
+    bm = bn = None
+    rowptr, keys, rows = None, [], []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            tok = line.split()
+            if tok[0] == "bm":
+                bm = int(tok[1])
+            elif tok[0] == "bn":
+                bn = int(tok[1])
+            elif tok[0] == "rowptr":
+                rowptr = [int(t) for t in tok[1:]]
+            elif tok[0] == "entry":
+                keys.append([int(t) for t in tok[1:]])
+                rows.append([])
+            else:
+                rows[-1].append([int(c) for c in line])
+    return bm, bn, np.array(rowptr), np.array(keys, np.int32), np.array(rows, np.uint8)
+
+
+def _unpack(bits, bn):
+    """uint32 [E][bm][wpr] -> 0/1 [E][bm][bn]"""
+    b = (bits[:, :, :, None] >> np.arange(32, dtype=np.uint32)) & 1
+    return b.reshape(bits.shape[0], bits.shape[1], -1)[:, :, :bn].astype(np.uint8)
+
+
+def test_keylists_hand_written(oracle):
+    level, parent, _, _ = read_golden_mask("mask_doc16.txt")
+    bm, bn, rowptr, keys, rows = _read_golden_keylists("keylists_doc16.txt")
+    sch = oracle.keylist_schedule(level, parent, bm, bn)
+    np.testing.assert_array_equal(sch.q_rowptr, rowptr)
+    np.testing.assert_array_equal(sch.q_keys, keys)
+    np.testing.assert_array_equal(_unpack(sch.bits, bn), rows)
+    np.testing.assert_array_equal(sch.pairs, rows.reshape(rows.shape[0], -1).sum(axis=1))
+
+
+def _check_keylists_against_dense_mask(sch, M, kperm, bm, bn):
+    """Everything the definition fixes, derived from a dense mask that is pinned elsewhere:
+    the lists hold exactly the non-empty key columns of each query block, in key order, packed
+    without gaps, and the bitmaps put back together give the mask."""
+    n = M.shape[0]
+    tr = -(-n // bm)
+    slot = np.empty(n, dtype=np.int64)
+    slot[kperm] = np.arange(n)
+    rebuilt = np.zeros_like(M)
+    dense_bits = _unpack(sch.bits, bn)
+    assert sch.q_rowptr[0] == 0 and len(sch.q_rowptr) == tr + 1
+    for I in range(tr):
+        blk = M[I * bm:(I + 1) * bm]
+        want = kperm[np.nonzero(blk[:, kperm].any(axis=0))[0]]      # non-empty columns, key order
+        e0, e1 = sch.q_rowptr[I], sch.q_rowptr[I + 1]
+        assert e1 - e0 == -(-len(want) // bn)
+        flat = sch.q_keys[e0:e1].reshape(-1)
+        np.testing.assert_array_equal(flat[:len(want)], want)
+        assert (flat[len(want):] == -1).all()
+        assert (np.diff(slot[flat[:len(want)]]) > 0).all()
+        for e in range(e0, e1):
+            for c in range(bn):
+                j = sch.q_keys[e, c]
+                col = dense_bits[e, :, c]
+                if j < 0:
+                    assert col.sum() == 0
+                else:
+                    assert rebuilt[I * bm:(I + 1) * bm, j].sum() == 0     # a key appears once per block
+                    rebuilt[I * bm:(I + 1) * bm, j] = col[:blk.shape[0]]
+                    assert col[blk.shape[0]:].sum() == 0                   # rows past n
+                    assert col.sum() > 0
+    np.testing.assert_array_equal(rebuilt, M)
+    assert sch.nnz == M.sum()
+    np.testing.assert_array_equal(sch.pairs, dense_bits.reshape(dense_bits.shape[0], -1).sum(axis=1))
+
+
+@pytest.mark.parametrize("bm,bn", [(128, 64), (32, 32), (64, 96), (128, 128)])
+def test_keylists_against_equation_mask(oracle, bm, bn):
+    wl = inputs.make_workload(1)
+    M = mask_from_equations(wl.sections[0], wl.n_pos)
+    level = wl.level[0]
+    kp = np.argsort(np.where(level < 0, np.iinfo(np.int32).max, level), kind="stable")
+    sch = oracle.keylist_schedule(level, wl.parent[0], bm, bn)
+    _check_keylists_against_dense_mask(sch, M, kp, bm, bn)
+    # sub-block summaries from the unpacked bitmaps
+    d = _unpack(sch.bits, bn)
+    for e in range(d.shape[0]):
+        for r in range(bm // 32):
+            for c in range(bn // 32):
+                sb = d[e, r * 32:(r + 1) * 32, c * 32:(c + 1) * 32]
+                bit = r * (bn // 32) + c
+                assert ((sch.q_sub[e] >> bit) & 1) == sb.any()
+                assert ((sch.q_sub[e] >> (16 + bit)) & 1) == sb.all()
+
+
+@pytest.mark.parametrize("name", ["mask_doc16.txt", "mask_tree10.txt"])
+def test_keylists_against_hand_masks(oracle, name):
+    level, parent, kperm, M = read_golden_mask(name)
+    for bm, bn in [(4, 4), (3, 5), (32, 32)]:
+        sch = oracle.keylist_schedule(level, parent, bm, bn)
+        _check_keylists_against_dense_mask(sch, M, kperm, bm, bn)
+
+
+def test_keylists_without_sort_list_keys_in_document_order(oracle):
+    level, parent, _, M = read_golden_mask("mask_doc16.txt")
+    sch = oracle.keylist_schedule(level, parent, 4, 4, use_sort=False)
+    _check_keylists_against_dense_mask(sch, M, np.arange(16), 4, 4)
+
+
+def test_keylists_need_fewer_entries_than_windows(oracle):
+    # the point of the refinement: fewer gathered key tiles for the same mask
+    for cfg in (2, 3):
+        wl = inputs.make_workload(cfg, batch=1)
+        a = oracle.keylist_schedule(wl.level[0], wl.parent[0], 128, 64)
+        b = oracle.block_schedule(wl.level[0], wl.parent[0], 128, 64)
+        assert a.q_keys.shape[0] < 0.75 * b.q_cols.shape[0]
+        assert a.nnz == b.nnz
+
+
+def test_window_schedule_key_positions(oracle):
+    # positions behind the key slots of the windowed schedule: kperm cut into windows, pads -> -1
+    level, parent, kperm, _ = read_golden_mask("mask_doc16.txt")
+    level = np.concatenate([level, np.full(48, -1, np.int32)])
+    parent = np.concatenate([parent, np.full(48, -1, np.int32)])
+    sch = oracle.block_schedule(level, parent, 32, 32)
+    assert sch.q_cols.tolist() == [0]
+    assert sch.q_keys[0].tolist() == kperm[:12].tolist() + [-1] * 20
