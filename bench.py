@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--windowed", action="store_true",
+                    help="key tiles = fixed windows of the level-sorted key order (Alg. 1 as printed) instead of "
+                         "the default per-query-tile key lists")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events (for external profilers)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -81,7 +84,7 @@ def main() -> int:
             outs.update(dq=torch.empty_like(t[0]), dk=torch.empty_like(t[0]), dv=torch.empty_like(t[0]))
         sets.append((t, outs))
     del xs
-    probe = hdt.hdt_build_layout(level, parent)
+    probe = hdt.hdt_build_layout(level, parent, windowed=args.windowed)
     info = probe.info()
     ws_bytes = hdt.hdt_attn_bwd_workspace_bytes(probe, H, D, 0)
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
@@ -89,7 +92,7 @@ def main() -> int:
 
     def step(i):
         t, outs = sets[i % n_sets]
-        lay = hdt.hdt_build_layout(level, parent)
+        lay = hdt.hdt_build_layout(level, parent, windowed=args.windowed)
         hdt.hdt_attn_fwd(lay, t[0], t[1], t[2], scale, o=outs["o"], lse=outs["lse"])
         if do_bwd:
             hdt.hdt_attn_bwd(lay, t[0], t[1], t[2], outs["o"], outs["lse"], t[3], scale, dq=outs["dq"],
@@ -178,7 +181,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "batch": B, "heads": H, "head_dim": D,
-                   "n_pos": N, "real_positions": wl.n_real, "tile": "128x64", "n_tiles": n_tiles, "nnz": nnz},
+                   "n_pos": N, "real_positions": wl.n_real, "tile": "128x64",
+                   "schedule": "windowed" if args.windowed else "key-lists", "n_tiles": n_tiles, "nnz": nnz},
         "useful_tflops": round(useful_flop / (ms_per_step * 1e-3) / 1e12, 3),
         "phase_us_per_step": {k: round(v, 2) for k, v in phase_us.items()},
         "kernels": {n: {"launches": kv["launches"], "avg_us": round(kv["avg_us"], 2)} for n, kv in per_kernel.items()},

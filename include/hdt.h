@@ -63,12 +63,16 @@ typedef struct {
     int32_t tile_n;      /* key slots per tile,   0 = default (64);  multiple of 32, <= 128   */
     int32_t force_dense; /* 1: issue every tile (dense masked-attention baseline)             */
     int32_t no_sort;     /* 1: keep keys in document order (block-sparse baseline w/o sort)   */
+    int32_t windowed;    /* 1: key tiles are fixed windows of the key order (Alg. 1 as printed); */
+                         /* 0: every query tile gets its own packed key list (default)         */
 } hdt_layout_opts_t;
 
 typedef struct {
     int32_t batch, n_pos, tile_m, tile_n;
     int32_t q_tiles, k_tiles; /* per sample: ceil(n_pos/tile_m), ceil(n_pos/tile_n)  */
-    int64_t n_tiles;          /* surviving tiles, summed over the batch              */
+    int32_t windowed;         /* 1: fixed key windows, 0: per-query-tile key lists   */
+    int32_t reserved;
+    int64_t n_tiles;          /* surviving tiles (list entries), summed over the batch */
     int64_t nnz;              /* allowed (query, key) pairs, summed over the batch   */
     int64_t device_bytes;     /* device memory held by the layout                    */
 } hdt_layout_info_t;
@@ -86,13 +90,21 @@ typedef struct {
  *   out      receives the layout; destroy it with hdt_layout_destroy
  *
  * The schedule, per sample:
- *   kperm    key order: positions sorted by level (0, 1, 2, ...; pads last), ties in document order;
- *   tile (I, J) = query rows [I*tile_m, (I+1)*tile_m) in document order x key slots
- *            [J*tile_n, (J+1)*tile_n) in kperm order; it survives iff some pair in it is allowed:
- *            allowed(i, j) = both non-pad and (i == j, or parent[i] == parent[j] >= 0,
- *                            or parent[i] == j, or parent[j] == i);
- *   per surviving tile: its column, a bitmap of the allowed pairs and a summary of its 32x32
- *            sub-blocks; lists by query tile (columns ascending) and the transpose by key tile.
+ *   kperm    key order: positions sorted by level (0, 1, 2, ...; pads last), ties in document order
+ *            (document order throughout with no_sort);
+ *   allowed(i, j) = both non-pad and (i == j, or parent[i] == parent[j] >= 0, or parent[i] == j,
+ *            or parent[j] == i);
+ *   a tile = tile_m consecutive query rows [I*tile_m, (I+1)*tile_m) in document order x tile_n keys.
+ *   windowed = 1 (Alg. 1 as printed): the keys of tile (I, J) are the slots [J*tile_n, (J+1)*tile_n)
+ *            of the key order; the tile survives iff some pair in it is allowed; the tiles of a
+ *            query tile are listed with J ascending.
+ *   windowed = 0 (default): query tile I lists U_I = { j : some row of the tile may attend to j } in
+ *            key order and cuts that list into tiles of tile_n keys (the last one filled up with
+ *            "no key"); no tile is empty and no key without an allowed pair is ever gathered.  This is
+ *            the same partition of the same mask with fewer, fuller tiles (the paper's closing remark
+ *            of Sec. 3.2 leaves better permutations open); the attention results are identical.
+ *   per tile: the document position behind each of its tile_n key slots, a bitmap of the allowed
+ *            pairs and a summary of its 32x32 sub-blocks.  force_dense implies windowed.
  *
  * Enqueues kernels on `stream` and returns as soon as the first of them has reported, through pinned
  * host memory, that the hierarchy is valid and how many tiles the lists need: the call waits for that
@@ -122,21 +134,25 @@ hdt_status_t hdt_layout_sample_info(const hdt_layout_t *layout, int32_t sample, 
 /*
  * hdt_layout_export -- copy one sample's schedule to host arrays (for inspection and tests).
  * Any output pointer may be NULL.  Sizes, with T = the sample's n_tiles:
- *   h_kperm    int32  [n_pos]        sorted slot -> position
+ *   h_kperm    int32  [n_pos]        key order: sorted slot -> position
  *   h_q_rowptr int32  [q_tiles + 1]  tiles of query tile I are entries [q_rowptr[I], q_rowptr[I+1])
- *   h_q_cols   int32  [T]            key tile of each entry, ascending inside a query tile
+ *   h_q_cols   int32  [T]            windowed: key window J of each entry, ascending inside a query tile;
+ *                                    otherwise the ordinal of the entry inside its query tile
+ *   h_q_keys   int32  [T][tile_n]    document position behind every key slot of every entry; -1 where the
+ *                                    slot holds no key (pads, slots past n_pos, the tail of a key list)
  *   h_q_sub    uint32 [T]            32x32 sub-block (r, c) -> bit r*(tile_n/32)+c: bits 0..15 set iff the
  *                                    sub-block holds an allowed pair, bits 16..31 iff all its pairs are allowed
  *   h_bits     uint32 [T][tile_m][tile_n/32]  bitmap, word r*(tile_n/32)+c/32, bit c%32 <=> row r, slot c allowed
- *   h_k_colptr int32  [k_tiles + 1]  transpose: entries of key tile J
- *   h_k_rows   int32  [T]            query tile of each transposed entry, ascending inside a key tile
+ *   h_k_colptr int32  [k_tiles + 1]  windowed layouts only: the transpose, entries of key window J
+ *   h_k_rows   int32  [T]            query tile of each transposed entry, ascending inside a key window
  *   h_k_tile   int32  [T]            index (into the q-ordered entries) of each transposed entry
- * `tile_capacity` is the number of entries the T-sized arrays can hold; HDT_ERR_SHAPE if too small.
+ * `tile_capacity` is the number of entries the T-sized arrays can hold; HDT_ERR_SHAPE if too small;
+ * HDT_ERR_UNSUPPORTED if one of the h_k_* arrays is asked of a layout that is not windowed.
  * Synchronises the device.
  */
 hdt_status_t hdt_layout_export(const hdt_layout_t *layout, int32_t sample, int32_t *h_kperm,
-                               int32_t *h_q_rowptr, int32_t *h_q_cols, uint32_t *h_q_sub, uint32_t *h_bits,
-                               int32_t *h_k_colptr, int32_t *h_k_rows, int32_t *h_k_tile,
+                               int32_t *h_q_rowptr, int32_t *h_q_cols, int32_t *h_q_keys, uint32_t *h_q_sub,
+                               uint32_t *h_bits, int32_t *h_k_colptr, int32_t *h_k_rows, int32_t *h_k_tile,
                                int64_t tile_capacity);
 
 /* Destroys the layout.  NULL is accepted.  Its device buffers go to a cache (at most 16 buffers /
@@ -150,7 +166,8 @@ hdt_status_t hdt_release_cached_memory(void);
 
 /*
  * hdt_attn_fwd -- forward pass over the surviving tiles (App. A.1, Alg. 1: per query tile, loop
- * over its key tiles, mask, online softmax, accumulate P V; O and the softmax statistics are
+ * over its key tiles, gathered row by row through the layout's key positions, mask, online softmax,
+ * accumulate P V; O and the softmax statistics are
  * written once at the end instead of once per key tile).
  *
  *   q, k, v  device, [batch][heads][n_pos][head_dim], dtype `dt`

@@ -32,13 +32,13 @@ class HdtError(RuntimeError):
 
 class _Opts(ctypes.Structure):
     _fields_ = [("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32), ("force_dense", ctypes.c_int32),
-                ("no_sort", ctypes.c_int32)]
+                ("no_sort", ctypes.c_int32), ("windowed", ctypes.c_int32)]
 
 
 class _Info(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_pos", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("q_tiles", ctypes.c_int32), ("k_tiles", ctypes.c_int32),
-                ("n_tiles", ctypes.c_int64), ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("windowed", ctypes.c_int32), ("reserved", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
 
 
 def library_path() -> str:
@@ -64,7 +64,7 @@ def load_library():
     lib.hdt_layout_info.restype = ctypes.c_int
     lib.hdt_layout_sample_info.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.hdt_layout_sample_info.restype = ctypes.c_int
-    lib.hdt_layout_export.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i64]
+    lib.hdt_layout_export.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64]
     lib.hdt_layout_export.restype = ctypes.c_int
     lib.hdt_layout_destroy.argtypes = [vp]
     lib.hdt_layout_destroy.restype = ctypes.c_int
@@ -137,15 +137,19 @@ class Layout:
         n, tr, tc, bm, bn = inf["n_pos"], inf["q_tiles"], inf["k_tiles"], inf["tile_m"], inf["tile_n"]
         out = dict(
             kperm=np.zeros(max(n, 1), np.int32), q_rowptr=np.zeros(tr + 1, np.int32),
-            q_cols=np.zeros(max(T, 1), np.int32), q_sub=np.zeros(max(T, 1), np.uint32),
-            bits=np.zeros((max(T, 1), bm, bn // 32), np.uint32), k_colptr=np.zeros(tc + 1, np.int32),
-            k_rows=np.zeros(max(T, 1), np.int32), k_tile=np.zeros(max(T, 1), np.int32))
+            q_cols=np.zeros(max(T, 1), np.int32), q_keys=np.zeros((max(T, 1), bn), np.int32),
+            q_sub=np.zeros(max(T, 1), np.uint32), bits=np.zeros((max(T, 1), bm, bn // 32), np.uint32))
+        if inf["windowed"]:  # only a windowed layout has a transpose by key window
+            out.update(k_colptr=np.zeros(tc + 1, np.int32), k_rows=np.zeros(max(T, 1), np.int32),
+                       k_tile=np.zeros(max(T, 1), np.int32))
         p = {k: ctypes.c_void_p(v.ctypes.data) for k, v in out.items()}
-        _check(load_library().hdt_layout_export(self._h, sample, p["kperm"], p["q_rowptr"], p["q_cols"], p["q_sub"],
-                                                p["bits"], p["k_colptr"], p["k_rows"], p["k_tile"], max(T, 1)))
+        _check(load_library().hdt_layout_export(self._h, sample, p["kperm"], p["q_rowptr"], p["q_cols"], p["q_keys"],
+                                                p["q_sub"], p["bits"], p.get("k_colptr"), p.get("k_rows"),
+                                                p.get("k_tile"), max(T, 1)))
         out["kperm"] = out["kperm"][:n]
-        for key in ("q_cols", "q_sub", "bits", "k_rows", "k_tile"):
-            out[key] = out[key][:T]
+        for key in ("q_cols", "q_keys", "q_sub", "bits", "k_rows", "k_tile"):
+            if key in out:
+                out[key] = out[key][:T]
         return out
 
     def destroy(self):
@@ -161,7 +165,7 @@ class Layout:
 
 
 def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dense: bool = False,
-                     no_sort: bool = False, stream=None) -> Layout:
+                     no_sort: bool = False, windowed: bool = False, stream=None) -> Layout:
     """level, parent: int32 device tensors [batch][n_pos]."""
     import torch
     if level.dtype != torch.int32 or parent.dtype != torch.int32:
@@ -170,7 +174,7 @@ def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dens
         raise ValueError("level and parent must both be [batch][n_pos]")
     if not (level.is_cuda and parent.is_cuda and level.is_contiguous() and parent.is_contiguous()):
         raise ValueError("level and parent must be contiguous device tensors")
-    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort))
+    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort), int(windowed))
     h = ctypes.c_void_p(0)
     B, N = level.shape
     _check(load_library().hdt_build_layout(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,

@@ -133,6 +133,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(c
     info->tile_n = l->s.bn;
     info->q_tiles = l->s.tr;
     info->k_tiles = l->s.tc;
+    info->windowed = l->windowed;
+    info->reserved = 0;
     info->n_tiles = 0;
     info->nnz = 0;
     for (int b = 0; b < l->s.batch; b++) {
@@ -157,8 +159,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_sample
 }
 
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export(
-    const hdt_layout_t *layout, int32_t sample, int32_t *kperm, int32_t *q_rowptr, int32_t *q_cols, uint32_t *q_sub,
-    uint32_t *bits, int32_t *k_colptr, int32_t *k_rows, int32_t *k_tile, int64_t tile_capacity)
+    const hdt_layout_t *layout, int32_t sample, int32_t *kperm, int32_t *q_rowptr, int32_t *q_cols, int32_t *q_keys,
+    uint32_t *q_sub, uint32_t *bits, int32_t *k_colptr, int32_t *k_rows, int32_t *k_tile, int64_t tile_capacity)
 {
     if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_export: invalid layout");
     const HdtSchedule &s = layout->s;
@@ -166,7 +168,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: sample %d outside [0, %d)", sample, s.batch);
     if (hdt_status_t st = hdt_layout_stats(layout)) return st;
     const int64_t T = layout->h_stats[2 * (size_t)sample];
-    const bool want_tiles = q_cols || q_sub || bits || k_rows || k_tile;
+    if ((k_colptr || k_rows || k_tile) && !layout->windowed)
+        return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_layout_export: only a windowed layout has a transpose by key window");
+    const bool want_tiles = q_cols || q_keys || q_sub || bits || k_rows || k_tile;
     if (want_tiles && tile_capacity < T)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: capacity %lld < %lld tiles", (long long)tile_capacity,
                         (long long)T);
@@ -184,7 +188,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
     std::vector<int32_t> cols((size_t)E), cnt((size_t)E);
     std::vector<uint32_t> sub((size_t)E);
     if (E > 0) {
-        HDT_HIP_TRY(hipMemcpy(cols.data(), s.q_cols, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
+        if (layout->windowed)
+            HDT_HIP_TRY(hipMemcpy(cols.data(), s.q_cols, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
         HDT_HIP_TRY(hipMemcpy(cnt.data(), layout->d_cnt, sizeof(int32_t) * E, hipMemcpyDeviceToHost));
         HDT_HIP_TRY(hipMemcpy(sub.data(), s.q_sub, sizeof(uint32_t) * E, hipMemcpyDeviceToHost));
     }
@@ -194,7 +199,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
             return hdt_fail(HDT_ERR_HIP, "hdt_layout_export: corrupt list range of query tile %d", I);
         for (int32_t e = rg[2 * I]; e < rg[2 * I + 1]; e++)
             if (cnt[e] > 0 || layout->force_dense) {
-                keep_col.push_back(cols[e]);
+                keep_col.push_back(layout->windowed ? cols[e] : e - rg[2 * I]);
                 keep_row.push_back(I);
                 keep_entry.push_back(e);
             }
@@ -208,6 +213,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
     for (int64_t t = 0; t < T; t++) {
         if (q_cols) q_cols[t] = keep_col[t];
         if (q_sub) q_sub[t] = sub[keep_entry[t]];
+        if (q_keys)
+            HDT_HIP_TRY(hipMemcpy(q_keys + (size_t)t * s.bn, s.q_keys + (size_t)keep_entry[t] * s.bn,
+                                  sizeof(int32_t) * s.bn, hipMemcpyDeviceToHost));
         if (bits)
             HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + (size_t)keep_entry[t] * words,
                                   sizeof(uint32_t) * words, hipMemcpyDeviceToHost));

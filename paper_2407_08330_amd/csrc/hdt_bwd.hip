@@ -6,15 +6,15 @@
 //         dS = P o (dP - D),  dQ = scale dS K,  dK = scale dS^T Q.
 //
 // Two deterministic passes, no atomics, both with the forward kernel's skeleton (hdt_tile.h):
-//   k_bwd_dq   a workgroup owns a query tile (rows in document order), walks its key tiles (slots of
-//              the level-sorted order, gathered through kperm), recomputes S^T and dP^T with queries
+//   k_bwd_dq   a workgroup owns a query tile (rows in document order), walks its key tiles (the 64 key
+//              positions of each list entry, gathered row by row), recomputes S^T and dP^T with queries
 //              along the MFMA columns (LSE_i and D_i are per-lane scalars) and accumulates
 //              dQ^T = K^T dS^T.  It also writes D.
 //   k_bwd_dkv  the mask is symmetric (i may attend to j iff j may attend to i: parent/child and
-//              sibling relations are mutual), so the tile list of "query rows I x key slots J" is also
-//              the list of "key rows I x query slots J", bitmaps included.  A workgroup therefore owns
+//              sibling relations are mutual), so the entries of "query rows I x the keys they attend to"
+//              are also the entries of "key rows I x the queries attending to them", bitmaps included.  A workgroup therefore owns
 //              128 KEYS in document order (K, V rows in registers), walks the same list, gathers the
-//              Q and dO rows (and LSE, D) of 64 level-sorted QUERY slots into LDS and accumulates
+//              Q and dO rows (and LSE, D) of an entry's 64 QUERY positions into LDS and accumulates
 //              dV^T = dO^T P and dK^T = Q^T dS with keys along the MFMA columns.  Same load balance
 //              as the forward, no transposed lists, no cross-wave reduction, contiguous stores.
 // Both passes recompute the scores, which costs two extra contractions but keeps dQ out of HBM
@@ -69,7 +69,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     const size_t row = (size_t)b * s.tr + I;
     const cptr_i32 range = as_const(s.q_range);
     const int t0 = range[2 * row], n = range[2 * row + 1] - t0;
-    const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
 
     P pipe;
@@ -77,7 +76,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     pipe.smem_addr = lds_addr(smem);
     pipe.wave = wave;
     pipe.lane = lane;
-    pipe.kperm = s.kperm + (size_t)b * s.n_slots;
+    pipe.keys = s.q_keys + (size_t)t0 * BN;
     pipe.a = k + base;
     pipe.b = v + base;
     pipe.aux0 = pipe.aux1 = nullptr;
@@ -92,8 +91,8 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     __shared__ float sDi[BM];
     stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, STG_Q);
     stage_own_rows(pipe, d_o + base, I * BM, s.n_pos, D, STG_DO);
-    R::start(pipe, n, [&](int j) { return cols[j]; });
-    R::template prologue<0, S - 2>(pipe, n, [&](int j) { return cols[j]; });
+    R::start(pipe, n);
+    R::template prologue<0, S - 2>(pipe, n);
     if (S == 2 || n == 0) wait_vmcnt<0>();  // otherwise the prologue's first wait covered the staged rows
 
     // D_i = sum_c dO_ic O_ic from full-row reads: lane (row l/CPR, chunk l%CPR) multiplies 8 values of O
@@ -128,7 +127,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     // the compiler must finish its own loads before the hand-scheduled ones continue
     asm volatile("" ::"v"(Di), "v"(lse2));
     wg_barrier();  // every wave has read its fragments: the ring may use all stages
-    R::template prologue<S - 2, S - 1>(pipe, n, [&](int j) { return cols[j]; });
+    R::template prologue<S - 2, S - 1>(pipe, n);
 
     f32x16 dqacc[DBLK];
 #pragma unroll
@@ -136,7 +135,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
 #pragma unroll
         for (int e = 0; e < 16; e++) dqacc[i][e] = 0.f;
 
-    int col_ahead = (S < n) ? cols[S] : 0;
     uint32_t sub_next = n > 0 ? subs[0] : 0u;
     for (int i = 0; i < n; i++) {
         const uint32_t sub = sub_next;
@@ -146,8 +144,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
         }
         R::top(i, n);
         wg_barrier();
-        R::advance(pipe, i, n, col_ahead);
-        col_ahead = (i + 1 + S < n) ? cols[i + 1 + S] : 0;
+        R::advance(pipe, i, n);
         const char *sK = pipe.tile_a(i % S), *sV = pipe.tile_b(i % S);
 
 #pragma unroll
@@ -208,7 +205,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     const size_t row = (size_t)b * s.tr + I;
     const cptr_i32 range = as_const(s.q_range);
     const int t0 = range[2 * row], n = range[2 * row + 1] - t0;
-    const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
 
     P pipe;
@@ -216,7 +212,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     pipe.smem_addr = lds_addr(smem);
     pipe.wave = wave;
     pipe.lane = lane;
-    pipe.kperm = s.kperm + (size_t)b * s.n_slots;
+    pipe.keys = s.q_keys + (size_t)t0 * BN;
     pipe.a = q + base;
     pipe.b = d_o + base;
     pipe.aux0 = lse + (size_t)bh * s.n_pos;
@@ -228,8 +224,8 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     constexpr uint32_t STG_K = (uint32_t)(S - 1) * 2 * P::TILE, STG_V = (uint32_t)(S - 2) * 2 * P::TILE;
     stage_own_rows(pipe, k + base, I * BM, s.n_pos, D, STG_K);
     stage_own_rows(pipe, v + base, I * BM, s.n_pos, D, STG_V);
-    R::start(pipe, n, [&](int j) { return cols[j]; });
-    R::template prologue<0, S - 2>(pipe, n, [&](int j) { return cols[j]; });
+    R::start(pipe, n);
+    R::template prologue<0, S - 2>(pipe, n);
     if (S == 2 || n == 0) wait_vmcnt<0>();
     bf16x8 kf[KSTEPS], vf[KSTEPS];
 #pragma unroll
@@ -238,7 +234,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
         vf[st] = read_row<ROWB>(smem + STG_V, rl, wave * 32, st);
     }
     wg_barrier();
-    R::template prologue<S - 2, S - 1>(pipe, n, [&](int j) { return cols[j]; });
+    R::template prologue<S - 2, S - 1>(pipe, n);
 
     f32x16 dkacc[DBLK], dvacc[DBLK];
 #pragma unroll
@@ -246,7 +242,6 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
 #pragma unroll
         for (int e = 0; e < 16; e++) dkacc[i][e] = dvacc[i][e] = 0.f;
 
-    int col_ahead = (S < n) ? cols[S] : 0;
     uint32_t sub_next = n > 0 ? subs[0] : 0u;
     for (int i = 0; i < n; i++) {
         const uint32_t sub = sub_next;
@@ -256,8 +251,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
         }
         R::top(i, n);
         wg_barrier();
-        R::advance(pipe, i, n, col_ahead);
-        col_ahead = (i + 1 + S < n) ? cols[i + 1 + S] : 0;
+        R::advance(pipe, i, n);
         const char *sQ = pipe.tile_a(i % S), *sDO = pipe.tile_b(i % S);
         const float *sLse = pipe.aux_buf(i % S, 0), *sDelta = pipe.aux_buf(i % S, 1);
 

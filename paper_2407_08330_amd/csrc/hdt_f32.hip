@@ -24,11 +24,10 @@ __global__ __launch_bounds__(128) void k_fwd_f32(HdtSchedule s, const float *__r
     float m = -INFINITY, l = 0.f;
     const size_t row = (size_t)b * s.tr + I;
     for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
-        const int J = s.q_cols[t];
         const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
-            const int pos = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];
+            const int pos = s.q_keys[(size_t)t * s.bn + c];
             if (pos < 0) continue;
             const float *kj = k + base + (size_t)pos * D;
             const float *vj = v + base + (size_t)pos * D;
@@ -72,11 +71,10 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     for (int c = 0; c < D; c++) acc[c] = 0.f;
     const size_t row = (size_t)b * s.tr + I;
     for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
-        const int J = s.q_cols[t];
         const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
-            const int pos = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];
+            const int pos = s.q_keys[(size_t)t * s.bn + c];
             if (pos < 0) continue;
             const float *kj = k + base + (size_t)pos * D;
             const float *vj = v + base + (size_t)pos * D;
@@ -96,7 +94,7 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
 
 // dK, dV: the mask is symmetric (i may attend to j iff j may attend to i), so the list of query tile I
 // x key slots J is also the list of key rows I x query slots J with the same bitmaps.  One thread per
-// key row (document order) walks that list and gathers the query rows through kperm.
+// key row (document order) walks that list and gathers the query rows its entries name.
 template <int D>
 __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float *__restrict__ q,
                                                      const float *__restrict__ k, const float *__restrict__ v,
@@ -115,11 +113,10 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
     for (int e = 0; e < D; e++) ak[e] = av[e] = 0.f;
     const size_t row = (size_t)b * s.tr + I;
     for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
-        const int J = s.q_cols[t];
         const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
-            const int i = s.kperm[(size_t)b * s.n_slots + J * s.bn + c];  // query position
+            const int i = s.q_keys[(size_t)t * s.bn + c];  // query position
             if (i < 0) continue;
             const float *qi = q + base + (size_t)i * D;
             const float *doi = d_o + base + (size_t)i * D;

@@ -5,8 +5,8 @@
 // statistics stay in registers until the last tile and are written once.
 //
 // Work split: one workgroup (4 waves) per (sample, head, query tile of 128 rows); wave w owns
-// query rows 32w .. 32w+31.  A key tile is 64 slots of the level-sorted key order, gathered row
-// by row through kperm straight into LDS (hdt_tile.h).  Inside a tile a wave works on 32x32
+// query rows 32w .. 32w+31.  A key tile is one list entry of the query tile: 64 key positions in
+// level-sorted order, gathered row by row straight into LDS (hdt_tile.h).  Inside a tile a wave works on 32x32
 // sub-blocks and skips those the layout marks empty.
 //
 // The scores are computed transposed, S^T = K Q^T (keys along the MFMA rows, queries along the
@@ -138,7 +138,6 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const size_t row = (size_t)b * s.tr + I;
     const cptr_i32 range = as_const(s.q_range);
     const int t0 = range[2 * row], n = range[2 * row + 1] - t0;
-    const cptr_i32 cols = as_const(s.q_cols) + t0;
     const cptr_u32 subs = as_const(s.q_sub) + t0;
 
     P pipe;
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     pipe.smem_addr = lds_addr(smem);
     pipe.wave = wave;
     pipe.lane = lane;
-    pipe.kperm = s.kperm + (size_t)b * s.n_slots;
+    pipe.keys = s.q_keys + (size_t)t0 * BN;
     pipe.a = k + base;
     pipe.b = v + base;
     pipe.aux0 = pipe.aux1 = nullptr;
@@ -161,8 +160,8 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     bf16x8 qf[KSTEPS];
     if (n > 0) {
         stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, Q_STAGE);
-        R::start(pipe, n, [&](int j) { return cols[j]; });
-        R::template prologue<0, S - 1>(pipe, n, [&](int j) { return cols[j]; });  // its first wait covers the Q rows
+        R::start(pipe, n);
+        R::template prologue<0, S - 1>(pipe, n);  // its first wait covers the Q rows
 #pragma unroll
         for (int st = 0; st < KSTEPS; st++) qf[st] = read_row<ROWB>(smem + Q_STAGE, rl, wave * 32, st);
     }
@@ -175,7 +174,6 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     float m_ref = -INFINITY, l_part = 0.f;
     const int xlane = (lane ^ 32) << 2;  // ds_bpermute address of the partner lane in the other half-wave
 
-    int col_ahead = (S < n) ? cols[S] : 0;  // column of tile i+S
     uint32_t sub_next = n > 0 ? subs[0] : 0u;
     for (int i = 0; i < n; i++) {
         const uint32_t sub = sub_next;
@@ -185,8 +183,7 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
         }
         R::top(i, n);
         wg_barrier();
-        R::advance(pipe, i, n, col_ahead);
-        col_ahead = (i + 1 + S < n) ? cols[i + 1 + S] : 0;
+        R::advance(pipe, i, n);
         const char *sK = pipe.tile_a(i % S), *sV = pipe.tile_b(i % S);
 
         // this wave's two 32x32 sub-blocks of the tile (wave-uniform flags); one straight-line code path

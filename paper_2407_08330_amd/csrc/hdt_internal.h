@@ -13,19 +13,23 @@
 
 // Device-side view of a tile schedule, passed by value to the attention kernels.
 //
-// The lists hold the CANDIDATE tiles of every query tile, columns ascending.  Every candidate has
-// been evaluated exactly; one that turned out to hold no allowed pair keeps its place in the list with
-// an all-zero summary (q_sub == 0) and all-zero bitmaps, which makes every kernel skip it.  For
-// documents laid out in pre-order there are no such entries; hdt_layout_export filters them out.
+// Every query tile (b, I) owns a contiguous run of list entries; an entry is one key tile: bn key
+// slots, each naming the document position to gather (q_keys, -1 = no key), with the bitmaps of the
+// allowed pairs.  Windowed layouts fill an entry's slots from a window of the key order kperm, the
+// default layouts with the next bn keys of the query tile's own key list; the kernels do not care.
+// In a windowed layout an entry may turn out to hold no allowed pair (only for documents that are not
+// in pre-order); it keeps its place with an all-zero summary (q_sub == 0) and all-zero bitmaps, which
+// makes every kernel skip it, and hdt_layout_export filters it out.
 struct HdtSchedule {
     int32_t batch, n_pos;
     int32_t bm, bn;        // tile shape (query rows x key slots)
     int32_t tr, tc;        // tiles per sample along queries / keys
     int32_t n_slots;       // tc * bn: length of one sample's padded key order
     int32_t wpr;           // bitmap words per tile row = bn / 32
-    const int32_t *kperm;  // [batch][n_slots] sorted slot -> position, -1 beyond n_pos
+    const int32_t *kperm;  // [batch][n_slots] sorted slot -> position, -1 beyond n_pos (not read by the attention kernels)
     const int32_t *q_range;   // [batch][tr][2] first and one-past-last list entry of query tile (b, I)
-    const int32_t *q_cols;    // [entries] key tile of each entry
+    const int32_t *q_cols;    // [entries] windowed layouts: key window of each entry
+    const int32_t *q_keys;    // [entries][bn] document position behind each key slot, -1 = none
     const uint32_t *q_sub;    // [entries] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
     const uint32_t *bits;     // [entries][bm][wpr]   row r, word c/32, bit c%32
     // [entries][(bm/32)*(bn/32)][16] per 32x32 sub-block (r, c) = index r*(bn/32)+c: bit l of word e <=>
@@ -38,6 +42,7 @@ struct hdt_layout {
     HdtSchedule s;       // pointers into the arenas
     int32_t device;      // device the buffers live on
     int32_t force_dense; // every candidate counts as a tile, empty or not
+    int32_t windowed;    // key tiles are windows of the key order (else per-query-tile key lists)
     int64_t capacity;    // entries the per-tile arrays can hold
     int64_t device_bytes;
     void *arena;         // key order, list pointers, scratch of the build

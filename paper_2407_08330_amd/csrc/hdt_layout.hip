@@ -2,7 +2,7 @@
 //
 // What is computed is fixed by the paper (Sec. 3.2: a position attends to parent, siblings and
 // children; App. A.1, Alg. 1: sort keys by hierarchy level, partition into blocks, process a block
-// only if its mask has a non-zero entry).  How it is computed is ours.  Four small kernels:
+// only if its mask has a non-zero entry).  How it is computed is ours.  Four small kernels per build:
 //
 //  sort_count / sort_scatter (one workgroup per 1024 positions)
 //   1. key order: stable counting sort by level with wave ballots; the first kernel counts the levels
@@ -10,19 +10,23 @@
 //      out the slots in document order;
 //   2. per anchor, the range of sorted slots its children occupy (integer atomic min/max, one
 //      pair of atomics per run of consecutive children);
-//  candidates (one wave per query tile)
-//   3. candidate tiles per query tile: every allowed key of a row lies in one of <= 2 slot ranges
+//  key_lists (default; one workgroup per query tile)
+//   3. the key list of the query tile: every allowed key of a row lies in one of <= 2 slot ranges
 //      (its siblings = the children of its parent, and its own children) or is one of 2 single
-//      slots (itself, its parent), so a row marks O(1) ranges instead of testing n keys.  For
-//      documents laid out in pre-order the ranges are exact; for any other forest they are a
-//      superset;
-//   4. a slice of the per-tile arrays reserved with one atomic add per workgroup, and the key tile of
-//      every candidate written out: these ARE the tile lists (first/last entry per query tile);
-//  tile_bitmaps (grid-stride over candidates)
-//   5. every candidate tile is evaluated exactly, pair by pair (bitmap, pair count, 32x32
-//      sub-block summary), so the result never depends on step 3 being tight.  A candidate without
-//      any allowed pair keeps its list entry with an all-zero summary, which every kernel skips;
-//      it is not counted as a tile and hdt_layout_export leaves it out.
+//      slots (itself, its parent), so a row marks O(1) ranges in a bitmap over the key order instead
+//      of testing n keys; every marked slot is then tested exactly against the rows of the tile (for
+//      documents laid out in pre-order the ranges are already exact, for other forests they are a
+//      superset), and the surviving slots are packed, in key order, into entries of tile_n keys;
+//  candidates (windowed layouts; one wave per query tile)
+//   3'. the same marking on the granularity of key windows: the candidate windows of the query tile;
+//   4. either kernel reserves a slice of the per-tile arrays with one atomic add per workgroup and
+//      writes its entries there: these ARE the tile lists (first/last entry per query tile);
+//  tile_bitmaps (grid-stride over entries)
+//   5. every entry is evaluated exactly, pair by pair (bitmap, pair count, 32x32 sub-block summary,
+//      and for windowed layouts the positions behind its key slots), so the result never depends on
+//      step 3 being tight.  A windowed candidate without any allowed pair keeps its list entry with an
+//      all-zero summary, which every kernel skips; it is not counted as a tile and hdt_layout_export
+//      leaves it out.
 //
 // The per-tile arrays are sized before the number of candidates is known (a heuristic, raised by
 // what earlier builds needed); the kernels check the capacity.  The candidate kernel reports the count
@@ -344,9 +348,152 @@ __global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
     }
 }
 
+struct KeyListArgs {
+    const int32_t *level, *parent, *slot, *cmin, *cmax, *kperm;
+    int n, n_slots, bm, bn, tr;
+    int64_t capacity;
+    int32_t *q_range;  // [B][tr][2]
+    int32_t *c_row, *q_keys;
+    int32_t *counters;
+    unsigned long long *report;
+    uint32_t ticket;
+};
+
+constexpr int kListThreads = 256, kListWaves = kListThreads / 64;
+
+// set bits lo..hi of an LDS bitmap
+__device__ __forceinline__ void mark_slots(uint32_t *bits, int lo, int hi) { mark_tiles(bits, lo, hi); }
+
+// ---- key list of every query tile: one workgroup per query tile, a bitmap over the key order in LDS ----
+__global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
+{
+    extern __shared__ uint32_t s_mark[];  // [2 * groups of 64 slots]: marked, later exactly needed, key slots
+    __shared__ int2 s_row[128];           // (position, parent) of the tile's rows, (-2, -2) for pads and rows past n
+    __shared__ int s_cnt[kListWaves];
+    __shared__ int s_base;
+    const int b = blockIdx.x / a.tr, I = blockIdx.x - b * a.tr, n = a.n;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int bm = a.bm, bn = a.bn;
+    const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
+    const int32_t *slot = a.slot + (size_t)b * n, *cmin = a.cmin + (size_t)b * n, *cmax = a.cmax + (size_t)b * n;
+    const int32_t *kperm = a.kperm + (size_t)b * a.n_slots;
+    const int ng = (a.n_slots + 63) >> 6;
+    for (int w = tid; w < 2 * ng; w += kListThreads) s_mark[w] = 0;
+    int i = -2, p = -2;
+    bool ok = false;
+    if (tid < 128) {
+        i = I * bm + tid;
+        ok = tid < bm && i < n;
+        const int ii = ok ? i : 0;
+        const int lv = level[ii];
+        p = parent[ii];
+        ok = ok && lv >= 0;
+        s_row[tid] = ok ? make_int2(i, p) : make_int2(-2, -2);
+    }
+    __syncthreads();
+    if (ok) {
+        // consecutive rows with the same parent (the tokens of a sentence) would mark the same ranges
+        const bool okp = p >= 0 && p < n && level[p] >= 0;
+        const bool first_of_run = tid == 0 || s_row[tid - 1].y != p;
+        const int sl = slot[i];
+        if (sl >= 0 && sl < n) mark_slots(s_mark, sl, sl);  // itself
+        if (okp && first_of_run) {
+            const int sp = slot[p], lo = cmin[p], hi = cmax[p];
+            if (sp >= 0 && sp < n) mark_slots(s_mark, sp, sp);              // its parent
+            if (lo <= hi && lo >= 0 && hi < n) mark_slots(s_mark, lo, hi);  // its siblings: the children of its parent
+        }
+        const int lo = cmin[i], hi = cmax[i];
+        if (lo <= hi && lo >= 0 && hi < n) mark_slots(s_mark, lo, hi);  // its children
+    }
+    __syncthreads();
+    // exact test of every marked slot against the rows of the tile; groups of 64 slots dealt out to the waves
+    for (int g = wave; g < ng; g += kListWaves) {
+        const int s = g * 64 + lane;
+        const bool marked = (s_mark[s >> 5] >> (s & 31)) & 1u;
+        if (__ballot(marked) == 0ull) continue;
+        int j = -3, pj = -3;  // values no row matches
+        if (marked && s < a.n_slots) {
+            const int kj = kperm[s];
+            if (kj >= 0 && kj < n && level[kj] >= 0) {
+                j = kj;
+                pj = parent[kj];
+            }
+        }
+        bool hit = false;
+#pragma unroll 4
+        for (int r = 0; r < bm; r++) {
+            const int2 row = s_row[r];
+            hit |= row.x == j || (row.y >= 0 && row.y == pj) || row.y == j || pj == row.x;
+        }
+        const unsigned long long m = __ballot(hit);
+        if (lane == 0) {
+            s_mark[2 * g] = (uint32_t)m;
+            s_mark[2 * g + 1] = (uint32_t)(m >> 32);
+        }
+    }
+    __syncthreads();
+    // keys of the tile: each wave counts a contiguous quarter of the groups
+    const int gpw = (ng + kListWaves - 1) / kListWaves;
+    const int g0 = min(wave * gpw, ng), g1 = min(g0 + gpw, ng);
+    {
+        int c = 0;
+        for (int w = 2 * g0 + lane; w < 2 * g1; w += 64) c += __popc(s_mark[w]);
+        c = wave_sum(c);
+        if (lane == 0) s_cnt[wave] = c;
+    }
+    __syncthreads();
+    int total = 0, before = 0;
+#pragma unroll
+    for (int w = 0; w < kListWaves; w++) {
+        if (w < wave) before += s_cnt[w];
+        total += s_cnt[w];
+    }
+    const int n_ent = (total + bn - 1) / bn;
+    if (tid == 0) {
+        // this tile's slice of the per-entry arrays
+        s_base = atomicAdd(&a.counters[CNT_CAND], n_ent);
+        // the last workgroup to get here knows the final counters: it tells the host, which is waiting
+        // for exactly this word, while the lists and the bitmaps are still being written
+        __threadfence();
+        if (atomicAdd(&a.counters[CNT_ARRIVED], 1) == (int)gridDim.x - 1) {
+            __threadfence();
+            const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int need = __hip_atomic_load(&a.counters[CNT_CAND], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)need), __ATOMIC_RELEASE,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    __syncthreads();
+    const int64_t base = s_base;
+    const size_t row = (size_t)b * a.tr + I;
+    if (tid == 0) {
+        a.q_range[2 * row] = (int32_t)base;
+        a.q_range[2 * row + 1] = (int32_t)(base + n_ent);
+    }
+    // entries past the capacity are not written (the host then repeats the build with larger arrays); the
+    // ones below it are, because the bitmap kernel evaluates every entry below the capacity
+    const int64_t room = a.capacity - base;
+    const int n_fit = room <= 0 ? 0 : (room < n_ent ? (int)room : n_ent);
+    const int key_fit = n_fit * bn;
+    for (int e = tid; e < n_fit; e += kListThreads) a.c_row[base + e] = (int32_t)row;
+    int32_t *keys = a.q_keys + (size_t)base * bn;
+    for (int t = total + tid; t < key_fit; t += kListThreads) keys[t] = -1;  // tail of the last entry
+    int run = before;
+    for (int g = g0; g < g1; g++) {
+        const int s = g * 64 + lane;
+        const bool set = (s_mark[s >> 5] >> (s & 31)) & 1u;
+        const unsigned long long m = __ballot(set);
+        if (m == 0ull) continue;
+        const int t = run + __popcll(m & lanemask_lt());
+        if (set && t < key_fit) keys[t] = kperm[s];
+        run += __popcll(m);
+    }
+}
+
 // ---- bitmaps: exact evaluation of every candidate tile ------------------------------------------
-// One candidate per workgroup iteration, one row per lane (two waves cover up to 128 rows).  The keys
-// of the tile sit in registers, one or two per lane, and are broadcast by lane index; each lane tests
+// One entry per workgroup iteration, one row per lane (two waves cover up to 128 rows).  The keys
+// of the tile (a window of the key order, which is then also written to q_keys, or the entry's slots of
+// q_keys) sit in registers, one or two per lane, and are broadcast by lane index; each lane tests
 // its row against every key.  Outputs: the row-major bitmap (export, fp32 path), per 32x32 sub-block
 // the 16 x 64-bit lane masks the MFMA kernels apply to their accumulator registers (wave ballots), the
 // pair count and the sub-block summary.
@@ -354,7 +501,8 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
                                                       const int32_t *__restrict__ parent,
                                                       const int32_t *__restrict__ kperm,
                                                       const int32_t *__restrict__ c_row,
-                                                      const int32_t *__restrict__ c_col,
+                                                      const int32_t *__restrict__ c_col, int32_t *q_keys,
+                                                      int windowed,
                                                       const int32_t *__restrict__ counters, int64_t capacity,
                                                       int n, int n_slots, int bm, int bn, int tr, uint32_t *bits,
                                                       unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
@@ -366,7 +514,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
     const size_t words = (size_t)bm * wpr;
     const int64_t total = min((int64_t)counters[CNT_CAND], capacity);
     for (int64_t c = blockIdx.x; c < total; c += gridDim.x) {
-        const int row = c_row[c], J = c_col[c];
+        const int row = c_row[c], J = windowed ? c_col[c] : 0;
         const int b = row / tr, I = row - b * tr;
         const size_t o = (size_t)b * n;
         // keys: lane l holds slots l and 64 + l of the tile
@@ -374,7 +522,10 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
 #pragma unroll
         for (int u = 0; u < 2; u++) {
             const int si = 64 * u + lane, s = J * bn + si;
-            kpos[u] = (si < bn && s < n_slots) ? kperm[(size_t)b * n_slots + s] : -1;
+            if (windowed)
+                kpos[u] = (si < bn && s < n_slots) ? kperm[(size_t)b * n_slots + s] : -1;
+            else
+                kpos[u] = si < bn ? q_keys[(size_t)c * bn + si] : -1;
         }
         // this lane's row
         const int r = wave * 64 + lane, i = I * bm + r;
@@ -389,6 +540,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
             const int lv = level[o + pp], pr = parent[o + pp];
             kpos[u] = (okp && lv >= 0) ? kpos[u] : -1;
             kpar[u] = (okp && lv >= 0) ? pr : -1;
+            if (windowed && wave == 0 && 64 * u + lane < bn) q_keys[(size_t)c * bn + 64 * u + lane] = kpos[u];
         }
         uint32_t w[4] = {0u, 0u, 0u, 0u};
         int cnt = 0;
@@ -536,7 +688,7 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int nchunks)
 }
 
 struct Phase2 {
-    int32_t *q_cols, *c_row, *c_cnt;
+    int32_t *q_cols, *c_row, *c_cnt, *q_keys;
     uint32_t *q_sub, *bits;
     unsigned long long *bits_rm;
     size_t bytes;
@@ -551,6 +703,7 @@ Phase2 carve_phase2(char *base, int64_t cap, int bm, int bn)
     p.q_sub = c.take<uint32_t>(n);
     p.c_row = c.take<int32_t>(n);
     p.c_cnt = c.take<int32_t>(n);
+    p.q_keys = c.take<int32_t>(n * (size_t)bn);
     p.bits = c.take<uint32_t>(n * words);
     p.bits_rm = c.take<unsigned long long>(n * nsub * 16);
     p.bytes = c.off;
@@ -662,12 +815,13 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     *out = nullptr;
     if (batch < 0 || n_pos < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: negative size");
     if (n_pos > (1 << 19)) return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: n_pos %d > 2^19", n_pos);
-    int bm = 128, bn = 64, force_dense = 0, no_sort = 0;
+    int bm = 128, bn = 64, force_dense = 0, no_sort = 0, windowed = 0;
     if (opts) {
         if (opts->tile_m) bm = opts->tile_m;
         if (opts->tile_n) bn = opts->tile_n;
         force_dense = opts->force_dense != 0;
         no_sort = opts->no_sort != 0;
+        windowed = opts->windowed != 0 || force_dense;
     }
     if (bm < 32 || bm > 128 || bm % 32 || bn < 32 || bn > 128 || bn % 32)
         return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_build_layout: tile %dx%d (each side: 32, 64, 96 or 128)", bm, bn);
@@ -685,6 +839,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     L->n_entries = 0;
     L->stats_ready = false;
     L->force_dense = force_dense;
+    L->windowed = windowed;
     L->device_bytes = 0;
     L->device = 0;
     HdtSchedule &s = L->s;
@@ -761,18 +916,29 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                     HdtTimer t("hdt_layout_sort_scatter", st);
                     hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
                 }
-                CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, cap,
-                            p.q_range, q.c_row, q.q_cols, p.counters, report, ticket};
-                HdtTimer t("hdt_layout_candidates", st);
-                hipLaunchKernelGGL(k_candidates, dim3((unsigned)B * groups), dim3(kThreads),
-                                   (size_t)kWaves * wc * sizeof(uint32_t), st, ca);
+                if (windowed) {
+                    CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, cap,
+                                p.q_range, q.c_row, q.q_cols, p.counters, report, ticket};
+                    HdtTimer t("hdt_layout_candidates", st);
+                    hipLaunchKernelGGL(k_candidates, dim3((unsigned)B * groups), dim3(kThreads),
+                                       (size_t)kWaves * wc * sizeof(uint32_t), st, ca);
+                } else {
+                    KeyListArgs ka{d_level, d_parent, p.slot, p.cmin, p.cmax, p.kperm, n, s.n_slots, bm, bn, tr, cap,
+                                   p.q_range, q.c_row, q.q_keys, p.counters, report, ticket};
+                    const size_t lds = (size_t)2 * ((s.n_slots + 63) / 64) * sizeof(uint32_t);
+                    if (lds > 48 * 1024)
+                        BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists,
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+                    HdtTimer t("hdt_layout_key_lists", st);
+                    hipLaunchKernelGGL(k_key_lists, dim3((unsigned)B * tr), dim3(kListThreads), lds, st, ka);
+                }
             }
             {
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
                 hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(128), 0, st, d_level, d_parent, p.kperm, q.c_row,
-                                   q.q_cols, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits, q.bits_rm, q.c_cnt,
-                                   q.q_sub);
+                                   q.q_cols, q.q_keys, windowed, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits,
+                                   q.bits_rm, q.c_cnt, q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
             // The host needs two facts before it can hand the layout out: whether the hierarchy was valid and
@@ -806,6 +972,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 s.kperm = p.kperm;
                 s.q_range = p.q_range;
                 s.q_cols = q.q_cols;
+                s.q_keys = q.q_keys;
                 s.q_sub = q.q_sub;
                 s.bits = q.bits;
                 s.bits_rm = q.bits_rm;

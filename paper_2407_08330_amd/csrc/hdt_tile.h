@@ -1,15 +1,16 @@
 // Pieces shared by the three bf16 kernels (forward, dQ pass, dK/dV pass).  All of them have the same
 // skeleton: a workgroup of 4 waves owns 128 consecutive rows of the schedule (wave w the rows
-// 32w..32w+31, whose operands stay in registers as MFMA B fragments), walks the row tile's list of
-// column tiles, and for each column tile gathers 64 rows of two [n_pos][D] tensors through kperm into
-// LDS.
+// 32w..32w+31, whose operands stay in registers as MFMA B fragments), walks the row tile's list
+// entries, and for each entry gathers the 64 rows of two [n_pos][D] tensors that the entry's key
+// positions name into LDS.
 //
 // The gather uses the CDNA direct-to-LDS loads (global_load_lds_*: every lane supplies a global
 // address, the 64 results land in LDS at M0 + lane*size) into a ring of S stages, so that several
 // tiles are in flight per workgroup without holding them in registers:
 //   iteration t:  wait until tile t has landed -> barrier -> start tile t+S-1 -> compute tile t.
-// The key order kperm is read the same way, one tile further ahead than the rows it addresses, and
-// the list entries are read with scalar loads, so no iteration waits on a chain of dependent loads.
+// The key positions of an entry are read the same way, one tile further ahead than the rows they
+// address, and the entries' summaries with scalar loads, so no iteration waits on a chain of dependent
+// loads.
 // The only vector-memory instructions inside the loop are those issued here with inline asm, which
 // is what makes the hand-counted s_waitcnt vmcnt(N) exact.
 //
@@ -97,7 +98,7 @@ struct Pipe {
     char *smem;
     uint32_t smem_addr;
     int wave, lane;
-    const int32_t *kperm;      // this sample's key order
+    const int32_t *keys;       // key positions of this row tile's entries: [n][BN]
     const __bf16 *a, *b;       // the two gathered tensors, already offset to this (sample, head)
     const float *aux0, *aux1;  // per-position floats gathered with the rows (AUX only), same offset
 
@@ -113,13 +114,13 @@ struct Pipe {
         return reinterpret_cast<const float *>(smem + DATA_BYTES + POS_BYTES) + (stage * 4 + which) * BN;
     }
 
-    // start loading the positions of column tile `col` (every wave keeps its own copy)
-    __device__ __forceinline__ void issue_pos(int col, int ps) const
+    // start loading the key positions of the row tile's j-th entry (every wave keeps its own copy)
+    __device__ __forceinline__ void issue_pos(int j, int ps) const
     {
-        dma4(kperm + col * BN + lane, smem_addr + DATA_BYTES + ((ps * 4 + wave) * BN) * 4);
+        dma4(keys + j * BN + lane, smem_addr + DATA_BYTES + ((ps * 4 + wave) * BN) * 4);
     }
 
-    // start gathering the rows of a column tile whose positions sit in position stage ps
+    // start gathering the rows of an entry whose positions sit in position stage ps
     __device__ __forceinline__ void issue_data(int stage, int ps) const
     {
         const int *pb = pos_buf(ps);
@@ -127,7 +128,7 @@ struct Pipe {
 #pragma unroll
         for (int i = 0; i < NI; i++) {
             const int r = wave * 16 + i * RPI + lr;
-            const int pos = max(pb[r], 0);  // slots past n_pos: any readable row, the bitmap masks them
+            const int pos = max(pb[r], 0);  // slots without a key: any readable row, the bitmap masks them
             const size_t off = (size_t)pos * D + (size_t)((c ^ swz(r & 7)) * 8);
             const uint32_t dst = (uint32_t)((wave * 16 + i * RPI) * ROWB);
             dma16(a + off, smem_addr + (stage * 2 + 0) * TILE + dst);
@@ -159,31 +160,30 @@ __device__ __forceinline__ void wait_vmcnt_tail(int k)
 // Ring schedule (positions run one tile ahead of their rows).  Per wave the vector-memory
 // instructions are issued in the order  pos(0), pos(1), data(0), pos(2), data(1), ..., pos(j+1), data(j), ...
 // where data(j) is NDMA instructions and pos(j) one.
-//   prologue(n, cols): starts pos(0..S-1) and data(0..S-2) as far as they exist
+//   start(n), prologue(n): start pos(0..S-1) and data(0..S-2) as far as they exist
 //   top(i, n):         call at the top of iteration i: returns when data(i) and pos(i+S-1) have landed
 //                      in LDS for this wave; the caller then executes a workgroup barrier
-//   advance(i, n, col_next): after the barrier: starts pos(i+S) (column col_next) and data(i+S-1)
+//   advance(i, n):     after the barrier: starts pos(i+S) and data(i+S-1)
 template <typename P>
 struct Ring {
     static constexpr int S = P::S, NDMA = P::NDMA, PS = P::PS;
 
     // first half of the prologue: pos(0), pos(1).  The caller may issue its own (compiler-scheduled)
     // loads after this and before prologue(); the compiler's wait for those also covers these two.
-    template <typename ColFn>
-    static __device__ __forceinline__ void start(const P &p, int n, ColFn col_of)
+    static __device__ __forceinline__ void start(const P &p, int n)
     {
-        if (n > 0) p.issue_pos(col_of(0), 0);
-        if (n > 1) p.issue_pos(col_of(1), 1);
+        if (n > 0) p.issue_pos(0, 0);
+        if (n > 1) p.issue_pos(1, 1);
     }
 
     // second half: pos(j+1), data(j) for j in [J0, J1) (the whole prologue is J0 = 0, J1 = S-1; it may be
     // issued in two pieces when some ring stages are still in use, see the backward kernels)
-    template <int J0, int J1, typename ColFn>
-    static __device__ __forceinline__ void prologue(const P &p, int n, ColFn col_of)
+    template <int J0, int J1>
+    static __device__ __forceinline__ void prologue(const P &p, int n)
     {
 #pragma unroll
         for (int j = J0; j < J1; j++) {
-            if (j > 0 && j + 1 < n) p.issue_pos(col_of(j + 1), (j + 1) % PS);
+            if (j > 0 && j + 1 < n) p.issue_pos(j + 1, (j + 1) % PS);
             if (j < n) {
                 // pos(j) must have landed; issued after it: [data(j-1)], [pos(j+1)]
                 if (j == 0) {
@@ -208,9 +208,9 @@ struct Ring {
         }
     }
 
-    static __device__ __forceinline__ void advance(const P &p, int i, int n, int col_next)
+    static __device__ __forceinline__ void advance(const P &p, int i, int n)
     {
-        if (i + S < n) p.issue_pos(col_next, (i + S) % PS);
+        if (i + S < n) p.issue_pos(i + S, (i + S) % PS);
         if (i + S - 1 < n) p.issue_data((i + S - 1) % S, (i + S - 1) % PS);
     }
 };

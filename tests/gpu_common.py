@@ -45,23 +45,32 @@ def make_inputs(B, H, N, D, seed, dtype, n_tensors=3):
     return xs, dev
 
 
-def compare_layout(oracle, layout, level, parent, bm, bn, **kw):
-    """Bit-exact comparison of every exported array of every sample with the oracle's schedule."""
+def compare_layout(oracle, layout, level, parent, bm, bn, windowed=False, **kw):
+    """Bit-exact comparison of every exported array of every sample with the oracle's schedule:
+    the per-query-tile key lists (default) or the windowed block schedule."""
     B = level.shape[0]
     total_tiles = total_nnz = 0
+    assert bool(layout.info()["windowed"]) == bool(windowed or kw.get("force_dense"))
     for b in range(B):
-        ref = oracle.block_schedule(level[b], parent[b], bm, bn, **kw)
         got = layout.export(b)
+        if windowed or kw.get("force_dense"):
+            ref = oracle.block_schedule(level[b], parent[b], bm, bn, **kw)
+            np.testing.assert_array_equal(got["q_cols"], ref.q_cols, err_msg=f"q_cols sample {b}")
+            np.testing.assert_array_equal(got["k_colptr"], ref.k_colptr, err_msg=f"k_colptr sample {b}")
+            np.testing.assert_array_equal(got["k_rows"], ref.k_rows, err_msg=f"k_rows sample {b}")
+            np.testing.assert_array_equal(got["k_tile"], ref.k_tile, err_msg=f"k_tile sample {b}")
+        else:
+            ref = oracle.keylist_schedule(level[b], parent[b], bm, bn, **kw)
+            ordinal = np.arange(ref.q_keys.shape[0]) - np.repeat(ref.q_rowptr[:-1], np.diff(ref.q_rowptr))
+            np.testing.assert_array_equal(got["q_cols"], ordinal, err_msg=f"entry ordinals sample {b}")
+            assert "k_rows" not in got
         np.testing.assert_array_equal(got["kperm"], ref.kperm, err_msg=f"kperm sample {b}")
         np.testing.assert_array_equal(got["q_rowptr"], ref.q_rowptr, err_msg=f"q_rowptr sample {b}")
-        np.testing.assert_array_equal(got["q_cols"], ref.q_cols, err_msg=f"q_cols sample {b}")
+        np.testing.assert_array_equal(got["q_keys"], ref.q_keys, err_msg=f"q_keys sample {b}")
         np.testing.assert_array_equal(got["q_sub"], ref.q_sub, err_msg=f"q_sub sample {b}")
         np.testing.assert_array_equal(got["bits"], ref.bits, err_msg=f"bits sample {b}")
-        np.testing.assert_array_equal(got["k_colptr"], ref.k_colptr, err_msg=f"k_colptr sample {b}")
-        np.testing.assert_array_equal(got["k_rows"], ref.k_rows, err_msg=f"k_rows sample {b}")
-        np.testing.assert_array_equal(got["k_tile"], ref.k_tile, err_msg=f"k_tile sample {b}")
         n_tiles, nnz = layout.sample_info(b)
-        assert n_tiles == ref.q_cols.shape[0] and nnz == ref.nnz
+        assert n_tiles == ref.q_keys.shape[0] and nnz == ref.nnz
         total_tiles += n_tiles
         total_nnz += nnz
     info = layout.info()

@@ -12,13 +12,13 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 5e-2, "f32": 1e-4}
 
 
-def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None):
+def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v, d_o), (q_, k_, v_, do_) = make_inputs(B, H, N, D, seed, dtype, n_tensors=4)
-    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent))
+    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed)
     o_, lse_ = hdt.hdt_attn_fwd(lay, q_, k_, v_, scale)
     dq_ = torch.full_like(q_, float("nan"))
     dk_ = torch.full_like(q_, float("nan"))
@@ -77,6 +77,21 @@ def test_bwd_ragged_lengths_and_deep_trees(oracle, dtype, D, n):
         pr.append(np.concatenate([p, np.full(n - p.shape[0], -1, np.int32)]))
     say(f"[bwd] ragged n={n} {dtype} d={D}")
     run_bwd_case(oracle, np.stack(lv), np.stack(pr), 3, D, dtype, 177 + n)
+
+
+def test_bwd_windowed_schedule(oracle):
+    # the schedule of Alg. 1 as printed (key tiles = fixed windows of the level-sorted key order)
+    wl = inputs.make_workload(4, batch=2)
+    say("[bwd] windowed schedule: config 4 hierarchy (skewed document included), 2 samples, 4 heads")
+    run_bwd_case(oracle, wl.level, wl.parent, 4, 64, "bf16", inputs.sample_seed(4, 70), windowed=True)
+    rng = np.random.default_rng(4244)
+    n = 777
+    l, p = inputs.tree_document([(1, 5), (0, 6), (0, 9), (0, 30)], rng, max_nodes=n)
+    level = np.concatenate([l, np.full(n - l.shape[0], -1, np.int32)])[None]
+    parent = np.concatenate([p, np.full(n - p.shape[0], -1, np.int32)])[None]
+    for dtype, D in (("bf16", 128), ("f32", 64)):
+        say(f"[bwd] windowed schedule: ragged n={n} {dtype} d={D}")
+        run_bwd_case(oracle, level, parent, 2, D, dtype, 4245, windowed=True)
 
 
 def test_bwd_all_pad_sample_and_dense_document(oracle):

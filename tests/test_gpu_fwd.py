@@ -12,13 +12,13 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
 
 
-def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, check_rows=None):
+def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v), (dq_, dk_, dv_) = make_inputs(B, H, N, D, seed, dtype)
-    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent))
+    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed)
     o = torch.full_like(dq_, float("nan"))
     lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
     hdt.hdt_attn_fwd(lay, dq_, dk_, dv_, scale, o=o, lse=lse)
@@ -86,6 +86,21 @@ def test_fwd_all_pad_sample_and_dense_document(oracle):
         lay = run_fwd_case(oracle, level, parent, 2, 64, dtype, 5)
         assert lay.sample_info(0) == (0, 0)
         assert lay.sample_info(1) == (3 * 6, n * n)
+
+
+def test_fwd_windowed_schedule(oracle):
+    # the schedule of Alg. 1 as printed (key tiles = fixed windows of the level-sorted key order)
+    wl = inputs.make_workload(3, batch=2)
+    say("[fwd] windowed schedule: config 3 hierarchy (skewed document included), 2 samples, 4 heads")
+    run_fwd_case(oracle, wl.level, wl.parent, 4, 64, "bf16", inputs.sample_seed(3, 70), windowed=True)
+    rng = np.random.default_rng(4242)
+    n = 777
+    l, p = inputs.tree_document([(1, 5), (0, 6), (0, 9), (0, 30)], rng, max_nodes=n)
+    level = np.concatenate([l, np.full(n - l.shape[0], -1, np.int32)])[None]
+    parent = np.concatenate([p, np.full(n - p.shape[0], -1, np.int32)])[None]
+    for dtype, D in (("bf16", 128), ("f32", 64)):
+        say(f"[fwd] windowed schedule: ragged n={n} {dtype} d={D}")
+        run_fwd_case(oracle, level, parent, 2, D, dtype, 4243, windowed=True)
 
 
 def test_fwd_large_logits_and_scale(oracle):

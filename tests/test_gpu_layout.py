@@ -1,4 +1,5 @@
-"""GPU parity: hdt_build_layout against the oracle's brute-force block schedule, bit-exact."""
+"""GPU parity: hdt_build_layout against the oracle's brute-force schedules, bit-exact: the
+per-query-tile key lists (the default) and the windowed block schedule of Alg. 1."""
 import numpy as np
 import pytest
 
@@ -13,36 +14,43 @@ def _build(level, parent, **kw):
     return hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), **kw)
 
 
+WINDOWED = pytest.mark.parametrize("windowed", [False, True], ids=["keylists", "windowed"])
+
+
+@WINDOWED
 @pytest.mark.parametrize("config", [1, 2, 3, 5])
-def test_layout_matches_oracle_on_benchmark_configs(oracle, config):
+def test_layout_matches_oracle_on_benchmark_configs(oracle, config, windowed):
     wl = inputs.make_workload(config)
-    say(f"[layout] config {config} B={wl.batch} N={wl.n_pos}")
-    lay = _build(wl.level, wl.parent)
-    tiles, nnz = compare_layout(oracle, lay, wl.level, wl.parent, 128, 64)
+    say(f"[layout] config {config} B={wl.batch} N={wl.n_pos} windowed={windowed}")
+    lay = _build(wl.level, wl.parent, windowed=windowed)
+    tiles, nnz = compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, windowed=windowed)
     say(f"[layout] config {config}: {tiles} tiles, nnz {nnz}")
     lay.destroy()
 
 
+@WINDOWED
 @pytest.mark.parametrize("bm,bn", [(64, 32), (32, 32), (128, 128), (96, 64)])
-def test_layout_other_tile_shapes(oracle, bm, bn):
+def test_layout_other_tile_shapes(oracle, bm, bn, windowed):
     wl = inputs.make_workload(2, batch=2)
-    say(f"[layout] tile {bm}x{bn}")
-    lay = _build(wl.level, wl.parent, tile_m=bm, tile_n=bn)
-    compare_layout(oracle, lay, wl.level, wl.parent, bm, bn)
+    say(f"[layout] tile {bm}x{bn} windowed={windowed}")
+    lay = _build(wl.level, wl.parent, tile_m=bm, tile_n=bn, windowed=windowed)
+    compare_layout(oracle, lay, wl.level, wl.parent, bm, bn, windowed=windowed)
 
 
+@WINDOWED
 @pytest.mark.parametrize("n", [1, 31, 100, 129, 1000, 4097])
-def test_layout_ragged_lengths(oracle, n):
+def test_layout_ragged_lengths(oracle, n, windowed):
     rng = np.random.default_rng(n)
     level, parent = inputs.tree_document([(1, 6), (0, 7), (0, 20)], rng, max_nodes=n)
     level = np.concatenate([level, np.full(n - level.shape[0], -1, np.int32)])[None]
     parent = np.concatenate([parent, np.full(n - parent.shape[0], -1, np.int32)])[None]
-    say(f"[layout] ragged n={n} real={(level >= 0).sum()}")
-    lay = _build(level, parent)
-    compare_layout(oracle, lay, level, parent, 128, 64)
+    say(f"[layout] ragged n={n} real={(level >= 0).sum()} windowed={windowed}")
+    lay = _build(level, parent, windowed=windowed)
+    compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed)
 
 
-def test_layout_deep_trees_and_all_pad_sample(oracle):
+@WINDOWED
+def test_layout_deep_trees_and_all_pad_sample(oracle, windowed):
     rng = np.random.default_rng(11)
     n = 768
     lv, pr = [], []
@@ -53,15 +61,16 @@ def test_layout_deep_trees_and_all_pad_sample(oracle):
     lv.append(np.full(n, -1, np.int32))   # an empty document: all pads
     pr.append(np.full(n, -1, np.int32))
     level, parent = np.stack(lv), np.stack(pr)
-    say("[layout] deep trees + all-pad sample")
-    lay = _build(level, parent)
-    compare_layout(oracle, lay, level, parent, 128, 64)
+    say(f"[layout] deep trees + all-pad sample windowed={windowed}")
+    lay = _build(level, parent, windowed=windowed)
+    compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed)
     assert lay.sample_info(3) == (0, 0)
 
 
-def test_layout_positions_not_in_preorder(oracle):
-    # a shuffled document: sibling groups are scattered, candidate ranges over-approximate and the
-    # exact per-tile evaluation has to drop the empty ones
+@WINDOWED
+def test_layout_positions_not_in_preorder(oracle, windowed):
+    # a shuffled document: sibling groups are scattered, the marked ranges over-approximate and the
+    # exact evaluation has to drop the empty windows / the keys no row of the tile attends to
     wl = inputs.make_workload(1)
     rng = np.random.default_rng(5)
     n = wl.n_pos
@@ -71,9 +80,9 @@ def test_layout_positions_not_in_preorder(oracle):
     level[perm] = wl.level[0]
     old_parent = wl.parent[0]
     parent[perm] = np.where(old_parent >= 0, perm[np.maximum(old_parent, 0)], -1)
-    say("[layout] shuffled positions")
-    lay = _build(level[None], parent[None])
-    compare_layout(oracle, lay, level[None], parent[None], 128, 64)
+    say(f"[layout] shuffled positions windowed={windowed}")
+    lay = _build(level[None], parent[None], windowed=windowed)
+    compare_layout(oracle, lay, level[None], parent[None], 128, 64, windowed=windowed)
 
 
 def test_layout_force_dense_and_no_sort(oracle):
@@ -82,8 +91,50 @@ def test_layout_force_dense_and_no_sort(oracle):
     lay = _build(wl.level, wl.parent, force_dense=True)
     tiles, _ = compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, force_dense=True)
     assert tiles == 4 * 8
-    lay = _build(wl.level, wl.parent, no_sort=True)
-    compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, use_sort=False)
+    for windowed in (True, False):
+        lay = _build(wl.level, wl.parent, no_sort=True, windowed=windowed)
+        compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, windowed=windowed, use_sort=False)
+
+
+def test_layout_long_documents_need_a_large_slot_bitmap(oracle):
+    # 2^17 positions: the key-list kernel's bitmap over the key order (one bit per slot) takes 16 KB of LDS
+    rng = np.random.default_rng(77)
+    n = 1 << 17
+    secs = [[int(rng.integers(5, 61)) for _ in range(int(rng.integers(5, 41)))] for _ in range(120)]
+    level, parent = inputs.document_from_sections(secs, n)
+    say(f"[layout] n = {n}, real = {(level >= 0).sum()}")
+    lay = _build(level[None], parent[None])
+    got = lay.export(0)
+    ref_kperm = oracle.kperm(level)
+    np.testing.assert_array_equal(got["kperm"], ref_kperm)
+    # the full brute force is n^2; check sampled query tiles against the oracle's pair test instead
+    rowptr = got["q_rowptr"]
+    slot = np.empty(n, np.int64)
+    slot[ref_kperm] = np.arange(n)
+    for I in rng.choice(n // 128, size=12, replace=False).tolist() + [0]:
+        rows = np.arange(I * 128, (I + 1) * 128)
+        keys = got["q_keys"][rowptr[I]:rowptr[I + 1]].reshape(-1)
+        real = keys[keys >= 0]
+        assert (keys[len(real):] == -1).all() and (np.diff(slot[real]) > 0).all()
+        want = set()
+        for i in rows:
+            if level[i] < 0:
+                continue
+            cand = {int(i)} | ({int(parent[i])} if parent[i] >= 0 else set())
+            cand |= set(np.nonzero(parent == i)[0].tolist())
+            if parent[i] >= 0:
+                cand |= set(np.nonzero(parent == parent[i])[0].tolist())
+            for j in cand:
+                assert oracle.allowed(level, parent, int(i), j)
+            want |= cand
+        assert set(real.tolist()) == want, f"query tile {I}"
+        bits = got["bits"][rowptr[I]:rowptr[I + 1]]
+        for e in range(bits.shape[0]):
+            for c in range(64):
+                j = keys[e * 64 + c]
+                col = (bits[e, :, c // 32] >> np.uint32(c % 32)) & 1
+                exp = [oracle.allowed(level, parent, int(i), int(j)) if j >= 0 else 0 for i in rows]
+                np.testing.assert_array_equal(col, np.array(exp, np.uint32))
 
 
 def test_layout_rejects_bad_hierarchies():
