@@ -176,6 +176,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
                         (long long)T);
     HDT_HIP_TRY(hipDeviceSynchronize());
     if (kperm && s.n_pos > 0)
+        if (hdt_status_t st = hdt_layout_ensure_kperm(layout)) return st;
+    if (kperm && s.n_pos > 0)
         HDT_HIP_TRY(hipMemcpy(kperm, s.kperm + (size_t)sample * s.n_slots, sizeof(int32_t) * s.n_pos,
                               hipMemcpyDeviceToHost));
     // the device lists hold every candidate tile; the exported schedule keeps those with an allowed pair

@@ -55,6 +55,12 @@ struct hdt_layout {
     // query that needs them (hdt_layout_stats), not by the build
     mutable std::vector<int64_t> h_stats;
     mutable bool stats_ready;
+    // Key-list layouts do not need the global key order; it is sorted from the layout's copy of the ids
+    // on demand (hdt_layout_ensure_kperm).
+    mutable bool kperm_ready;
+    int32_t no_sort;
+    int32_t *sort_hist, *sort_counters;
+    const int32_t *level_copy, *parent_copy;
 };
 
 // --- error reporting (hdt_api.hip) ---
@@ -68,6 +74,7 @@ hdt_status_t hdt_fail(hdt_status_t st, const char *fmt, ...);
     } while (0)
 
 bool hdt_layout_ok(const hdt_layout_t *l);
+hdt_status_t hdt_layout_ensure_kperm(const hdt_layout_t *l);  // sorts s.kperm if the build did not (waits for the device) (hdt_layout.hip)
 hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (waits for the device) (hdt_layout.hip)
 void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
 

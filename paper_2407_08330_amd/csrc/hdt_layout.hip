@@ -52,7 +52,20 @@ constexpr int kWaves = kThreads / 64;
 constexpr int kBuckets = HDT_MAX_LEVELS + 1;  // levels 0..31, pads in the last bucket
 constexpr int kChunk = kThreads;              // positions per workgroup of the two sort kernels
 
-enum { CNT_ERR = 0, CNT_CAND = 1, CNT_ARRIVED = 2 };
+// counters[CNT_ERR]: hierarchy error flag.  counters[CNT_CAND], counters[CNT_CAND + 1]: ONE 64-bit word,
+// [39:0] list entries reserved so far, [63:40] workgroups that have reserved theirs: a single returning
+// atomic gives a workgroup its slice and tells the last one that it is the last.
+enum { CNT_ERR = 0, CNT_CAND = 2 };
+
+// reserves `count` entries; returns the first one; *final_total >= 0 iff this was the last workgroup
+__device__ __forceinline__ int reserve_entries(int32_t *counters, int count, int *final_total)
+{
+    unsigned long long *word = reinterpret_cast<unsigned long long *>(counters + CNT_CAND);
+    const unsigned long long old = atomicAdd(word, (1ull << 40) + (unsigned long long)count);
+    const int base = (int)(old & 0xffffffffffull);
+    *final_total = (int)(old >> 40) == (int)gridDim.x - 1 ? base + count : -1;
+    return base;
+}
 
 // What the candidate kernel reports to the host through pinned host memory: one 64-bit word
 // [63:40] ticket of the build, [39] hierarchy error, [31:0] list entries needed.
@@ -103,6 +116,7 @@ struct SortArgs {
     int32_t *hist;  // [B][nchunks][kBuckets] positions of every level in every chunk of kChunk positions
     int32_t *kperm, *slot, *cmin, *cmax;
     int32_t *counters;
+    int ranges;  // also compute the slot range of every node's children (windowed layouts)
 };
 
 // ---- sort, first half: validate, count the levels of each chunk ---------------------------------
@@ -118,8 +132,10 @@ __global__ __launch_bounds__(kThreads) void k_sort_count(SortArgs a)
     if (in) {
         l = a.level[o + i];
         p = a.parent[o + i];
-        a.cmin[o + i] = INT_MAX;
-        a.cmax[o + i] = -1;
+        if (a.ranges) {
+            a.cmin[o + i] = INT_MAX;
+            a.cmax[o + i] = -1;
+        }
     }
     const bool bad = in && (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1));
     if (__ballot(bad) && lane == 0) atomicOr(&a.counters[CNT_ERR], 1);
@@ -211,9 +227,13 @@ __global__ __launch_bounds__(kThreads) void k_sort_scatter(SortArgs a)
     }
     if (a.no_sort) my_slot = i;
     if (in) {
-        a.slot[o + i] = my_slot;
         a.kperm[(size_t)b * a.n_slots + my_slot] = i;
     }
+    if (!a.ranges) {
+        if (valid && lp < 0) atomicOr(&a.counters[CNT_ERR], 1);  // a parent must be a real position
+        return;
+    }
+    if (in) a.slot[o + i] = my_slot;
     // Slot range of every node's children.  Consecutive positions with the same parent and consecutive
     // slots (the tokens of a sentence, for one) form a run whose minimum and maximum are its first and
     // last slot: one atomic each per run.
@@ -312,15 +332,14 @@ __global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
 #pragma unroll
         for (int w = 0; w < kWaves; w++) total += s_n[w];
         // this workgroup's slice of the list arrays
-        s_base = atomicAdd(&a.counters[CNT_CAND], total);
-        // the last workgroup to get here knows the final counters: it tells the host, which is waiting
-        // for exactly this word, while the lists and the bitmaps are still being written
-        __threadfence();
-        if (atomicAdd(&a.counters[CNT_ARRIVED], 1) == (int)gridDim.x - 1) {
-            __threadfence();
+        // this workgroup's slice of the list arrays; the last workgroup to get here knows the final count
+        // and tells the host, which is waiting for exactly this word, while the lists and the bitmaps are
+        // still being written (no device-scope fence: it would write back the whole L2 of this XCD)
+        int final_total;
+        s_base = reserve_entries(a.counters, total, &final_total);
+        if (final_total >= 0) {
             const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int need = __hip_atomic_load(&a.counters[CNT_CAND], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)need), __ATOMIC_RELEASE,
+            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)final_total), __ATOMIC_RELEASE,
                                __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
@@ -348,161 +367,326 @@ __global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
     }
 }
 
+// ---- exact evaluation of one list entry by two or four waves ---------------------------------------
+// Wave `wsub` (0 or 1) holds rows 64*wsub + lane of the query tile (position i, parent pi, rowok = a
+// real position) and evaluates them against all keys (khalf < 0) or against one half of the entry's
+// 32-key words (khalf = 0, 1); every wave holds the entry's keys, lane l the slots l and 64 + l (position
+// and parent, -1 where the slot holds no key), which are broadcast by lane index while each lane tests
+// its row against every key.  Outputs of entry c: the row-major bitmap (export, fp32 path), per 32x32
+// sub-block the 16 x 64-bit lane masks the MFMA kernels apply to their accumulator registers (wave
+// ballots), and through `part` (this wave's slot of a pair's scratch in LDS) the pair count and the
+// sub-block summary, which the caller adds up after a barrier.
+struct EntryPart {
+    int cnt;
+    uint32_t any, all;
+};
+
+__device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int wsub, int khalf, int lane, int i, int pi,
+                                                   bool rowok,
+                                                   const int (&kpos)[2], const int (&kpar)[2], int bm, int bn,
+                                                   uint32_t *bits, unsigned long long *bits_rm)
+{
+    const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
+    const size_t words = (size_t)bm * wpr;
+    const int r = wsub * 64 + lane;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    int cnt = 0;
+#pragma unroll
+    for (int wd = 0; wd < 4; wd++) {
+        if (wd < wpr && (khalf < 0 || (wd * 2) / wpr == khalf)) {
+            const int kp = kpos[wd >> 1], kq = kpar[wd >> 1];
+            uint32_t out = 0;
+#pragma unroll 8
+            for (int cc = 0; cc < 32; cc++) {
+                const int kj = __builtin_amdgcn_readlane(kp, (wd & 1) * 32 + cc);
+                const int kr = __builtin_amdgcn_readlane(kq, (wd & 1) * 32 + cc);
+                const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kr) || pi == kj || kr == i);
+                out |= (uint32_t)ok << cc;
+            }
+            w[wd] = rowok ? out : 0u;
+            cnt += __popc(w[wd]);
+            if (active && r < bm) bits[(size_t)c * words + (size_t)r * wpr + wd] = w[wd];
+        }
+    }
+    EntryPart part;
+    part.cnt = wave_sum(cnt);
+    part.any = part.all = 0;
+    // register-major masks of sub-block (rblk, cblk), accumulator register e: bit l <=> row
+    // rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
+#pragma unroll
+    for (int rr = 0; rr < 2; rr++) {
+        const int rblk = 2 * wsub + rr;
+        if (rblk < nrb) {
+#pragma unroll
+            for (int cblk = 0; cblk < 4; cblk++) {
+                if (cblk < wpr && (khalf < 0 || (cblk * 2) / wpr == khalf)) {
+                    const uint32_t x = (uint32_t)__shfl((int)w[cblk], rr * 32 + (lane & 31));
+                    unsigned long long mine = 0;
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        const int bit = (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
+                        const unsigned long long m = __ballot((x >> bit) & 1u);
+                        if (lane == e) mine = m;
+                    }
+                    const int sb = rblk * wpr + cblk;
+                    if (active && lane < 16) bits_rm[((size_t)c * nsub + sb) * 16 + lane] = mine;
+                    if (__ballot(x != 0u) != 0ull) part.any |= 1u << sb;
+                    if (__ballot(x == 0xffffffffu) == ~0ull) part.all |= 1u << sb;
+                }
+            }
+        }
+    }
+    return part;
+}
+
 struct KeyListArgs {
-    const int32_t *level, *parent, *slot, *cmin, *cmax, *kperm;
-    int n, n_slots, bm, bn, tr;
+    const int32_t *level, *parent;
+    int n, bm, bn, tr, no_sort;
     int64_t capacity;
     int32_t *q_range;  // [B][tr][2]
-    int32_t *c_row, *q_keys;
+    int32_t *c_row, *q_keys, *q_kpar, *c_cnt;
+    int32_t *level_copy, *parent_copy;  // the layout's own copy of the ids (the key order is sorted from it on demand)
+    uint32_t *q_sub, *bits;
+    unsigned long long *bits_rm;
     int32_t *counters;
     unsigned long long *report;
     uint32_t ticket;
 };
 
-constexpr int kListThreads = 256, kListWaves = kListThreads / 64;
+constexpr int kListThreads = 1024, kListWaves = kListThreads / 64, kBatch = 8;
 
-// set bits lo..hi of an LDS bitmap
-__device__ __forceinline__ void mark_slots(uint32_t *bits, int lo, int hi) { mark_tiles(bits, lo, hi); }
-
-// ---- key list of every query tile: one workgroup per query tile, a bitmap over the key order in LDS ----
+// ---- key lists: ONE kernel from level/parent to the finished entries, a workgroup per query tile ----
+// Key j is needed by the tile iff it is one of the tile's rows, the parent of one (bitmap over the
+// positions, in LDS), a child of one (its parent is a row of the tile) or a sibling of one (its parent
+// is the parent of a row).  All four tests are exact, for any forest.  The workgroup scans level[] and
+// parent[] of the whole sample once (two coalesced streams, nothing waits on a chain of dependent
+// loads), keeps the needed positions as a bitmap, and packs them in KEY ORDER - by level, ties in
+// document order, i.e. the order of kperm restricted to the needed keys - with a counting sort over the
+// needed keys only: every wave counts the levels in its contiguous share, the counts are turned into
+// first indices (level major, then wave), and after the workgroup has reserved its entries each wave
+// hands out indices in document order.  The global key order is therefore not an input of this kernel.
+// The workgroup then evaluates its own entries pair by pair (bitmaps, lane masks, summaries), four waves
+// per entry.  It also validates its own rows.
 __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
 {
-    extern __shared__ uint32_t s_mark[];  // [2 * groups of 64 slots]: marked, later exactly needed, key slots
-    __shared__ int2 s_row[128];           // (position, parent) of the tile's rows, (-2, -2) for pads and rows past n
+    extern __shared__ uint32_t s_dyn[];  // [ceil(n/32)] parents of the tile's rows, then [2 * groups] needed positions
+    __shared__ uint32_t s_rowok[4];      // valid rows of the tile
+    __shared__ int2 s_row[128];          // (position, parent) of the tile's rows; position -2: no such row
+    __shared__ int s_lcnt[kListWaves][kBuckets];  // needed keys per (wave, level), then their first index
     __shared__ int s_cnt[kListWaves];
-    __shared__ int s_base;
+    __shared__ uint32_t s_any[kListWaves], s_all[kListWaves];
+    __shared__ int s_base, s_total;
     const int b = blockIdx.x / a.tr, I = blockIdx.x - b * a.tr, n = a.n;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int bm = a.bm, bn = a.bn;
     const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
-    const int32_t *slot = a.slot + (size_t)b * n, *cmin = a.cmin + (size_t)b * n, *cmax = a.cmax + (size_t)b * n;
-    const int32_t *kperm = a.kperm + (size_t)b * a.n_slots;
-    const int ng = (a.n_slots + 63) >> 6;
-    for (int w = tid; w < 2 * ng; w += kListThreads) s_mark[w] = 0;
-    int i = -2, p = -2;
-    bool ok = false;
+    const int pw = (n + 31) >> 5, ng = (n + 63) >> 6;
+    uint32_t *s_par = s_dyn, *s_need = s_dyn + pw;
+    for (int w = tid; w < pw; w += kListThreads) s_par[w] = 0;
+    if (tid < 4) s_rowok[tid] = 0;
+    __syncthreads();
+    const int row0 = I * bm;
+    bool check_parent = false;
+    int my_parent = 0;
     if (tid < 128) {
-        i = I * bm + tid;
-        ok = tid < bm && i < n;
-        const int ii = ok ? i : 0;
-        const int lv = level[ii];
-        p = parent[ii];
-        ok = ok && lv >= 0;
-        s_row[tid] = ok ? make_int2(i, p) : make_int2(-2, -2);
-    }
-    __syncthreads();
-    if (ok) {
-        // consecutive rows with the same parent (the tokens of a sentence) would mark the same ranges
-        const bool okp = p >= 0 && p < n && level[p] >= 0;
-        const bool first_of_run = tid == 0 || s_row[tid - 1].y != p;
-        const int sl = slot[i];
-        if (sl >= 0 && sl < n) mark_slots(s_mark, sl, sl);  // itself
-        if (okp && first_of_run) {
-            const int sp = slot[p], lo = cmin[p], hi = cmax[p];
-            if (sp >= 0 && sp < n) mark_slots(s_mark, sp, sp);              // its parent
-            if (lo <= hi && lo >= 0 && hi < n) mark_slots(s_mark, lo, hi);  // its siblings: the children of its parent
-        }
-        const int lo = cmin[i], hi = cmax[i];
-        if (lo <= hi && lo >= 0 && hi < n) mark_slots(s_mark, lo, hi);  // its children
-    }
-    __syncthreads();
-    // exact test of every marked slot against the rows of the tile; groups of 64 slots dealt out to the waves
-    for (int g = wave; g < ng; g += kListWaves) {
-        const int s = g * 64 + lane;
-        const bool marked = (s_mark[s >> 5] >> (s & 31)) & 1u;
-        if (__ballot(marked) == 0ull) continue;
-        int j = -3, pj = -3;  // values no row matches
-        if (marked && s < a.n_slots) {
-            const int kj = kperm[s];
-            if (kj >= 0 && kj < n && level[kj] >= 0) {
-                j = kj;
-                pj = parent[kj];
+        int2 me = make_int2(-2, -2);
+        if (tid < bm && row0 + tid < n) {
+            const int i = row0 + tid;
+            const int l = level[i], p = parent[i];
+            a.level_copy[(size_t)b * n + i] = l;
+            a.parent_copy[(size_t)b * n + i] = p;
+            if (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1))
+                atomicOr(&a.counters[CNT_ERR], 1);
+            else if (l >= 0) {
+                me = make_int2(i, p);
+                atomicOr(&s_rowok[tid >> 5], 1u << (tid & 31));
+                if (p >= 0) {
+                    atomicOr(&s_par[p >> 5], 1u << (p & 31));
+                    check_parent = true;
+                    my_parent = p;
+                }
             }
         }
-        bool hit = false;
-#pragma unroll 4
-        for (int r = 0; r < bm; r++) {
-            const int2 row = s_row[r];
-            hit |= row.x == j || (row.y >= 0 && row.y == pj) || row.y == j || pj == row.x;
-        }
-        const unsigned long long m = __ballot(hit);
-        if (lane == 0) {
-            s_mark[2 * g] = (uint32_t)m;
-            s_mark[2 * g + 1] = (uint32_t)(m >> 32);
-        }
+        s_row[tid] = me;
     }
+    const int parent_level = check_parent ? level[my_parent] : 0;  // looked at once the scan is under way
     __syncthreads();
-    // keys of the tile: each wave counts a contiguous quarter of the groups
     const int gpw = (ng + kListWaves - 1) / kListWaves;
     const int g0 = min(wave * gpw, ng), g1 = min(g0 + gpw, ng);
-    {
-        int c = 0;
-        for (int w = 2 * g0 + lane; w < 2 * g1; w += 64) c += __popc(s_mark[w]);
-        c = wave_sum(c);
-        if (lane == 0) s_cnt[wave] = c;
-    }
-    __syncthreads();
-    int total = 0, before = 0;
+    auto in_tile = [&](int x) { return x >= row0 && x < row0 + bm && ((s_rowok[(x - row0) >> 5] >> ((x - row0) & 31)) & 1u); };
+    auto is_par = [&](int x) { return (s_par[x >> 5] >> (x & 31)) & 1u; };
+    // kBatch groups of 64 positions at a time: all their loads are issued before the first is used
+    int klv[kBatch], kp[kBatch];
+    auto load_batch = [&](int gb) {
 #pragma unroll
-    for (int w = 0; w < kListWaves; w++) {
-        if (w < wave) before += s_cnt[w];
-        total += s_cnt[w];
+        for (int u = 0; u < kBatch; u++) {
+            const int j = (gb + u) * 64 + lane;
+            const bool ok = gb + u < g1 && j < n;
+            klv[u] = ok ? level[j] : -1;
+            kp[u] = ok ? parent[j] : -1;
+        }
+    };
+    int lcount = 0;  // lane k: needed keys of level k in this wave's share
+    for (int gb = g0; gb < g1; gb += kBatch) {
+        load_batch(gb);
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {
+            if (gb + u >= g1) break;
+            const int j = (gb + u) * 64 + lane, pj = kp[u];
+            bool need = false;
+            if (klv[u] >= 0 && j < n) {
+                need = in_tile(j) || is_par(j);
+                if (!need && pj >= 0 && pj < n) need = in_tile(pj) || is_par(pj);
+            }
+            const unsigned long long m = __ballot(need);
+            if (lane == 0) {
+                s_need[2 * (gb + u)] = (uint32_t)m;
+                s_need[2 * (gb + u) + 1] = (uint32_t)(m >> 32);
+            }
+            if (m != 0ull) lcount += wave_bucket_count(need, a.no_sort ? 0 : bucket_of(klv[u]));
+        }
     }
-    const int n_ent = (total + bn - 1) / bn;
-    if (tid == 0) {
-        // this tile's slice of the per-entry arrays
-        s_base = atomicAdd(&a.counters[CNT_CAND], n_ent);
-        // the last workgroup to get here knows the final counters: it tells the host, which is waiting
-        // for exactly this word, while the lists and the bitmaps are still being written
-        __threadfence();
-        if (atomicAdd(&a.counters[CNT_ARRIVED], 1) == (int)gridDim.x - 1) {
-            __threadfence();
-            const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int need = __hip_atomic_load(&a.counters[CNT_CAND], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)need), __ATOMIC_RELEASE,
-                               __HIP_MEMORY_SCOPE_SYSTEM);
+    const bool one_batch = g1 - g0 <= kBatch;  // the registers still hold the wave's whole share
+    if (lane < kBuckets) s_lcnt[wave][lane] = lcount;
+    if (check_parent && parent_level < 0) atomicOr(&a.counters[CNT_ERR], 1);  // a parent must be a real position
+    __syncthreads();
+    if (wave == 0) {  // first index of every (level, wave): level major, then wave
+        int t = 0;
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < kListWaves; w++) t += s_lcnt[w][lane];
+        }
+        int incl = t;  // inclusive scan of the level totals over lanes
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
+        }
+        int run = incl - t;
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < kListWaves; w++) {
+                const int c = s_lcnt[w][lane];
+                s_lcnt[w][lane] = run;
+                run += c;
+            }
+        }
+        const int total = __shfl(incl, 63);
+        if (lane == 0) {
+            // this tile's slice of the per-entry arrays; the last workgroup to get here knows the final count
+            // and tells the host, which is waiting for exactly this word, while the lists and the bitmaps
+            // are still being written (no device-scope fence: it would write back the whole L2 of this XCD)
+            s_total = total;
+            int final_total;
+            s_base = reserve_entries(a.counters, (total + bn - 1) / bn, &final_total);
+            if (final_total >= 0) {
+                const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)final_total), __ATOMIC_RELEASE,
+                                   __HIP_MEMORY_SCOPE_SYSTEM);
+            }
         }
     }
     __syncthreads();
+    const int total = s_total, n_ent = (total + bn - 1) / bn;
     const int64_t base = s_base;
     const size_t row = (size_t)b * a.tr + I;
     if (tid == 0) {
         a.q_range[2 * row] = (int32_t)base;
         a.q_range[2 * row + 1] = (int32_t)(base + n_ent);
     }
-    // entries past the capacity are not written (the host then repeats the build with larger arrays); the
-    // ones below it are, because the bitmap kernel evaluates every entry below the capacity
+    // entries past the capacity are not written (the host then repeats the build with larger arrays)
     const int64_t room = a.capacity - base;
     const int n_fit = room <= 0 ? 0 : (room < n_ent ? (int)room : n_ent);
     const int key_fit = n_fit * bn;
     for (int e = tid; e < n_fit; e += kListThreads) a.c_row[base + e] = (int32_t)row;
-    int32_t *keys = a.q_keys + (size_t)base * bn;
+    int32_t *keys = a.q_keys + (size_t)base * bn, *kpars = a.q_kpar + (size_t)base * bn;
     for (int t = total + tid; t < key_fit; t += kListThreads) keys[t] = -1;  // tail of the last entry
-    int run = before;
-    for (int g = g0; g < g1; g++) {
-        const int s = g * 64 + lane;
-        const bool set = (s_mark[s >> 5] >> (s & 31)) & 1u;
-        const unsigned long long m = __ballot(set);
-        if (m == 0ull) continue;
-        const int t = run + __popcll(m & lanemask_lt());
-        if (set && t < key_fit) keys[t] = kperm[s];
-        run += __popcll(m);
+    int mybase = lane < kBuckets ? s_lcnt[wave][lane] : 0;  // lane k: next index of level k in this wave
+    for (int gb = g0; gb < g1; gb += kBatch) {
+        if (!one_batch) load_batch(gb);
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {
+            if (gb + u >= g1) break;
+            const int g = gb + u;
+            const unsigned long long m = (unsigned long long)s_need[2 * g] | ((unsigned long long)s_need[2 * g + 1] << 32);
+            if (m == 0ull) continue;
+            const bool need = (m >> lane) & 1ull;
+            const int bucket = a.no_sort ? 0 : bucket_of(klv[u]);
+            int t = 0;
+            unsigned long long remaining = m;
+            while (remaining) {
+                const int leader = __ffsll((long long)remaining) - 1;
+                const int bk = __builtin_amdgcn_readlane(bucket, leader);
+                const bool is_bk = need && bucket == bk;
+                const unsigned long long mm = __ballot(is_bk);
+                const int first = __builtin_amdgcn_readlane(mybase, bk);
+                if (is_bk) t = first + __popcll(mm & lanemask_lt());
+                if (lane == bk) mybase += __popcll(mm);
+                remaining &= ~mm;
+            }
+            if (need && t < key_fit) {
+                keys[t] = g * 64 + lane;
+                kpars[t] = kp[u];
+            }
+        }
+    }
+    // The entries of this tile, four waves each (two halves of the rows x two halves of the keys).  Their
+    // keys were written to global memory by other waves of this workgroup; the barrier orders those stores
+    // before the loads below at workgroup scope, which is all that is needed on one compute unit (the
+    // loads also bypass the vector cache).
+    __syncthreads();
+    const int wsub = wave & 1, khalf = (wave >> 1) & 1, quad = wave >> 2;
+    const int2 me = s_row[wsub * 64 + lane];
+    for (int e0 = 0; e0 < n_fit; e0 += kListWaves / 4) {
+        const int e = e0 + quad;
+        const bool active = e < n_fit;
+        int kpos[2], kparent[2];
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int si = 64 * u + lane;
+            kpos[u] = -1;
+            kparent[u] = -1;
+            if (active && si < bn) {
+                const int kk = __hip_atomic_load(&keys[e * bn + si], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (kk >= 0 && kk < n) {  // a real key: its parent was written next to it
+                    kpos[u] = kk;
+                    kparent[u] = __hip_atomic_load(&kpars[e * bn + si], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        const EntryPart part = entry_bitmaps(active, base + e, wsub, khalf, lane, me.x, me.y, me.x >= 0, kpos, kparent,
+                                             bm, bn, a.bits, a.bits_rm);
+        __syncthreads();  // the previous round's partial results have been read
+        if (lane == 0) {
+            s_cnt[wave] = part.cnt;
+            s_any[wave] = part.any;
+            s_all[wave] = part.all;
+        }
+        __syncthreads();
+        if (active && (wave & 3) == 0 && lane == 0) {
+            int c = 0;
+            uint32_t any = 0, all = 0;
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                c += s_cnt[wave + w];
+                any |= s_any[wave + w];
+                all |= s_all[wave + w];
+            }
+            a.c_cnt[base + e] = c;
+            a.q_sub[base + e] = any | (all << 16);
+        }
     }
 }
 
-// ---- bitmaps: exact evaluation of every candidate tile ------------------------------------------
-// One entry per workgroup iteration, one row per lane (two waves cover up to 128 rows).  The keys
-// of the tile (a window of the key order, which is then also written to q_keys, or the entry's slots of
-// q_keys) sit in registers, one or two per lane, and are broadcast by lane index; each lane tests
-// its row against every key.  Outputs: the row-major bitmap (export, fp32 path), per 32x32 sub-block
-// the 16 x 64-bit lane masks the MFMA kernels apply to their accumulator registers (wave ballots), the
-// pair count and the sub-block summary.
+// ---- bitmaps of a windowed layout: exact evaluation of every candidate tile -----------------------
+// One candidate per workgroup iteration, a pair of waves (entry_bitmaps).  The keys of the tile are a
+// window of the key order; the positions behind its slots are also written to q_keys, which is what the
+// attention kernels read.
 __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict__ level,
                                                       const int32_t *__restrict__ parent,
                                                       const int32_t *__restrict__ kperm,
                                                       const int32_t *__restrict__ c_row,
                                                       const int32_t *__restrict__ c_col, int32_t *q_keys,
-                                                      int windowed,
                                                       const int32_t *__restrict__ counters, int64_t capacity,
                                                       int n, int n_slots, int bm, int bn, int tr, uint32_t *bits,
                                                       unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
@@ -510,11 +694,9 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
     __shared__ int s_cnt[2];
     __shared__ uint32_t s_any[2], s_all[2];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
-    const size_t words = (size_t)bm * wpr;
-    const int64_t total = min((int64_t)counters[CNT_CAND], capacity);
+    const int64_t total = min((int64_t)(uint32_t)counters[CNT_CAND], capacity);  // low word of the combined counter
     for (int64_t c = blockIdx.x; c < total; c += gridDim.x) {
-        const int row = c_row[c], J = windowed ? c_col[c] : 0;
+        const int row = c_row[c], J = c_col[c];
         const int b = row / tr, I = row - b * tr;
         const size_t o = (size_t)b * n;
         // keys: lane l holds slots l and 64 + l of the tile
@@ -522,10 +704,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
 #pragma unroll
         for (int u = 0; u < 2; u++) {
             const int si = 64 * u + lane, s = J * bn + si;
-            if (windowed)
-                kpos[u] = (si < bn && s < n_slots) ? kperm[(size_t)b * n_slots + s] : -1;
-            else
-                kpos[u] = si < bn ? q_keys[(size_t)c * bn + si] : -1;
+            kpos[u] = (si < bn && s < n_slots) ? kperm[(size_t)b * n_slots + s] : -1;
         }
         // this lane's row
         const int r = wave * 64 + lane, i = I * bm + r;
@@ -540,59 +719,14 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
             const int lv = level[o + pp], pr = parent[o + pp];
             kpos[u] = (okp && lv >= 0) ? kpos[u] : -1;
             kpar[u] = (okp && lv >= 0) ? pr : -1;
-            if (windowed && wave == 0 && 64 * u + lane < bn) q_keys[(size_t)c * bn + 64 * u + lane] = kpos[u];
+            if (wave == 0 && 64 * u + lane < bn) q_keys[(size_t)c * bn + 64 * u + lane] = kpos[u];
         }
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-        int cnt = 0;
-#pragma unroll
-        for (int wd = 0; wd < 4; wd++) {
-            if (wd < wpr) {
-                const int kp = kpos[wd >> 1], kq = kpar[wd >> 1];
-                uint32_t out = 0;
-#pragma unroll
-                for (int cc = 0; cc < 32; cc++) {
-                    const int kj = __builtin_amdgcn_readlane(kp, (wd & 1) * 32 + cc);
-                    const int kr = __builtin_amdgcn_readlane(kq, (wd & 1) * 32 + cc);
-                    const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kr) || pi == kj || kr == i);
-                    out |= (uint32_t)ok << cc;
-                }
-                w[wd] = rowok ? out : 0u;
-                cnt += __popc(w[wd]);
-                if (r < bm) bits[(size_t)c * words + (size_t)r * wpr + wd] = w[wd];
-            }
-        }
-        cnt = wave_sum(cnt);
-        // register-major masks of sub-block (rblk, cblk), accumulator register e: bit l <=> row
-        // rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
-        uint32_t sub_any = 0, sub_all = 0;
-#pragma unroll
-        for (int rr = 0; rr < 2; rr++) {
-            const int rblk = 2 * wave + rr;
-            if (rblk < nrb) {
-#pragma unroll
-                for (int cblk = 0; cblk < 4; cblk++) {
-                    if (cblk < wpr) {
-                        const uint32_t x = (uint32_t)__shfl((int)w[cblk], rr * 32 + (lane & 31));
-                        unsigned long long mine = 0;
-#pragma unroll
-                        for (int e = 0; e < 16; e++) {
-                            const int bit = (lane >> 5) * 4 + 8 * (e >> 2) + (e & 3);
-                            const unsigned long long m = __ballot((x >> bit) & 1u);
-                            if (lane == e) mine = m;
-                        }
-                        const int sb = rblk * wpr + cblk;
-                        if (lane < 16) bits_rm[((size_t)c * nsub + sb) * 16 + lane] = mine;
-                        if (__ballot(x != 0u) != 0ull) sub_any |= 1u << sb;
-                        if (__ballot(x == 0xffffffffu) == ~0ull) sub_all |= 1u << sb;
-                    }
-                }
-            }
-        }
+        const EntryPart part = entry_bitmaps(true, c, wave, -1, lane, i, pi, rowok, kpos, kpar, bm, bn, bits, bits_rm);
         __syncthreads();  // the previous candidate's partial results have been read
         if (lane == 0) {
-            s_cnt[wave] = cnt;
-            s_any[wave] = sub_any;
-            s_all[wave] = sub_all;
+            s_cnt[wave] = part.cnt;
+            s_any[wave] = part.any;
+            s_all[wave] = part.all;
         }
         __syncthreads();
         if (tid == 0) {
@@ -665,7 +799,7 @@ struct Carver {
 };
 
 struct Phase1 {
-    int32_t *kperm, *slot, *cmin, *cmax, *hist, *q_range, *counters;
+    int32_t *kperm, *slot, *cmin, *cmax, *hist, *q_range, *counters, *level_copy, *parent_copy;
     size_t zero_begin, zero_end;  // byte range that must start at zero
     size_t bytes;
 };
@@ -680,6 +814,8 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int nchunks)
     p.cmax = c.take<int32_t>((size_t)B * n);
     p.hist = c.take<int32_t>((size_t)B * nchunks * kBuckets);
     p.q_range = c.take<int32_t>((size_t)B * tr * 2);
+    p.level_copy = c.take<int32_t>((size_t)B * n);
+    p.parent_copy = c.take<int32_t>((size_t)B * n);
     p.zero_begin = c.off;
     p.counters = c.take<int32_t>(64);
     p.zero_end = c.off;
@@ -688,7 +824,7 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int nchunks)
 }
 
 struct Phase2 {
-    int32_t *q_cols, *c_row, *c_cnt, *q_keys;
+    int32_t *q_cols, *c_row, *c_cnt, *q_keys, *q_kpar;
     uint32_t *q_sub, *bits;
     unsigned long long *bits_rm;
     size_t bytes;
@@ -704,6 +840,7 @@ Phase2 carve_phase2(char *base, int64_t cap, int bm, int bn)
     p.c_row = c.take<int32_t>(n);
     p.c_cnt = c.take<int32_t>(n);
     p.q_keys = c.take<int32_t>(n * (size_t)bn);
+    p.q_kpar = c.take<int32_t>(n * (size_t)bn);
     p.bits = c.take<uint32_t>(n * words);
     p.bits_rm = c.take<unsigned long long>(n * nsub * 16);
     p.bytes = c.off;
@@ -789,6 +926,32 @@ hdt_status_t hdt_layout_stats(const hdt_layout_t *L)
     return HDT_OK;
 }
 
+// The key order of a layout built from key lists: sorted from the layout's own copy of the ids by the
+// first caller that asks for it (the build itself never needs it).  Waits for the device.
+hdt_status_t hdt_layout_ensure_kperm(const hdt_layout_t *L)
+{
+    static std::mutex kperm_mutex;
+    std::lock_guard<std::mutex> lk(kperm_mutex);
+    if (L->kperm_ready || L->s.batch == 0 || L->s.n_pos == 0) return HDT_OK;
+    int dev = 0;
+    HDT_HIP_TRY(hipGetDevice(&dev));
+    if (dev != L->device) HDT_HIP_TRY(hipSetDevice(L->device));
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) {
+        const int B = L->s.batch, n = L->s.n_pos, nchunks = (n + kChunk - 1) / kChunk;
+        SortArgs sa{L->level_copy, L->parent_copy, n, L->s.n_slots, nchunks, L->no_sort, L->sort_hist,
+                    const_cast<int32_t *>(L->s.kperm), nullptr, nullptr, nullptr, L->sort_counters, 0};
+        hipLaunchKernelGGL(k_sort_count, dim3((unsigned)B * nchunks), dim3(kThreads), 0, nullptr, sa);
+        hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)B * nchunks), dim3(kThreads), 0, nullptr, sa);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+    }
+    if (dev != L->device) (void)hipSetDevice(dev);
+    if (e != hipSuccess) return hdt_fail(HDT_ERR_HIP, "hdt_layout_ensure_kperm: %s", hipGetErrorString(e));
+    L->kperm_ready = true;
+    return HDT_OK;
+}
+
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_release_cached_memory(void)
 {
     std::vector<CachedBlock> blocks;
@@ -838,6 +1001,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     L->d_row = nullptr;
     L->n_entries = 0;
     L->stats_ready = false;
+    L->kperm_ready = true;
+    L->no_sort = 0;
+    L->sort_hist = L->sort_counters = nullptr;
+    L->level_copy = L->parent_copy = nullptr;
     L->force_dense = force_dense;
     L->windowed = windowed;
     L->device_bytes = 0;
@@ -905,9 +1072,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 goto fail;
             }
             BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
-            {
-                SortArgs sa{d_level, d_parent, n, s.n_slots, nchunks, no_sort, p.hist, p.kperm, p.slot, p.cmin, p.cmax,
-                            p.counters};
+            if (windowed) {
+                SortArgs sa{d_level, d_parent, n, s.n_slots, nchunks, no_sort, p.hist, p.kperm, p.slot, p.cmin,
+                            p.cmax, p.counters, 1};
                 {
                     HdtTimer t("hdt_layout_sort_count", st);
                     hipLaunchKernelGGL(k_sort_count, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
@@ -916,28 +1083,29 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                     HdtTimer t("hdt_layout_sort_scatter", st);
                     hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
                 }
-                if (windowed) {
-                    CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, cap,
-                                p.q_range, q.c_row, q.q_cols, p.counters, report, ticket};
-                    HdtTimer t("hdt_layout_candidates", st);
-                    hipLaunchKernelGGL(k_candidates, dim3((unsigned)B * groups), dim3(kThreads),
-                                       (size_t)kWaves * wc * sizeof(uint32_t), st, ca);
-                } else {
-                    KeyListArgs ka{d_level, d_parent, p.slot, p.cmin, p.cmax, p.kperm, n, s.n_slots, bm, bn, tr, cap,
-                                   p.q_range, q.c_row, q.q_keys, p.counters, report, ticket};
-                    const size_t lds = (size_t)2 * ((s.n_slots + 63) / 64) * sizeof(uint32_t);
-                    if (lds > 48 * 1024)
-                        BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists,
-                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-                    HdtTimer t("hdt_layout_key_lists", st);
-                    hipLaunchKernelGGL(k_key_lists, dim3((unsigned)B * tr), dim3(kListThreads), lds, st, ka);
-                }
+                CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, cap,
+                            p.q_range, q.c_row, q.q_cols, p.counters, report, ticket};
+                HdtTimer t("hdt_layout_candidates", st);
+                hipLaunchKernelGGL(k_candidates, dim3((unsigned)B * groups), dim3(kThreads),
+                                   (size_t)kWaves * wc * sizeof(uint32_t), st, ca);
+            } else {
+                // one kernel from the ids to the finished entries; the global key order is not needed for it
+                // and is sorted from the layout's copy of the ids only when someone asks (hdt_layout_export)
+                KeyListArgs ka{d_level, d_parent, n, bm, bn, tr, no_sort, cap, p.q_range, q.c_row, q.q_keys, q.q_kpar,
+                               q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits, q.bits_rm, p.counters, report,
+                               ticket};
+                const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
+                if (lds > 48 * 1024)
+                    BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                  (int)lds));
+                HdtTimer t("hdt_layout_key_lists", st);
+                hipLaunchKernelGGL(k_key_lists, dim3((unsigned)B * tr), dim3(kListThreads), lds, st, ka);
             }
-            {
+            if (windowed) {
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
                 hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(128), 0, st, d_level, d_parent, p.kperm, q.c_row,
-                                   q.q_cols, q.q_keys, windowed, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits,
+                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits,
                                    q.bits_rm, q.c_cnt, q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
@@ -951,7 +1119,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 int32_t cnt[4] = {0, 0, 0, 0};
                 BUILD_TRY(hipStreamSynchronize(st));
                 BUILD_TRY(hipMemcpy(cnt, p.counters, sizeof(cnt), hipMemcpyDeviceToHost));
-                word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);
+                word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);  // low word of the combined counter
             }
             if ((word >> 39) & 1u) {
                 BUILD_TRY(hipStreamSynchronize(st));  // the bitmap kernel still reads the arenas
@@ -970,6 +1138,12 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 L->capacity = cap;
                 L->n_entries = need;
                 s.kperm = p.kperm;
+                L->kperm_ready = windowed != 0;
+                L->no_sort = no_sort;
+                L->sort_hist = p.hist;
+                L->sort_counters = p.counters;
+                L->level_copy = p.level_copy;
+                L->parent_copy = p.parent_copy;
                 s.q_range = p.q_range;
                 s.q_cols = q.q_cols;
                 s.q_keys = q.q_keys;
