@@ -11,7 +11,8 @@
  *   - the attention mask, pair by pair from explicit parent pointers: a position
  *     sees its parent, its siblings (itself included) and its children
  *     (Sec. 3.2 "Hierarchical Attention", Eqs. for M^DOC / M^SEC / M^SENT and
- *     their OR; Fig. 2 caption);
+ *     their OR; Fig. 2 caption); and the thinned, directed variants of it that
+ *     Sec. 4.1 uses on ListOps (no edge to the parent; no edges between siblings);
  *   - masked softmax attention by its definition, two-pass softmax, no tiling
  *     and no online rescaling (Sec. 3.2, the equation S = softmax(A (.) 1_M),
  *     A = Q K^T / sqrt(d_k), O = S V; -inf where M = 0);
@@ -47,15 +48,38 @@
 
 /* ---- mask: parent / siblings / children, pair by pair ------------------- */
 
+/* Which kinds of edges of the hierarchy carry attention (Sec. 4.1 "Mathematical Reasoning": the
+ * full pattern of Sec. 3.2 is red + green + blue; the sparser ListOps variants drop the edge from a
+ * position to its parent ("operands do not attend to their operators": green + blue) and then
+ * also the edges between siblings ("operands do not attend to each other": blue only)).
+ * A position always attends to itself. */
+#define ORACLE_EDGE_UP 1      /* a position attends to its parent             */
+#define ORACLE_EDGE_SIBLING 2 /* a position attends to its siblings           */
+#define ORACLE_EDGE_DOWN 4    /* a position attends to its children           */
+#define ORACLE_EDGE_ALL 7
+
+/* 1 iff position i may attend to position j under the edge kinds `edges`. */
+int oracle_allowed_edges(const int32_t *level, const int32_t *parent, int64_t i, int64_t j, int edges)
+{
+    if (level[i] < 0 || level[j] < 0) return 0;        /* pads */
+    if (i == j) return 1;                               /* itself */
+    if ((edges & ORACLE_EDGE_SIBLING) && parent[i] >= 0 && parent[i] == parent[j]) return 1; /* same parent */
+    if ((edges & ORACLE_EDGE_UP) && parent[i] == j) return 1;   /* j is i's parent */
+    if ((edges & ORACLE_EDGE_DOWN) && parent[j] == i) return 1; /* j is i's child */
+    return 0;
+}
+
+/* The edge kinds every function below uses; ORACLE_EDGE_ALL (the paper's full pattern) unless a test
+ * selects a variant.  (A process-wide setting: the oracle is test infrastructure, called from one
+ * thread at a time; the OpenMP workers only read it.) */
+static int g_edges = ORACLE_EDGE_ALL;
+void oracle_set_edges(int edges) { g_edges = edges & ORACLE_EDGE_ALL; }
+int oracle_get_edges(void) { return g_edges; }
+
 /* 1 iff position i may attend to position j. */
 int oracle_allowed(const int32_t *level, const int32_t *parent, int64_t i, int64_t j)
 {
-    if (level[i] < 0 || level[j] < 0) return 0;        /* pads */
-    if (i == j) return 1;                               /* itself (a sibling of itself) */
-    if (parent[i] >= 0 && parent[i] == parent[j]) return 1; /* siblings: same parent */
-    if (parent[i] == j) return 1;                       /* j is i's parent */
-    if (parent[j] == i) return 1;                       /* j is i's child */
-    return 0;
+    return oracle_allowed_edges(level, parent, i, j, g_edges);
 }
 
 /* Dense mask M[n][n] (row i, column j in document order). */

@@ -43,6 +43,12 @@ def _load():
         i64 = ctypes.c_int64
         lib.oracle_allowed.argtypes = [i32p, i32p, i64, i64]
         lib.oracle_allowed.restype = ctypes.c_int
+        lib.oracle_allowed_edges.argtypes = [i32p, i32p, i64, i64, ctypes.c_int]
+        lib.oracle_allowed_edges.restype = ctypes.c_int
+        lib.oracle_set_edges.argtypes = [ctypes.c_int]
+        lib.oracle_set_edges.restype = None
+        lib.oracle_get_edges.argtypes = []
+        lib.oracle_get_edges.restype = ctypes.c_int
         lib.oracle_mask.argtypes = [i32p, i32p, i64, ctypes.POINTER(ctypes.c_uint8)]
         lib.oracle_mask.restype = None
         lib.oracle_row_counts.argtypes = [i32p, i32p, i64, i64p]
@@ -76,6 +82,27 @@ def _p(a, ct):
 
 def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
+
+
+EDGE_UP, EDGE_SIBLING, EDGE_DOWN, EDGE_ALL = 1, 2, 4, 7
+
+
+class edges:
+    """``with oracle.edges(EDGE_SIBLING | EDGE_DOWN): ...`` evaluates every oracle function inside the
+    block under a thinned mask (Sec. 4.1: the ListOps variants); the full pattern is restored after."""
+
+    def __init__(self, kinds: int):
+        self.kinds = int(kinds)
+
+    def __enter__(self):
+        lib = _load()
+        self.saved = lib.oracle_get_edges()
+        lib.oracle_set_edges(self.kinds)
+        return self
+
+    def __exit__(self, *exc):
+        _load().oracle_set_edges(self.saved)
+        return False
 
 
 def num_threads() -> int:

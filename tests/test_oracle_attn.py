@@ -158,3 +158,50 @@ def test_backward_closed_form_q_zero(oracle):
     cnt = M.sum(axis=1).astype(np.float64)
     w = np.divide(M, cnt[:, None], out=np.zeros((n, n)), where=cnt[:, None] > 0)
     np.testing.assert_allclose(dv[0, 0], w.T @ d_o[0, 0], rtol=1e-12, atol=1e-14)
+
+
+# ---- the thinned patterns of Sec. 4.1 (asymmetric masks) ------------------------------------------
+
+def _variant_masks():
+    import test_oracle_mask
+    return test_oracle_mask._read_variants("mask_tree10_variants.txt")
+
+
+@pytest.mark.parametrize("variant,kinds", [("gb", 2 | 4), ("blue", 4)])
+def test_forward_on_listops_variants_against_textbook(oracle, variant, kinds):
+    level, parent, _, _ = read_golden_mask("mask_tree10.txt")
+    M = _variant_masks()[variant]
+    n, d, H = level.shape[0], 5, 2
+    q, k, v = (_rand((1, H, n, d), s) for s in (31, 32, 33))
+    with oracle.edges(kinds):
+        o, lse = oracle.attn_fwd(q, k, v, level[None], parent[None], 0.45)
+    for h in range(H):
+        o_ref, lse_ref, _ = dense_masked_attention(q[0, h], k[0, h], v[0, h], M, 0.45)
+        np.testing.assert_allclose(o[0, h], o_ref, rtol=1e-12, atol=1e-13)
+        fin = np.isfinite(lse_ref)
+        np.testing.assert_allclose(lse[0, h][fin], lse_ref[fin], rtol=1e-12)
+        assert np.isneginf(lse[0, h][~fin]).all()
+
+
+@pytest.mark.parametrize("kinds", [2 | 4, 4, 1 | 2])
+def test_backward_finite_differences_on_asymmetric_masks(oracle, kinds):
+    level, parent, _, _ = read_golden_mask("mask_tree10.txt")
+    n, d, H = level.shape[0], 3, 1
+    q, k, v, d_o = (_rand((1, H, n, d), s) for s in (40, 41, 42, 43))
+    lv, pr = level[None], parent[None]
+    with oracle.edges(kinds):
+        dq, dk, dv = oracle.attn_bwd(q, k, v, d_o, lv, pr, 0.5)
+        eps = 1e-6
+        for x, g in ((q, dq), (k, dk), (v, dv)):
+            num = np.zeros_like(x)
+            it = np.nditer(x, flags=["multi_index"])
+            for _ in it:
+                idx = it.multi_index
+                old = x[idx]
+                x[idx] = old + eps
+                lp = _loss(oracle, q, k, v, d_o, lv, pr, 0.5)
+                x[idx] = old - eps
+                lm = _loss(oracle, q, k, v, d_o, lv, pr, 0.5)
+                x[idx] = old
+                num[idx] = (lp - lm) / (2 * eps)
+            np.testing.assert_allclose(g, num, rtol=2e-6, atol=2e-8)

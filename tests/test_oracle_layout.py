@@ -243,3 +243,18 @@ def test_window_schedule_key_positions(oracle):
     sch = oracle.block_schedule(level, parent, 32, 32)
     assert sch.q_cols.tolist() == [0]
     assert sch.q_keys[0].tolist() == kperm[:12].tolist() + [-1] * 20
+
+
+@pytest.mark.parametrize("variant,kinds", [("gb", 2 | 4), ("blue", 4)])
+def test_schedules_of_the_listops_variants(oracle, variant, kinds):
+    # asymmetric masks (Sec. 4.1): the schedules describe the thinned mask, rows = queries
+    import test_oracle_mask
+    level, parent, kperm, _ = read_golden_mask("mask_tree10.txt")
+    M = test_oracle_mask._read_variants("mask_tree10_variants.txt")[variant]
+    with oracle.edges(kinds):
+        for bm, bn in [(4, 4), (32, 32)]:
+            _check_keylists_against_dense_mask(oracle.keylist_schedule(level, parent, bm, bn), M, kperm, bm, bn)
+        sch = oracle.block_schedule(level, parent, 32, 32)
+    got = ((sch.bits[0][:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(32, 32)
+    np.testing.assert_array_equal(got[:10, :10], M[:, kperm])
+    assert sch.nnz == M.sum()

@@ -99,3 +99,79 @@ def test_two_roots_are_not_siblings(oracle):
     parent = np.array([-1, 0, -1, 2], dtype=np.int32)
     M = oracle.mask(level, parent)
     np.testing.assert_array_equal(M, np.array([[1, 1, 0, 0], [1, 1, 0, 0], [0, 0, 1, 1], [0, 0, 1, 1]]))
+
+
+# ---- the thinned patterns of Sec. 4.1 (ListOps): no edge to the parent; no edges between siblings ----
+
+def _read_variants(name):
+    import os
+    from helpers import GOLDEN
+    out, cur = {}, None
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line.startswith("variant"):
+                cur = line.split()[1]
+                out[cur] = []
+            else:
+                out[cur].append([int(c) for c in line])
+    return {k: np.array(v, np.uint8) for k, v in out.items()}
+
+
+def test_hand_enumerated_listops_variants(oracle):
+    level, parent, _, M_full = read_golden_mask("mask_tree10.txt")
+    var = _read_variants("mask_tree10_variants.txt")
+    with oracle.edges(oracle.EDGE_SIBLING | oracle.EDGE_DOWN):
+        np.testing.assert_array_equal(oracle.mask(level, parent), var["gb"])
+    with oracle.edges(oracle.EDGE_DOWN):
+        np.testing.assert_array_equal(oracle.mask(level, parent), var["blue"])
+    np.testing.assert_array_equal(oracle.mask(level, parent), M_full)   # the full pattern is back
+
+
+def test_edge_kinds_partition_the_full_mask(oracle):
+    # off the diagonal every allowed pair is exactly one of: parent, sibling, child; swapping the
+    # parent and child kinds transposes the mask
+    wl = inputs.make_workload(1)
+    level, parent = wl.level[0][:300], wl.parent[0][:300]
+    full = oracle.mask(level, parent)
+    parts = {}
+    for kind in (oracle.EDGE_UP, oracle.EDGE_SIBLING, oracle.EDGE_DOWN):
+        with oracle.edges(kind):
+            parts[kind] = oracle.mask(level, parent)
+    eye = np.diag((level >= 0).astype(np.uint8))
+    total = sum(p.astype(np.int32) - eye for p in parts.values()) + eye
+    np.testing.assert_array_equal(total, full)
+    np.testing.assert_array_equal(parts[oracle.EDGE_UP], parts[oracle.EDGE_DOWN].T)
+    np.testing.assert_array_equal(parts[oracle.EDGE_SIBLING], parts[oracle.EDGE_SIBLING].T)
+    with oracle.edges(oracle.EDGE_SIBLING | oracle.EDGE_UP):
+        a = oracle.mask(level, parent)
+    with oracle.edges(oracle.EDGE_SIBLING | oracle.EDGE_DOWN):
+        b = oracle.mask(level, parent)
+    np.testing.assert_array_equal(a, b.T)
+    # the parent edge: exactly one per position that has a parent
+    assert (parts[oracle.EDGE_UP] - eye).sum() == (parent >= 0).sum()
+    idx = np.nonzero(parent >= 0)[0]
+    assert all(parts[oracle.EDGE_UP][i, parent[i]] for i in idx)
+
+
+def test_listops_variant_row_counts_closed_form(oracle):
+    wl = inputs.make_workload(2, batch=1)
+    level, parent, sections = wl.level[0], wl.parent[0], wl.sections[0]
+    S = len(sections)
+    gb, blue = [S + 1], [S + 1]       # [DOC]: itself and its sections under both variants
+    for sec in sections:
+        k = len(sec)
+        gb.append(k + S)              # [SEC]: its k sentences + the S sections (itself among them), no parent
+        blue.append(k + 1)
+        for l in sec:
+            gb.append(l + k)          # [SENT]: l tokens + k sentence anchors
+            blue.append(l + 1)
+            gb.extend([l] * l)        # token: the l tokens of its sentence
+            blue.extend([1] * l)
+    pad = [0] * (wl.n_pos - len(gb))
+    with oracle.edges(oracle.EDGE_SIBLING | oracle.EDGE_DOWN):
+        np.testing.assert_array_equal(np.diff(oracle.row_lists(level, parent)[0]), np.array(gb + pad))
+    with oracle.edges(oracle.EDGE_DOWN):
+        np.testing.assert_array_equal(np.diff(oracle.row_lists(level, parent)[0]), np.array(blue + pad))
