@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--windowed", action="store_true",
                     help="key tiles = fixed windows of the level-sorted key order (Alg. 1 as printed) instead of "
                          "the default per-query-tile key lists")
+    ap.add_argument("--edges", type=int, default=0,
+                    help="edge kinds of the mask (1 parent, 2 siblings, 4 children, OR-ed; 0 = all): the thinned "
+                         "patterns of the paper's ListOps study applied to the workload's documents")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events (for external profilers)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -84,7 +87,7 @@ def main() -> int:
             outs.update(dq=torch.empty_like(t[0]), dk=torch.empty_like(t[0]), dv=torch.empty_like(t[0]))
         sets.append((t, outs))
     del xs
-    probe = hdt.hdt_build_layout(level, parent, windowed=args.windowed)
+    probe = hdt.hdt_build_layout(level, parent, windowed=args.windowed, edges=args.edges)
     info = probe.info()
     ws_bytes = hdt.hdt_attn_bwd_workspace_bytes(probe, H, D, 0)
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
@@ -92,7 +95,7 @@ def main() -> int:
 
     def step(i):
         t, outs = sets[i % n_sets]
-        lay = hdt.hdt_build_layout(level, parent, windowed=args.windowed)
+        lay = hdt.hdt_build_layout(level, parent, windowed=args.windowed, edges=args.edges)
         hdt.hdt_attn_fwd(lay, t[0], t[1], t[2], scale, o=outs["o"], lse=outs["lse"])
         if do_bwd:
             hdt.hdt_attn_bwd(lay, t[0], t[1], t[2], outs["o"], outs["lse"], t[3], scale, dq=outs["dq"],
@@ -182,7 +185,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "batch": B, "heads": H, "head_dim": D,
                    "n_pos": N, "real_positions": wl.n_real, "tile": "128x64",
-                   "schedule": "windowed" if args.windowed else "key-lists", "n_tiles": n_tiles, "nnz": nnz},
+                   "schedule": "windowed" if args.windowed else "key-lists", "edges": info["edges"],
+                   "n_tiles": n_tiles, "nnz": nnz},
         "useful_tflops": round(useful_flop / (ms_per_step * 1e-3) / 1e12, 3),
         "phase_us_per_step": {k: round(v, 2) for k, v in phase_us.items()},
         "kernels": {n: {"launches": kv["launches"], "avg_us": round(kv["avg_us"], 2)} for n, kv in per_kernel.items()},
@@ -206,9 +210,10 @@ def main() -> int:
         xs = [inputs.round_to_bf16(x) for x in inputs.make_qkv(B, H, N, D, inputs.sample_seed(args.config, 70),
                                                                4 if do_bwd else 3)]
         c0 = time.perf_counter()
-        oracle.attn_fwd(xs[0], xs[1], xs[2], wl.level, wl.parent, scale)
-        if do_bwd:
-            oracle.attn_bwd(xs[0], xs[1], xs[2], xs[3], wl.level, wl.parent, scale)
+        with oracle.edges(args.edges or oracle.EDGE_ALL):
+            oracle.attn_fwd(xs[0], xs[1], xs[2], wl.level, wl.parent, scale)
+            if do_bwd:
+                oracle.attn_bwd(xs[0], xs[1], xs[2], xs[3], wl.level, wl.parent, scale)
         c1 = time.perf_counter()
         out["cpu_baseline"] = {"value": round(tokens / (c1 - c0), 1), "unit": "tokens/s",
                                "cores": oracle.num_threads(), "kind": "oracle",

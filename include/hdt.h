@@ -56,6 +56,16 @@ typedef enum {
 #define HDT_LEVEL_PAD (-1)
 #define HDT_MAX_LEVELS 32
 
+/* Kinds of hierarchy edges that carry attention (hdt_layout_opts_t.edges).  All three together are the
+ * pattern of Sec. 3.2; the paper's ListOps study (Sec. 4.1) thins it: HDT_EDGE_SIBLING | HDT_EDGE_DOWN
+ * ("operands do not attend to their operators") and HDT_EDGE_DOWN alone ("nor to each other").  A
+ * position always attends to itself.  Without HDT_EDGE_UP == HDT_EDGE_DOWN symmetry the mask is directed;
+ * the layout then also holds the schedule of the transposed mask, which the backward pass needs. */
+#define HDT_EDGE_UP 1      /* a position attends to its parent   */
+#define HDT_EDGE_SIBLING 2 /* a position attends to its siblings */
+#define HDT_EDGE_DOWN 4    /* a position attends to its children */
+#define HDT_EDGE_ALL 7
+
 typedef struct hdt_layout hdt_layout_t; /* opaque; owns its device buffers */
 
 typedef struct {
@@ -65,13 +75,14 @@ typedef struct {
     int32_t no_sort;     /* 1: keep keys in document order (block-sparse baseline w/o sort)   */
     int32_t windowed;    /* 1: key tiles are fixed windows of the key order (Alg. 1 as printed); */
                          /* 0: every query tile gets its own packed key list (default)         */
+    int32_t edges;       /* OR of HDT_EDGE_*; 0 = HDT_EDGE_ALL                                  */
 } hdt_layout_opts_t;
 
 typedef struct {
     int32_t batch, n_pos, tile_m, tile_n;
     int32_t q_tiles, k_tiles; /* per sample: ceil(n_pos/tile_m), ceil(n_pos/tile_n)  */
     int32_t windowed;         /* 1: fixed key windows, 0: per-query-tile key lists   */
-    int32_t reserved;
+    int32_t edges;            /* OR of HDT_EDGE_* the mask was built with            */
     int64_t n_tiles;          /* surviving tiles (list entries), summed over the batch */
     int64_t nnz;              /* allowed (query, key) pairs, summed over the batch   */
     int64_t device_bytes;     /* device memory held by the layout                    */
@@ -92,8 +103,9 @@ typedef struct {
  * The schedule, per sample:
  *   kperm    key order: positions sorted by level (0, 1, 2, ...; pads last), ties in document order
  *            (document order throughout with no_sort);
- *   allowed(i, j) = both non-pad and (i == j, or parent[i] == parent[j] >= 0, or parent[i] == j,
- *            or parent[j] == i);
+ *   allowed(i, j) = both non-pad and (i == j, or parent[i] == parent[j] >= 0 [HDT_EDGE_SIBLING], or
+ *            parent[i] == j [HDT_EDGE_UP], or parent[j] == i [HDT_EDGE_DOWN]), the bracketed kinds as enabled
+ *            by opts->edges;
  *   a tile = tile_m consecutive query rows [I*tile_m, (I+1)*tile_m) in document order x tile_n keys.
  *   windowed = 1 (Alg. 1 as printed): the keys of tile (I, J) are the slots [J*tile_n, (J+1)*tile_n)
  *            of the key order; the tile survives iff some pair in it is allowed; the tiles of a
@@ -114,7 +126,7 @@ typedef struct {
  * layout comes from a cache of buffers of destroyed layouts (hipMalloc when the cache has nothing
  * that fits).  batch == 0 or n_pos == 0 gives an empty layout on which the attention calls are no-ops.
  *
- * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (n_pos > 2^19),
+ * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes, edges outside HDT_EDGE_ALL), HDT_ERR_SHAPE (n_pos > 2^19),
  * HDT_ERR_UNSUPPORTED (tile shape), HDT_ERR_HIERARCHY (level outside [-1, HDT_MAX_LEVELS),
  * parent outside [-1, n_pos), parent[i] == i, a pad with a parent, a parent that is a pad),
  * HDT_ERR_OOM, HDT_ERR_HIP.  On error *out is NULL.

@@ -2,6 +2,10 @@
 kernels behind a C ABI (``include/hdt.h``), with a thin ctypes binding.  PyTorch is only used for
 device memory and streams."""
 from .binding import (  # noqa: F401
+    HDT_EDGE_ALL,
+    HDT_EDGE_DOWN,
+    HDT_EDGE_SIBLING,
+    HDT_EDGE_UP,
     HdtError,
     Layout,
     hdt_attn_bwd,

@@ -15,6 +15,7 @@ _LIB_PATH = os.environ.get("HDT_LIBRARY_PATH") or os.path.join(_PKG, "libhdt.so"
 _lib = None
 
 HDT_BF16, HDT_F32 = 0, 1
+HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 
 EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
@@ -32,13 +33,13 @@ class HdtError(RuntimeError):
 
 class _Opts(ctypes.Structure):
     _fields_ = [("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32), ("force_dense", ctypes.c_int32),
-                ("no_sort", ctypes.c_int32), ("windowed", ctypes.c_int32)]
+                ("no_sort", ctypes.c_int32), ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32)]
 
 
 class _Info(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_pos", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("q_tiles", ctypes.c_int32), ("k_tiles", ctypes.c_int32),
-                ("windowed", ctypes.c_int32), ("reserved", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
 
 
 def library_path() -> str:
@@ -165,8 +166,8 @@ class Layout:
 
 
 def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dense: bool = False,
-                     no_sort: bool = False, windowed: bool = False, stream=None) -> Layout:
-    """level, parent: int32 device tensors [batch][n_pos]."""
+                     no_sort: bool = False, windowed: bool = False, edges: int = 0, stream=None) -> Layout:
+    """level, parent: int32 device tensors [batch][n_pos].  ``edges``: OR of HDT_EDGE_* (0 = all)."""
     import torch
     if level.dtype != torch.int32 or parent.dtype != torch.int32:
         raise TypeError("level and parent must be int32")
@@ -174,7 +175,7 @@ def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dens
         raise ValueError("level and parent must both be [batch][n_pos]")
     if not (level.is_cuda and parent.is_cuda and level.is_contiguous() and parent.is_contiguous()):
         raise ValueError("level and parent must be contiguous device tensors")
-    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort), int(windowed))
+    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort), int(windowed), int(edges))
     h = ctypes.c_void_p(0)
     B, N = level.shape
     _check(load_library().hdt_build_layout(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,

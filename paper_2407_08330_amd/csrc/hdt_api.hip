@@ -134,7 +134,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(c
     info->q_tiles = l->s.tr;
     info->k_tiles = l->s.tc;
     info->windowed = l->windowed;
-    info->reserved = 0;
+    info->edges = l->edges;
     info->n_tiles = 0;
     info->nnz = 0;
     for (int b = 0; b < l->s.batch; b++) {
@@ -243,6 +243,13 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destro
 {
     if (!layout) return HDT_OK;
     if (layout->magic != HDT_LAYOUT_MAGIC) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_destroy: not a layout");
+    if (layout->transposed) {
+        hdt_layout_t *t = layout->transposed;
+        layout->transposed = nullptr;
+        t->magic = 0;
+        hdt_layout_release(t);
+        delete t;
+    }
     layout->magic = 0;
     hdt_layout_release(layout);
     delete layout;
@@ -327,9 +334,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) > 0x7fffffffLL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
+    const HdtSchedule &s_tr = layout->transposed ? layout->transposed->s : s;
     if (dt == HDT_BF16)
-        return hdt_launch_bwd_bf16(s, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, (float *)workspace, hs);
-    return hdt_launch_bwd_f32(s, (const float *)q, (const float *)k, (const float *)v, (const float *)o, lse,
+        return hdt_launch_bwd_bf16(s, s_tr, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, (float *)workspace, hs);
+    return hdt_launch_bwd_f32(s, s_tr, (const float *)q, (const float *)k, (const float *)v, (const float *)o, lse,
                               (const float *)d_o, (float *)dq, (float *)dk, (float *)dv, heads, head_dim, scale,
                               (float *)workspace, hs);
 }

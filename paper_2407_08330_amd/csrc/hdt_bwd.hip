@@ -10,13 +10,15 @@
 //              positions of each list entry, gathered row by row), recomputes S^T and dP^T with queries
 //              along the MFMA columns (LSE_i and D_i are per-lane scalars) and accumulates
 //              dQ^T = K^T dS^T.  It also writes D.
-//   k_bwd_dkv  the mask is symmetric (i may attend to j iff j may attend to i: parent/child and
-//              sibling relations are mutual), so the entries of "query rows I x the keys they attend to"
+//   k_bwd_dkv  walks the schedule of the TRANSPOSED mask.  The paper's mask is symmetric (i may attend to
+//              j iff j may attend to i: parent/child and sibling relations are mutual), so the entries of "query rows I x the keys they attend to"
 //              are also the entries of "key rows I x the queries attending to them", bitmaps included.  A workgroup therefore owns
 //              128 KEYS in document order (K, V rows in registers), walks the same list, gathers the
 //              Q and dO rows (and LSE, D) of an entry's 64 QUERY positions into LDS and accumulates
 //              dV^T = dO^T P and dK^T = Q^T dS with keys along the MFMA columns.  Same load balance
-//              as the forward, no transposed lists, no cross-wave reduction, contiguous stores.
+//              as the forward, no cross-wave reduction, contiguous stores.  For the directed variants
+//              (edge kinds without up/down symmetry) the layout holds a second schedule, built from
+//              the same ids with the parent and child kinds exchanged.
 // Both passes recompute the scores, which costs two extra contractions but keeps dQ out of HBM
 // as fp32 partial sums.
 #include "hdt_tile.h"
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
 
 }  // namespace
 
-hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const void *q, const void *k, const void *v,
+hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const HdtSchedule &st_, const void *q, const void *k, const void *v,
                                  const void *o, const float *lse, const void *d_o, void *dq, void *dk, void *dv,
                                  int heads, int head_dim, float scale, float *delta, hipStream_t st)
 {
@@ -326,10 +328,10 @@ hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const void *q, const void
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_dkv_bf16_d64" : "hdt_bwd_dkv_bf16_d128", st);
         if (head_dim == 64)
-            hipLaunchKernelGGL(k_bwd_dkv_bf16<64>, grid, block, 0, st, s, Q, K, V, lse, DO, delta, (__bf16 *)dk,
+            hipLaunchKernelGGL(k_bwd_dkv_bf16<64>, grid, block, 0, st, st_, Q, K, V, lse, DO, delta, (__bf16 *)dk,
                                (__bf16 *)dv, heads, scale);
         else
-            hipLaunchKernelGGL(k_bwd_dkv_bf16<128>, grid, block, 0, st, s, Q, K, V, lse, DO, delta, (__bf16 *)dk,
+            hipLaunchKernelGGL(k_bwd_dkv_bf16<128>, grid, block, 0, st, st_, Q, K, V, lse, DO, delta, (__bf16 *)dk,
                                (__bf16 *)dv, heads, scale);
     }
     HDT_HIP_TRY(hipGetLastError());

@@ -92,8 +92,9 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     for (int c = 0; c < D; c++) dqi[c] = acc[c];
 }
 
-// dK, dV: the mask is symmetric (i may attend to j iff j may attend to i), so the list of query tile I
-// x key slots J is also the list of key rows I x query slots J with the same bitmaps.  One thread per
+// dK, dV: walks the schedule of the transposed mask (for the paper's symmetric mask that is the forward's
+// own schedule: the list of query tile I x key slots J is also the list of key rows I x query slots J with
+// the same bitmaps; directed variants bring a second schedule).  One thread per
 // key row (document order) walks that list and gathers the query rows its entries name.
 template <int D>
 __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float *__restrict__ q,
@@ -157,7 +158,7 @@ hdt_status_t hdt_launch_fwd_f32(const HdtSchedule &s, const float *q, const floa
     return HDT_OK;
 }
 
-hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const float *q, const float *k, const float *v,
+hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const HdtSchedule &st_, const float *q, const float *k, const float *v,
                                 const float *o, const float *lse, const float *d_o, float *dq, float *dk,
                                 float *dv, int heads, int head_dim, float scale, float *delta, hipStream_t st)
 {
@@ -173,9 +174,9 @@ hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const float *q, const floa
     {
         HdtTimer t("hdt_bwd_dkv_f32", st);
         if (head_dim == 64)
-            hipLaunchKernelGGL(k_bwd_dkv_f32<64>, gk, block, 0, st, s, q, k, v, lse, d_o, delta, dk, dv, heads, scale);
+            hipLaunchKernelGGL(k_bwd_dkv_f32<64>, gk, block, 0, st, st_, q, k, v, lse, d_o, delta, dk, dv, heads, scale);
         else
-            hipLaunchKernelGGL(k_bwd_dkv_f32<128>, gk, block, 0, st, s, q, k, v, lse, d_o, delta, dk, dv, heads, scale);
+            hipLaunchKernelGGL(k_bwd_dkv_f32<128>, gk, block, 0, st, st_, q, k, v, lse, d_o, delta, dk, dv, heads, scale);
     }
     HDT_HIP_TRY(hipGetLastError());
     return HDT_OK;

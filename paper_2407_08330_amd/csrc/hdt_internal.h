@@ -43,6 +43,10 @@ struct hdt_layout {
     int32_t device;      // device the buffers live on
     int32_t force_dense; // every candidate counts as a tile, empty or not
     int32_t windowed;    // key tiles are windows of the key order (else per-query-tile key lists)
+    int32_t edges;       // OR of HDT_EDGE_*
+    // directed masks (edges without up/down symmetry): the schedule of the transposed mask (rows = keys,
+    // list entries = the queries attending to them), owned by this layout; NULL for symmetric masks
+    hdt_layout *transposed;
     int64_t capacity;    // entries the per-tile arrays can hold
     int64_t device_bytes;
     void *arena;         // key order, list pointers, scratch of the build
@@ -91,11 +95,13 @@ hdt_status_t hdt_launch_fwd_bf16(const HdtSchedule &s, const void *q, const void
                                  float *lse, int heads, int head_dim, float scale, hipStream_t st);
 hdt_status_t hdt_launch_fwd_f32(const HdtSchedule &s, const float *q, const float *k, const float *v, float *o,
                                 float *lse, int heads, int head_dim, float scale, hipStream_t st);
-hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const void *q, const void *k, const void *v,
+// backward launchers: `s` schedules the dQ pass, `s_transposed` (the transposed mask's schedule; the same as `s` for
+// symmetric masks) the dK/dV pass
+hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const HdtSchedule &s_transposed, const void *q, const void *k, const void *v,
                                  const void *o, const float *lse, const void *d_o, void *dq, void *dk,
                                  void *dv, int heads, int head_dim, float scale, float *ws_delta,
                                  hipStream_t st);
-hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const float *q, const float *k, const float *v,
+hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const HdtSchedule &s_transposed, const float *q, const float *k, const float *v,
                                 const float *o, const float *lse, const float *d_o, float *dq, float *dk,
                                 float *dv, int heads, int head_dim, float scale, float *ws_delta,
                                 hipStream_t st);

@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void k_sort_scatter(SortArgs a)
 
 struct CandArgs {
     const int32_t *level, *parent, *slot, *cmin, *cmax;
-    int n, bm, bn, tr, tc, wc, force_dense;
+    int n, bm, bn, tr, tc, wc, force_dense, edges;
     int64_t capacity;
     int32_t *q_range;  // [B][tr][2]: first and one-past-last list entry of every query tile
     int32_t *c_row, *q_cols;
@@ -313,11 +313,11 @@ __global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
             if (!ok[u]) continue;
             mark_tiles(wbits, sl2[u] / bn, sl2[u] / bn);  // itself
             if (okp[u]) {
-                mark_tiles(wbits, sp2[u] / bn, sp2[u] / bn);  // its parent
-                if (lo_s[u] <= hi_s[u] && lo_s[u] >= 0 && hi_s[u] < n)
+                if (a.edges & HDT_EDGE_UP) mark_tiles(wbits, sp2[u] / bn, sp2[u] / bn);  // its parent
+                if ((a.edges & HDT_EDGE_SIBLING) && lo_s[u] <= hi_s[u] && lo_s[u] >= 0 && hi_s[u] < n)
                     mark_tiles(wbits, lo_s[u] / bn, hi_s[u] / bn);  // its siblings: the children of its parent
             }
-            if (lo_c[u] <= hi_c[u] && lo_c[u] >= 0 && hi_c[u] < n)
+            if ((a.edges & HDT_EDGE_DOWN) && lo_c[u] <= hi_c[u] && lo_c[u] >= 0 && hi_c[u] < n)
                 mark_tiles(wbits, lo_c[u] / bn, hi_c[u] / bn);  // its children
         }
     }
@@ -383,12 +383,16 @@ struct EntryPart {
 
 __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int wsub, int khalf, int lane, int i, int pi,
                                                    bool rowok,
-                                                   const int (&kpos)[2], const int (&kpar)[2], int bm, int bn,
+                                                   const int (&kpos)[2], const int (&kpar)[2], int bm, int bn, int edges,
                                                    uint32_t *bits, unsigned long long *bits_rm)
 {
     const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
     const size_t words = (size_t)bm * wpr;
     const int r = wsub * 64 + lane;
+    // a disabled edge kind is a comparison against a value no key carries
+    const int pi_sib = (edges & HDT_EDGE_SIBLING) && pi >= 0 ? pi : -3;  // my parent, for "same parent"
+    const int pi_up = (edges & HDT_EDGE_UP) ? pi : -3;                   // my parent, for "is my parent"
+    const int i_down = (edges & HDT_EDGE_DOWN) ? i : -3;                 // me, for "is my child"
     uint32_t w[4] = {0u, 0u, 0u, 0u};
     int cnt = 0;
 #pragma unroll
@@ -400,7 +404,7 @@ __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int w
             for (int cc = 0; cc < 32; cc++) {
                 const int kj = __builtin_amdgcn_readlane(kp, (wd & 1) * 32 + cc);
                 const int kr = __builtin_amdgcn_readlane(kq, (wd & 1) * 32 + cc);
-                const bool ok = kj >= 0 && (kj == i || (pi >= 0 && pi == kr) || pi == kj || kr == i);
+                const bool ok = kj >= 0 && (kj == i || pi_sib == kr || pi_up == kj || kr == i_down);
                 out |= (uint32_t)ok << cc;
             }
             w[wd] = rowok ? out : 0u;
@@ -441,7 +445,7 @@ __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int w
 
 struct KeyListArgs {
     const int32_t *level, *parent;
-    int n, bm, bn, tr, no_sort;
+    int n, bm, bn, tr, no_sort, edges;
     int64_t capacity;
     int32_t *q_range;  // [B][tr][2]
     int32_t *c_row, *q_keys, *q_kpar, *c_cnt;
@@ -458,7 +462,8 @@ constexpr int kListThreads = 1024, kListWaves = kListThreads / 64, kBatch = 8;
 // ---- key lists: ONE kernel from level/parent to the finished entries, a workgroup per query tile ----
 // Key j is needed by the tile iff it is one of the tile's rows, the parent of one (bitmap over the
 // positions, in LDS), a child of one (its parent is a row of the tile) or a sibling of one (its parent
-// is the parent of a row).  All four tests are exact, for any forest.  The workgroup scans level[] and
+// is the parent of a row) - each kind only if its edges are enabled.  All four tests are exact, for any
+// forest.  The workgroup scans level[] and
 // parent[] of the whole sample once (two coalesced streams, nothing waits on a chain of dependent
 // loads), keeps the needed positions as a bitmap, and packs them in KEY ORDER - by level, ties in
 // document order, i.e. the order of kperm restricted to the needed keys - with a counting sort over the
@@ -515,6 +520,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     const int g0 = min(wave * gpw, ng), g1 = min(g0 + gpw, ng);
     auto in_tile = [&](int x) { return x >= row0 && x < row0 + bm && ((s_rowok[(x - row0) >> 5] >> ((x - row0) & 31)) & 1u); };
     auto is_par = [&](int x) { return (s_par[x >> 5] >> (x & 31)) & 1u; };
+    const bool e_up = a.edges & HDT_EDGE_UP, e_sib = a.edges & HDT_EDGE_SIBLING, e_down = a.edges & HDT_EDGE_DOWN;
     // kBatch groups of 64 positions at a time: all their loads are issued before the first is used
     int klv[kBatch], kp[kBatch];
     auto load_batch = [&](int gb) {
@@ -535,8 +541,8 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
             const int j = (gb + u) * 64 + lane, pj = kp[u];
             bool need = false;
             if (klv[u] >= 0 && j < n) {
-                need = in_tile(j) || is_par(j);
-                if (!need && pj >= 0 && pj < n) need = in_tile(pj) || is_par(pj);
+                need = in_tile(j) || (e_up && is_par(j));
+                if (!need && pj >= 0 && pj < n) need = (e_down && in_tile(pj)) || (e_sib && is_par(pj));
             }
             const unsigned long long m = __ballot(need);
             if (lane == 0) {
@@ -655,7 +661,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
             }
         }
         const EntryPart part = entry_bitmaps(active, base + e, wsub, khalf, lane, me.x, me.y, me.x >= 0, kpos, kparent,
-                                             bm, bn, a.bits, a.bits_rm);
+                                             bm, bn, a.edges, a.bits, a.bits_rm);
         __syncthreads();  // the previous round's partial results have been read
         if (lane == 0) {
             s_cnt[wave] = part.cnt;
@@ -688,7 +694,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
                                                       const int32_t *__restrict__ c_row,
                                                       const int32_t *__restrict__ c_col, int32_t *q_keys,
                                                       const int32_t *__restrict__ counters, int64_t capacity,
-                                                      int n, int n_slots, int bm, int bn, int tr, uint32_t *bits,
+                                                      int n, int n_slots, int bm, int bn, int tr, int edges, uint32_t *bits,
                                                       unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
 {
     __shared__ int s_cnt[2];
@@ -721,7 +727,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
             kpar[u] = (okp && lv >= 0) ? pr : -1;
             if (wave == 0 && 64 * u + lane < bn) q_keys[(size_t)c * bn + 64 * u + lane] = kpos[u];
         }
-        const EntryPart part = entry_bitmaps(true, c, wave, -1, lane, i, pi, rowok, kpos, kpar, bm, bn, bits, bits_rm);
+        const EntryPart part = entry_bitmaps(true, c, wave, -1, lane, i, pi, rowok, kpos, kpar, bm, bn, edges, bits, bits_rm);
         __syncthreads();  // the previous candidate's partial results have been read
         if (lane == 0) {
             s_cnt[wave] = part.cnt;
@@ -968,6 +974,14 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_release_cache
     return HDT_OK;
 }
 
+static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
+                              const hdt_layout_opts_t *opts, int edges, void *stream, hdt_layout_t **out);
+
+static int swap_up_down(int edges)
+{
+    return (edges & HDT_EDGE_SIBLING) | ((edges & HDT_EDGE_UP) ? HDT_EDGE_DOWN : 0) | ((edges & HDT_EDGE_DOWN) ? HDT_EDGE_UP : 0);
+}
+
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(const int32_t *d_level,
                                                                                  const int32_t *d_parent,
                                                                                  int32_t batch, int32_t n_pos,
@@ -975,6 +989,29 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                                                                                  void *stream, hdt_layout_t **out)
 {
     if (!out) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: out is NULL");
+    *out = nullptr;
+    int edges = opts && opts->edges ? opts->edges : HDT_EDGE_ALL;
+    if (edges & ~HDT_EDGE_ALL) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: edges = %d", edges);
+    hdt_layout_t *L = nullptr;
+    hdt_status_t st = build_one(d_level, d_parent, batch, n_pos, opts, edges, stream, &L);
+    if (st != HDT_OK) return st;
+    if (swap_up_down(edges) != edges) {
+        // a directed mask: the backward pass also needs the schedule of its transpose, which is the same
+        // construction with the parent and child kinds exchanged
+        st = build_one(d_level, d_parent, batch, n_pos, opts, swap_up_down(edges), stream, &L->transposed);
+        if (st != HDT_OK) {
+            (void)hdt_layout_destroy(L);
+            return st;
+        }
+        L->device_bytes += L->transposed->device_bytes;
+    }
+    *out = L;
+    return HDT_OK;
+}
+
+static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
+                              const hdt_layout_opts_t *opts, int edges, void *stream, hdt_layout_t **out)
+{
     *out = nullptr;
     if (batch < 0 || n_pos < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: negative size");
     if (n_pos > (1 << 19)) return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: n_pos %d > 2^19", n_pos);
@@ -1007,6 +1044,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
     L->level_copy = L->parent_copy = nullptr;
     L->force_dense = force_dense;
     L->windowed = windowed;
+    L->edges = edges;
+    L->transposed = nullptr;
     L->device_bytes = 0;
     L->device = 0;
     HdtSchedule &s = L->s;
@@ -1083,7 +1122,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                     HdtTimer t("hdt_layout_sort_scatter", st);
                     hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
                 }
-                CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, cap,
+                CandArgs ca{d_level, d_parent, p.slot, p.cmin, p.cmax, n, bm, bn, tr, tc, wc, force_dense, edges, cap,
                             p.q_range, q.c_row, q.q_cols, p.counters, report, ticket};
                 HdtTimer t("hdt_layout_candidates", st);
                 hipLaunchKernelGGL(k_candidates, dim3((unsigned)B * groups), dim3(kThreads),
@@ -1091,7 +1130,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
             } else {
                 // one kernel from the ids to the finished entries; the global key order is not needed for it
                 // and is sorted from the layout's copy of the ids only when someone asks (hdt_layout_export)
-                KeyListArgs ka{d_level, d_parent, n, bm, bn, tr, no_sort, cap, p.q_range, q.c_row, q.q_keys, q.q_kpar,
+                KeyListArgs ka{d_level, d_parent, n, bm, bn, tr, no_sort, edges, cap, p.q_range, q.c_row, q.q_keys, q.q_kpar,
                                q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits, q.bits_rm, p.counters, report,
                                ticket};
                 const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
@@ -1105,7 +1144,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_layout(
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
                 hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(128), 0, st, d_level, d_parent, p.kperm, q.c_row,
-                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, q.bits,
+                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, edges, q.bits,
                                    q.bits_rm, q.c_cnt, q.q_sub);
             }
             BUILD_TRY(hipGetLastError());

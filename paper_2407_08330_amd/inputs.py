@@ -104,6 +104,36 @@ def tree_document(children_counts_by_depth, rng: np.random.Generator, n_pos: Opt
     return level, parent
 
 
+def listops_like_tree(rng: np.random.Generator, n_pos: int, max_depth: int = 20, max_nodes: Optional[int] = None):
+    """A nested-list expression in the shape of the ListOps task (paper Sec. 4.1: operators with 2-5
+    operands, nesting depth up to 20), written in pre-order: an operator position followed by its
+    operands, each a leaf or another bracketed expression.  Only the SHAPE is drawn (which operand is
+    nested, how many operands); no operator names, digits or task items are involved.
+    level = nesting depth, parent = the enclosing operator.  Returns (level[n_pos], parent[n_pos])
+    padded with pads; the tree holds at most ``max_nodes`` (default n_pos) positions."""
+    cap = n_pos if max_nodes is None else min(max_nodes, n_pos)
+    levels: List[int] = [0]
+    parents: List[int] = [-1]
+    # depth-first growth in pre-order; the stack holds (operator position, depth, operands still to write)
+    stack = [(0, 0, int(rng.integers(2, 6)))]
+    while stack and len(levels) < cap:
+        op, depth, left = stack.pop()
+        if left == 0:
+            continue
+        stack.append((op, depth, left - 1))
+        me = len(levels)
+        levels.append(depth + 1)
+        parents.append(op)
+        # a nested expression with a probability that keeps the expected size finite but reaches deep trees
+        if depth + 1 < max_depth and rng.random() < 0.42:
+            stack.append((me, depth + 1, int(rng.integers(2, 6))))
+    level = np.full(n_pos, LEVEL_PAD, dtype=np.int32)
+    parent = np.full(n_pos, -1, dtype=np.int32)
+    level[:len(levels)] = levels
+    parent[:len(parents)] = parents
+    return level, parent
+
+
 def _fill_sections(rng, n_pos, sent_per_sec, sent_len, forced=None):
     """Append sections sentence by sentence until the next piece does not fit.
 

@@ -45,9 +45,15 @@ def make_inputs(B, H, N, D, seed, dtype, n_tensors=3):
     return xs, dev
 
 
-def compare_layout(oracle, layout, level, parent, bm, bn, windowed=False, **kw):
+def compare_layout(oracle, layout, level, parent, bm, bn, windowed=False, edges=0, **kw):
     """Bit-exact comparison of every exported array of every sample with the oracle's schedule:
-    the per-query-tile key lists (default) or the windowed block schedule."""
+    the per-query-tile key lists (default) or the windowed block schedule; ``edges`` selects the
+    edge kinds both sides use."""
+    with oracle.edges(edges or oracle.EDGE_ALL):
+        return _compare_layout(oracle, layout, level, parent, bm, bn, windowed, **kw)
+
+
+def _compare_layout(oracle, layout, level, parent, bm, bn, windowed=False, **kw):
     B = level.shape[0]
     total_tiles = total_nnz = 0
     assert bool(layout.info()["windowed"]) == bool(windowed or kw.get("force_dense"))

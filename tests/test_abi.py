@@ -57,8 +57,10 @@ def test_build_layout_argument_errors_without_gpu(lib):
     assert lib.hdt_build_layout(None, None, 1, 8, None, None, ctypes.byref(h)) == 1          # NULL id arrays
     from paper_2407_08330_amd.binding import _Opts
     for tm, tn in [(48, 64), (128, 16), (256, 64), (128, 160)]:
-        opts = _Opts(tm, tn, 0, 0, 0)
+        opts = _Opts(tm, tn, 0, 0, 0, 0)
         assert lib.hdt_build_layout(None, None, 0, 0, ctypes.byref(opts), None, ctypes.byref(h)) == 4  # UNSUPPORTED
+    opts = _Opts(0, 0, 0, 0, 0, 8)   # an edge kind that does not exist
+    assert lib.hdt_build_layout(None, None, 0, 0, ctypes.byref(opts), None, ctypes.byref(h)) == 1
     assert h.value is None or h.value == 0
 
 

@@ -12,20 +12,21 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 5e-2, "f32": 1e-4}
 
 
-def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False):
+def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v, d_o), (q_, k_, v_, do_) = make_inputs(B, H, N, D, seed, dtype, n_tensors=4)
-    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed)
+    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed, edges=edges)
     o_, lse_ = hdt.hdt_attn_fwd(lay, q_, k_, v_, scale)
     dq_ = torch.full_like(q_, float("nan"))
     dk_ = torch.full_like(q_, float("nan"))
     dv_ = torch.full_like(q_, float("nan"))
     hdt.hdt_attn_bwd(lay, q_, k_, v_, o_, lse_, do_, scale, dq=dq_, dk=dk_, dv=dv_)
     torch.cuda.synchronize()
-    ref = oracle.attn_bwd(q, k, v, d_o, level, parent, scale)
+    with oracle.edges(edges or oracle.EDGE_ALL):
+        ref = oracle.attn_bwd(q, k, v, d_o, level, parent, scale)
     pad = np.broadcast_to((level < 0)[:, None, :, None], q.shape)
     worst = 0.0
     for name, g_dev, g_ref in zip(("dq", "dk", "dv"), (dq_, dk_, dv_), ref):
@@ -92,6 +93,17 @@ def test_bwd_windowed_schedule(oracle):
     for dtype, D in (("bf16", 128), ("f32", 64)):
         say(f"[bwd] windowed schedule: ragged n={n} {dtype} d={D}")
         run_bwd_case(oracle, level, parent, 2, D, dtype, 4245, windowed=True)
+
+
+@pytest.mark.parametrize("edges", [2 | 4, 4, 1 | 2, 1], ids=["green+blue", "blue", "up+sibling", "up"])
+def test_bwd_listops_mask_variants(oracle, edges):
+    # directed masks: dK/dV walk the schedule of the transposed mask, which the layout builds as well
+    lv, pr = zip(*(inputs.listops_like_tree(np.random.default_rng(s), 1536) for s in (21, 22)))
+    level, parent = np.stack(lv), np.stack(pr)
+    say(f"[bwd] ListOps-shaped trees, edges={edges}: depth {level.max()}, real {(level >= 0).sum()}")
+    run_bwd_case(oracle, level, parent, 4, 64, "bf16", 600 + edges, edges=edges)
+    run_bwd_case(oracle, level[:1], parent[:1], 2, 128, "bf16", 610 + edges, edges=edges, windowed=True)
+    run_bwd_case(oracle, level[:1], parent[:1], 1, 64, "f32", 620 + edges, edges=edges)
 
 
 def test_bwd_all_pad_sample_and_dense_document(oracle):

@@ -12,19 +12,20 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
 
 
-def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False):
+def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v), (dq_, dk_, dv_) = make_inputs(B, H, N, D, seed, dtype)
-    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed)
+    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed, edges=edges)
     o = torch.full_like(dq_, float("nan"))
     lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
     hdt.hdt_attn_fwd(lay, dq_, dk_, dv_, scale, o=o, lse=lse)
     torch.cuda.synchronize()
     o_g, lse_g = from_dev(o), lse.cpu().numpy()
-    o_ref, lse_ref = oracle.attn_fwd(q, k, v, level, parent, scale)
+    with oracle.edges(edges or oracle.EDGE_ALL):
+        o_ref, lse_ref = oracle.attn_fwd(q, k, v, level, parent, scale)
     tol_o, tol_l = TOL[dtype]
     pad = level < 0
     padb = np.broadcast_to(pad[:, None, :], lse_g.shape)
@@ -101,6 +102,22 @@ def test_fwd_windowed_schedule(oracle):
     for dtype, D in (("bf16", 128), ("f32", 64)):
         say(f"[fwd] windowed schedule: ragged n={n} {dtype} d={D}")
         run_fwd_case(oracle, level, parent, 2, D, dtype, 4243, windowed=True)
+
+
+def _listops_batch(n, seeds):
+    lv, pr = zip(*(inputs.listops_like_tree(np.random.default_rng(s), n) for s in seeds))
+    return np.stack(lv), np.stack(pr)
+
+
+@pytest.mark.parametrize("edges", [2 | 4, 4, 1 | 2, 1], ids=["green+blue", "blue", "up+sibling", "up"])
+def test_fwd_listops_mask_variants(oracle, edges):
+    # the thinned, directed patterns of the paper's ListOps study on deep expression trees (depth <= 20)
+    level, parent = _listops_batch(1536, (11, 12))
+    say(f"[fwd] ListOps-shaped trees, edges={edges}: depth {level.max()}, real {(level >= 0).sum()}")
+    run_fwd_case(oracle, level, parent, 4, 64, "bf16", 500 + edges, edges=edges)
+    run_fwd_case(oracle, level[:1, :700], np.where(parent[:1, :700] < 700, parent[:1, :700], -1), 2, 128, "bf16",
+                 510 + edges, edges=edges, windowed=True)
+    run_fwd_case(oracle, level[:1], parent[:1], 1, 64, "f32", 520 + edges, edges=edges)
 
 
 def test_fwd_large_logits_and_scale(oracle):

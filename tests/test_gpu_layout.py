@@ -137,6 +137,20 @@ def test_layout_long_documents_need_a_large_slot_bitmap(oracle):
                 np.testing.assert_array_equal(col, np.array(exp, np.uint32))
 
 
+@WINDOWED
+@pytest.mark.parametrize("edges", [2 | 4, 4, 1 | 2, 1, 2], ids=["green+blue", "blue", "up+sibling", "up", "sibling"])
+def test_layout_listops_mask_variants(oracle, edges, windowed):
+    # thinned / directed masks (paper Sec. 4.1) on ListOps-shaped trees and on a document
+    rng = np.random.default_rng(99)
+    lv, pr = inputs.listops_like_tree(rng, 1000)
+    wl = inputs.make_workload(1)
+    for level, parent in ((lv[None], pr[None]), (wl.level, wl.parent)):
+        say(f"[layout] edges={edges} windowed={windowed} n={level.shape[1]}")
+        lay = _build(level, parent, edges=edges, windowed=windowed)
+        assert lay.info()["edges"] == edges
+        compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed, edges=edges)
+
+
 def test_layout_rejects_bad_hierarchies():
     import paper_2407_08330_amd as hdt
     good_l = np.array([[0, 1, 2, 3, -1, -1]], np.int32)
