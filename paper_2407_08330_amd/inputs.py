@@ -166,6 +166,15 @@ def _fill_sections(rng, n_pos, sent_per_sec, sent_len, forced=None):
     return sections
 
 
+def pseudo_section_document(rng: np.random.Generator, n_pos: int, sent_len=(10, 80), per_section: int = 32):
+    """Unstructured text as the paper treats it (Sec. 4.2, SCROLLS): sentences grouped into
+    pseudo-sections of a fixed number of sentences (32).  Sentence lengths are drawn uniform; the
+    document is filled as by the other recipes (a sentence only if it fits entirely)."""
+    sections = _fill_sections(rng, n_pos, (per_section, per_section), sent_len)
+    level, parent = document_from_sections(sections, n_pos)
+    return level, parent, sections
+
+
 def _budgeted_sections(rng, n_pos, n_sections, sent_per_sec, sent_len):
     """Exactly ``n_sections`` sections under a running position budget: section s may grow
     until the document holds floor((s+1)*(n_pos-1)/n_sections) positions (at least one

@@ -106,6 +106,16 @@ def test_bwd_listops_mask_variants(oracle, edges):
     run_bwd_case(oracle, level[:1], parent[:1], 1, 64, "f32", 620 + edges, edges=edges)
 
 
+def test_fwd_bwd_pseudo_sections_of_32_sentences(oracle):
+    # unstructured text: pseudo-sections of 32 sentences (paper Sec. 4.2); run_bwd_case runs the forward too
+    rng = np.random.default_rng(3232)
+    docs = [inputs.pseudo_section_document(rng, 4096) for _ in range(2)]
+    level, parent = np.stack([d[0] for d in docs]), np.stack([d[1] for d in docs])
+    assert all(len(sec) == 32 for d in docs for sec in d[2][:-1])
+    say(f"[bwd] pseudo-sections: {[len(d[2]) for d in docs]} sections, real {(level >= 0).sum()}")
+    run_bwd_case(oracle, level, parent, 4, 64, "bf16", 3233)
+
+
 def test_bwd_all_pad_sample_and_dense_document(oracle):
     n = 384
     level = np.stack([np.full(n, -1, np.int32), np.array([0] + [1] * (n - 1), np.int32)])
