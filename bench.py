@@ -2,15 +2,20 @@
 """Benchmark of the hierarchical-attention hot path on one MI355X.
 
 A step = one pass of the whole path over one synthetic batch: hdt_build_layout (level/parent ids ->
-tile schedule), hdt_attn_fwd and hdt_attn_bwd, all through the C ABI, inputs resident in HBM.
+tile schedule), hdt_attn_fwd and hdt_attn_bwd, all through the C ABI, inputs resident in HBM.  Every
+step builds its own layout; by default the build of the next step's layout runs on a second stream
+while the current step's attention kernels run (it depends only on the ids), --serial keeps everything
+on one stream.  Per-kernel times always come from a serial, event-bracketed pass.
 Workload = the training step at 8192 positions (batch 4, 12 heads, head_dim 64, bf16), the
 configuration the headline metric is quoted on.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2|3|4|5] [--serial] [--windowed] [--edges E]
+                    [--no-cpu-baseline]
 """
 from __future__ import annotations
 
 import argparse
+import collections
 import json
 import os
 import sys
@@ -48,6 +53,9 @@ def main() -> int:
     ap.add_argument("--windowed", action="store_true",
                     help="key tiles = fixed windows of the level-sorted key order (Alg. 1 as printed) instead of "
                          "the default per-query-tile key lists")
+    ap.add_argument("--serial", action="store_true",
+                    help="one stream, strictly build -> forward -> backward per step (default: the next step's "
+                         "layout is built on a second stream while this step's attention kernels run)")
     ap.add_argument("--edges", type=int, default=0,
                     help="edge kinds of the mask (1 parent, 2 siblings, 4 children, OR-ed; 0 = all): the thinned "
                          "patterns of the paper's ListOps study applied to the workload's documents")
@@ -93,14 +101,57 @@ def main() -> int:
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
     probe.destroy()
 
-    def step(i):
+    def attention(lay, i):
         t, outs = sets[i % n_sets]
-        lay = hdt.hdt_build_layout(level, parent, windowed=args.windowed, edges=args.edges)
         hdt.hdt_attn_fwd(lay, t[0], t[1], t[2], scale, o=outs["o"], lse=outs["lse"])
         if do_bwd:
             hdt.hdt_attn_bwd(lay, t[0], t[1], t[2], outs["o"], outs["lse"], t[3], scale, dq=outs["dq"],
                              dk=outs["dk"], dv=outs["dv"], workspace=workspace)
-        lay.destroy()   # buffers go back to the library's cache; the next build reuses them in stream order
+
+    def build(stream=None):
+        return hdt.hdt_build_layout(level, parent, windowed=args.windowed, edges=args.edges, stream=stream)
+
+    def run_serial(k0, k1):
+        """Steps k0..k1-1, everything on one stream: build, forward, backward, destroy."""
+        for i in range(k0, k1):
+            lay = build()
+            attention(lay, i)
+            lay.destroy()   # buffers go back to the library's cache; the next build reuses them in stream order
+
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream()   # default priority
+
+    def run_pipelined(k0, k1):
+        """The same steps, with the layout of step i+1 built on a second stream while the attention
+        kernels of step i run (the build depends only on the ids).  Every step still does its own
+        build; a layout is destroyed only after the attention calls that use it have finished."""
+        if k1 <= k0:
+            return
+        live = collections.deque()
+        nxt = build(side_stream)
+        ready = torch.cuda.Event()
+        ready.record(side_stream)
+        for i in range(k0, k1):
+            lay = nxt
+            main_stream.wait_event(ready)
+            attention(lay, i)
+            done = torch.cuda.Event()
+            done.record(main_stream)
+            live.append((lay, done))
+            if i + 1 < k1:
+                nxt = build(side_stream)
+                ready = torch.cuda.Event()
+                ready.record(side_stream)
+            while len(live) > 2:
+                old_lay, old_done = live.popleft()
+                old_done.synchronize()
+                old_lay.destroy()
+        while live:
+            old_lay, old_done = live.popleft()
+            old_done.synchronize()
+            old_lay.destroy()
+
+    run = run_serial if args.serial else run_pipelined
 
     if args.calibrate_copy:
         # a copy kernel of known size: 256 MiB read + 256 MiB written per launch
@@ -110,18 +161,26 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    for i in range(args.warmup):
-        step(i)
+    run(0, args.warmup)
     torch.cuda.synchronize()
 
     # timed region: exactly K steps, nothing but the path's own calls between the two synchronisations
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    run(0, args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # for reference: the same K steps strictly one after the other on a single stream
+    ms_per_step_serial = ms_per_step
+    if not args.serial:
+        run_serial(0, args.warmup)
+        torch.cuda.synchronize()
+        s0 = time.perf_counter()
+        run_serial(0, args.steps)
+        torch.cuda.synchronize()
+        ms_per_step_serial = (time.perf_counter() - s0) * 1e3 / args.steps
 
     # the same K steps once more with every kernel launch bracketed by HIP events on its stream (the
     # events themselves cost ~10 % of a step, so they stay out of the region `value` is taken from)
@@ -131,8 +190,7 @@ def main() -> int:
         hdt.hdt_timing_reset()
         torch.cuda.synchronize()
         e0 = time.perf_counter()
-        for i in range(args.steps):
-            step(i)
+        run_serial(0, args.steps)
         torch.cuda.synchronize()
         ms_per_step_events = (time.perf_counter() - e0) * 1e3 / args.steps
         kernels = hdt.hdt_timing_read()
@@ -180,6 +238,8 @@ def main() -> int:
         if do_bwd else "hier-attn fwd tokens/s (layout build + forward per step)",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_serial": round(ms_per_step_serial, 4),
+        "pipelining": "none" if args.serial else "layout of step i+1 built on a second stream during the attention of step i",
         "ms_per_step_with_kernel_events": None if ms_per_step_events is None else round(ms_per_step_events, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
