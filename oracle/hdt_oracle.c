@@ -25,7 +25,9 @@
  *   - per-query-block key lists (the keys any row of the block may attend to, in
  *     that key order, cut into entries of a fixed number of keys), again by brute
  *     force: the library's default schedule, a refinement of the fixed windows
- *     that the paper's closing remark of Sec. 3.2 on better permutations invites.
+ *     that the paper's closing remark of Sec. 3.2 on better permutations invites;
+ *   - the hierarchical positional encoding: index vectors from the tree and the
+ *     sum of sinusoidal encodings over the levels (Sec. 3.2, Eq. pos_enc).
  *
  * Readings where the paper is silent (each also listed in the design notes):
  *   - a position attends to itself (M^SENT_ii = 1);
@@ -351,6 +353,58 @@ void oracle_keylist_fill(const int32_t *level, const int32_t *parent, const int3
             }
         }
     }
+}
+
+/* ---- hierarchical positional encoding -------------------------------------
+ *
+ * Sec. 3.2 "Hierarchical Positional Encoding", Eq. (pos_enc) and the caption of Fig. 3: every
+ * position carries one linear index p^l per hierarchy level l = 1..L (level 0, the document,
+ * needs none); each index goes through the standard sinusoidal functions and the L encodings
+ * are summed:
+ *     HPE(p, i) = sum_l sin(w_k p^l)  if i = 2k,   sum_l cos(w_k p^l)  if i = 2k + 1,
+ *     w_k = 10000^(-2k / d_model).
+ * Reading of the (missing) figure: indices are 1-based ordinals among the siblings, and an
+ * anchor carries 0 at every level below its own: [DOC] = (0,0,0), the k-th [SEC] = (k,0,0), its
+ * m-th [SENT] = (k,m,0), that sentence's t-th token = (k,m,t).  For a general tree: the entry
+ * for level l of position i is the ordinal (among the children of its parent, in document order)
+ * of i's ancestor-or-self whose level is l, and 0 if there is none.  Pads carry all zeros. */
+
+/* p[i*L + (l-1)], l = 1..L */
+void oracle_index_vectors(const int32_t *level, const int32_t *parent, int64_t n, int64_t L, int32_t *p)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < n; i++) {
+        for (int64_t l = 0; l < L; l++) p[i * L + l] = 0;
+        if (level[i] < 0) continue;
+        int64_t a = i;
+        for (int steps = 0; a >= 0 && steps < 64; steps++) {
+            int64_t l = level[a];
+            if (l >= 1 && l <= L) {
+                int32_t ord = 1; /* earlier positions with the same parent */
+                for (int64_t j = 0; j < a; j++)
+                    if (level[j] >= 0 && parent[j] == parent[a]) ord++;
+                p[i * L + (l - 1)] = ord;
+            }
+            a = parent[a];
+        }
+    }
+}
+
+/* out[i*d_model + c] = HPE(p_i, c) */
+void oracle_hpe(const int32_t *p, int64_t n, int64_t L, int64_t d_model, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; i++)
+        for (int64_t c = 0; c < d_model; c++) {
+            int64_t k = c / 2;
+            double w = pow(10000.0, -2.0 * (double)k / (double)d_model);
+            double acc = 0.0;
+            for (int64_t l = 0; l < L; l++) {
+                double x = w * (double)p[i * L + l];
+                acc += (c % 2 == 0) ? sin(x) : cos(x);
+            }
+            out[i * d_model + c] = acc;
+        }
 }
 
 int oracle_num_threads(void)

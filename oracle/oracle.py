@@ -70,6 +70,10 @@ def _load():
         lib.oracle_keylist_counts.restype = None
         lib.oracle_keylist_fill.argtypes = [i32p, i32p, i32p, i64, i64, i64, i64p, i32p, u32p, i32p]
         lib.oracle_keylist_fill.restype = None
+        lib.oracle_index_vectors.argtypes = [i32p, i32p, i64, i64, i32p]
+        lib.oracle_index_vectors.restype = None
+        lib.oracle_hpe.argtypes = [i32p, i64, i64, i64, f64p]
+        lib.oracle_hpe.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -318,3 +322,24 @@ def keylist_schedule(level, parent, bm: int, bn: int, use_sort: bool = True) -> 
     q_sub = _sub_summary(bits, bm, bn) if (bm % 32 == 0 and bn % 32 == 0) else np.zeros(E, np.uint32)
     return KeyListSchedule(bm=bm, bn=bn, kperm=kp, q_rowptr=entry_ptr.astype(np.int32), q_keys=keys, bits=bits,
                            pairs=pairs, q_sub=q_sub, nnz=int(pairs.sum()))
+
+
+def index_vectors(level, parent, n_levels: int) -> np.ndarray:
+    """int32 [n][n_levels]: the index vector p = (p^1 .. p^L) of every position of one sample."""
+    level, parent = _i32(level), _i32(parent)
+    n = level.shape[0]
+    p = np.zeros((max(n, 1), n_levels), dtype=np.int32)
+    if n:
+        _load().oracle_index_vectors(_p(level, ctypes.c_int32), _p(parent, ctypes.c_int32), n, n_levels,
+                                     _p(p, ctypes.c_int32))
+    return p[:n]
+
+
+def hpe(p, d_model: int) -> np.ndarray:
+    """fp64 [n][d_model]: the hierarchical positional encoding of index vectors p [n][L]."""
+    p = np.ascontiguousarray(p, dtype=np.int32)
+    n, L = p.shape
+    out = np.zeros((max(n, 1), d_model), dtype=np.float64)
+    if n:
+        _load().oracle_hpe(_p(p, ctypes.c_int32), n, L, d_model, _p(out, ctypes.c_double))
+    return out[:n]
