@@ -263,6 +263,30 @@ def main() -> int:
             "hbm_gbs_algorithmic": round(algorithmic_bytes_per_unit(fwd_name, D) * B * H * N / (fwd_us * 1e-6) / 1e9, 1),
         }
 
+    if not args.no_kernel_timing:
+        # the step before the path (not part of `value`): hierarchical positional encoding of the same batch,
+        # index vectors from the ids and the fused add into bf16 embeddings of d_model = heads * head_dim
+        d_model, n_lev = H * D, 3
+        emb = torch.zeros((B, N, d_model), dtype=torch.bfloat16, device=dev)
+        table = hdt.hdt_hpe_table(1024, d_model)
+        pvec = hdt.hdt_index_vectors(level, parent, n_lev)
+        hdt.hdt_hpe_add(pvec, table, emb)
+        torch.cuda.synchronize()
+        hdt.hdt_timing_enable(True)
+        hdt.hdt_timing_reset()
+        for _ in range(20):
+            hdt.hdt_index_vectors(level, parent, n_lev, out=pvec)
+            hdt.hdt_hpe_add(pvec, table, emb)
+        torch.cuda.synchronize()
+        tk = {n: round(1e3 * ms / c, 2) for n, (c, ms) in hdt.hdt_timing_read().items() if n.startswith("hdt_hpe")}
+        hdt.hdt_timing_enable(False)
+        add_us = tk.get("hdt_hpe_add_bf16")
+        add_bytes = B * N * (2 * 2 * d_model + 4 * n_lev)   # x read + written, index vector read
+        out["hpe"] = {"d_model": d_model, "levels": n_lev, "kernels_us": tk,
+                      "add_algorithmic_bytes": add_bytes,
+                      "add_gbs": None if not add_us else round(add_bytes / (add_us * 1e-6) / 1e9, 1),
+                      "add_frac_of_hbm_peak": None if not add_us else round(add_bytes / (add_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host cores: mask enumeration + forward (+ backward) of the
         # same batch with fresh seeded inputs, once

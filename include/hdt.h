@@ -215,6 +215,31 @@ hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void 
                           int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Hierarchical positional encoding (Sec. 3.2 "Hierarchical Positional Encoding", Eq. pos_enc, Fig. 3):
+ * every position carries one linear index p^l per hierarchy level l = 1 .. n_levels (level 0 needs none);
+ *     HPE(p, c) = sum_l sin(w_k p^l) if c = 2k,  sum_l cos(w_k p^l) if c = 2k + 1,  w_k = 10000^(-2k/d_model),
+ * is added to the embeddings.
+ *
+ * hdt_index_vectors -- level/parent ids (as for hdt_build_layout) -> d_p [batch][n_pos][n_levels] int32,
+ *   device: entry l-1 of position i = the 1-based ordinal, among the children of its parent in document
+ *   order, of i's ancestor-or-self whose level is l; 0 if there is none ([DOC] = (0,0,0), k-th [SEC] =
+ *   (k,0,0), its m-th [SENT] = (k,m,0), that sentence's t-th token = (k,m,t)); pads carry zeros.
+ *   `workspace`: device scratch of hdt_index_vectors_workspace_bytes(batch, n_pos) bytes, 16-byte aligned.
+ *   The ids are not validated here (hdt_build_layout does that); out-of-range parents count as roots.
+ * hdt_hpe_table -- d_table [rows][d_model] float, device: T[v][c] = sin / cos (w_k v); d_model % 8 == 0.
+ * hdt_hpe_add -- x [batch][n_pos][d_model] (dtype dt, device, in place): x += sum_l T[p^l]; indices outside
+ *   [0, table_rows) are evaluated directly, so any table size (even 0) gives the same result.
+ * All three only enqueue work on `stream`.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED (dtype), HDT_ERR_HIP.
+ */
+size_t hdt_index_vectors_workspace_bytes(int32_t batch, int32_t n_pos);
+hdt_status_t hdt_index_vectors(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
+                               int32_t n_levels, int32_t *d_p, void *workspace, size_t workspace_bytes,
+                               void *stream);
+hdt_status_t hdt_hpe_table(float *d_table, int32_t rows, int32_t d_model, void *stream);
+hdt_status_t hdt_hpe_add(const int32_t *d_p, int32_t batch, int32_t n_pos, int32_t n_levels, const float *d_table,
+                         int32_t table_rows, void *x, int32_t d_model, hdt_dtype_t dt, void *stream);
+
 /* Text of a status code / of the last error on this thread (never NULL). */
 const char *hdt_status_string(hdt_status_t status);
 const char *hdt_last_error(void);

@@ -12,6 +12,9 @@ from .binding import (  # noqa: F401
     hdt_attn_bwd_workspace_bytes,
     hdt_attn_fwd,
     hdt_build_layout,
+    hdt_hpe_add,
+    hdt_hpe_table,
+    hdt_index_vectors,
     hdt_release_cached_memory,
     hdt_timing_enable,
     hdt_timing_read,

@@ -21,6 +21,7 @@ EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
     "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
+    "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
 ]
 
 
@@ -89,6 +90,14 @@ def load_library():
     lib.hdt_timing_read.restype = i32
     lib.hdt_release_cached_memory.argtypes = []
     lib.hdt_release_cached_memory.restype = ctypes.c_int
+    lib.hdt_index_vectors_workspace_bytes.argtypes = [i32, i32]
+    lib.hdt_index_vectors_workspace_bytes.restype = ctypes.c_size_t
+    lib.hdt_index_vectors.argtypes = [vp, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, vp]
+    lib.hdt_index_vectors.restype = ctypes.c_int
+    lib.hdt_hpe_table.argtypes = [vp, i32, i32, vp]
+    lib.hdt_hpe_table.restype = ctypes.c_int
+    lib.hdt_hpe_add.argtypes = [vp, i32, i32, i32, vp, i32, vp, i32, ctypes.c_int, vp]
+    lib.hdt_hpe_add.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -261,3 +270,42 @@ def hdt_timing_read() -> dict:
     ms = (ctypes.c_double * cap)()
     n = load_library().hdt_timing_read(names, launches, ms, cap)
     return {names[i].decode(): (int(launches[i]), float(ms[i])) for i in range(min(n, cap))}
+
+
+def hdt_index_vectors(level, parent, n_levels: int, out=None, workspace=None, stream=None):
+    """level, parent: int32 device tensors [batch][n_pos] -> int32 device tensor [batch][n_pos][n_levels]."""
+    import torch
+    if level.dtype != torch.int32 or parent.dtype != torch.int32 or level.shape != parent.shape or level.dim() != 2:
+        raise TypeError("level and parent must be int32 [batch][n_pos]")
+    if not (level.is_cuda and parent.is_cuda and level.is_contiguous() and parent.is_contiguous()):
+        raise ValueError("level and parent must be contiguous device tensors")
+    B, N = level.shape
+    if out is None:
+        out = torch.empty((B, N, n_levels), dtype=torch.int32, device=level.device)
+    need = int(load_library().hdt_index_vectors_workspace_bytes(B, N))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=level.device)
+    _check(load_library().hdt_index_vectors(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,
+                                            n_levels, _ptr(out), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return out
+
+
+def hdt_hpe_table(rows: int, d_model: int, device="cuda", stream=None):
+    """float32 device tensor [rows][d_model]: the sinusoidal table."""
+    import torch
+    table = torch.empty((rows, d_model), dtype=torch.float32, device=device)
+    _check(load_library().hdt_hpe_table(_ptr(table) if rows else None, rows, d_model, _stream_ptr(stream)))
+    return table
+
+
+def hdt_hpe_add(p, table, x, stream=None):
+    """x [batch][n_pos][d_model] (bf16 or fp32 device tensor) += HPE(p), in place.  Returns x."""
+    _check_tensors((x,))
+    B, N, L = p.shape
+    if tuple(x.shape[:2]) != (B, N):
+        raise ValueError("x and p disagree on [batch][n_pos]")
+    rows = 0 if table is None else table.shape[0]
+    _check(load_library().hdt_hpe_add(_ptr(p), B, N, L, _ptr(table) if rows else None, rows, _ptr(x), x.shape[2],
+                                      _dtype_code(x), _stream_ptr(stream)))
+    return x
