@@ -107,3 +107,20 @@ def test_timing_calls_without_gpu(lib):
     assert lib.hdt_timing_reset() == 0
     assert lib.hdt_timing_read(None, None, None, 0) == 0
     assert lib.hdt_release_cached_memory() == 0
+
+
+def test_hpe_argument_errors_without_gpu(lib):
+    assert lib.hdt_index_vectors_workspace_bytes(0, 128) == 0
+    assert lib.hdt_index_vectors_workspace_bytes(2, 100) >= 4 * (2 * 101 + 2 * 100)
+    assert lib.hdt_index_vectors(None, None, -1, 8, 3, None, None, 0, None) == 1
+    assert lib.hdt_index_vectors(None, None, 1, 8, 0, None, None, 0, None) == 1        # n_levels < 1
+    assert lib.hdt_index_vectors(None, None, 1, 8, 32, None, None, 0, None) == 1       # n_levels too large
+    assert lib.hdt_index_vectors(None, None, 0, 8, 3, None, None, 0, None) == 0        # empty: nothing to do
+    assert lib.hdt_index_vectors(None, None, 1, 8, 3, None, None, 0, None) == 1        # NULL pointers
+    assert lib.hdt_hpe_table(None, 4, 12, None) == 1                                   # d_model % 8
+    assert lib.hdt_hpe_table(None, 0, 16, None) == 0
+    assert lib.hdt_hpe_table(None, 4, 16, None) == 1
+    assert lib.hdt_hpe_add(None, 0, 8, 3, None, 0, None, 16, 0, None) == 0
+    assert lib.hdt_hpe_add(None, 1, 8, 3, None, 0, None, 12, 0, None) == 1
+    assert lib.hdt_hpe_add(None, 1, 8, 3, None, 0, None, 16, 5, None) == 4             # dtype
+    assert lib.hdt_hpe_add(None, 1, 8, 3, None, 0, None, 16, 0, None) == 1             # NULL pointers

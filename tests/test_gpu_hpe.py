@@ -51,6 +51,13 @@ def test_index_vectors_deep_trees_ragged_and_shuffled(oracle):
     assert (got[1] == 0).all()
 
 
+def test_index_vectors_forest_with_pads_in_front(oracle):
+    level = np.array([[-1, 1, -1, 1, 2, 1]], np.int32)
+    parent = np.array([[-1, -1, -1, -1, 3, -1]], np.int32)
+    got = _check_index_vectors(oracle, level, parent, 2)
+    assert got[0].tolist() == [[0, 0], [1, 0], [0, 0], [2, 0], [2, 1], [3, 0]]
+
+
 def test_hpe_table(oracle):
     import paper_2407_08330_amd as hdt
     for rows, d in ((700, 768), (33, 64)):

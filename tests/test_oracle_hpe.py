@@ -66,3 +66,12 @@ def test_hpe_sums_over_levels_and_closed_forms(oracle):
     # highest frequencies vanish: w_k -> 10000^-1 at the top channels, so cos(w p) ~ 1 for small p
     small = oracle.hpe(np.full((1, 1), 3, np.int32), 512)
     assert abs(small[0, -1] - np.cos(3 * 10000.0 ** (-(512 - 2) / 512))) < 1e-12
+
+
+def test_index_vectors_of_a_forest_with_pads_in_front(oracle):
+    # positions without a parent are numbered among themselves; pads are not counted (by hand):
+    # pad, X (level 1, no parent), pad, Y (level 1, no parent), y1 (child of Y), Z (level 1, no parent)
+    level = np.array([-1, 1, -1, 1, 2, 1], np.int32)
+    parent = np.array([-1, -1, -1, -1, 3, -1], np.int32)
+    want = [(0, 0), (1, 0), (0, 0), (2, 0), (2, 1), (3, 0)]
+    np.testing.assert_array_equal(oracle.index_vectors(level, parent, 2), np.array(want))
