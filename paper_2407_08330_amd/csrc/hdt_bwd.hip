@@ -176,11 +176,12 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
         }
     }
 
-    wg_barrier();  // every wave is done reading the ring
     {
+        // through this wave's slice of the stage tile n would have used: free since the last barrier (see
+        // the forward kernel), so waves leave independently
         const int wrow0 = I * BM + wave * 32;
-        store_rows_via_lds<P, D>(smem + wave * 32 * ROWB, lane, dqacc, scale, dq + base + (size_t)wrow0 * D,
-                                 s.n_pos - wrow0);
+        store_rows_via_lds<P, D>(smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB, lane, dqacc, scale,
+                                 dq + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     }
 }
 
@@ -298,10 +299,10 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
         }
     }
 
-    wg_barrier();  // every wave is done reading the ring
     {
+        // through this wave's slice of the stage tile n would have used: free since the last barrier
         const int wrow0 = I * BM + wave * 32;
-        char *wl = smem + wave * 32 * ROWB;
+        char *wl = smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB;
         store_rows_via_lds<P, D>(wl, lane, dkacc, scale, dk + base + (size_t)wrow0 * D, s.n_pos - wrow0);
         store_rows_via_lds<P, D>(wl, lane, dvacc, 1.f, dv + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     }

@@ -202,9 +202,13 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     // epilogue: O = acc / l, LSE = ln(sum exp) = ln2 * (m_ref + log2 l); O leaves through LDS as full rows
     const float l_tot = l_part + __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(xlane, __builtin_bit_cast(int, l_part)));
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    wg_barrier();  // every wave is done reading the ring
+    // The rows leave through this wave's slice of the ring stage that tile n would have used: nothing was
+    // loaded into it after tile n - S, which every wave finished reading before the last barrier (for the
+    // first S tiles: only each wave's own staged rows), so no barrier is needed and a wave that is done
+    // early does not wait for the others.
     const int wrow0 = I * BM + wave * 32;
-    store_rows_via_lds<P, D>(smem + wave * 32 * ROWB, lane, oacc, inv, o + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+    store_rows_via_lds<P, D>(smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB, lane, oacc, inv,
+                             o + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     if (qrow < s.n_pos && hf == 0)
         lse[(size_t)bh * s.n_pos + qrow] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * LN2 : -INFINITY;
 }

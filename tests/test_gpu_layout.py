@@ -96,11 +96,13 @@ def test_layout_force_dense_and_no_sort(oracle):
         compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, windowed=windowed, use_sort=False)
 
 
-def test_layout_long_documents_need_a_large_slot_bitmap(oracle):
-    # 2^17 positions: the key-list kernel's bitmap over the key order (one bit per slot) takes 16 KB of LDS
+@pytest.mark.parametrize("log2n,n_sections", [(17, 120), (19, 500)])
+def test_layout_long_documents_need_a_large_slot_bitmap(oracle, log2n, n_sections):
+    # 2^17 / 2^19 (the largest accepted) positions: the key-list kernel's bitmaps over the positions take
+    # 32 KB / 128 KB of LDS
     rng = np.random.default_rng(77)
-    n = 1 << 17
-    secs = [[int(rng.integers(5, 61)) for _ in range(int(rng.integers(5, 41)))] for _ in range(120)]
+    n = 1 << log2n
+    secs = [[int(rng.integers(5, 61)) for _ in range(int(rng.integers(5, 41)))] for _ in range(n_sections)]
     level, parent = inputs.document_from_sections(secs, n)
     say(f"[layout] n = {n}, real = {(level >= 0).sum()}")
     lay = _build(level[None], parent[None])
