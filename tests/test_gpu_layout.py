@@ -153,6 +153,22 @@ def test_layout_listops_mask_variants(oracle, edges, windowed):
         compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed, edges=edges)
 
 
+@WINDOWED
+def test_layout_grows_its_arrays_when_the_first_guess_is_too_small(oracle, windowed):
+    # a dense document (one root, everything else its children) needs n/64 entries per query tile, far more
+    # than the size guessed from the previous (tiny) build: the build is repeated with the exact size
+    tiny_l = np.array([[0, 1, 1, -1]], np.int32)
+    tiny_p = np.array([[-1, 0, 0, -1]], np.int32)
+    _build(tiny_l, tiny_p, windowed=windowed).destroy()
+    n = 3000
+    level = np.array([[0] + [1] * (n - 1)], np.int32)
+    parent = np.array([[-1] + [0] * (n - 1)], np.int32)
+    say(f"[layout] dense document n={n} after a tiny one, windowed={windowed}")
+    lay = _build(level, parent, windowed=windowed)
+    tiles, nnz = compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed)
+    assert nnz == n * n and tiles == 24 * 47
+
+
 def test_layout_rejects_bad_hierarchies():
     import paper_2407_08330_amd as hdt
     good_l = np.array([[0, 1, 2, 3, -1, -1]], np.int32)
