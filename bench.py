@@ -53,6 +53,7 @@ def main() -> int:
     ap.add_argument("--windowed", action="store_true",
                     help="key tiles = fixed windows of the level-sorted key order (Alg. 1 as printed) instead of "
                          "the default per-query-tile key lists")
+    ap.add_argument("--tile", default="", help="tile shape of the layout, 64x32 or 128x64 (default: the library's)")
     ap.add_argument("--serial", action="store_true",
                     help="one stream, strictly build -> forward -> backward per step (default: the next step's "
                          "layout is built on a second stream while this step's attention kernels run)")
@@ -95,7 +96,8 @@ def main() -> int:
             outs.update(dq=torch.empty_like(t[0]), dk=torch.empty_like(t[0]), dv=torch.empty_like(t[0]))
         sets.append((t, outs))
     del xs
-    probe = hdt.hdt_build_layout(level, parent, windowed=args.windowed, edges=args.edges)
+    tile_m, tile_n = (int(x) for x in args.tile.split("x")) if args.tile else (0, 0)
+    probe = hdt.hdt_build_layout(level, parent, tile_m=tile_m, tile_n=tile_n, windowed=args.windowed, edges=args.edges)
     info = probe.info()
     ws_bytes = hdt.hdt_attn_bwd_workspace_bytes(probe, H, D, 0)
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
@@ -109,7 +111,8 @@ def main() -> int:
                              dk=outs["dk"], dv=outs["dv"], workspace=workspace)
 
     def build(stream=None):
-        return hdt.hdt_build_layout(level, parent, windowed=args.windowed, edges=args.edges, stream=stream)
+        return hdt.hdt_build_layout(level, parent, tile_m=tile_m, tile_n=tile_n, windowed=args.windowed,
+                                    edges=args.edges, stream=stream)
 
     def run_serial(k0, k1):
         """Steps k0..k1-1, everything on one stream: build, forward, backward, destroy."""
@@ -200,7 +203,7 @@ def main() -> int:
     value = tokens / (ms_per_step * 1e-3)
     nnz, n_tiles = info["nnz"], info["n_tiles"]
     useful_flop = (4 + (10 if do_bwd else 0)) * nnz * D * H
-    issued_fwd_flop = 4 * n_tiles * 128 * 64 * D * H
+    issued_fwd_flop = 4 * n_tiles * info["tile_m"] * info["tile_n"] * D * H
 
     per_kernel = {name: {"launches": c, "avg_us": 1e3 * ms / c} for name, (c, ms) in kernels.items() if c}
     phase_us = {"layout": 0.0, "fwd": 0.0, "bwd": 0.0}
@@ -244,7 +247,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"config{args.config}:{wl.name}", "batch": B, "heads": H, "head_dim": D,
-                   "n_pos": N, "real_positions": wl.n_real, "tile": "128x64",
+                   "n_pos": N, "real_positions": wl.n_real, "tile": f"{info['tile_m']}x{info['tile_n']}",
                    "schedule": "windowed" if args.windowed else "key-lists", "edges": info["edges"],
                    "n_tiles": n_tiles, "nnz": nnz},
         "useful_tflops": round(useful_flop / (ms_per_step * 1e-3) / 1e12, 3),

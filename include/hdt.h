@@ -188,7 +188,7 @@ hdt_status_t hdt_release_cached_memory(void);
  *            of each row; -inf on pad rows
  *   head_dim 64 or 128;  softmax_scale > 0 (the paper uses 1/sqrt(head_dim))
  *
- * HDT_BF16 needs a layout with tiles 128 x 64; HDT_F32 takes any layout.  batch and n_pos come from
+ * HDT_BF16 needs a layout with tiles 128 x 64 or 64 x 32; HDT_F32 takes any layout.  batch and n_pos come from
  * the layout.  Errors: INVALID_ARG, UNSUPPORTED (head_dim, dtype, tile shape), HDT_ERR_HIP (launch).
  */
 hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v, void *o,

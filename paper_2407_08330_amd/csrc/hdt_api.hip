@@ -267,8 +267,8 @@ static hdt_status_t check_attn_args(const char *fn, const hdt_layout_t *layout, 
     if (dt != HDT_BF16 && dt != HDT_F32) return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: unknown dtype %d", fn, (int)dt);
     if (head_dim != 64 && head_dim != 128)
         return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: head_dim %d (supported: 64, 128)", fn, head_dim);
-    if (dt == HDT_BF16 && (layout->s.bm != 128 || layout->s.bn != 64))
-        return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: bf16 kernels need 128x64 tiles, layout has %dx%d", fn,
+    if (dt == HDT_BF16 && !((layout->s.bm == 64 && layout->s.bn == 32) || (layout->s.bm == 128 && layout->s.bn == 64)))
+        return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: bf16 kernels need 64x32 or 128x64 tiles, layout has %dx%d", fn,
                         layout->s.bm, layout->s.bn);
     return HDT_OK;
 }

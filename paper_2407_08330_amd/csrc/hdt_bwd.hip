@@ -49,14 +49,15 @@ struct BwdCfg {
 };
 
 // ------------------------------------------------------------------------------------------- dQ
-template <int D>
-__global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
+template <int D, typename G>
+__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
     HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
     const __bf16 *__restrict__ o, const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
     __bf16 *__restrict__ dq, float *__restrict__ delta, int heads, float scale)
 {
-    using P = Pipe<D, BwdCfg<D>::S_DQ, false>;
+    using P = Pipe<D, BwdCfg<D>::S_DQ, false, G>;
     using R = Ring<P>;
+    constexpr int BM = G::BM, BN = G::BN, KB = G::KB;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
     __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
 
@@ -150,8 +151,8 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
         const char *sK = pipe.tile_a(i % S), *sV = pipe.tile_b(i % S);
 
 #pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-            const int sb = wave * 2 + kb;
+        for (int kb = 0; kb < KB; kb++) {
+            const int sb = wave * KB + kb;
             if (!((sub >> sb) & 1u)) continue;
             f32x16 sacc, dpacc;
 #pragma unroll
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
             }
 #pragma unroll
             for (int e = 0; e < 16; e++) sacc[e] = fast_exp2(fmaf(sacc[e], scale_log2, -lse2));  // P^T
-            if (!((sub >> (16 + sb)) & 1u)) apply_mask(sacc, s.bits_rm + ((size_t)bidx * 8 + sb) * 16, 0.f);
+            if (!((sub >> (16 + sb)) & 1u)) apply_mask(sacc, s.bits_rm + ((size_t)bidx * G::NSUB + sb) * 16, 0.f);
 #pragma unroll
             for (int e = 0; e < 16; e++) sacc[e] *= dpacc[e] - Di;  // dS^T
             // dQ^T += K^T dS^T
@@ -186,14 +187,15 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
-template <int D>
-__global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
+template <int D, typename G>
+__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
     HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
     const float *__restrict__ lse, const __bf16 *__restrict__ d_o, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int heads, float scale)
 {
-    using P = Pipe<D, BwdCfg<D>::S_DKV, true>;
+    using P = Pipe<D, BwdCfg<D>::S_DKV, true, G>;
     using R = Ring<P>;
+    constexpr int BM = G::BM, BN = G::BN, KB = G::KB;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
     __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
 
@@ -259,8 +261,8 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
         const float *sLse = pipe.aux_buf(i % S, 0), *sDelta = pipe.aux_buf(i % S, 1);
 
 #pragma unroll
-        for (int kb = 0; kb < 2; kb++) {  // 32 query slots
-            const int sb = wave * 2 + kb;
+        for (int kb = 0; kb < KB; kb++) {  // 32 query slots
+            const int sb = wave * KB + kb;
             if (!((sub >> sb) & 1u)) continue;
             f32x16 sacc, dpacc;
 #pragma unroll
@@ -279,7 +281,7 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
                 for (int e = 0; e < 4; e++)  // a pad query has LSE = -inf -> +inf here, removed by its mask
                     pacc[gq * 4 + e] = fast_exp2(fmaf(sacc[gq * 4 + e], scale_log2, -lv[e] * LOG2E));
             }
-            if (!((sub >> (16 + sb)) & 1u)) apply_mask(pacc, s.bits_rm + ((size_t)bidx * 8 + sb) * 16, 0.f);
+            if (!((sub >> (16 + sb)) & 1u)) apply_mask(pacc, s.bits_rm + ((size_t)bidx * G::NSUB + sb) * 16, 0.f);
 #pragma unroll
             for (int gq = 0; gq < 4; gq++) {
                 const float4 d4 = *reinterpret_cast<const float4 *>(&sDelta[kb * 32 + hf * 4 + gq * 8]);
@@ -310,31 +312,42 @@ __global__ __launch_bounds__(THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
 
 }  // namespace
 
-hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const HdtSchedule &st_, const void *q, const void *k, const void *v,
-                                 const void *o, const float *lse, const void *d_o, void *dq, void *dk, void *dv,
-                                 int heads, int head_dim, float scale, float *delta, hipStream_t st)
+template <typename G>
+static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf16 *Q, const __bf16 *K, const __bf16 *V,
+                       const __bf16 *O, const float *lse, const __bf16 *DO, void *dq, void *dk, void *dv, int heads,
+                       int head_dim, float scale, float *delta, hipStream_t st)
 {
-    const __bf16 *Q = (const __bf16 *)q, *K = (const __bf16 *)k, *V = (const __bf16 *)v;
-    const __bf16 *O = (const __bf16 *)o, *DO = (const __bf16 *)d_o;
-    dim3 grid((unsigned)((size_t)s.batch * heads * s.tr)), block(THREADS);
+    dim3 grid((unsigned)((size_t)s.batch * heads * s.tr)), block(G::THREADS);
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_dq_bf16_d64" : "hdt_bwd_dq_bf16_d128", st);
         if (head_dim == 64)
-            hipLaunchKernelGGL(k_bwd_dq_bf16<64>, grid, block, 0, st, s, Q, K, V, O, lse, DO, (__bf16 *)dq, delta,
+            hipLaunchKernelGGL((k_bwd_dq_bf16<64, G>), grid, block, 0, st, s, Q, K, V, O, lse, DO, (__bf16 *)dq, delta,
                                heads, scale);
         else
-            hipLaunchKernelGGL(k_bwd_dq_bf16<128>, grid, block, 0, st, s, Q, K, V, O, lse, DO, (__bf16 *)dq, delta,
+            hipLaunchKernelGGL((k_bwd_dq_bf16<128, G>), grid, block, 0, st, s, Q, K, V, O, lse, DO, (__bf16 *)dq, delta,
                                heads, scale);
     }
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_dkv_bf16_d64" : "hdt_bwd_dkv_bf16_d128", st);
         if (head_dim == 64)
-            hipLaunchKernelGGL(k_bwd_dkv_bf16<64>, grid, block, 0, st, st_, Q, K, V, lse, DO, delta, (__bf16 *)dk,
+            hipLaunchKernelGGL((k_bwd_dkv_bf16<64, G>), grid, block, 0, st, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dk,
                                (__bf16 *)dv, heads, scale);
         else
-            hipLaunchKernelGGL(k_bwd_dkv_bf16<128>, grid, block, 0, st, st_, Q, K, V, lse, DO, delta, (__bf16 *)dk,
+            hipLaunchKernelGGL((k_bwd_dkv_bf16<128, G>), grid, block, 0, st, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dk,
                                (__bf16 *)dv, heads, scale);
     }
+}
+
+hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const HdtSchedule &st_, const void *q, const void *k,
+                                 const void *v, const void *o, const float *lse, const void *d_o, void *dq, void *dk,
+                                 void *dv, int heads, int head_dim, float scale, float *delta, hipStream_t st)
+{
+    const __bf16 *Q = (const __bf16 *)q, *K = (const __bf16 *)k, *V = (const __bf16 *)v;
+    const __bf16 *O = (const __bf16 *)o, *DO = (const __bf16 *)d_o;
+    if (s.bm == 64)
+        launch_bwd<Geo<64, 32>>(s, st_, Q, K, V, O, lse, DO, dq, dk, dv, heads, head_dim, scale, delta, st);
+    else
+        launch_bwd<Geo<128, 64>>(s, st_, Q, K, V, O, lse, DO, dq, dk, dv, heads, head_dim, scale, delta, st);
     HDT_HIP_TRY(hipGetLastError());
     return HDT_OK;
 }

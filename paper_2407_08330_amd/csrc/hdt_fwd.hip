@@ -4,9 +4,9 @@
 // softmax, accumulate P V) over the precomputed list of surviving tiles; O and the softmax
 // statistics stay in registers until the last tile and are written once.
 //
-// Work split: one workgroup (4 waves) per (sample, head, query tile of 128 rows); wave w owns
-// query rows 32w .. 32w+31.  A key tile is one list entry of the query tile: 64 key positions in
-// level-sorted order, gathered row by row straight into LDS (hdt_tile.h).  Inside a tile a wave works on 32x32
+// Work split: one workgroup per (sample, head, query tile of BM rows); wave w owns query rows
+// 32w .. 32w+31.  A key tile is one list entry of the query tile: BN key positions in level-sorted
+// order, gathered row by row straight into LDS (hdt_tile.h).  Inside a tile a wave works on 32x32
 // sub-blocks and skips those the layout marks empty.
 //
 // The scores are computed transposed, S^T = K Q^T (keys along the MFMA rows, queries along the
@@ -35,7 +35,7 @@ struct FwdCfg {
 #ifndef HDT_FWD_W64
 #define HDT_FWD_W64 4
 #endif
-    static constexpr int S = (D == 64) ? HDT_FWD_S64 : 2;      // ring stages (LDS: 36 KB / 68 KB per workgroup)
+    static constexpr int S = (D == 64) ? HDT_FWD_S64 : 2;      // ring stages (LDS at 128 x 64: 36 KB / 68 KB per workgroup)
     static constexpr int WAVES = (D == 64) ? HDT_FWD_W64 : 2;  // waves per SIMD the register budget allows
 };
 
@@ -118,13 +118,14 @@ __device__ __forceinline__ void fwd_step(const char *sK, const char *sV, const R
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
+template <int D, typename G>
+__global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
     __bf16 *__restrict__ o, float *__restrict__ lse, int heads, float scale_log2)
 {
-    using P = Pipe<D, FwdCfg<D>::S, false>;
+    using P = Pipe<D, FwdCfg<D>::S, false, G>;
     using R = Ring<P>;
+    constexpr int BM = G::BM, BN = G::BN, KB = G::KB;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
     __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
 
@@ -188,14 +189,14 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
 
         // this wave's two 32x32 sub-blocks of the tile (wave-uniform flags); one straight-line code path
         // per combination, so that the two sub-blocks' loads, MFMA chains and exponentials interleave
-        const bool act0 = (sub >> (wave * 2)) & 1u, act1 = (sub >> (wave * 2 + 1)) & 1u;
+        const bool act0 = (sub >> (wave * KB)) & 1u, act1 = KB > 1 && ((sub >> (wave * KB + 1)) & 1u);
         if (!(act0 || act1)) continue;
-        const unsigned long long *mk = s.bits_rm + ((size_t)bidx * 8 + wave * 2) * 16;
-        if (act0 && act1)
+        const unsigned long long *mk = s.bits_rm + ((size_t)bidx * G::NSUB + wave * KB) * 16;
+        if (KB > 1 && act0 && act1)
             fwd_step<D, true, true>(sK, sV, rl, tl, qf, oacc, m_ref, l_part, mk, xlane, scale_log2);
         else if (act0)
             fwd_step<D, true, false>(sK, sV, rl, tl, qf, oacc, m_ref, l_part, mk, xlane, scale_log2);
-        else
+        else if (KB > 1)
             fwd_step<D, false, true>(sK, sV, rl, tl, qf, oacc, m_ref, l_part, mk, xlane, scale_log2);
     }
 
@@ -215,18 +216,28 @@ __global__ __launch_bounds__(THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
 
 }  // namespace
 
+template <typename G>
+static void launch_fwd(const HdtSchedule &s, const void *q, const void *k, const void *v, void *o, float *lse,
+                       int heads, int head_dim, float scale_log2, hipStream_t st)
+{
+    dim3 grid((unsigned)((size_t)s.batch * heads * s.tr)), block(G::THREADS);
+    if (head_dim == 64)
+        hipLaunchKernelGGL((k_fwd_bf16<64, G>), grid, block, 0, st, s, (const __bf16 *)q, (const __bf16 *)k,
+                           (const __bf16 *)v, (__bf16 *)o, lse, heads, scale_log2);
+    else
+        hipLaunchKernelGGL((k_fwd_bf16<128, G>), grid, block, 0, st, s, (const __bf16 *)q, (const __bf16 *)k,
+                           (const __bf16 *)v, (__bf16 *)o, lse, heads, scale_log2);
+}
+
 hdt_status_t hdt_launch_fwd_bf16(const HdtSchedule &s, const void *q, const void *k, const void *v, void *o,
                                  float *lse, int heads, int head_dim, float scale, hipStream_t st)
 {
     const float scale_log2 = scale * LOG2E;
-    dim3 grid((unsigned)((size_t)s.batch * heads * s.tr)), block(THREADS);
     HdtTimer t(head_dim == 64 ? "hdt_fwd_bf16_d64" : "hdt_fwd_bf16_d128", st);
-    if (head_dim == 64)
-        hipLaunchKernelGGL(k_fwd_bf16<64>, grid, block, 0, st, s, (const __bf16 *)q, (const __bf16 *)k,
-                           (const __bf16 *)v, (__bf16 *)o, lse, heads, scale_log2);
+    if (s.bm == 64)
+        launch_fwd<Geo<64, 32>>(s, q, k, v, o, lse, heads, head_dim, scale_log2, st);
     else
-        hipLaunchKernelGGL(k_fwd_bf16<128>, grid, block, 0, st, s, (const __bf16 *)q, (const __bf16 *)k,
-                           (const __bf16 *)v, (__bf16 *)o, lse, heads, scale_log2);
+        launch_fwd<Geo<128, 64>>(s, q, k, v, o, lse, heads, head_dim, scale_log2, st);
     HDT_HIP_TRY(hipGetLastError());
     return HDT_OK;
 }

@@ -1,8 +1,13 @@
 // Pieces shared by the three bf16 kernels (forward, dQ pass, dK/dV pass).  All of them have the same
-// skeleton: a workgroup of 4 waves owns 128 consecutive rows of the schedule (wave w the rows
+// skeleton: a workgroup of BM/32 waves owns BM consecutive rows of the schedule (wave w the rows
 // 32w..32w+31, whose operands stay in registers as MFMA B fragments), walks the row tile's list
-// entries, and for each entry gathers the 64 rows of two [n_pos][D] tensors that the entry's key
-// positions name into LDS.
+// entries, and for each entry gathers the BN rows of two [n_pos][D] tensors that the entry's key
+// positions name into LDS.  Two tile shapes are built: 128 x 64 (four waves; the layout's default) and
+// 64 x 32 (two waves).  The waves of a workgroup meet at a barrier once per entry and the mask is close to
+// block diagonal, so with four waves a wave often waits through entries that hold nothing for its rows;
+// the finer shape loses fewer such slots and skips more of the mask, but walks more entries and needs
+// twice the workgroups.  Measured, the two are within a few percent of each other at head size 64 and the
+// finer one is ~5-10 % ahead at head size 128, before the doubled cost of building its layout.
 //
 // The gather uses the CDNA direct-to-LDS loads (global_load_lds_*: every lane supplies a global
 // address, the 64 results land in LDS at M0 + lane*size) into a ring of S stages, so that several
@@ -24,7 +29,17 @@
 
 namespace hdt_tile {
 
-constexpr int BM = 128, BN = 64, THREADS = 256;
+// tile geometry: BM query rows x BN key slots, one wave per 32 rows; a ring stage (two tiles of BN rows)
+// also has to hold the workgroup's own BM rows, hence BM = 2 BN, and every wave loads 16 rows of a tile
+template <int BM_, int BN_>
+struct Geo {
+    static constexpr int BM = BM_, BN = BN_;
+    static constexpr int NW = BM_ / 32;               // waves per workgroup
+    static constexpr int THREADS = NW * 64;
+    static constexpr int KB = BN_ / 32;               // 32-key sub-blocks per tile
+    static constexpr int NSUB = (BM_ / 32) * KB;      // 32x32 sub-blocks per tile
+    static_assert(BM_ == 2 * BN_ && BN_ / NW == 16, "unsupported tile shape");
+};
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
@@ -78,8 +93,9 @@ __device__ __forceinline__ void wg_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <int D, int S_, bool AUX>
+template <int D, int S_, bool AUX, typename G>
 struct Pipe {
+    static constexpr int BM = G::BM, BN = G::BN, NW = G::NW;
     static constexpr int S = S_;                      // data stages in the ring
     static constexpr int PS = 4;                      // position stages
     static constexpr int KSTEPS = D / 16;             // MFMA steps over the head dimension
@@ -88,11 +104,13 @@ struct Pipe {
     static constexpr int CPR = D / 8;                 // 16-byte chunks per row
     static constexpr int TILE = BN * ROWB;            // bytes of one gathered tile of one tensor
     static constexpr int RPI = 1024 / ROWB;           // rows per wave-level load
-    static constexpr int NI = 16 / RPI;               // wave-level loads per tensor per tile per wave
+    static constexpr int LPW = BN / NW;               // rows of a tile each wave loads (16)
+    static constexpr int NI = LPW / RPI;              // wave-level loads per tensor per tile per wave
+    static constexpr int POSW = 64;                   // ints per position buffer (one wave-level load; BN are used)
     static constexpr int NDMA = 2 * NI + (AUX ? 1 : 0);  // vector-memory instructions per tile per wave
     static constexpr int DATA_BYTES = S * 2 * TILE;
-    static constexpr int POS_BYTES = PS * 4 * BN * 4;
-    static constexpr int AUX_BYTES = AUX ? S * 4 * BN * 4 : 0;
+    static constexpr int POS_BYTES = PS * NW * POSW * 4;
+    static constexpr int AUX_BYTES = AUX ? S * NW * POSW * 4 : 0;
     static constexpr int SMEM_BYTES = DATA_BYTES + POS_BYTES + AUX_BYTES;
 
     char *smem;
@@ -106,18 +124,19 @@ struct Pipe {
     __device__ __forceinline__ const char *tile_b(int stage) const { return smem + (stage * 2 + 1) * TILE; }
     __device__ __forceinline__ const int *pos_buf(int ps) const
     {
-        return reinterpret_cast<const int *>(smem + DATA_BYTES) + (ps * 4 + wave) * BN;
+        return reinterpret_cast<const int *>(smem + DATA_BYTES) + (ps * NW + wave) * POSW;
     }
     // aux values of the 64 slots: array 0 is written by wave 0, array 1 by wave 1
     __device__ __forceinline__ const float *aux_buf(int stage, int which) const
     {
-        return reinterpret_cast<const float *>(smem + DATA_BYTES + POS_BYTES) + (stage * 4 + which) * BN;
+        return reinterpret_cast<const float *>(smem + DATA_BYTES + POS_BYTES) + (stage * NW + which) * POSW;
     }
 
     // start loading the key positions of the row tile's j-th entry (every wave keeps its own copy)
     __device__ __forceinline__ void issue_pos(int j, int ps) const
     {
-        dma4(keys + j * BN + lane, smem_addr + DATA_BYTES + ((ps * 4 + wave) * BN) * 4);
+        // (64 lanes load; with BN = 32 the upper half repeats the lower one)
+        dma4(keys + j * BN + (lane & (BN - 1)), smem_addr + DATA_BYTES + ((ps * NW + wave) * POSW) * 4);
     }
 
     // start gathering the rows of an entry whose positions sit in position stage ps
@@ -127,17 +146,17 @@ struct Pipe {
         const int lr = lane / CPR, c = lane % CPR;  // row inside the wave-level load, chunk slot
 #pragma unroll
         for (int i = 0; i < NI; i++) {
-            const int r = wave * 16 + i * RPI + lr;
+            const int r = wave * LPW + i * RPI + lr;
             const int pos = max(pb[r], 0);  // slots without a key: any readable row, the bitmap masks them
             const size_t off = (size_t)pos * D + (size_t)((c ^ swz(r & 7)) * 8);
-            const uint32_t dst = (uint32_t)((wave * 16 + i * RPI) * ROWB);
+            const uint32_t dst = (uint32_t)((wave * LPW + i * RPI) * ROWB);
             dma16(a + off, smem_addr + (stage * 2 + 0) * TILE + dst);
             dma16(b + off, smem_addr + (stage * 2 + 1) * TILE + dst);
         }
         if (AUX) {
-            const int pos = max(pb[lane], 0);
+            const int pos = max(pb[lane & (BN - 1)], 0);
             const float *src = (wave & 1) ? aux1 : aux0;
-            dma4(src + pos, smem_addr + DATA_BYTES + POS_BYTES + ((stage * 4 + wave) * BN) * 4);
+            dma4(src + pos, smem_addr + DATA_BYTES + POS_BYTES + ((stage * NW + wave) * POSW) * 4);
         }
     }
 };

@@ -12,13 +12,14 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 5e-2, "f32": 1e-4}
 
 
-def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0):
+def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0, tile=(0, 0)):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v, d_o), (q_, k_, v_, do_) = make_inputs(B, H, N, D, seed, dtype, n_tensors=4)
-    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed, edges=edges)
+    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), tile_m=tile[0], tile_n=tile[1],
+                               windowed=windowed, edges=edges)
     o_, lse_ = hdt.hdt_attn_fwd(lay, q_, k_, v_, scale)
     dq_ = torch.full_like(q_, float("nan"))
     dk_ = torch.full_like(q_, float("nan"))
@@ -114,6 +115,39 @@ def test_fwd_bwd_pseudo_sections_of_32_sentences(oracle):
     assert all(len(sec) == 32 for d in docs for sec in d[2][:-1])
     say(f"[bwd] pseudo-sections: {[len(d[2]) for d in docs]} sections, real {(level >= 0).sum()}")
     run_bwd_case(oracle, level, parent, 4, 64, "bf16", 3233)
+
+
+def _ragged_pair(n, seed):
+    rng = np.random.default_rng(seed)
+    lv, pr = [], []
+    for _ in range(2):
+        l, p = inputs.tree_document([(1, 5), (0, 6), (0, 9), (0, 30)], rng, max_nodes=n)
+        lv.append(np.concatenate([l, np.full(n - l.shape[0], -1, np.int32)]))
+        pr.append(np.concatenate([p, np.full(n - p.shape[0], -1, np.int32)]))
+    return np.stack(lv), np.stack(pr)
+
+
+@pytest.mark.parametrize("tile", [(64, 32), (128, 64)], ids=["64x32", "128x64"])
+def test_bwd_bf16_both_tile_shapes(oracle, tile):
+    # both tile shapes of the bf16 kernels, whichever is the default: benchmark hierarchy, ragged lengths at
+    # both head sizes, a directed mask (second schedule for dK/dV), the windowed schedule, all-pad / dense
+    wl = inputs.make_workload(1)
+    say(f"[bwd] tile {tile}: config 1 hierarchy")
+    run_bwd_case(oracle, wl.level, wl.parent, 2, 64, "bf16", 9100, tile=tile)
+    for n, D in ((333, 128), (1000, 64), (95, 64)):
+        level, parent = _ragged_pair(n, 9200 + n)
+        say(f"[bwd] tile {tile}: ragged n={n} d={D}")
+        run_bwd_case(oracle, level, parent, 3, D, "bf16", 9300 + n, tile=tile)
+    lv, pr = zip(*(inputs.listops_like_tree(np.random.default_rng(s), 1536) for s in (31, 32)))
+    level, parent = np.stack(lv), np.stack(pr)
+    say(f"[bwd] tile {tile}: ListOps-shaped trees, up edges only; windowed schedule")
+    run_bwd_case(oracle, level, parent, 2, 64, "bf16", 9400, edges=1, tile=tile)
+    run_bwd_case(oracle, level[:1], parent[:1], 2, 128, "bf16", 9401, windowed=True, tile=tile)
+    n = 384
+    level = np.stack([np.full(n, -1, np.int32), np.array([0] + [1] * (n - 1), np.int32)])
+    parent = np.stack([np.full(n, -1, np.int32), np.array([-1] + [0] * (n - 1), np.int32)])
+    say(f"[bwd] tile {tile}: all-pad + dense document")
+    run_bwd_case(oracle, level, parent, 2, 64, "bf16", 9500, tile=tile)
 
 
 def test_bwd_all_pad_sample_and_dense_document(oracle):

@@ -12,13 +12,14 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
 
 
-def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0):
+def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0, tile=(0, 0)):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v), (dq_, dk_, dv_) = make_inputs(B, H, N, D, seed, dtype)
-    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), windowed=windowed, edges=edges)
+    lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), tile_m=tile[0], tile_n=tile[1],
+                               windowed=windowed, edges=edges)
     o = torch.full_like(dq_, float("nan"))
     lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
     hdt.hdt_attn_fwd(lay, dq_, dk_, dv_, scale, o=o, lse=lse)
@@ -118,6 +119,41 @@ def test_fwd_listops_mask_variants(oracle, edges):
     run_fwd_case(oracle, level[:1, :700], np.where(parent[:1, :700] < 700, parent[:1, :700], -1), 2, 128, "bf16",
                  510 + edges, edges=edges, windowed=True)
     run_fwd_case(oracle, level[:1], parent[:1], 1, 64, "f32", 520 + edges, edges=edges)
+
+
+def _ragged_pair(n, seed):
+    rng = np.random.default_rng(seed)
+    lv, pr = [], []
+    for _ in range(2):
+        l, p = inputs.tree_document([(1, 5), (0, 6), (0, 9), (0, 30)], rng, max_nodes=n)
+        lv.append(np.concatenate([l, np.full(n - l.shape[0], -1, np.int32)]))
+        pr.append(np.concatenate([p, np.full(n - p.shape[0], -1, np.int32)]))
+    return np.stack(lv), np.stack(pr)
+
+
+@pytest.mark.parametrize("tile", [(64, 32), (128, 64)], ids=["64x32", "128x64"])
+def test_fwd_bf16_both_tile_shapes(oracle, tile):
+    # the bf16 kernels exist for two tile shapes (two and four waves per workgroup); whichever one is the
+    # default, both are held to the same bar: the benchmark hierarchy, ragged lengths at both head sizes, a
+    # directed mask on deep trees, the windowed schedule, and the all-pad / dense pair
+    wl = inputs.make_workload(1)
+    say(f"[fwd] tile {tile}: config 1 hierarchy")
+    run_fwd_case(oracle, wl.level, wl.parent, 2, 64, "bf16", 8100, tile=tile)
+    for n, D in ((333, 128), (1000, 64), (95, 64)):
+        level, parent = _ragged_pair(n, 8200 + n)
+        say(f"[fwd] tile {tile}: ragged n={n} d={D}")
+        run_fwd_case(oracle, level, parent, 3, D, "bf16", 8300 + n, tile=tile)
+    level, parent = _listops_batch(1536, (21, 22))
+    say(f"[fwd] tile {tile}: ListOps-shaped trees, up edges only; windowed schedule")
+    run_fwd_case(oracle, level, parent, 2, 64, "bf16", 8400, edges=1, tile=tile)
+    run_fwd_case(oracle, level[:1], parent[:1], 2, 128, "bf16", 8401, windowed=True, tile=tile)
+    n = 384
+    level = np.stack([np.full(n, -1, np.int32), np.array([0] + [1] * (n - 1), np.int32)])
+    parent = np.stack([np.full(n, -1, np.int32), np.array([-1] + [0] * (n - 1), np.int32)])
+    say(f"[fwd] tile {tile}: all-pad + dense document")
+    lay = run_fwd_case(oracle, level, parent, 2, 64, "bf16", 8500, tile=tile)
+    assert lay.sample_info(0) == (0, 0)
+    assert lay.sample_info(1) == ((n // tile[0]) * (n // tile[1]), n * n)
 
 
 def test_fwd_large_logits_and_scale(oracle):
