@@ -31,15 +31,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 def algorithmic_bytes_per_unit(kernel: str, d: int) -> int:
     """Compulsory HBM bytes per (position, head) of one launch of `kernel` (bf16 tensors, fp32 LSE/D):
-    forward reads Q,K,V and writes O,LSE; the dQ pass reads Q,K,V,O,dO,LSE and writes dQ,D; the
-    dK/dV pass reads Q,K,V,dO,LSE,D and writes dK,dV."""
+    forward reads Q,K,V and writes O,LSE; the D pass reads O,dO and writes D; the backward kernel reads
+    Q,K,V,dO,LSE,D and writes dQ,dK,dV."""
     row = 2 * d
     if kernel.startswith("hdt_fwd"):
         return 4 * row + 4
-    if kernel.startswith("hdt_bwd_dq"):
-        return 6 * row + 8
-    if kernel.startswith("hdt_bwd_dkv"):
-        return 6 * row + 8
+    if kernel.startswith("hdt_bwd_delta"):
+        return 2 * row + 4
+    if kernel.startswith("hdt_bwd_bf16"):
+        return 7 * row + 8
     raise KeyError(kernel)
 
 

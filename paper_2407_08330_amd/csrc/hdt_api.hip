@@ -331,8 +331,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if (!workspace || workspace_bytes < need)
         return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: workspace of %zu bytes needed, %zu given", need,
                         workspace_bytes);
-    if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) > 0x7fffffffLL)
-        return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
+    if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) * 2 > 0x7fffffffLL)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: 2*batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
     const HdtSchedule &s_tr = layout->transposed ? layout->transposed->s : s;
     if (dt == HDT_BF16)

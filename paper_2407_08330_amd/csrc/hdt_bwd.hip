@@ -5,22 +5,30 @@
 // walks:  D_i = sum_c dO_ic O_ic,  P = exp(S - LSE),  dV = P^T dO,  dP = dO V^T,
 //         dS = P o (dP - D),  dQ = scale dS K,  dK = scale dS^T Q.
 //
-// Two deterministic passes, no atomics, both with the forward kernel's skeleton (hdt_tile.h):
-//   k_bwd_dq   a workgroup owns a query tile (rows in document order), walks its key tiles (the 64 key
-//              positions of each list entry, gathered row by row), recomputes S^T and dP^T with queries
-//              along the MFMA columns (LSE_i and D_i are per-lane scalars) and accumulates
-//              dQ^T = K^T dS^T.  It also writes D.
-//   k_bwd_dkv  walks the schedule of the TRANSPOSED mask.  The paper's mask is symmetric (i may attend to
-//              j iff j may attend to i: parent/child and sibling relations are mutual), so the entries of "query rows I x the keys they attend to"
-//              are also the entries of "key rows I x the queries attending to them", bitmaps included.  A workgroup therefore owns
-//              128 KEYS in document order (K, V rows in registers), walks the same list, gathers the
-//              Q and dO rows (and LSE, D) of an entry's 64 QUERY positions into LDS and accumulates
-//              dV^T = dO^T P and dK^T = Q^T dS with keys along the MFMA columns.  Same load balance
-//              as the forward, no cross-wave reduction, contiguous stores.  For the directed variants
-//              (edge kinds without up/down symmetry) the layout holds a second schedule, built from
-//              the same ids with the parent and child kinds exchanged.
-// Both passes recompute the scores, which costs two extra contractions but keeps dQ out of HBM
-// as fp32 partial sums.
+// Deterministic, no atomics.  Two launches:
+//   k_bwd_delta  D for every row (a streaming pass over O and dO).
+//   k_bwd_bf16   two workgroups per row tile I (rows in document order), one per role, both with the
+//                forward kernel's skeleton (hdt_tile.h):
+//     dQ role      the tile's rows as QUERIES: walks their key tiles (the key positions of each list
+//                  entry, gathered row by row), recomputes S^T and dP^T with queries along the MFMA
+//                  columns (LSE_i and D_i are per-lane scalars) and accumulates dQ^T = K^T dS^T.
+//     dK/dV role   the tile's rows as KEYS: walks the schedule of the TRANSPOSED mask.  The paper's mask
+//                  is symmetric (i may attend to j iff j may attend to i: parent/child and sibling
+//                  relations are mutual), so the entries of "query rows I x the keys they attend to" are
+//                  also the entries of "key rows I x the queries attending to them", bitmaps included.
+//                  K, V rows of the tile sit in registers; the Q and dO rows (and LSE, D) of an entry's
+//                  QUERY positions are gathered into LDS and dV^T = dO^T P, dK^T = Q^T dS accumulate
+//                  with keys along the MFMA columns.  Same load balance as the forward, no cross-wave
+//                  reduction, contiguous stores.  For the directed variants (edge kinds without up/down
+//                  symmetry) the layout holds a second schedule, built from the same ids with the
+//                  parent and child kinds exchanged.
+// Both roles recompute the scores, which costs two extra contractions but keeps dQ out of HBM as fp32
+// partial sums.  The two workgroups of a tile are neighbours in the launch order and run on the same XCD
+// at the same time.  That is what the pairing is for: the dQ role reads the tile's Q, dO rows and gathers
+// K, V rows of the neighbourhood, the dK/dV role reads the tile's K, V rows and gathers Q, dO rows of the
+// same neighbourhood, so each role finds in the XCD's L2 what the other (or a neighbouring pair) has just
+// fetched, and Q, K, V, dO come from HBM once per backward pass instead of once per role (measured: the
+// L2 fetch volume of this kernel is that of four tensors; as two separate passes it was that of eight).
 #include "hdt_tile.h"
 
 namespace {
@@ -32,40 +40,65 @@ struct BwdCfg {
 #ifndef HDT_DQ_S64
 #define HDT_DQ_S64 3
 #endif
-#ifndef HDT_DQ_W64
-#define HDT_DQ_W64 3
-#endif
 #ifndef HDT_DKV_S64
 #define HDT_DKV_S64 2
 #endif
-#ifndef HDT_DKV_W64
-#define HDT_DKV_W64 3
+#ifndef HDT_BWD_W64
+#define HDT_BWD_W64 3
 #endif
-    // ring stages and waves per SIMD (register budget) of the two passes
+#ifndef HDT_BWD_W128
+#define HDT_BWD_W128 1
+#endif
+    // ring stages of the two roles and waves per SIMD (register budget) of the kernel
     static constexpr int S_DQ = (D == 64) ? HDT_DQ_S64 : 2;
     static constexpr int S_DKV = (D == 64) ? HDT_DKV_S64 : 2;
-    static constexpr int WAVES_DQ = (D == 64) ? HDT_DQ_W64 : 2;
-    static constexpr int WAVES_DKV = (D == 64) ? HDT_DKV_W64 : 1;
+    static constexpr int WAVES = (D == 64) ? HDT_BWD_W64 : HDT_BWD_W128;
 };
+
+// ---------------------------------------------------------------------------------------- D
+// D_i = sum_c dO_ic O_ic for all rows of [rows][D] tensors: every lane multiplies 8 values (16 bytes of each
+// tensor), the lanes of a row are added up.  kRows rows per lane in flight.
+template <int D>
+__global__ __launch_bounds__(256) void k_bwd_delta(const __bf16 *__restrict__ o, const __bf16 *__restrict__ d_o,
+                                                   float *__restrict__ delta, long long rows)
+{
+    constexpr int CPR = D / 8, RPB = 256 / CPR, kRows = 4;
+    const int lr = threadIdx.x / CPR, c = threadIdx.x % CPR;
+    const long long r0 = (long long)blockIdx.x * (RPB * kRows) + lr;
+    bf16x8 a[kRows], b[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; u++) {
+        const long long r = min(r0 + (long long)u * RPB, rows - 1);
+        a[u] = *reinterpret_cast<const bf16x8 *>(o + (size_t)r * D + c * 8);
+        b[u] = *reinterpret_cast<const bf16x8 *>(d_o + (size_t)r * D + c * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < kRows; u++) {
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) part += (float)a[u][e] * (float)b[u][e];
+#pragma unroll
+        for (int m = 1; m < CPR; m <<= 1) part += __shfl_xor(part, m);
+        const long long r = r0 + (long long)u * RPB;
+        if (c == 0 && r < rows) delta[r] = part;
+    }
+}
 
 // ------------------------------------------------------------------------------------------- dQ
 template <int D, typename G>
-__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16(
-    HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
-    const __bf16 *__restrict__ o, const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
-    __bf16 *__restrict__ dq, float *__restrict__ delta, int heads, float scale)
+__device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const __bf16 *__restrict__ q,
+                                         const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
+                                         const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
+                                         const float *__restrict__ delta, __bf16 *__restrict__ dq, int wave, int I, int bh,
+                                         int b, float scale)
 {
     using P = Pipe<D, BwdCfg<D>::S_DQ, false, G>;
     using R = Ring<P>;
     constexpr int BM = G::BM, BN = G::BN, KB = G::KB;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
-    __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int qn = lane & 31, hf = lane >> 5;
-    const unsigned lb = logical_block(blockIdx.x, gridDim.x);
-    const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
+    const int lane = threadIdx.x & 63;
+    const int qn = lane & 31;
     const size_t base = (size_t)bh * s.n_pos * D;
     const float scale_log2 = scale * LOG2E;
 
@@ -91,31 +124,11 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16
     // the B fragments are read back from there.  The ring may only take those stages over after a
     // barrier, so the prologue is issued in two pieces.
     constexpr uint32_t STG_Q = (uint32_t)(S - 1) * 2 * P::TILE, STG_DO = (uint32_t)(S - 2) * 2 * P::TILE;
-    __shared__ float sDi[BM];
     stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, STG_Q);
     stage_own_rows(pipe, d_o + base, I * BM, s.n_pos, D, STG_DO);
     R::start(pipe, n);
     R::template prologue<0, S - 2>(pipe, n);
     if (S == 2 || n == 0) wait_vmcnt<0>();  // otherwise the prologue's first wait covered the staged rows
-
-    // D_i = sum_c dO_ic O_ic from full-row reads: lane (row l/CPR, chunk l%CPR) multiplies 8 values of O
-    // (global, coalesced) with the staged dO chunk, the CPR lanes of a row are then added up
-    {
-        const int lr = lane / P::CPR, c = lane % P::CPR;
-#pragma unroll
-        for (int i = 0; i < 32 / P::RPI; i++) {
-            const int r = wave * 32 + i * P::RPI + lr;
-            const int g = min(I * BM + r, s.n_pos - 1);
-            const bf16x8 ov = *reinterpret_cast<const bf16x8 *>(o + base + (size_t)g * D + c * 8);
-            const bf16x8 dv8 = lds_read_8(smem + STG_DO + r * ROWB + ((c ^ swz(r & 7)) << 4));
-            float part = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; e++) part += (float)ov[e] * (float)dv8[e];
-#pragma unroll
-            for (int m = 1; m < P::CPR; m <<= 1) part += __shfl_xor(part, m);
-            if (c == 0) sDi[r] = part;
-        }
-    }
     bf16x8 qf[KSTEPS], dof[KSTEPS];
 #pragma unroll
     for (int st = 0; st < KSTEPS; st++) {
@@ -125,8 +138,7 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16
     const int qrow_ld = min(qrow, s.n_pos - 1);
     float lse2 = lse[(size_t)bh * s.n_pos + qrow_ld];
     lse2 = (lse2 == -INFINITY) ? 0.f : lse2 * LOG2E;  // pad rows are masked by the bitmap anyway
-    const float Di = sDi[wave * 32 + qn];  // written by this wave
-    if (qrow < s.n_pos && hf == 0) delta[(size_t)bh * s.n_pos + qrow] = Di;
+    const float Di = delta[(size_t)bh * s.n_pos + qrow_ld];
     // the compiler must finish its own loads before the hand-scheduled ones continue
     asm volatile("" ::"v"(Di), "v"(lse2));
     wg_barrier();  // every wave has read its fragments: the ring may use all stages
@@ -181,29 +193,26 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DQ) void k_bwd_dq_bf16
         // through this wave's slice of the stage tile n would have used: free since the last barrier (see
         // the forward kernel), so waves leave independently
         const int wrow0 = I * BM + wave * 32;
-        store_rows_via_lds<P, D>(smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB, lane, dqacc, scale,
+        store_rows_via_lds<P, D>(smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB, opaque(lane), dqacc, scale,
                                  dq + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     }
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
 template <int D, typename G>
-__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf16(
-    HdtSchedule s, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
-    const float *__restrict__ lse, const __bf16 *__restrict__ d_o, const float *__restrict__ delta,
-    __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int heads, float scale)
+__device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const __bf16 *__restrict__ q,
+                                          const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
+                                          const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
+                                          const float *__restrict__ delta, __bf16 *__restrict__ dk,
+                                          __bf16 *__restrict__ dv, int wave, int I, int bh, int b, float scale)
 {
     using P = Pipe<D, BwdCfg<D>::S_DKV, true, G>;
     using R = Ring<P>;
     constexpr int BM = G::BM, BN = G::BN, KB = G::KB;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
-    __shared__ __attribute__((aligned(1024))) char smem[P::SMEM_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = threadIdx.x & 63;
     const int hf = lane >> 5;
-    const unsigned lb = logical_block(blockIdx.x, gridDim.x);
-    const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     const size_t base = (size_t)bh * s.n_pos * D;
     const float scale_log2 = scale * LOG2E;
 
@@ -305,9 +314,31 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES_DKV) void k_bwd_dkv_bf
         // through this wave's slice of the stage tile n would have used: free since the last barrier
         const int wrow0 = I * BM + wave * 32;
         char *wl = smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB;
-        store_rows_via_lds<P, D>(wl, lane, dkacc, scale, dk + base + (size_t)wrow0 * D, s.n_pos - wrow0);
-        store_rows_via_lds<P, D>(wl, lane, dvacc, 1.f, dv + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+        const int le = opaque(lane);
+        store_rows_via_lds<P, D>(wl, le, dkacc, scale, dk + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+        store_rows_via_lds<P, D>(wl, le, dvacc, 1.f, dv + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     }
+}
+
+template <int D, typename G>
+__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES) void k_bwd_bf16(
+    HdtSchedule s, HdtSchedule s_tr, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
+    const __bf16 *__restrict__ v, const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
+    const float *__restrict__ delta, __bf16 *__restrict__ dq, __bf16 *__restrict__ dk, __bf16 *__restrict__ dv,
+    int heads, float scale)
+{
+    using PQ = Pipe<D, BwdCfg<D>::S_DQ, false, G>;
+    using PK = Pipe<D, BwdCfg<D>::S_DKV, true, G>;
+    constexpr int SMEM = PQ::SMEM_BYTES > PK::SMEM_BYTES ? PQ::SMEM_BYTES : PK::SMEM_BYTES;
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM];
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const unsigned lb2 = logical_block(blockIdx.x, gridDim.x);
+    const unsigned lb = lb2 >> 1;
+    const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
+    if (lb2 & 1u)
+        dkv_role<D, G>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
+    else
+        dq_role<D, G>(smem, s, q, k, v, lse, d_o, delta, dq, wave, I, bh, b, scale);
 }
 
 }  // namespace
@@ -317,24 +348,25 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
                        const __bf16 *O, const float *lse, const __bf16 *DO, void *dq, void *dk, void *dv, int heads,
                        int head_dim, float scale, float *delta, hipStream_t st)
 {
-    dim3 grid((unsigned)((size_t)s.batch * heads * s.tr)), block(G::THREADS);
     {
-        HdtTimer t(head_dim == 64 ? "hdt_bwd_dq_bf16_d64" : "hdt_bwd_dq_bf16_d128", st);
+        HdtTimer t(head_dim == 64 ? "hdt_bwd_delta_d64" : "hdt_bwd_delta_d128", st);
+        const long long rows = (long long)s.batch * heads * s.n_pos;
+        const int rpb = (256 / (head_dim / 8)) * 4;
+        dim3 grid((unsigned)((rows + rpb - 1) / rpb)), block(256);
         if (head_dim == 64)
-            hipLaunchKernelGGL((k_bwd_dq_bf16<64, G>), grid, block, 0, st, s, Q, K, V, O, lse, DO, (__bf16 *)dq, delta,
-                               heads, scale);
+            hipLaunchKernelGGL(k_bwd_delta<64>, grid, block, 0, st, O, DO, delta, rows);
         else
-            hipLaunchKernelGGL((k_bwd_dq_bf16<128, G>), grid, block, 0, st, s, Q, K, V, O, lse, DO, (__bf16 *)dq, delta,
-                               heads, scale);
+            hipLaunchKernelGGL(k_bwd_delta<128>, grid, block, 0, st, O, DO, delta, rows);
     }
     {
-        HdtTimer t(head_dim == 64 ? "hdt_bwd_dkv_bf16_d64" : "hdt_bwd_dkv_bf16_d128", st);
+        HdtTimer t(head_dim == 64 ? "hdt_bwd_bf16_d64" : "hdt_bwd_bf16_d128", st);
+        dim3 grid((unsigned)((size_t)s.batch * heads * s.tr * 2)), block(G::THREADS);
         if (head_dim == 64)
-            hipLaunchKernelGGL((k_bwd_dkv_bf16<64, G>), grid, block, 0, st, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dk,
-                               (__bf16 *)dv, heads, scale);
+            hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
+                               (__bf16 *)dk, (__bf16 *)dv, heads, scale);
         else
-            hipLaunchKernelGGL((k_bwd_dkv_bf16<128, G>), grid, block, 0, st, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dk,
-                               (__bf16 *)dv, heads, scale);
+            hipLaunchKernelGGL((k_bwd_bf16<128, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
+                               (__bf16 *)dk, (__bf16 *)dv, heads, scale);
     }
 }
 

@@ -70,15 +70,16 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p)
     return (uint32_t)(uintptr_t)(HDT_LDS const char *)p;
 }
 
-// direct-to-LDS loads: lane l's 16 (4) bytes at `g` land at lds_base + 16*l (4*l)
-__device__ __forceinline__ void dma16(const void *g, uint32_t lds_base)
+// direct-to-LDS loads: lane l's 16 (4) bytes at base + off (a wave-uniform base pointer in scalar registers,
+// a per-lane byte offset below 2^31) land at lds_base + 16*l (4*l)
+__device__ __forceinline__ void dma16(const void *base, uint32_t off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_base)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base)
                  : "memory", "m0");
 }
-__device__ __forceinline__ void dma4(const void *g, uint32_t lds_base)
+__device__ __forceinline__ void dma4(const void *base, uint32_t off, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds_base)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base)
                  : "memory", "m0");
 }
 template <int N>
@@ -136,7 +137,7 @@ struct Pipe {
     __device__ __forceinline__ void issue_pos(int j, int ps) const
     {
         // (64 lanes load; with BN = 32 the upper half repeats the lower one)
-        dma4(keys + j * BN + (lane & (BN - 1)), smem_addr + DATA_BYTES + ((ps * NW + wave) * POSW) * 4);
+        dma4(keys + j * BN, (uint32_t)(lane & (BN - 1)) * 4u, smem_addr + DATA_BYTES + ((ps * NW + wave) * POSW) * 4);
     }
 
     // start gathering the rows of an entry whose positions sit in position stage ps
@@ -148,15 +149,15 @@ struct Pipe {
         for (int i = 0; i < NI; i++) {
             const int r = wave * LPW + i * RPI + lr;
             const int pos = max(pb[r], 0);  // slots without a key: any readable row, the bitmap masks them
-            const size_t off = (size_t)pos * D + (size_t)((c ^ swz(r & 7)) * 8);
+            const uint32_t off = (uint32_t)pos * ROWB + (uint32_t)((c ^ swz(r & 7)) * 16);  // bytes
             const uint32_t dst = (uint32_t)((wave * LPW + i * RPI) * ROWB);
-            dma16(a + off, smem_addr + (stage * 2 + 0) * TILE + dst);
-            dma16(b + off, smem_addr + (stage * 2 + 1) * TILE + dst);
+            dma16(a, off, smem_addr + (stage * 2 + 0) * TILE + dst);
+            dma16(b, off, smem_addr + (stage * 2 + 1) * TILE + dst);
         }
         if (AUX) {
             const int pos = max(pb[lane & (BN - 1)], 0);
             const float *src = (wave & 1) ? aux1 : aux0;
-            dma4(src + pos, smem_addr + DATA_BYTES + POS_BYTES + ((stage * NW + wave) * POSW) * 4);
+            dma4(src, (uint32_t)pos * 4u, smem_addr + DATA_BYTES + POS_BYTES + ((stage * NW + wave) * POSW) * 4);
         }
     }
 };
@@ -246,9 +247,18 @@ __device__ __forceinline__ void stage_own_rows(const P &p, const __bf16 *t, int 
     for (int i = 0; i < 32 / P::RPI; i++) {
         const int r = p.wave * 32 + i * P::RPI + lr;
         const int g = min(row0 + r, n_pos - 1);
-        dma16(t + (size_t)g * D + (size_t)((c ^ swz(r & 7)) * 8),
+        dma16(t, (uint32_t)g * P::ROWB + (uint32_t)((c ^ swz(r & 7)) * 16),
               p.smem_addr + lds_off + (uint32_t)((p.wave * 32 + i * P::RPI) * P::ROWB));
     }
+}
+
+// A value the compiler cannot see through: what is derived from it is computed after this point.  Used on
+// the lane index in front of an epilogue, whose per-lane addresses would otherwise be hoisted above the
+// tile loop and held in registers throughout it.
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
 }
 
 // Epilogue: a wave's 32 x D accumulator block, held transposed in C fragments (lane (row l%32, hf)
@@ -274,7 +284,8 @@ __device__ __forceinline__ void store_rows_via_lds(char *wave_lds, int lane, con
     for (int i = 0; i < 32 / P::RPI; i++) {
         const int row = i * P::RPI + lr;
         const u32x4 v = *reinterpret_cast<const u32x4 *>(wave_lds + row * P::ROWB + ((c ^ (row & 7)) << 4));
-        if (row < rows_valid) *reinterpret_cast<u32x4 *>(dst + (size_t)row * D + c * 8) = v;
+        // streaming store: results are not read again by this launch and should not displace its inputs in L2
+        if (row < rows_valid) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(dst + (size_t)row * D + c * 8));
     }
 }
 
