@@ -287,7 +287,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd(cons
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || ((uintptr_t)lse & 3u))
         return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_fwd: tensor pointers must be 16-byte aligned");
     if (o == q || o == k || o == v) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_fwd: output aliases an input");
-    if ((int64_t)s.batch * heads * s.tr > 0x7fffffffLL)
+    if ((int64_t)s.batch * heads * s.tr > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_fwd: batch*heads*q_tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
     if (dt == HDT_BF16) return hdt_launch_fwd_bf16(s, q, k, v, o, lse, heads, head_dim, scale, hs);
@@ -331,7 +331,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if (!workspace || workspace_bytes < need)
         return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: workspace of %zu bytes needed, %zu given", need,
                         workspace_bytes);
-    if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) * 2 > 0x7fffffffLL)
+    if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) * 2 > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: 2*batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
     const HdtSchedule &s_tr = layout->transposed ? layout->transposed->s : s;

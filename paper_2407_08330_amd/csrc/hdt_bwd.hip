@@ -332,7 +332,8 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES) void k_bwd_bf16(
     constexpr int SMEM = PQ::SMEM_BYTES > PK::SMEM_BYTES ? PQ::SMEM_BYTES : PK::SMEM_BYTES;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-    const unsigned lb2 = logical_block(blockIdx.x, gridDim.x);
+    const unsigned lb2 = logical_block(blockIdx.x, 2 * kXcdChunk);
+    if (lb2 >= 2u * s.batch * heads * s.tr) return;  // padding of the grid
     const unsigned lb = lb2 >> 1;
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     if (lb2 & 1u)
@@ -360,7 +361,7 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
     }
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_bf16_d64" : "hdt_bwd_bf16_d128", st);
-        dim3 grid((unsigned)((size_t)s.batch * heads * s.tr * 2)), block(G::THREADS);
+        dim3 grid(padded_grid((unsigned)((size_t)s.batch * heads * s.tr * 2), 2 * kXcdChunk)), block(G::THREADS);
         if (head_dim == 64)
             hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
                                (__bf16 *)dk, (__bf16 *)dv, heads, scale);

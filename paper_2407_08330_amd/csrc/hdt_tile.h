@@ -52,12 +52,20 @@ typedef const uint32_t HDT_CONST *cptr_u32;
 __device__ __forceinline__ cptr_i32 as_const(const int32_t *p) { return (cptr_i32)(uintptr_t)p; }
 __device__ __forceinline__ cptr_u32 as_const(const uint32_t *p) { return (cptr_u32)(uintptr_t)p; }
 
-// Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous range of logical
-// work items so that the row tiles of one (sample, head) share an L2.
-__device__ __forceinline__ unsigned logical_block(unsigned bid, unsigned grid)
+// Workgroups are handed to the 8 XCDs round-robin (workgroup id mod 8).  Logical work items are dealt to
+// the XCDs in chunks of kXcdChunk consecutive items, so that neighbouring row tiles (which gather largely the
+// same rows) share an L2, while every XCD still gets an even mix of the samples: with whole (sample, head)
+// ranges per XCD, one long document made two XCDs finish well after the others.  The grid is padded to a
+// multiple of 8 * kXcdChunk; padding workgroups get an index >= n_items and leave at once.
+constexpr unsigned kXcdChunk = 32;
+__host__ __device__ __forceinline__ unsigned padded_grid(unsigned n_items, unsigned chunk)
 {
-    if (grid % 8u) return bid;
-    return (bid % 8u) * (grid / 8u) + bid / 8u;
+    return (n_items + 8u * chunk - 1u) / (8u * chunk) * (8u * chunk);
+}
+__device__ __forceinline__ unsigned logical_block(unsigned bid, unsigned chunk)
+{
+    const unsigned x = bid & 7u, k = bid >> 3;
+    return ((k / chunk) * 8u + x) * chunk + k % chunk;
 }
 
 // chunk swizzle of row r: 8 consecutive rows get 8 different values (conflict-free 16-byte reads
