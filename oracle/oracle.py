@@ -343,3 +343,113 @@ def hpe(p, d_model: int) -> np.ndarray:
     if n:
         _load().oracle_hpe(_p(p, ctypes.c_int32), n, L, d_model, _p(out, ctypes.c_double))
     return out[:n]
+
+
+# ---------------------------------------------------------------------------------------------------
+# Decoder cross-attention over a subset of the encoder's positions (Sec. 4.2, FacetSum study: the decoder
+# attends only to the [SEC] anchors, or additionally to the [SENT] anchors, or additionally to the regular
+# tokens).  The subset is the set of non-pad encoder positions whose level is in a given set of levels
+# (bit l of ``level_mask`` <=> level l is visible); every decoder row attends to all of it.  Plain numpy in
+# fp64: the definition (softmax over the visible positions, then the weighted sum of their values), heads and
+# rows at once through einsum.
+
+def cross_select(level_enc, level_mask: int) -> np.ndarray:
+    """Visible encoder positions of one sample, in document order."""
+    lv = _i32(level_enc)
+    vis = np.array([l >= 0 and l < 32 and ((level_mask >> int(l)) & 1) == 1 for l in lv], dtype=bool)
+    return np.flatnonzero(vis).astype(np.int32)
+
+
+def cross_attn_fwd(q, k, v, level_enc, level_mask: int, scale: float):
+    """q [B][H][n_dec][d], k, v [B][H][n_enc][d], level_enc [B][n_enc] -> (o [B][H][n_dec][d], lse [B][H][n_dec]).
+    A sample without visible positions gives o = 0, lse = -inf."""
+    q, k, v = (np.asarray(x, dtype=np.float64) for x in (q, k, v))
+    B, H, nd, d = q.shape
+    o = np.zeros((B, H, nd, d))
+    lse = np.full((B, H, nd), -np.inf)
+    for b in range(B):
+        sel = cross_select(level_enc[b], level_mask)
+        if sel.size == 0:
+            continue
+        s = scale * np.einsum("hic,hjc->hij", q[b], k[b][:, sel])
+        m = s.max(axis=-1, keepdims=True)
+        e = np.exp(s - m)
+        l = e.sum(axis=-1, keepdims=True)
+        lse[b] = (m + np.log(l))[..., 0]
+        o[b] = np.einsum("hij,hjc->hic", e / l, v[b][:, sel])
+    return o, lse
+
+
+def cross_attn_bwd(q, k, v, d_o, level_enc, level_mask: int, scale: float):
+    """Gradients of cross_attn_fwd's o with respect to q, k, v given d_o (rows of k, v that are not visible
+    get zero)."""
+    q, k, v, d_o = (np.asarray(x, dtype=np.float64) for x in (q, k, v, d_o))
+    B = q.shape[0]
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for b in range(B):
+        sel = cross_select(level_enc[b], level_mask)
+        if sel.size == 0:
+            continue
+        ks, vs = k[b][:, sel], v[b][:, sel]
+        s = scale * np.einsum("hic,hjc->hij", q[b], ks)
+        s -= s.max(axis=-1, keepdims=True)
+        p = np.exp(s)
+        p /= p.sum(axis=-1, keepdims=True)
+        o = np.einsum("hij,hjc->hic", p, vs)
+        big_d = (d_o[b] * o).sum(axis=-1, keepdims=True)       # D_i = sum_c dO_ic O_ic
+        dp = np.einsum("hic,hjc->hij", d_o[b], vs)
+        ds = p * (dp - big_d)
+        dq[b] = scale * np.einsum("hij,hjc->hic", ds, ks)
+        dk[b][:, sel] = scale * np.einsum("hij,hic->hjc", ds, q[b])
+        dv[b][:, sel] = np.einsum("hij,hic->hjc", p, d_o[b])
+    return dq, dk, dv
+
+
+def _rect_schedule(row_ok: np.ndarray, keys: np.ndarray, bm: int, bn: int, per_tile_has_rows: bool) -> KeyListSchedule:
+    """Schedule of a mask that is a rectangle: row r (of len(row_ok) rows, tiled by bm) may attend to every
+    key of ``keys`` iff row_ok[r].  Every row tile gets the same list (all keys, bn per entry, the last entry
+    filled with -1); with ``per_tile_has_rows`` a tile without any allowed row gets no entries."""
+    n_rows, wpr = row_ok.shape[0], -(-bn // 32)
+    tr = -(-n_rows // bm)
+    n_ent = -(-keys.shape[0] // bn)
+    rowptr = np.zeros(tr + 1, dtype=np.int32)
+    q_keys, bits, pairs = [], [], []
+    for I in range(tr):
+        ok = np.zeros(bm, dtype=bool)
+        seg = row_ok[I * bm:(I + 1) * bm]
+        ok[:seg.shape[0]] = seg
+        if not (per_tile_has_rows and not ok.any()):
+            for e in range(n_ent):
+                kk = np.full(bn, -1, dtype=np.int32)
+                chunk = keys[e * bn:(e + 1) * bn]
+                kk[:chunk.shape[0]] = chunk
+                w = np.zeros((bm, wpr), dtype=np.uint32)
+                for r in range(bm):
+                    if ok[r]:
+                        for c in range(chunk.shape[0]):
+                            w[r, c >> 5] |= np.uint32(1) << np.uint32(c & 31)
+                q_keys.append(kk)
+                bits.append(w)
+                pairs.append(int(ok.sum()) * chunk.shape[0])
+        rowptr[I + 1] = len(q_keys)
+    E = len(q_keys)
+    q_keys = np.array(q_keys, dtype=np.int32).reshape(E, bn)
+    bits = np.array(bits, dtype=np.uint32).reshape(E, bm, wpr)
+    pairs = np.array(pairs, dtype=np.int32).reshape(E)
+    q_sub = _sub_summary(bits, bm, bn) if (bm % 32 == 0 and bn % 32 == 0) else np.zeros(E, np.uint32)
+    return KeyListSchedule(bm=bm, bn=bn, kperm=np.zeros(0, np.int32), q_rowptr=rowptr, q_keys=q_keys, bits=bits,
+                           pairs=pairs, q_sub=q_sub, nnz=int(pairs.sum()))
+
+
+def cross_schedule(level_enc, n_dec: int, level_mask: int, bm: int, bn: int):
+    """(forward schedule, transposed schedule) of one sample's cross-attention mask.  Forward: rows are the
+    decoder positions, every row tile lists the visible encoder positions in document order.  Transposed
+    (for dK, dV): rows are the encoder positions (allowed iff visible), a tile with a visible row lists all
+    decoder positions."""
+    sel = cross_select(level_enc, level_mask)
+    n_enc = _i32(level_enc).shape[0]
+    fwd = _rect_schedule(np.ones(n_dec, dtype=bool), sel, bm, bn, per_tile_has_rows=False)
+    vis = np.zeros(n_enc, dtype=bool)
+    vis[sel] = True
+    tr_ = _rect_schedule(vis, np.arange(n_dec, dtype=np.int32), bm, bn, per_tile_has_rows=True)
+    return fwd, tr_

@@ -99,7 +99,7 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
 
     const int lane = threadIdx.x & 63;
     const int qn = lane & 31;
-    const size_t base = (size_t)bh * s.n_pos * D;
+    const size_t base = (size_t)bh * s.n_pos * D, kv_base = (size_t)bh * s.n_kv * D;
     const float scale_log2 = scale * LOG2E;
 
     const size_t row = (size_t)b * s.tr + I;
@@ -113,8 +113,8 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
     pipe.wave = wave;
     pipe.lane = lane;
     pipe.keys = s.q_keys + (size_t)t0 * BN;
-    pipe.a = k + base;
-    pipe.b = v + base;
+    pipe.a = k + kv_base;
+    pipe.b = v + kv_base;
     pipe.aux0 = pipe.aux1 = nullptr;
     const int qrow = I * BM + wave * 32 + qn;
     const RowLane rl = row_lane(lane);
@@ -213,7 +213,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
 
     const int lane = threadIdx.x & 63;
     const int hf = lane >> 5;
-    const size_t base = (size_t)bh * s.n_pos * D;
+    const size_t base = (size_t)bh * s.n_pos * D, q_base = (size_t)bh * s.n_kv * D;  // rows are keys here
     const float scale_log2 = scale * LOG2E;
 
     const size_t row = (size_t)b * s.tr + I;
@@ -227,10 +227,10 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     pipe.wave = wave;
     pipe.lane = lane;
     pipe.keys = s.q_keys + (size_t)t0 * BN;
-    pipe.a = q + base;
-    pipe.b = d_o + base;
-    pipe.aux0 = lse + (size_t)bh * s.n_pos;
-    pipe.aux1 = delta + (size_t)bh * s.n_pos;
+    pipe.a = q + q_base;
+    pipe.b = d_o + q_base;
+    pipe.aux0 = lse + (size_t)bh * s.n_kv;
+    pipe.aux1 = delta + (size_t)bh * s.n_kv;
     const RowLane rl = row_lane(lane);
     const TrLane tl = tr_lane(lane);
 
@@ -332,14 +332,28 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES) void k_bwd_bf16(
     constexpr int SMEM = PQ::SMEM_BYTES > PK::SMEM_BYTES ? PQ::SMEM_BYTES : PK::SMEM_BYTES;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    // the two roles tile different tensors (the same ones for self-attention): pairs (2t, 2t+1) as far as both
+    // have a tile t, the rest of the longer one behind them
     const unsigned lb2 = logical_block(blockIdx.x, 2 * kXcdChunk);
-    if (lb2 >= 2u * s.batch * heads * s.tr) return;  // padding of the grid
-    const unsigned lb = lb2 >> 1;
-    const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
-    if (lb2 & 1u)
+    const unsigned nq = (unsigned)s.batch * heads * s.tr, nk = (unsigned)s_tr.batch * heads * s_tr.tr;
+    const unsigned common = nq < nk ? nq : nk;
+    if (lb2 >= nq + nk) return;  // padding of the grid
+    bool keys_role;
+    unsigned lb;
+    if (lb2 < 2u * common) {
+        keys_role = lb2 & 1u;
+        lb = lb2 >> 1;
+    } else {
+        keys_role = nk > nq;
+        lb = lb2 - common;
+    }
+    if (keys_role) {
+        const int I = lb % s_tr.tr, bh = lb / s_tr.tr, b = bh / heads;
         dkv_role<D, G>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
-    else
+    } else {
+        const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
         dq_role<D, G>(smem, s, q, k, v, lse, d_o, delta, dq, wave, I, bh, b, scale);
+    }
 }
 
 }  // namespace
@@ -361,7 +375,7 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
     }
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_bf16_d64" : "hdt_bwd_bf16_d128", st);
-        dim3 grid(padded_grid((unsigned)((size_t)s.batch * heads * s.tr * 2), 2 * kXcdChunk)), block(G::THREADS);
+        dim3 grid(padded_grid((unsigned)((size_t)s.batch * heads * (s.tr + s_tr.tr)), 2 * kXcdChunk)), block(G::THREADS);
         if (head_dim == 64)
             hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
                                (__bf16 *)dk, (__bf16 *)dv, heads, scale);

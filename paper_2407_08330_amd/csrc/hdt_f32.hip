@@ -17,7 +17,7 @@ __global__ __launch_bounds__(128) void k_fwd_f32(HdtSchedule s, const float *__r
     if (r >= s.bm) return;
     const int i = I * s.bm + r;
     if (i >= s.n_pos) return;
-    const size_t base = (size_t)bh * s.n_pos * D;
+    const size_t base = (size_t)bh * s.n_pos * D, kv_base = (size_t)bh * s.n_kv * D;
     const float *qi = q + base + (size_t)i * D;
     float acc[D];
     for (int c = 0; c < D; c++) acc[c] = 0.f;
@@ -29,8 +29,8 @@ __global__ __launch_bounds__(128) void k_fwd_f32(HdtSchedule s, const float *__r
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
             const int pos = s.q_keys[(size_t)t * s.bn + c];
             if (pos < 0) continue;
-            const float *kj = k + base + (size_t)pos * D;
-            const float *vj = v + base + (size_t)pos * D;
+            const float *kj = k + kv_base + (size_t)pos * D;
+            const float *vj = v + kv_base + (size_t)pos * D;
             float sc = 0.f;
             for (int e = 0; e < D; e++) sc += qi[e] * kj[e];
             sc *= scale;
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     if (r >= s.bm) return;
     const int i = I * s.bm + r;
     if (i >= s.n_pos) return;
-    const size_t base = (size_t)bh * s.n_pos * D;
+    const size_t base = (size_t)bh * s.n_pos * D, kv_base = (size_t)bh * s.n_kv * D;
     const float *qi = q + base + (size_t)i * D;
     const float *doi = d_o + base + (size_t)i * D;
     const float *oi = o + base + (size_t)i * D;
@@ -76,8 +76,8 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
             const int pos = s.q_keys[(size_t)t * s.bn + c];
             if (pos < 0) continue;
-            const float *kj = k + base + (size_t)pos * D;
-            const float *vj = v + base + (size_t)pos * D;
+            const float *kj = k + kv_base + (size_t)pos * D;
+            const float *vj = v + kv_base + (size_t)pos * D;
             float sc = 0.f, dp = 0.f;
             for (int e = 0; e < D; e++) {
                 sc += qi[e] * kj[e];
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
     if (r >= s.bm) return;
     const int j = I * s.bm + r;  // key position
     if (j >= s.n_pos) return;
-    const size_t base = (size_t)bh * s.n_pos * D;
+    const size_t base = (size_t)bh * s.n_pos * D, q_base = (size_t)bh * s.n_kv * D;  // rows are keys here
     const float *kj = k + base + (size_t)j * D;
     const float *vj = v + base + (size_t)j * D;
     float ak[D], av[D];
@@ -119,15 +119,15 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
             if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
             const int i = s.q_keys[(size_t)t * s.bn + c];  // query position
             if (i < 0) continue;
-            const float *qi = q + base + (size_t)i * D;
-            const float *doi = d_o + base + (size_t)i * D;
+            const float *qi = q + q_base + (size_t)i * D;
+            const float *doi = d_o + q_base + (size_t)i * D;
             float sc = 0.f, dp = 0.f;
             for (int e = 0; e < D; e++) {
                 sc += qi[e] * kj[e];
                 dp += doi[e] * vj[e];
             }
-            const float p = expf(sc * scale - lse[(size_t)bh * s.n_pos + i]);
-            const float ds = p * (dp - delta[(size_t)bh * s.n_pos + i]) * scale;
+            const float p = expf(sc * scale - lse[(size_t)bh * s.n_kv + i]);
+            const float ds = p * (dp - delta[(size_t)bh * s.n_kv + i]) * scale;
             for (int e = 0; e < D; e++) {
                 av[e] += p * doi[e];
                 ak[e] += ds * qi[e];
@@ -163,7 +163,7 @@ hdt_status_t hdt_launch_bwd_f32(const HdtSchedule &s, const HdtSchedule &st_, co
                                 float *dv, int heads, int head_dim, float scale, float *delta, hipStream_t st)
 {
     if ((int64_t)s.batch * heads > 65535) return hdt_fail(HDT_ERR_SHAPE, "fp32 path: batch*heads > 65535");
-    dim3 gq(s.tr, s.batch * heads), gk(s.tr, s.batch * heads), block(128);
+    dim3 gq(s.tr, s.batch * heads), gk(st_.tr, s.batch * heads), block(128);
     {
         HdtTimer t("hdt_bwd_dq_f32", st);
         if (head_dim == 64)

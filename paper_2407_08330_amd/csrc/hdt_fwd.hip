@@ -135,7 +135,7 @@ __global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const unsigned lb = logical_block(blockIdx.x, kXcdChunk);
     if (lb >= (unsigned)s.batch * heads * s.tr) return;  // padding of the grid
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
-    const size_t base = (size_t)bh * s.n_pos * D;
+    const size_t base = (size_t)bh * s.n_pos * D, kv_base = (size_t)bh * s.n_kv * D;
 
     const size_t row = (size_t)b * s.tr + I;
     const cptr_i32 range = as_const(s.q_range);
@@ -148,8 +148,8 @@ __global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     pipe.wave = wave;
     pipe.lane = lane;
     pipe.keys = s.q_keys + (size_t)t0 * BN;
-    pipe.a = k + base;
-    pipe.b = v + base;
+    pipe.a = k + kv_base;
+    pipe.b = v + kv_base;
     pipe.aux0 = pipe.aux1 = nullptr;
     // this lane's query row; rows past n_pos are computed on a clamped copy and never stored
     const int qrow = I * BM + wave * 32 + qn;

@@ -21,7 +21,8 @@
 // in pre-order); it keeps its place with an all-zero summary (q_sub == 0) and all-zero bitmaps, which
 // makes every kernel skip it, and hdt_layout_export filters it out.
 struct HdtSchedule {
-    int32_t batch, n_pos;
+    int32_t batch, n_pos;  // n_pos: rows per sample of the row-side tensors (the ones tiled by bm)
+    int32_t n_kv;          // rows per sample of the gathered tensors (= n_pos for self-attention)
     int32_t bm, bn;        // tile shape (query rows x key slots)
     int32_t tr, tc;        // tiles per sample along queries / keys
     int32_t n_slots;       // tc * bn: length of one sample's padded key order

@@ -1052,6 +1052,7 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     memset(&s, 0, sizeof(s));
     s.batch = batch;
     s.n_pos = n_pos;
+    s.n_kv = n_pos;
     s.bm = bm;
     s.bn = bn;
     s.wpr = bn / 32;
