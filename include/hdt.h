@@ -86,6 +86,11 @@ typedef struct {
     int64_t n_tiles;          /* surviving tiles (list entries), summed over the batch */
     int64_t nnz;              /* allowed (query, key) pairs, summed over the batch   */
     int64_t device_bytes;     /* device memory held by the layout                    */
+    int32_t n_kv;             /* rows per sample of the gathered tensors (K, V in the forward): n_pos for a
+                                 self-attention layout, the encoder length for a cross-attention layout */
+    int32_t cross;            /* 1: built by hdt_build_cross_layout                  */
+    uint32_t cross_level_mask;
+    int32_t reserved_;
 } hdt_layout_info_t;
 
 /*
@@ -133,6 +138,42 @@ typedef struct {
  */
 hdt_status_t hdt_build_layout(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
                               const hdt_layout_opts_t *opts, void *stream, hdt_layout_t **out);
+
+/*
+ * hdt_build_cross_layout -- schedule of decoder cross-attention over a subset of the encoder's positions.
+ * (Sec. 4.2, the summarisation study: the decoder of the encoder-decoder model cross-attends only to the
+ * [SEC] anchors, or additionally to the [SENT] anchors, or additionally to the regular tokens.)
+ *
+ *   d_level_enc [batch][n_enc] int32, device: hierarchy level of each encoder position (HDT_LEVEL_PAD for pads)
+ *   n_dec       decoder rows per sample
+ *   level_mask  bit l set <=> encoder positions of level l are visible (e.g. 1<<1 for [SEC] only,
+ *               (1<<1)|(1<<2) with [SENT], |(1<<3) with the tokens; whether [DOC], level 0, joins is the
+ *               caller's choice); pads and levels outside [0, 32) are never visible
+ *   opts        host, may be NULL; only tile_m / tile_n are honoured, any other option set is UNSUPPORTED
+ *
+ * Every decoder row attends to every visible position of its sample.  The layout is then used with the
+ * ordinary attention calls, whose tensors take two lengths: q, o, d_o, dq are [batch][heads][n_dec][d] and
+ * lse [batch][heads][n_dec]; k, v, dk, dv are [batch][heads][n_enc][d].  K and V rows of the visible
+ * positions are gathered by the attention kernels themselves (no compacted copy is made); dk and dv of
+ * invisible positions are written as zeros; a sample without visible positions gives O = 0, LSE = -inf.
+ * hdt_layout_info reports n_pos = n_dec and n_kv = n_enc.  The layout holds a second schedule for the
+ * backward pass (rows = encoder positions), reachable through hdt_layout_transposed.
+ *
+ * The build is asynchronous (kernels on `stream`, no read-back); device memory as for hdt_build_layout,
+ * sized for the case that every position is visible.
+ * batch == 0 gives an empty layout on which the attention calls are no-ops.
+ * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (a length of 0 or > 2^19, too many
+ * entries), HDT_ERR_UNSUPPORTED (tile shape, other options), HDT_ERR_OOM, HDT_ERR_HIP.  On error *out is NULL.
+ */
+hdt_status_t hdt_build_cross_layout(const int32_t *d_level_enc, int32_t batch, int32_t n_enc, int32_t n_dec,
+                                    uint32_t level_mask, const hdt_layout_opts_t *opts, void *stream,
+                                    hdt_layout_t **out);
+
+/* The schedule of the transposed mask that a layout holds for the backward pass (directed masks of
+ * hdt_build_layout, every cross-attention layout), as a borrowed handle for hdt_layout_info /
+ * hdt_layout_sample_info / hdt_layout_export: *out is NULL if the layout has none (symmetric mask); it is
+ * owned by `layout` and dies with it. */
+hdt_status_t hdt_layout_transposed(const hdt_layout_t *layout, const hdt_layout_t **out);
 
 /* Sizes of a layout (host struct).  n_tiles and nnz are read back from the device by the first call
  * of hdt_layout_info / hdt_layout_sample_info / hdt_layout_export on a layout, which synchronises

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     hdt_attn_bwd,
     hdt_attn_bwd_workspace_bytes,
     hdt_attn_fwd,
+    hdt_build_cross_layout,
     hdt_build_layout,
     hdt_hpe_add,
     hdt_hpe_table,

@@ -18,7 +18,7 @@ HDT_BF16, HDT_F32 = 0, 1
 HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 
 EXPORTED_SYMBOLS = [
-    "hdt_build_layout", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
+    "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
     "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
     "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
@@ -40,7 +40,9 @@ class _Opts(ctypes.Structure):
 class _Info(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("n_pos", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("q_tiles", ctypes.c_int32), ("k_tiles", ctypes.c_int32),
-                ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32), ("n_tiles", ctypes.c_int64),
+                ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64), ("n_kv", ctypes.c_int32),
+                ("cross", ctypes.c_int32), ("cross_level_mask", ctypes.c_uint32), ("reserved_", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -62,6 +64,10 @@ def load_library():
     vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
     lib.hdt_build_layout.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_Opts), vp, ctypes.POINTER(vp)]
     lib.hdt_build_layout.restype = ctypes.c_int
+    lib.hdt_build_cross_layout.argtypes = [vp, i32, i32, i32, ctypes.c_uint32, ctypes.POINTER(_Opts), vp, ctypes.POINTER(vp)]
+    lib.hdt_build_cross_layout.restype = ctypes.c_int
+    lib.hdt_layout_transposed.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.hdt_layout_transposed.restype = ctypes.c_int
     lib.hdt_layout_info.argtypes = [vp, ctypes.POINTER(_Info)]
     lib.hdt_layout_info.restype = ctypes.c_int
     lib.hdt_layout_sample_info.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -122,9 +128,17 @@ def _ptr(t):
 class Layout:
     """Owns an ``hdt_layout_t``."""
 
-    def __init__(self, handle: int, batch: int, n_pos: int):
+    def __init__(self, handle: int, batch: int, n_pos: int, n_kv: Optional[int] = None, owner=None):
         self._h = ctypes.c_void_p(handle)
         self.batch, self.n_pos = int(batch), int(n_pos)
+        self.n_kv = int(n_pos if n_kv is None else n_kv)   # rows of the gathered tensors (cross-attention: encoder)
+        self._owner = owner                                 # a borrowed handle keeps its owner alive
+
+    def transposed(self) -> Optional["Layout"]:
+        """The schedule of the transposed mask held for the backward pass (borrowed), or None."""
+        h = ctypes.c_void_p(0)
+        _check(load_library().hdt_layout_transposed(self._h, ctypes.byref(h)))
+        return Layout(h.value, self.batch, self.n_kv, self.n_pos, owner=self) if h.value else None
 
     @property
     def handle(self):
@@ -146,26 +160,30 @@ class Layout:
         T, _ = self.sample_info(sample)
         n, tr, tc, bm, bn = inf["n_pos"], inf["q_tiles"], inf["k_tiles"], inf["tile_m"], inf["tile_n"]
         out = dict(
-            kperm=np.zeros(max(n, 1), np.int32), q_rowptr=np.zeros(tr + 1, np.int32),
+            q_rowptr=np.zeros(tr + 1, np.int32),
             q_cols=np.zeros(max(T, 1), np.int32), q_keys=np.zeros((max(T, 1), bn), np.int32),
             q_sub=np.zeros(max(T, 1), np.uint32), bits=np.zeros((max(T, 1), bm, bn // 32), np.uint32))
+        if not inf["cross"]:  # a cross-attention layout has no key order
+            out["kperm"] = np.zeros(max(n, 1), np.int32)
         if inf["windowed"]:  # only a windowed layout has a transpose by key window
             out.update(k_colptr=np.zeros(tc + 1, np.int32), k_rows=np.zeros(max(T, 1), np.int32),
                        k_tile=np.zeros(max(T, 1), np.int32))
         p = {k: ctypes.c_void_p(v.ctypes.data) for k, v in out.items()}
-        _check(load_library().hdt_layout_export(self._h, sample, p["kperm"], p["q_rowptr"], p["q_cols"], p["q_keys"],
+        _check(load_library().hdt_layout_export(self._h, sample, p.get("kperm"), p["q_rowptr"], p["q_cols"], p["q_keys"],
                                                 p["q_sub"], p["bits"], p.get("k_colptr"), p.get("k_rows"),
                                                 p.get("k_tile"), max(T, 1)))
-        out["kperm"] = out["kperm"][:n]
+        if "kperm" in out:
+            out["kperm"] = out["kperm"][:n]
         for key in ("q_cols", "q_keys", "q_sub", "bits", "k_rows", "k_tile"):
             if key in out:
                 out[key] = out[key][:T]
         return out
 
     def destroy(self):
-        if self._h is not None and self._h.value:
+        if self._owner is None and self._h is not None and self._h.value:
             _check(load_library().hdt_layout_destroy(self._h))
         self._h = None
+        self._owner = None
 
     def __del__(self):
         try:
@@ -192,6 +210,24 @@ def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dens
     return Layout(h.value, B, N)
 
 
+def hdt_build_cross_layout(level_enc, n_dec: int, level_mask: int, tile_m: int = 0, tile_n: int = 0,
+                           stream=None) -> Layout:
+    """level_enc: int32 device tensor [batch][n_enc]; decoder rows attend to the encoder positions whose
+    level has its bit set in ``level_mask``.  The layout takes q, o of n_dec rows and k, v of n_enc rows."""
+    import torch
+    if level_enc.dtype != torch.int32 or level_enc.dim() != 2:
+        raise TypeError("level_enc must be int32 [batch][n_enc]")
+    if not (level_enc.is_cuda and level_enc.is_contiguous()):
+        raise ValueError("level_enc must be a contiguous device tensor")
+    opts = _Opts(tile_m, tile_n, 0, 0, 0, 0)
+    h = ctypes.c_void_p(0)
+    B, n_enc = level_enc.shape
+    _check(load_library().hdt_build_cross_layout(_ptr(level_enc) if B * n_enc else None, B, n_enc, int(n_dec),
+                                                 int(level_mask), ctypes.byref(opts), _stream_ptr(stream),
+                                                 ctypes.byref(h)))
+    return Layout(h.value, B, int(n_dec), n_enc)
+
+
 def _dtype_code(t):
     import torch
     if t.dtype == torch.bfloat16:
@@ -210,12 +246,14 @@ def _check_tensors(ts, shape=None):
 
 
 def hdt_attn_fwd(layout: Layout, q, k, v, softmax_scale: float, o=None, lse=None, stream=None):
-    """q, k, v: [batch][heads][n_pos][head_dim] device tensors (bf16 or fp32).  Returns (o, lse)."""
+    """q: [batch][heads][n_pos][head_dim], k, v: [batch][heads][n_kv][head_dim] device tensors (bf16 or fp32;
+    n_kv = n_pos unless the layout is a cross-attention layout).  Returns (o, lse)."""
     import torch
-    _check_tensors((q, k, v), q.shape)
     B, H, N, D = q.shape
-    if (B, N) != (layout.batch, layout.n_pos):
-        raise ValueError("q shape does not match the layout")
+    _check_tensors((q,), q.shape)
+    _check_tensors((k, v), (B, H, layout.n_kv, D))
+    if (B, N) != (layout.batch, layout.n_pos) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("tensor shapes or dtypes do not match the layout")
     if o is None:
         o = torch.empty_like(q)
     if lse is None:
@@ -231,15 +269,16 @@ def hdt_attn_bwd_workspace_bytes(layout: Layout, heads: int, head_dim: int, dtyp
 
 def hdt_attn_bwd(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq=None, dk=None, dv=None,
                  workspace=None, stream=None):
-    """Returns (dq, dk, dv)."""
+    """Returns (dq, dk, dv); dq like q, dk and dv like k."""
     import torch
-    _check_tensors((q, k, v, o, d_o), q.shape)
     B, H, N, D = q.shape
-    if (B, N) != (layout.batch, layout.n_pos):
-        raise ValueError("q shape does not match the layout")
+    _check_tensors((q, o, d_o), q.shape)
+    _check_tensors((k, v), (B, H, layout.n_kv, D))
+    if (B, N) != (layout.batch, layout.n_pos) or any(t.dtype != q.dtype for t in (k, v, o, d_o)):
+        raise ValueError("tensor shapes or dtypes do not match the layout")
     dq = torch.empty_like(q) if dq is None else dq
-    dk = torch.empty_like(q) if dk is None else dk
-    dv = torch.empty_like(q) if dv is None else dv
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(k) if dv is None else dv
     need = hdt_attn_bwd_workspace_bytes(layout, H, D, _dtype_code(q))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)

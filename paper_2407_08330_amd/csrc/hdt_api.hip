@@ -142,6 +142,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(c
         info->nnz += l->h_stats[2 * b + 1];
     }
     info->device_bytes = l->device_bytes;
+    info->n_kv = l->s.n_kv;
+    info->cross = l->cross;
+    info->cross_level_mask = l->cross_level_mask;
     return HDT_OK;
 }
 
@@ -168,6 +171,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
         return hdt_fail(HDT_ERR_SHAPE, "hdt_layout_export: sample %d outside [0, %d)", sample, s.batch);
     if (hdt_status_t st = hdt_layout_stats(layout)) return st;
     const int64_t T = layout->h_stats[2 * (size_t)sample];
+    if (kperm && layout->cross)
+        return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_layout_export: a cross-attention layout has no key order");
     if ((k_colptr || k_rows || k_tile) && !layout->windowed)
         return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_layout_export: only a windowed layout has a transpose by key window");
     const bool want_tiles = q_cols || q_keys || q_sub || bits || k_rows || k_tile;
@@ -236,6 +241,14 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
             if (k_tile) k_tile[e] = (int32_t)t;
         }
     }
+    return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_transposed(const hdt_layout_t *layout,
+                                                                                      const hdt_layout_t **out)
+{
+    if (!hdt_layout_ok(layout) || !out) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_transposed: NULL or invalid layout");
+    *out = layout->transposed;
     return HDT_OK;
 }
 
@@ -314,6 +327,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     hdt_status_t st = check_attn_args("hdt_attn_bwd", layout, heads, head_dim, dt, scale);
     if (st != HDT_OK) return st;
     const HdtSchedule &s = layout->s;
+    const HdtSchedule &s_tr = layout->transposed ? layout->transposed->s : s;
     if (s.batch == 0 || s.n_pos == 0 || heads == 0) return HDT_OK;
     if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv)
         return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: NULL tensor pointer");
@@ -331,10 +345,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if (!workspace || workspace_bytes < need)
         return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: workspace of %zu bytes needed, %zu given", need,
                         workspace_bytes);
-    if ((int64_t)s.batch * heads * (s.tr > s.tc ? s.tr : s.tc) * 2 > 0x7ffff000LL)
-        return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: 2*batch*heads*tiles exceeds the grid limit");
+    if ((int64_t)s.batch * heads * ((int64_t)s.tr + s_tr.tr) > 0x7ffff000LL)
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
-    const HdtSchedule &s_tr = layout->transposed ? layout->transposed->s : s;
     if (dt == HDT_BF16)
         return hdt_launch_bwd_bf16(s, s_tr, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, (float *)workspace, hs);
     return hdt_launch_bwd_f32(s, s_tr, (const float *)q, (const float *)k, (const float *)v, (const float *)o, lse,

@@ -1,0 +1,348 @@
+// hdt_build_cross_layout: the schedule of decoder cross-attention over a level subset of the encoder's
+// positions (Sec. 4.2, FacetSum study: the decoder attends only to the [SEC] anchors, or additionally to
+// the [SENT] anchors, or additionally to the regular tokens).
+//
+// The mask is a rectangle: every decoder row may attend to every visible encoder position (non-pad, level
+// in the given set).  In the terms of the attention kernels that is a key list per row tile, the same for
+// all row tiles of a sample: the visible positions in document order, tile_n per list entry.  So the
+// "gather of the anchor rows" is the gather the attention kernels do anyway, straight into LDS; no compacted
+// copy of K and V is made.  The backward pass needs the transposed schedule as well: rows are the encoder
+// positions (allowed iff visible), a row tile that holds a visible position lists all decoder rows.
+//
+// Nothing is read back: the list entries of a row tile sit at a fixed stride (room for the longest possible
+// list), the unused ones are marked empty, and a tile's range covers the ones in use.
+#include <string.h>
+
+#include <new>
+
+#include "hdt_internal.h"
+
+namespace {
+
+constexpr int kSelThreads = 1024;
+
+__device__ __forceinline__ bool visible(int level, uint32_t level_mask)
+{
+    return level >= 0 && level < 32 && ((level_mask >> level) & 1u);
+}
+
+// One workgroup per sample: the visible positions in document order (sel) and their number (count).
+__global__ __launch_bounds__(kSelThreads) void k_cross_select(const int32_t *__restrict__ level, int n_enc,
+                                                               uint32_t level_mask, int32_t *__restrict__ sel,
+                                                               int32_t *__restrict__ count)
+{
+    __shared__ int s_wave[kSelThreads / 64];
+    __shared__ int s_base;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t *lv = level + (size_t)b * n_enc;
+    int32_t *out = sel + (size_t)b * n_enc;
+    if (tid == 0) s_base = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < n_enc; i0 += kSelThreads) {
+        const int i = i0 + tid;
+        const bool vis = i < n_enc && visible(lv[i], level_mask);
+        const unsigned long long m = __ballot(vis);
+        if (lane == 0) s_wave[wave] = __popcll(m);
+        __syncthreads();
+        int before = s_base;
+        for (int w = 0; w < wave; w++) before += s_wave[w];
+        if (vis) out[before + __popcll(m & ((1ull << lane) - 1ull))] = i;
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+            for (int w = 0; w < kSelThreads / 64; w++) tot += s_wave[w];
+            s_base += tot;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) count[b] = s_base;
+}
+
+struct CrossArgs {
+    const int32_t *level;  // [B][n_enc]
+    const int32_t *sel;    // [B][n_enc] visible positions
+    const int32_t *count;  // [B]
+    uint32_t level_mask;
+    int n_enc, n_dec, bm, bn;
+    int transposed;  // 0: rows = decoder positions, keys = visible encoder positions; 1: rows = encoder positions
+                     // (allowed iff visible), keys = decoder positions
+    int tr, e_max;   // row tiles per sample, list entries reserved per row tile
+    int32_t *q_range, *c_row, *c_cnt, *q_keys;
+    uint32_t *q_sub, *bits;
+    unsigned long long *bits_rm;
+};
+
+// One wave per reserved list entry (b, I, e): its keys, bitmaps and summary, or the "empty" marks.
+__global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
+{
+    __shared__ uint32_t s_row[4], s_col[4];  // allowed rows / filled key slots of the entry, bit masks
+    const int lane = threadIdx.x;
+    const int e = blockIdx.x % a.e_max, tile = blockIdx.x / a.e_max;  // tile = b * tr + I
+    const int b = tile / a.tr, I = tile % a.tr;
+    const int64_t entry = blockIdx.x;
+    const int n_rows = a.transposed ? a.n_enc : a.n_dec;
+    const int n_keys = a.transposed ? a.n_dec : a.count[b];
+    // rows of the tile
+    bool any_row = false;
+    for (int h = 0; h < 2; h++) {
+        const int r = h * 64 + lane, i = I * a.bm + r;
+        bool ok = r < a.bm && i < n_rows;
+        if (ok && a.transposed) ok = visible(a.level[(size_t)b * a.n_enc + i], a.level_mask);
+        const unsigned long long m = __ballot(ok);
+        if (lane == 0) {
+            s_row[2 * h] = (uint32_t)m;
+            s_row[2 * h + 1] = (uint32_t)(m >> 32);
+        }
+        any_row |= m != 0ull;
+    }
+    const int n_ent = (a.transposed && !any_row) ? 0 : (n_keys + a.bn - 1) / a.bn;
+    if (e == 0 && lane == 0) {
+        a.q_range[2 * tile] = (int32_t)entry;
+        a.q_range[2 * tile + 1] = (int32_t)entry + n_ent;
+    }
+    if (lane == 0) a.c_row[entry] = tile;
+    if (e >= n_ent) {  // reserved, not in use
+        if (lane == 0) {
+            a.c_cnt[entry] = 0;
+            a.q_sub[entry] = 0u;
+        }
+        return;
+    }
+    // key slots
+    for (int h = 0; h < 2; h++) {
+        const int c = h * 64 + lane, idx = e * a.bn + c;
+        const bool ok = c < a.bn && idx < n_keys;
+        if (c < a.bn) a.q_keys[entry * a.bn + c] = ok ? (a.transposed ? idx : a.sel[(size_t)b * a.n_enc + idx]) : -1;
+        const unsigned long long m = __ballot(ok);
+        if (lane == 0) {
+            s_col[2 * h] = (uint32_t)m;
+            s_col[2 * h + 1] = (uint32_t)(m >> 32);
+        }
+    }
+    __syncthreads();
+    const int wpr = a.bn >> 5, nrb = a.bm >> 5, nsub = nrb * wpr;
+    // row-major bitmap
+    for (int w = lane; w < a.bm * wpr; w += 64) {
+        const int r = w / wpr, cw = w % wpr;
+        a.bits[(size_t)entry * a.bm * wpr + w] = ((s_row[r >> 5] >> (r & 31)) & 1u) ? s_col[cw] : 0u;
+    }
+    // lane masks of the MFMA accumulator registers: sub-block (rblk, cblk), register x: bit l <=> row
+    // rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(x/4) + x%4
+    for (int w = lane; w < nsub * 16; w += 64) {
+        const int sb = w >> 4, x = w & 15, rblk = sb / wpr, cblk = sb % wpr;
+        const uint32_t rows = s_row[rblk], cols = s_col[cblk];
+        unsigned long long m = 0;
+        for (int h = 0; h < 2; h++) {
+            const int col = h * 4 + 8 * (x >> 2) + (x & 3);
+            if ((cols >> col) & 1u) m |= (unsigned long long)rows << (32 * h);
+        }
+        a.bits_rm[((size_t)entry * nsub + sb) * 16 + x] = m;
+    }
+    if (lane == 0) {
+        uint32_t any = 0, all = 0;
+        int nr = 0, nc = 0;
+        for (int i = 0; i < 4; i++) {
+            nr += __popc(s_row[i]);
+            nc += __popc(s_col[i]);
+        }
+        for (int rblk = 0; rblk < nrb; rblk++)
+            for (int cblk = 0; cblk < wpr; cblk++) {
+                const int sb = rblk * wpr + cblk;
+                if (s_row[rblk] != 0u && s_col[cblk] != 0u) any |= 1u << sb;
+                if (s_row[rblk] == 0xffffffffu && s_col[cblk] == 0xffffffffu) all |= 1u << sb;
+            }
+        a.c_cnt[entry] = nr * nc;
+        a.q_sub[entry] = any | (all << 16);
+    }
+}
+
+struct CrossBuffers {
+    int32_t *sel, *count, *q_range;  // first arena
+    int32_t *c_row, *c_cnt, *q_keys;  // second arena
+    uint32_t *q_sub, *bits;
+    unsigned long long *bits_rm;
+    size_t bytes1, bytes2;
+};
+
+template <typename T>
+T *carve(char *base, size_t &off, size_t count)
+{
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += (count * sizeof(T) + 255) & ~(size_t)255;
+    return p;
+}
+
+CrossBuffers carve_cross(char *a1, char *a2, int B, int n_enc, int tr, int64_t entries, int bm, int bn, bool with_sel)
+{
+    CrossBuffers c{};
+    size_t o1 = 0, o2 = 0;
+    if (with_sel) {
+        c.sel = carve<int32_t>(a1, o1, (size_t)B * n_enc);
+        c.count = carve<int32_t>(a1, o1, (size_t)B);
+    }
+    c.q_range = carve<int32_t>(a1, o1, (size_t)B * tr * 2);
+    const size_t n = (size_t)entries;
+    c.c_row = carve<int32_t>(a2, o2, n);
+    c.c_cnt = carve<int32_t>(a2, o2, n);
+    c.q_sub = carve<uint32_t>(a2, o2, n);
+    c.q_keys = carve<int32_t>(a2, o2, n * (size_t)bn);
+    c.bits = carve<uint32_t>(a2, o2, n * (size_t)bm * (bn / 32));
+    c.bits_rm = carve<unsigned long long>(a2, o2, n * (size_t)(bm / 32) * (bn / 32) * 16);
+    c.bytes1 = o1;
+    c.bytes2 = o2;
+    return c;
+}
+
+hdt_layout_t *new_layout(int batch, int n_rows, int n_kv, int bm, int bn)
+{
+    hdt_layout_t *L = new (std::nothrow) hdt_layout_t();
+    if (!L) return nullptr;
+    L->magic = HDT_LAYOUT_MAGIC;
+    L->arena = L->arena2 = nullptr;
+    L->arena_bytes = L->arena2_bytes = 0;
+    L->capacity = 0;
+    L->d_cnt = L->d_row = nullptr;
+    L->n_entries = 0;
+    L->stats_ready = false;
+    L->kperm_ready = true;
+    L->no_sort = 0;
+    L->sort_hist = L->sort_counters = nullptr;
+    L->level_copy = L->parent_copy = nullptr;
+    L->force_dense = 0;
+    L->windowed = 0;
+    L->edges = 0;
+    L->cross = 1;
+    L->transposed = nullptr;
+    L->device_bytes = 0;
+    L->device = 0;
+    (void)hipGetDevice(&L->device);
+    HdtSchedule &s = L->s;
+    memset(&s, 0, sizeof(s));
+    s.batch = batch;
+    s.n_pos = n_rows;
+    s.n_kv = n_kv;
+    s.bm = bm;
+    s.bn = bn;
+    s.wpr = bn / 32;
+    s.tr = (n_rows + bm - 1) / bm;
+    s.tc = (n_kv + bn - 1) / bn;
+    s.n_slots = s.tc * bn;
+    L->h_stats.assign((size_t)batch * 2, 0);
+    return L;
+}
+
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_layout(
+    const int32_t *d_level_enc, int32_t batch, int32_t n_enc, int32_t n_dec, uint32_t level_mask,
+    const hdt_layout_opts_t *opts, void *stream, hdt_layout_t **out)
+{
+    if (!out) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_cross_layout: out is NULL");
+    *out = nullptr;
+    if (batch < 0 || n_enc < 0 || n_dec < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_cross_layout: negative size");
+    if (n_enc > (1 << 19) || n_dec > (1 << 19))
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_build_cross_layout: n_enc %d or n_dec %d > 2^19", n_enc, n_dec);
+    int bm = 128, bn = 64;
+    if (opts) {
+        if (opts->tile_m) bm = opts->tile_m;
+        if (opts->tile_n) bn = opts->tile_n;
+        if (opts->force_dense || opts->no_sort || opts->windowed || opts->edges)
+            return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_build_cross_layout: only the tile shape can be chosen");
+    }
+    if (bm < 32 || bm > 128 || bm % 32 || bn < 32 || bn > 128 || bn % 32)
+        return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_build_cross_layout: tile %dx%d (each side: 32, 64, 96 or 128)", bm, bn);
+    if (batch > 0 && (n_enc == 0 || n_dec == 0))
+        return hdt_fail(HDT_ERR_SHAPE, "hdt_build_cross_layout: n_enc = %d, n_dec = %d (both sides need rows)", n_enc, n_dec);
+    const bool empty = batch == 0;
+    if (!empty && !d_level_enc) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_cross_layout: NULL level array");
+
+    hdt_layout_t *L = new_layout(batch, n_dec, n_enc, bm, bn);
+    hdt_layout_t *T = L ? new_layout(batch, n_enc, n_dec, bm, bn) : nullptr;
+    if (!L || !T) {
+        delete L;
+        return hdt_fail(HDT_ERR_OOM, "hdt_build_cross_layout: host allocation failed");
+    }
+    L->transposed = T;
+    L->cross_level_mask = T->cross_level_mask = level_mask;
+    hdt_status_t status = HDT_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int e_fwd = (n_enc + bn - 1) / bn, e_tr = (n_dec + bn - 1) / bn;
+    const int64_t ent_fwd = (int64_t)batch * L->s.tr * e_fwd, ent_tr = (int64_t)batch * T->s.tr * e_tr;
+    if (ent_fwd >= (1LL << 31) || ent_tr >= (1LL << 31)) {
+        status = hdt_fail(HDT_ERR_SHAPE, "hdt_build_cross_layout: %lld list entries", (long long)(ent_fwd > ent_tr ? ent_fwd : ent_tr));
+        goto fail;
+    }
+#define CROSS_TRY(expr)                                                                                \
+    do {                                                                                               \
+        hipError_t _e = (expr);                                                                        \
+        if (_e != hipSuccess) {                                                                        \
+            status = hdt_fail(_e == hipErrorOutOfMemory ? HDT_ERR_OOM : HDT_ERR_HIP, "%s: %s", #expr, \
+                              hipGetErrorString(_e));                                                  \
+            goto fail;                                                                                 \
+        }                                                                                              \
+    } while (0)
+    {
+        CrossBuffers f = carve_cross(nullptr, nullptr, batch, n_enc, L->s.tr, ent_fwd, bm, bn, true);
+        CrossBuffers t = carve_cross(nullptr, nullptr, batch, n_enc, T->s.tr, ent_tr, bm, bn, false);
+        CROSS_TRY(hdt_pool_alloc(&L->arena, f.bytes1 + 256, &L->arena_bytes));
+        CROSS_TRY(hdt_pool_alloc(&L->arena2, f.bytes2 + 256, &L->arena2_bytes));
+        CROSS_TRY(hdt_pool_alloc(&T->arena, t.bytes1 + 256, &T->arena_bytes));
+        CROSS_TRY(hdt_pool_alloc(&T->arena2, t.bytes2 + 256, &T->arena2_bytes));
+        f = carve_cross((char *)L->arena, (char *)L->arena2, batch, n_enc, L->s.tr, ent_fwd, bm, bn, true);
+        t = carve_cross((char *)T->arena, (char *)T->arena2, batch, n_enc, T->s.tr, ent_tr, bm, bn, false);
+        if (!empty) {
+            {
+                HdtTimer tm("hdt_cross_select", st);
+                hipLaunchKernelGGL(k_cross_select, dim3((unsigned)batch), dim3(kSelThreads), 0, st, d_level_enc, n_enc,
+                                   level_mask, f.sel, f.count);
+            }
+            CrossArgs a{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 0, L->s.tr, e_fwd,
+                        f.q_range, f.c_row, f.c_cnt, f.q_keys, f.q_sub, f.bits, f.bits_rm};
+            {
+                HdtTimer tm("hdt_cross_entries", st);
+                hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_fwd), dim3(64), 0, st, a);
+            }
+            CrossArgs at{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 1, T->s.tr, e_tr,
+                         t.q_range, t.c_row, t.c_cnt, t.q_keys, t.q_sub, t.bits, t.bits_rm};
+            {
+                HdtTimer tm("hdt_cross_entries_transposed", st);
+                hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_tr), dim3(64), 0, st, at);
+            }
+            CROSS_TRY(hipGetLastError());
+        }
+        struct {
+            hdt_layout_t *l;
+            CrossBuffers *c;
+            int64_t n;
+        } both[2] = {{L, &f, empty ? 0 : ent_fwd}, {T, &t, empty ? 0 : ent_tr}};
+        for (auto &x : both) {
+            HdtSchedule &s = x.l->s;
+            s.q_range = x.c->q_range;
+            s.q_keys = x.c->q_keys;
+            s.q_sub = x.c->q_sub;
+            s.bits = x.c->bits;
+            s.bits_rm = x.c->bits_rm;
+            s.q_cols = nullptr;
+            s.kperm = nullptr;
+            x.l->d_cnt = x.c->c_cnt;
+            x.l->d_row = x.c->c_row;
+            x.l->n_entries = x.n;
+            x.l->capacity = x.n;
+            x.l->device_bytes = (int64_t)(x.l->arena_bytes + x.l->arena2_bytes);
+            if (x.n == 0) x.l->stats_ready = true;
+        }
+        L->device_bytes += T->device_bytes;
+        *out = L;
+        return HDT_OK;
+    }
+fail:
+    hdt_layout_release(T);
+    T->magic = 0;
+    delete T;
+    L->transposed = nullptr;
+    hdt_layout_release(L);
+    L->magic = 0;
+    delete L;
+    return status;
+#undef CROSS_TRY
+}

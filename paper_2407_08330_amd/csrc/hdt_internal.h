@@ -45,6 +45,8 @@ struct hdt_layout {
     int32_t force_dense; // every candidate counts as a tile, empty or not
     int32_t windowed;    // key tiles are windows of the key order (else per-query-tile key lists)
     int32_t edges;       // OR of HDT_EDGE_*
+    int32_t cross;       // 1: a cross-attention layout (rows and gathered tensors differ; hdt_cross.hip)
+    uint32_t cross_level_mask;
     // directed masks (edges without up/down symmetry): the schedule of the transposed mask (rows = keys,
     // list entries = the queries attending to them), owned by this layout; NULL for symmetric masks
     hdt_layout *transposed;
@@ -82,6 +84,8 @@ bool hdt_layout_ok(const hdt_layout_t *l);
 hdt_status_t hdt_layout_ensure_kperm(const hdt_layout_t *l);  // sorts s.kperm if the build did not (waits for the device) (hdt_layout.hip)
 hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (waits for the device) (hdt_layout.hip)
 void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
+// device buffer from the cache of destroyed layouts' buffers, or a new one; *got = its real size (hdt_layout.hip)
+hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got);
 
 // --- per-kernel timing (hdt_api.hip) ---
 struct HdtTimer {  // brackets one kernel launch with events when timing is enabled

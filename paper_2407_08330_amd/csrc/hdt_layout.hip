@@ -893,6 +893,8 @@ bool wait_for_report(const unsigned long long *slot, uint32_t ticket, unsigned l
 
 }  // namespace
 
+hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got) { return pool_alloc(out, bytes, got); }
+
 void hdt_layout_release(hdt_layout_t *L)
 {
     pool_free(L->arena, L->arena_bytes, L->device);
@@ -1045,6 +1047,8 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     L->force_dense = force_dense;
     L->windowed = windowed;
     L->edges = edges;
+    L->cross = 0;
+    L->cross_level_mask = 0;
     L->transposed = nullptr;
     L->device_bytes = 0;
     L->device = 0;
