@@ -290,6 +290,45 @@ def main() -> int:
                       "add_gbs": None if not add_us else round(add_bytes / (add_us * 1e-6) / 1e9, 1),
                       "add_frac_of_hbm_peak": None if not add_us else round(add_bytes / (add_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    if not args.no_kernel_timing:
+        # decoder cross-attention over level subsets of the same encoder batch (not part of `value`): 512
+        # decoder rows per sample attending to the [SEC] anchors, + [SENT] anchors, + tokens
+        n_dec = 512
+        qd = torch.randn((B, H, n_dec, D), device=dev).to(torch.bfloat16)
+        dod = torch.randn((B, H, n_dec, D), device=dev).to(torch.bfloat16)
+        kt, vt = sets[0][0][1], sets[0][0][2]
+        dkc, dvc = torch.empty_like(kt), torch.empty_like(kt)
+        cross = {}
+        for name, mask in (("sec", 2), ("sec+sent", 6), ("sec+sent+tokens", 14)):
+            lay_c = hdt.hdt_build_cross_layout(level, n_dec, mask)
+            ws_c = torch.empty(max(16, hdt.hdt_attn_bwd_workspace_bytes(lay_c, H, D, 0)), dtype=torch.uint8, device=dev)
+            oc, lc = hdt.hdt_attn_fwd(lay_c, qd, kt, vt, scale)
+            dqc = torch.empty_like(qd)
+            hdt.hdt_attn_bwd(lay_c, qd, kt, vt, oc, lc, dod, scale, dq=dqc, dk=dkc, dv=dvc, workspace=ws_c)
+            torch.cuda.synchronize()
+            hdt.hdt_timing_enable(True)
+            hdt.hdt_timing_reset()
+            for _ in range(20):
+                tmp = hdt.hdt_build_cross_layout(level, n_dec, mask)
+                tmp.destroy()
+                hdt.hdt_attn_fwd(lay_c, qd, kt, vt, scale, o=oc, lse=lc)
+                hdt.hdt_attn_bwd(lay_c, qd, kt, vt, oc, lc, dod, scale, dq=dqc, dk=dkc, dv=dvc, workspace=ws_c)
+            torch.cuda.synchronize()
+            tk = {n: round(1e3 * ms / c, 2) for n, (c, ms) in hdt.hdt_timing_read().items()}
+            hdt.hdt_timing_enable(False)
+            visible = lay_c.info()["nnz"] // n_dec
+            row = 2 * D
+            fwd_bytes = H * (B * n_dec * (2 * row + 4) + visible * 2 * row)          # Q, O, LSE; visible K, V rows
+            bwd_bytes = H * (B * n_dec * (3 * row + 8) + visible * 2 * row + B * N * 2 * row)  # Q, dO, dQ; K, V; all of dK, dV
+            fwd_us = tk.get(f"hdt_fwd_bf16_d{D}")
+            bwd_us = tk.get(f"hdt_bwd_bf16_d{D}")
+            cross[name] = {"visible_positions": int(visible), "kernels_us": tk,
+                           "fwd_algorithmic_bytes": fwd_bytes, "bwd_algorithmic_bytes": bwd_bytes,
+                           "fwd_gbs": None if not fwd_us else round(fwd_bytes / (fwd_us * 1e-6) / 1e9, 1),
+                           "bwd_gbs": None if not bwd_us else round(bwd_bytes / (bwd_us * 1e-6) / 1e9, 1)}
+            lay_c.destroy()
+        out["cross_attention"] = {"n_dec": n_dec, "n_enc": N, "cases": cross}
+
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host cores: mask enumeration + forward (+ backward) of the
         # same batch with fresh seeded inputs, once
