@@ -262,6 +262,11 @@ hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void 
  *     HPE(p, c) = sum_l sin(w_k p^l) if c = 2k,  sum_l cos(w_k p^l) if c = 2k + 1,  w_k = 10000^(-2k/d_model),
  * is added to the embeddings.
  *
+ * hdt_parents_from_levels -- d_level [batch][n_pos] int32 (device) -> d_parent [batch][n_pos] int32 (device) for
+ *   documents in the layout of Sec. 3.2 (every anchor in front of what it summarises, i.e. pre-order): the
+ *   parent of a position of level l > 0 is the nearest earlier position of level l - 1; level 0, pads, levels
+ *   outside [0, HDT_MAX_LEVELS) and positions without such a predecessor get -1.  The front end for callers
+ *   that only know where sections and sentences start.
  * hdt_index_vectors -- level/parent ids (as for hdt_build_layout) -> d_p [batch][n_pos][n_levels] int32,
  *   device: entry l-1 of position i = the 1-based ordinal, among the children of its parent in document
  *   order, of i's ancestor-or-self whose level is l; 0 if there is none ([DOC] = (0,0,0), k-th [SEC] =
@@ -271,8 +276,10 @@ hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void 
  * hdt_hpe_table -- d_table [rows][d_model] float, device: T[v][c] = sin / cos (w_k v); d_model % 8 == 0.
  * hdt_hpe_add -- x [batch][n_pos][d_model] (dtype dt, device, in place): x += sum_l T[p^l]; indices outside
  *   [0, table_rows) are evaluated directly, so any table size (even 0) gives the same result.
- * All three only enqueue work on `stream`.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED (dtype), HDT_ERR_HIP.
+ * All of them only enqueue work on `stream`.  Errors: INVALID_ARG, SHAPE, UNSUPPORTED (dtype), HDT_ERR_HIP.
  */
+hdt_status_t hdt_parents_from_levels(const int32_t *d_level, int32_t batch, int32_t n_pos, int32_t *d_parent,
+                                     void *stream);
 size_t hdt_index_vectors_workspace_bytes(int32_t batch, int32_t n_pos);
 hdt_status_t hdt_index_vectors(const int32_t *d_level, const int32_t *d_parent, int32_t batch, int32_t n_pos,
                                int32_t n_levels, int32_t *d_p, void *workspace, size_t workspace_bytes,

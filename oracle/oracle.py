@@ -453,3 +453,19 @@ def cross_schedule(level_enc, n_dec: int, level_mask: int, bm: int, bn: int):
     vis[sel] = True
     tr_ = _rect_schedule(vis, np.arange(n_dec, dtype=np.int32), bm, bn, per_tile_has_rows=True)
     return fwd, tr_
+
+
+def parents_from_levels(level) -> np.ndarray:
+    """Parent index of every position of a document laid out as Sec. 3.2 describes it: anchors in front of what
+    they summarise ([DOC] first, a [SEC] at the start of its section, a [SENT] at the start of its sentence),
+    i.e. in pre-order.  The parent of a position of level l > 0 is then the nearest earlier position of level
+    l - 1; level 0, pads and positions without such a predecessor have none (-1).  Plain loop."""
+    level = _i32(level)
+    parent = np.full(level.shape[0], -1, dtype=np.int32)
+    for i in range(level.shape[0]):
+        if level[i] > 0:
+            for j in range(i - 1, -1, -1):
+                if level[j] == level[i] - 1:
+                    parent[i] = j
+                    break
+    return parent

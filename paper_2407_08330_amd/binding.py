@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
     "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
-    "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
+    "hdt_parents_from_levels", "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
 ]
 
 
@@ -96,6 +96,8 @@ def load_library():
     lib.hdt_timing_read.restype = i32
     lib.hdt_release_cached_memory.argtypes = []
     lib.hdt_release_cached_memory.restype = ctypes.c_int
+    lib.hdt_parents_from_levels.argtypes = [vp, i32, i32, vp, vp]
+    lib.hdt_parents_from_levels.restype = ctypes.c_int
     lib.hdt_index_vectors_workspace_bytes.argtypes = [i32, i32]
     lib.hdt_index_vectors_workspace_bytes.restype = ctypes.c_size_t
     lib.hdt_index_vectors.argtypes = [vp, vp, i32, i32, i32, vp, vp, ctypes.c_size_t, vp]
@@ -309,6 +311,19 @@ def hdt_timing_read() -> dict:
     ms = (ctypes.c_double * cap)()
     n = load_library().hdt_timing_read(names, launches, ms, cap)
     return {names[i].decode(): (int(launches[i]), float(ms[i])) for i in range(min(n, cap))}
+
+
+def hdt_parents_from_levels(level, out=None, stream=None):
+    """level: int32 device tensor [batch][n_pos] of documents laid out with their anchors in front -> parent ids."""
+    import torch
+    if level.dtype != torch.int32 or level.dim() != 2 or not (level.is_cuda and level.is_contiguous()):
+        raise TypeError("level must be a contiguous int32 device tensor [batch][n_pos]")
+    B, N = level.shape
+    if out is None:
+        out = torch.empty_like(level)
+    _check(load_library().hdt_parents_from_levels(_ptr(level) if B * N else None, B, N, _ptr(out) if B * N else None,
+                                                  _stream_ptr(stream)))
+    return out
 
 
 def hdt_index_vectors(level, parent, n_levels: int, out=None, workspace=None, stream=None):

@@ -2,6 +2,7 @@
 // Fig. 3 caption): every position carries one index per hierarchy level, each index goes through the
 // standard sinusoidal functions, and the encodings of the levels are summed and added to the embeddings.
 //
+//   hdt_parents_from_levels  levels of a document in the paper's layout (anchors in front) -> parent ids
 //   hdt_index_vectors   level/parent ids -> index vectors p[B][N][L] (1-based ordinal among the siblings
 //                       of the position's ancestor-or-self at each level, 0 where there is none)
 //   hdt_hpe_table       the sinusoidal table T[v][c] = sin / cos (w_k v), w_k = 10000^(-2k/d_model)
@@ -18,6 +19,60 @@
 namespace {
 
 constexpr int kOrdThreads = 1024, kOrdWaves = kOrdThreads / 64;
+
+// ---- parents of a document laid out with its anchors in front (pre-order) ---------------------------
+// parent[i] = the nearest earlier position whose level is level[i] - 1 (none: -1).  One workgroup per
+// sample walks the positions in chunks of 1024 and keeps, per level, the last position seen so far:
+// inside a wave by ballots, across the waves of a chunk and across chunks through LDS.
+__global__ __launch_bounds__(kOrdThreads) void k_parents_from_levels(const int32_t *__restrict__ level, int n,
+                                                                      int32_t *__restrict__ parent)
+{
+    __shared__ int s_last[kOrdWaves][32];  // last position of each level in each wave of the chunk (-1: none)
+    __shared__ int s_carry[32];            // last position of each level in the chunks before
+    const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const size_t o = (size_t)b * n;
+    if (tid < 32) s_carry[tid] = -1;
+    __syncthreads();
+    for (int c0 = 0; c0 < n; c0 += kOrdThreads) {
+        const int i = c0 + tid;
+        int lv = i < n ? level[o + i] : -1;
+        if (lv < 0 || lv >= 32) lv = -1;
+        // the last lane of every level in this wave, kept by lane = level
+        int mine = -1;
+        for (int l = 0; l < 32; l++) {
+            const unsigned long long m = __ballot(lv == l);
+            if (lane == l && m) mine = c0 + wave * 64 + 63 - __builtin_clzll(m);
+        }
+        if (lane < 32) s_last[wave][lane] = mine;
+        // the nearest earlier lane of this wave with level lv - 1
+        int par = -1;
+        unsigned long long todo = __ballot(lv > 0);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int t = __builtin_amdgcn_readlane(lv, leader) - 1;
+            const unsigned long long m = __ballot(lv == t);
+            const bool me = lv - 1 == t && lv > 0;
+            const unsigned long long before = m & ((1ull << lane) - 1ull);
+            if (me && before) par = c0 + wave * 64 + 63 - __builtin_clzll(before);
+            todo &= ~__ballot(me);
+        }
+        __syncthreads();
+        if (lv > 0 && par < 0) {  // not in this wave: earlier waves of the chunk, then earlier chunks
+            for (int w = wave - 1; w >= 0 && par < 0; w--) par = s_last[w][lv - 1];
+            if (par < 0) par = s_carry[lv - 1];
+        }
+        if (i < n) parent[o + i] = par;
+        __syncthreads();
+        if (tid < 32) {
+            for (int w = kOrdWaves - 1; w >= 0; w--)
+                if (s_last[w][tid] >= 0) {
+                    s_carry[tid] = s_last[w][tid];
+                    break;
+                }
+        }
+        __syncthreads();
+    }
+}
 
 // ---- ordinal of every position among its siblings (same parent), in document order ---------------
 // One workgroup per sample walks the positions in chunks of 1024.  Inside a chunk, consecutive positions
@@ -209,6 +264,21 @@ __global__ __launch_bounds__(256) void k_hpe_add(const int32_t *__restrict__ p, 
 }
 
 }  // namespace
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_parents_from_levels(const int32_t *d_level,
+                                                                                        int32_t batch, int32_t n_pos,
+                                                                                        int32_t *d_parent, void *stream)
+{
+    if (batch < 0 || n_pos < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_parents_from_levels: negative size");
+    if (batch == 0 || n_pos == 0) return HDT_OK;
+    if (!d_level || !d_parent) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_parents_from_levels: NULL pointer");
+    if ((int64_t)batch * n_pos > (1LL << 30)) return hdt_fail(HDT_ERR_SHAPE, "hdt_parents_from_levels: batch * n_pos too large");
+    hipStream_t st = (hipStream_t)stream;
+    HdtTimer t("hdt_hpe_parents_from_levels", st);
+    hipLaunchKernelGGL(k_parents_from_levels, dim3((unsigned)batch), dim3(kOrdThreads), 0, st, d_level, n_pos, d_parent);
+    HDT_HIP_TRY(hipGetLastError());
+    return HDT_OK;
+}
 
 extern "C" __attribute__((visibility("default"))) size_t hdt_index_vectors_workspace_bytes(int32_t batch, int32_t n_pos)
 {

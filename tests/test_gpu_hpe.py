@@ -58,6 +58,40 @@ def test_index_vectors_forest_with_pads_in_front(oracle):
     assert got[0].tolist() == [[0, 0], [1, 0], [0, 0], [2, 0], [2, 1], [3, 0]]
 
 
+def _parents(level):
+    import paper_2407_08330_amd as hdt
+    return hdt.hdt_parents_from_levels(to_dev_i32(level)).cpu().numpy()
+
+
+@pytest.mark.parametrize("config", [1, 3])
+def test_parents_from_levels_on_benchmark_documents(oracle, config):
+    wl = inputs.make_workload(config)
+    say(f"[hpe] parents from levels, config {config}: B={wl.batch} N={wl.n_pos}")
+    got = _parents(wl.level)
+    for b in range(wl.batch):
+        np.testing.assert_array_equal(got[b], oracle.parents_from_levels(wl.level[b]), err_msg=f"sample {b}")
+    np.testing.assert_array_equal(got, wl.parent)   # and the generator's own parents
+
+
+def test_parents_from_levels_trees_ragged_lengths_and_odd_levels(oracle):
+    rng = np.random.default_rng(77)
+    for n in (1, 63, 64, 65, 1023, 1025, 3000):
+        lv, _ = inputs.listops_like_tree(np.random.default_rng(n), n)
+        # a second sample: random levels (a forest in no particular order), pads sprinkled in, and levels the
+        # library does not know (they get no parent and are nobody's parent)
+        rnd = rng.integers(-1, 6, size=n).astype(np.int32)
+        rnd[rng.random(n) < 0.02] = 40
+        rnd[rng.random(n) < 0.02] = -7
+        level = np.stack([lv, rnd])
+        say(f"[hpe] parents from levels, n={n}")
+        got = _parents(level)
+        np.testing.assert_array_equal(got[0], oracle.parents_from_levels(level[0]))
+        known = np.where((rnd >= 0) & (rnd < 32), rnd, -1).astype(np.int32)
+        np.testing.assert_array_equal(got[1], oracle.parents_from_levels(known))
+    hand = np.array([[-1, 3, 0, 1, 2, -1, 3, 3, 1, 0, 2, 1, 3]], np.int32)
+    np.testing.assert_array_equal(_parents(hand)[0], [-1, -1, -1, 2, 3, -1, 4, 4, 2, -1, 8, 9, 10])
+
+
 def test_hpe_table(oracle):
     import paper_2407_08330_amd as hdt
     for rows, d in ((700, 768), (33, 64)):

@@ -151,6 +151,15 @@ def test_layout_listops_mask_variants(oracle, edges, windowed):
         lay = _build(level, parent, edges=edges, windowed=windowed)
         assert lay.info()["edges"] == edges
         compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed, edges=edges)
+        # a directed mask also holds the schedule of its transpose (for dK, dV): the same construction with
+        # the parent and child kinds exchanged; a symmetric one has none
+        swapped = (edges & 2) | (4 if edges & 1 else 0) | (1 if edges & 4 else 0)
+        tr = lay.transposed()
+        if swapped == edges:
+            assert tr is None
+        else:
+            assert tr.info()["edges"] == swapped
+            compare_layout(oracle, tr, level, parent, 128, 64, windowed=windowed, edges=swapped)
 
 
 @WINDOWED

@@ -75,3 +75,23 @@ def test_index_vectors_of_a_forest_with_pads_in_front(oracle):
     parent = np.array([-1, -1, -1, -1, 3, -1], np.int32)
     want = [(0, 0), (1, 0), (0, 0), (2, 0), (2, 1), (3, 0)]
     np.testing.assert_array_equal(oracle.index_vectors(level, parent, 2), np.array(want))
+
+
+@pytest.mark.parametrize("name", ["mask_doc16.txt", "mask_tree10.txt"])
+def test_parents_from_levels_reproduce_the_hand_written_parents(oracle, name):
+    level, parent, _, _ = read_golden_mask(name)
+    np.testing.assert_array_equal(oracle.parents_from_levels(level), parent)
+
+
+def test_parents_from_levels_match_the_generators_and_handle_forests(oracle):
+    from paper_2407_08330_amd import inputs
+    # the document generator builds its parents while it lays the anchors out: an independent construction
+    wl = inputs.make_workload(1)
+    for b in range(wl.batch):
+        np.testing.assert_array_equal(oracle.parents_from_levels(wl.level[b]), wl.parent[b])
+    lv, pr = inputs.listops_like_tree(np.random.default_rng(7), 600)
+    np.testing.assert_array_equal(oracle.parents_from_levels(lv), pr)
+    # written out by hand: pads in front and between, a token before any sentence, two roots
+    level = np.array([-1, 3, 0, 1, 2, -1, 3, 3, 1, 0, 2, 1, 3], np.int32)
+    want = np.array([-1, -1, -1, 2, 3, -1, 4, 4, 2, -1, 8, 9, 10], np.int32)
+    np.testing.assert_array_equal(oracle.parents_from_levels(level), want)
