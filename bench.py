@@ -62,6 +62,8 @@ def main() -> int:
                          "patterns of the paper's ListOps study applied to the workload's documents")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket kernels with events (for external profilers)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements beside the path (positional encoding, cross-attention)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy 3 times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -266,7 +268,7 @@ def main() -> int:
             "hbm_gbs_algorithmic": round(algorithmic_bytes_per_unit(fwd_name, D) * B * H * N / (fwd_us * 1e-6) / 1e9, 1),
         }
 
-    if not args.no_kernel_timing:
+    if not args.no_kernel_timing and not args.no_extras:
         # the step before the path (not part of `value`): hierarchical positional encoding of the same batch,
         # index vectors from the ids and the fused add into bf16 embeddings of d_model = heads * head_dim
         d_model, n_lev = H * D, 3
@@ -290,7 +292,7 @@ def main() -> int:
                       "add_gbs": None if not add_us else round(add_bytes / (add_us * 1e-6) / 1e9, 1),
                       "add_frac_of_hbm_peak": None if not add_us else round(add_bytes / (add_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
 
-    if not args.no_kernel_timing:
+    if not args.no_kernel_timing and not args.no_extras:
         # decoder cross-attention over level subsets of the same encoder batch (not part of `value`): 512
         # decoder rows per sample attending to the [SEC] anchors, + [SENT] anchors, + tokens
         n_dec = 512
