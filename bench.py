@@ -55,8 +55,11 @@ def main() -> int:
                          "the default per-query-tile key lists")
     ap.add_argument("--tile", default="", help="tile shape of the layout, 64x32 or 128x64 (default: the library's)")
     ap.add_argument("--serial", action="store_true",
-                    help="one stream, strictly build -> forward -> backward per step (default: the next step's "
-                         "layout is built on a second stream while this step's attention kernels run)")
+                    help="one stream, strictly build -> forward -> backward per step (default for the forward-only "
+                         "configurations, whose steps are too short to hide a build that reports back to the host)")
+    ap.add_argument("--pipelined", action="store_true",
+                    help="the next step's layout is built on a second stream while this step's attention kernels "
+                         "run (default for configurations with a backward pass)")
     ap.add_argument("--edges", type=int, default=0,
                     help="edge kinds of the mask (1 parent, 2 siblings, 4 children, OR-ed; 0 = all): the thinned "
                          "patterns of the paper's ListOps study applied to the workload's documents")
@@ -156,7 +159,10 @@ def main() -> int:
             old_done.synchronize()
             old_lay.destroy()
 
-    run = run_serial if args.serial else run_pipelined
+    if args.serial and args.pipelined:
+        ap.error("--serial and --pipelined exclude each other")
+    serial = args.serial or (not args.pipelined and not do_bwd)
+    run = run_serial if serial else run_pipelined
 
     if args.calibrate_copy:
         # a copy kernel of known size: 256 MiB read + 256 MiB written per launch
@@ -179,7 +185,7 @@ def main() -> int:
 
     # for reference: the same K steps strictly one after the other on a single stream
     ms_per_step_serial = ms_per_step
-    if not args.serial:
+    if not serial:
         run_serial(0, args.warmup)
         torch.cuda.synchronize()
         s0 = time.perf_counter()
@@ -244,7 +250,7 @@ def main() -> int:
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "ms_per_step_serial": round(ms_per_step_serial, 4),
-        "pipelining": "none" if args.serial else "layout of step i+1 built on a second stream during the attention of step i",
+        "pipelining": "none" if serial else "layout of step i+1 built on a second stream during the attention of step i",
         "ms_per_step_with_kernel_events": None if ms_per_step_events is None else round(ms_per_step_events, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
