@@ -345,7 +345,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if (!workspace || workspace_bytes < need)
         return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_bwd: workspace of %zu bytes needed, %zu given", need,
                         workspace_bytes);
-    if ((int64_t)s.batch * heads * ((int64_t)s.tr + s_tr.tr) > 0x7ffff000LL)
+    if ((int64_t)s.batch * heads * ((int64_t)s.tr + 2 * (int64_t)s_tr.tr) > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
     if (dt == HDT_BF16)

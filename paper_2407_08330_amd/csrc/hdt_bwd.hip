@@ -23,7 +23,8 @@
 //                  symmetry) the layout holds a second schedule, built from the same ids with the
 //                  parent and child kinds exchanged.
 // Both roles recompute the scores, which costs two extra contractions but keeps dQ out of HBM as fp32
-// partial sums.  The two workgroups of a tile are neighbours in the launch order and run on the same XCD
+// partial sums.  At head size 128 the dK/dV role is split once more, into a dV role and a dK role (three
+// workgroups per tile): together they would need more registers than two waves per SIMD leave.  The two workgroups of a tile are neighbours in the launch order and run on the same XCD
 // at the same time.  That is what the pairing is for: the dQ role reads the tile's Q, dO rows and gathers
 // K, V rows of the neighbourhood, the dK/dV role reads the tile's K, V rows and gathers Q, dO rows of the
 // same neighbourhood, so each role finds in the XCD's L2 what the other (or a neighbouring pair) has just
@@ -47,12 +48,16 @@ struct BwdCfg {
 #define HDT_BWD_W64 3
 #endif
 #ifndef HDT_BWD_W128
-#define HDT_BWD_W128 1
+#define HDT_BWD_W128 2
 #endif
     // ring stages of the two roles and waves per SIMD (register budget) of the kernel
     static constexpr int S_DQ = (D == 64) ? HDT_DQ_S64 : 2;
     static constexpr int S_DKV = (D == 64) ? HDT_DKV_S64 : 2;
     static constexpr int WAVES = (D == 64) ? HDT_BWD_W64 : HDT_BWD_W128;
+    // At head size 128 the dK/dV role would need 128 accumulator registers per lane on top of 64 operand
+    // registers, which leaves one wave per SIMD.  It is split there into a dV role and a dK role (each
+    // recomputes the scores), so that every role fits two waves per SIMD.
+    static constexpr bool SPLIT_KV = D == 128;
 };
 
 // ---------------------------------------------------------------------------------------- D
@@ -199,7 +204,8 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
 }
 
 // ---------------------------------------------------------------------------------------- dK, dV
-template <int D, typename G>
+// WHICH: 0 = dK and dV, 1 = dV only, 2 = dK only
+template <int D, typename G, int WHICH>
 __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const __bf16 *__restrict__ q,
                                           const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
                                           const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
@@ -210,6 +216,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     using R = Ring<P>;
     constexpr int BM = G::BM, BN = G::BN, KB = G::KB;
     constexpr int ROWB = P::ROWB, KSTEPS = P::KSTEPS, DBLK = P::DBLK, S = P::S;
+    constexpr bool DO_DV = WHICH != 2, DO_DK = WHICH != 1;
 
     const int lane = threadIdx.x & 63;
     const int hf = lane >> 5;
@@ -237,7 +244,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     // K and V rows of this wave: through the two highest ring stages, as Q and dO in the dQ pass
     constexpr uint32_t STG_K = (uint32_t)(S - 1) * 2 * P::TILE, STG_V = (uint32_t)(S - 2) * 2 * P::TILE;
     stage_own_rows(pipe, k + base, I * BM, s.n_pos, D, STG_K);
-    stage_own_rows(pipe, v + base, I * BM, s.n_pos, D, STG_V);
+    if (DO_DK) stage_own_rows(pipe, v + base, I * BM, s.n_pos, D, STG_V);  // V only enters dP
     R::start(pipe, n);
     R::template prologue<0, S - 2>(pipe, n);
     if (S == 2 || n == 0) wait_vmcnt<0>();
@@ -245,7 +252,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
 #pragma unroll
     for (int st = 0; st < KSTEPS; st++) {
         kf[st] = read_row<ROWB>(smem + STG_K, rl, wave * 32, st);
-        vf[st] = read_row<ROWB>(smem + STG_V, rl, wave * 32, st);
+        if (DO_DK) vf[st] = read_row<ROWB>(smem + STG_V, rl, wave * 32, st);
     }
     wg_barrier();
     R::template prologue<S - 2, S - 1>(pipe, n);
@@ -279,7 +286,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
 #pragma unroll
             for (int st = 0; st < KSTEPS; st++) {
                 sacc = mfma_32x32x16(read_row<ROWB>(sQ, rl, kb * 32, st), kf[st], sacc);     // S  = Q K^T
-                dpacc = mfma_32x32x16(read_row<ROWB>(sDO, rl, kb * 32, st), vf[st], dpacc);  // dP = dO V^T
+                if (DO_DK) dpacc = mfma_32x32x16(read_row<ROWB>(sDO, rl, kb * 32, st), vf[st], dpacc);  // dP = dO V^T
             }
             f32x16 pacc;
 #pragma unroll
@@ -291,21 +298,28 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
                     pacc[gq * 4 + e] = fast_exp2(fmaf(sacc[gq * 4 + e], scale_log2, -lv[e] * LOG2E));
             }
             if (!((sub >> (16 + sb)) & 1u)) apply_mask(pacc, s.bits_rm + ((size_t)bidx * G::NSUB + sb) * 16, 0.f);
+            if (DO_DK) {
 #pragma unroll
-            for (int gq = 0; gq < 4; gq++) {
-                const float4 d4 = *reinterpret_cast<const float4 *>(&sDelta[kb * 32 + hf * 4 + gq * 8]);
-                const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
+                for (int gq = 0; gq < 4; gq++) {
+                    const float4 d4 = *reinterpret_cast<const float4 *>(&sDelta[kb * 32 + hf * 4 + gq * 8]);
+                    const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int e = 0; e < 4; e++) sacc[gq * 4 + e] = pacc[gq * 4 + e] * (dpacc[gq * 4 + e] - dl[e]);  // dS
+                    for (int e = 0; e < 4; e++) sacc[gq * 4 + e] = pacc[gq * 4 + e] * (dpacc[gq * 4 + e] - dl[e]);  // dS
+                }
+                const bf16x8 s0 = pack_bf16x8(sacc, 0), s1 = pack_bf16x8(sacc, 8);
+#pragma unroll
+                for (int j = 0; j < DBLK; j++) {
+                    dkacc[j] = mfma_32x32x16(read_tr<ROWB>(sQ, tl, kb * 32, j), s0, dkacc[j]);  // dK^T += Q^T dS
+                    dkacc[j] = mfma_32x32x16(read_tr<ROWB>(sQ, tl, kb * 32 + 16, j), s1, dkacc[j]);
+                }
             }
-            const bf16x8 p0 = pack_bf16x8(pacc, 0), p1 = pack_bf16x8(pacc, 8);
-            const bf16x8 s0 = pack_bf16x8(sacc, 0), s1 = pack_bf16x8(sacc, 8);
+            if (DO_DV) {
+                const bf16x8 p0 = pack_bf16x8(pacc, 0), p1 = pack_bf16x8(pacc, 8);
 #pragma unroll
-            for (int j = 0; j < DBLK; j++) {
-                dvacc[j] = mfma_32x32x16(read_tr<ROWB>(sDO, tl, kb * 32, j), p0, dvacc[j]);  // dV^T += dO^T P
-                dvacc[j] = mfma_32x32x16(read_tr<ROWB>(sDO, tl, kb * 32 + 16, j), p1, dvacc[j]);
-                dkacc[j] = mfma_32x32x16(read_tr<ROWB>(sQ, tl, kb * 32, j), s0, dkacc[j]);  // dK^T += Q^T dS
-                dkacc[j] = mfma_32x32x16(read_tr<ROWB>(sQ, tl, kb * 32 + 16, j), s1, dkacc[j]);
+                for (int j = 0; j < DBLK; j++) {
+                    dvacc[j] = mfma_32x32x16(read_tr<ROWB>(sDO, tl, kb * 32, j), p0, dvacc[j]);  // dV^T += dO^T P
+                    dvacc[j] = mfma_32x32x16(read_tr<ROWB>(sDO, tl, kb * 32 + 16, j), p1, dvacc[j]);
+                }
             }
         }
     }
@@ -315,8 +329,8 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
         const int wrow0 = I * BM + wave * 32;
         char *wl = smem + (n % S) * 2 * P::TILE + wave * 32 * ROWB;
         const int le = opaque(lane);
-        store_rows_via_lds<P, D>(wl, le, dkacc, scale, dk + base + (size_t)wrow0 * D, s.n_pos - wrow0);
-        store_rows_via_lds<P, D>(wl, le, dvacc, 1.f, dv + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+        if (DO_DK) store_rows_via_lds<P, D>(wl, le, dkacc, scale, dk + base + (size_t)wrow0 * D, s.n_pos - wrow0);
+        if (DO_DV) store_rows_via_lds<P, D>(wl, le, dvacc, 1.f, dv + base + (size_t)wrow0 * D, s.n_pos - wrow0);
     }
 }
 
@@ -332,27 +346,36 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES) void k_bwd_bf16(
     constexpr int SMEM = PQ::SMEM_BYTES > PK::SMEM_BYTES ? PQ::SMEM_BYTES : PK::SMEM_BYTES;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-    // the two roles tile different tensors (the same ones for self-attention): pairs (2t, 2t+1) as far as both
-    // have a tile t, the rest of the longer one behind them
-    const unsigned lb2 = logical_block(blockIdx.x, 2 * kXcdChunk);
+    // The roles tile different tensors (the same ones for self-attention): the workgroups of one tile follow each
+    // other as far as both sides have that tile, the rest of the longer side comes behind them.
+    constexpr unsigned R = BwdCfg<D>::SPLIT_KV ? 3u : 2u;  // roles per tile: dQ, then dK/dV or dV, dK
+    const unsigned w = logical_block(blockIdx.x, R * kXcdChunk);
     const unsigned nq = (unsigned)s.batch * heads * s.tr, nk = (unsigned)s_tr.batch * heads * s_tr.tr;
     const unsigned common = nq < nk ? nq : nk;
-    if (lb2 >= nq + nk) return;  // padding of the grid
-    bool keys_role;
-    unsigned lb;
-    if (lb2 < 2u * common) {
-        keys_role = lb2 & 1u;
-        lb = lb2 >> 1;
+    if (w >= nq + (R - 1u) * nk) return;  // padding of the grid
+    unsigned role, lb;
+    if (w < R * common) {
+        role = w % R;
+        lb = w / R;
+    } else if (nq > nk) {
+        role = 0u;
+        lb = w - (R - 1u) * common;
     } else {
-        keys_role = nk > nq;
-        lb = lb2 - common;
+        const unsigned rest = w - R * common;
+        role = 1u + rest % (R - 1u);
+        lb = common + rest / (R - 1u);
     }
-    if (keys_role) {
-        const int I = lb % s_tr.tr, bh = lb / s_tr.tr, b = bh / heads;
-        dkv_role<D, G>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
-    } else {
+    if (role == 0u) {
         const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
         dq_role<D, G>(smem, s, q, k, v, lse, d_o, delta, dq, wave, I, bh, b, scale);
+    } else {
+        const int I = lb % s_tr.tr, bh = lb / s_tr.tr, b = bh / heads;
+        if (!BwdCfg<D>::SPLIT_KV)
+            dkv_role<D, G, 0>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
+        else if (role == 1u)
+            dkv_role<D, G, 1>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
+        else
+            dkv_role<D, G, 2>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
     }
 }
 
@@ -375,7 +398,9 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
     }
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_bf16_d64" : "hdt_bwd_bf16_d128", st);
-        dim3 grid(padded_grid((unsigned)((size_t)s.batch * heads * (s.tr + s_tr.tr)), 2 * kXcdChunk)), block(G::THREADS);
+        const unsigned nq = (unsigned)s.batch * heads * s.tr, nk = (unsigned)s_tr.batch * heads * s_tr.tr;
+        const unsigned roles = head_dim == 128 ? 3u : 2u;  // BwdCfg<D>::SPLIT_KV
+        dim3 grid(padded_grid(nq + (roles - 1u) * nk, roles * kXcdChunk)), block(G::THREADS);
         if (head_dim == 64)
             hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
                                (__bf16 *)dk, (__bf16 *)dv, heads, scale);
