@@ -129,6 +129,15 @@ def test_cross_attention_both_tile_shapes_and_blind_sample(oracle, tile):
     run_cross_case(oracle, level, 1, SEC | SENT | TOK, 2, 128, "bf16", 802, tile=tile)
 
 
+@pytest.mark.parametrize("D", [64, 128])
+def test_cross_attention_more_decoder_rows_than_encoder_positions(oracle, D):
+    # more row tiles on the decoder side than on the encoder side: the backward's leftover workgroups are dQ roles
+    level = _encoder_levels(150, (33, 34))
+    say(f"[cross] n_enc=150 n_dec=1000 d={D}")
+    run_cross_case(oracle, level, 1000, SEC | SENT | TOK, 2, D, "bf16", 850 + D)
+    run_cross_case(oracle, level, 1000, SEC, 2, D, "bf16", 860 + D, tile=(64, 32))
+
+
 def test_cross_attention_benchmark_documents(oracle):
     # the encoder side of the benchmark's 8192-position batch; 512 decoder rows (section-level summaries)
     wl = inputs.make_workload(4)
