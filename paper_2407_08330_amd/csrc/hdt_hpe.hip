@@ -75,79 +75,129 @@ __global__ __launch_bounds__(kOrdThreads) void k_parents_from_levels(const int32
 }
 
 // ---- ordinal of every position among its siblings (same parent), in document order ---------------
-// One workgroup per sample walks the positions in chunks of 1024.  Inside a chunk, consecutive positions
-// with the same parent form a run (the tokens of a sentence, for one): a position's ordinal is
+// One workgroup per sample walks the positions in chunks of 1024 * kOrdV (a thread takes kOrdV consecutive
+// positions).  Inside a chunk, consecutive positions with the same parent form a run (the tokens of a sentence,
+// for one): a position's ordinal is
 //   1 + (siblings in earlier chunks: a per-parent counter in global memory)
-//     + (siblings in earlier runs of this chunk: summed by the run's first thread over the earlier run heads)
+//     + (siblings in earlier runs of this chunk: a sum over the earlier run heads, shared by kOrdSplit lanes)
 //     + (its offset inside its run).
 // Roots (parent -1) count as children of one virtual parent.  Pads and positions past n form runs of
 // their own (group -1), which only serve to end the runs before them.
+constexpr int kOrdV = 4, kOrdChunk = kOrdThreads * kOrdV, kOrdSplit = 16;
+
 __global__ __launch_bounds__(kOrdThreads) void k_sibling_ordinals(const int32_t *__restrict__ level,
                                                                    const int32_t *__restrict__ parent, int n,
                                                                    int32_t *cnt,  // [B][n + 1] scratch
                                                                    int32_t *ord)  // [B][n]
 {
-    __shared__ int s_head_parent[kOrdThreads], s_head_start[kOrdThreads], s_run_base[kOrdThreads];
+    // per run head of the chunk: its group, its first position in the chunk; per position of the chunk that
+    // starts a run: siblings before that run (s_run_base)
+    __shared__ int s_head_parent[kOrdChunk], s_head_start[kOrdChunk], s_run_base[kOrdChunk];
+    __shared__ int s_last_grp[kOrdThreads];
     __shared__ int s_wave_max[kOrdWaves], s_wave_heads[kOrdWaves];
     const int b = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const size_t o = (size_t)b * n;
     int32_t *my_cnt = cnt + (size_t)b * (n + 1);
     for (int i = tid; i <= n; i += kOrdThreads) my_cnt[i] = 0;
     __syncthreads();
-    const int nchunks = (n + kOrdThreads - 1) / kOrdThreads;
-    for (int c = 0; c < nchunks; c++) {
-        const int i = c * kOrdThreads + tid;
-        int grp = -1;  // the parent (n for roots), -1 for pads and positions past n
-        if (i < n && level[o + i] >= 0) {
-            const int p = parent[o + i];
-            grp = (p >= 0 && p < n) ? p : n;
+    for (int c0 = 0; c0 < n; c0 += kOrdChunk) {
+        const int idx0 = tid * kOrdV;  // this thread's first position inside the chunk
+        int grp[kOrdV];                // the parent (n for roots), -1 for pads and positions past n
+#pragma unroll
+        for (int u = 0; u < kOrdV; u++) {
+            const int i = c0 + idx0 + u;
+            grp[u] = -1;
+            if (i < n && level[o + i] >= 0) {
+                const int p = parent[o + i];
+                grp[u] = (p >= 0 && p < n) ? p : n;
+            }
         }
-        // run heads
-        const int prev = __shfl_up(grp, 1);
-        s_run_base[tid] = grp;  // (temporarily: this thread's group, for the first lane of the next wave)
+        s_last_grp[tid] = grp[kOrdV - 1];
         __syncthreads();
-        const int before = lane == 0 ? (tid == 0 ? -2 : s_run_base[tid - 1]) : prev;
-        const bool head = before != grp;
-        // start of my run: running maximum of the head positions
-        int start = head ? tid : -1;
+        // run heads; the last head at or before every position: a running maximum over the threads
+        int before = tid == 0 ? -2 : s_last_grp[tid - 1];
+        bool head[kOrdV];
+        int n_mine = 0, last_head = -1;
+#pragma unroll
+        for (int u = 0; u < kOrdV; u++) {
+            head[u] = grp[u] != before;
+            before = grp[u];
+            if (head[u]) {
+                n_mine++;
+                last_head = idx0 + u;
+            }
+        }
+        int run_max = last_head, heads_incl = n_mine;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(start, d);
-            if (lane >= d) start = max(start, y);
+            const int y = __shfl_up(run_max, d), z = __shfl_up(heads_incl, d);
+            if (lane >= d) {
+                run_max = max(run_max, y);
+                heads_incl += z;
+            }
         }
-        if (lane == 63) s_wave_max[wave] = start;
-        const unsigned long long hm = __ballot(head);
-        if (lane == 0) s_wave_heads[wave] = __popcll(hm);
-        __syncthreads();
-        int heads_before = 0;
-        for (int w = 0; w < wave; w++) {
-            start = max(start, s_wave_max[w]);
-            heads_before += s_wave_heads[w];
-        }
-        int n_heads = 0;
-        for (int w = 0; w < kOrdWaves; w++) n_heads += s_wave_heads[w];
-        const int my_head = heads_before + __popcll(hm & ((1ull << lane) - 1ull));
-        if (head) {
-            s_head_parent[my_head] = grp;
-            s_head_start[my_head] = tid;
+        if (lane == 63) {
+            s_wave_max[wave] = run_max;
+            s_wave_heads[wave] = heads_incl;
         }
         __syncthreads();
-        if (head && grp >= 0) {
-            // siblings in earlier runs of this chunk (a run ends where the next head starts)
+        int start_in = __shfl_up(run_max, 1);  // last head before this thread's positions
+        if (lane == 0) start_in = -1;
+        int my_head = heads_incl - n_mine, n_heads = 0;
+        for (int w = 0; w < kOrdWaves; w++) {
+            if (w < wave) {
+                start_in = max(start_in, s_wave_max[w]);
+                my_head += s_wave_heads[w];
+            }
+            n_heads += s_wave_heads[w];
+        }
+        int start[kOrdV];
+        {
+            int cur = start_in, h = my_head;
+#pragma unroll
+            for (int u = 0; u < kOrdV; u++) {
+                if (head[u]) {
+                    cur = idx0 + u;
+                    s_head_parent[h] = grp[u];
+                    s_head_start[h] = cur;
+                    h++;
+                }
+                start[u] = cur;
+            }
+        }
+        __syncthreads();
+        // siblings in earlier runs of this chunk: kOrdSplit lanes share the scan over the earlier heads of one head
+        for (int h = tid / kOrdSplit; h < n_heads; h += kOrdThreads / kOrdSplit) {
+            const int g = s_head_parent[h];
+            if (g < 0) continue;
             int k = 0;
-            for (int h = 0; h < my_head; h++)
-                if (s_head_parent[h] == grp) k += (h + 1 < n_heads ? s_head_start[h + 1] : kOrdThreads) - s_head_start[h];
-            // siblings in earlier chunks (the counter was last changed before the barrier that ended the previous chunk)
-            const int base = __hip_atomic_load(&my_cnt[grp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_run_base[tid] = base + k;
+            for (int e = tid % kOrdSplit; e < h; e += kOrdSplit)
+                if (s_head_parent[e] == g) k += s_head_start[e + 1] - s_head_start[e];
+#pragma unroll
+            for (int d = 1; d < kOrdSplit; d <<= 1) k += __shfl_xor(k, d);
+            if (tid % kOrdSplit == 0) {
+                // siblings in earlier chunks (the counter last changed before the barrier that ended the previous chunk)
+                const int base = __hip_atomic_load(&my_cnt[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_run_base[s_head_start[h]] = base + k;
+            }
         }
         __syncthreads();
-        if (grp >= 0) ord[o + i] = 1 + s_run_base[start] + (tid - start);
+#pragma unroll
+        for (int u = 0; u < kOrdV; u++)
+            if (grp[u] >= 0) ord[o + c0 + idx0 + u] = 1 + s_run_base[start[u]] + (idx0 + u - start[u]);
         // add this chunk's runs to the counters; the returned value makes the thread wait for the atomic
-        if (head && grp >= 0) {
-            const int end = my_head + 1 < n_heads ? s_head_start[my_head + 1] : kOrdThreads;
-            const int old = atomicAdd(&my_cnt[grp], end - tid);
-            asm volatile("" ::"v"(old));
+        {
+            int h = my_head;
+#pragma unroll
+            for (int u = 0; u < kOrdV; u++) {
+                if (!head[u]) continue;
+                if (grp[u] >= 0) {
+                    const int end = h + 1 < n_heads ? s_head_start[h + 1] : kOrdChunk;
+                    const int old = atomicAdd(&my_cnt[grp[u]], end - (idx0 + u));
+                    asm volatile("" ::"v"(old));
+                }
+                h++;
+            }
         }
         __syncthreads();
     }

@@ -31,13 +31,13 @@ def test_index_vectors_on_benchmark_documents(oracle, config):
 
 def test_index_vectors_deep_trees_ragged_and_shuffled(oracle):
     rng = np.random.default_rng(8)
-    for n in (1, 63, 1025, 3000):
+    for n in (1, 63, 1025, 3000, 4097, 9001):
         lv, pr = inputs.listops_like_tree(rng, n, max_nodes=max(1, n - 3))
         say(f"[hpe] ListOps-shaped tree n={n} depth {lv.max()}")
         _check_index_vectors(oracle, lv[None], pr[None], 20)
         _check_index_vectors(oracle, lv[None], pr[None], 4)       # deeper levels are cut
     # a document whose positions are shuffled (siblings scattered over the chunks) + an all-pad sample
-    wl = inputs.make_workload(2, batch=1)
+    wl = inputs.make_workload(3, batch=1)
     n = wl.n_pos
     perm = rng.permutation(n)
     level = np.empty(n, np.int32)
