@@ -217,15 +217,22 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
                         keep_col.size(), (long long)T);
     if (q_rowptr) memcpy(q_rowptr, new_rp.data(), sizeof(int32_t) * (s.tr + 1));
     const size_t words = (size_t)s.bm * s.wpr;
+    std::vector<unsigned long long> rm((size_t)(s.bm / 32) * s.wpr * 16);
     for (int64_t t = 0; t < T; t++) {
         if (q_cols) q_cols[t] = keep_col[t];
         if (q_sub) q_sub[t] = sub[keep_entry[t]];
         if (q_keys)
             HDT_HIP_TRY(hipMemcpy(q_keys + (size_t)t * s.bn, s.q_keys + (size_t)keep_entry[t] * s.bn,
                                   sizeof(int32_t) * s.bn, hipMemcpyDeviceToHost));
-        if (bits)
-            HDT_HIP_TRY(hipMemcpy(bits + (size_t)t * words, s.bits + (size_t)keep_entry[t] * words,
-                                  sizeof(uint32_t) * words, hipMemcpyDeviceToHost));
+        if (bits) {  // row-major bitmaps are derived here from the lane masks the device keeps
+            HDT_HIP_TRY(hipMemcpy(rm.data(), s.bits_rm + (size_t)keep_entry[t] * rm.size(),
+                                  sizeof(unsigned long long) * rm.size(), hipMemcpyDeviceToHost));
+            uint32_t *out = bits + (size_t)t * words;
+            memset(out, 0, sizeof(uint32_t) * words);
+            for (int r = 0; r < s.bm; r++)
+                for (int c = 0; c < s.bn; c++)
+                    if (hdt_pair_allowed(rm.data(), s.bm, s.wpr, 0, r, c)) out[(size_t)r * s.wpr + (c >> 5)] |= 1u << (c & 31);
+        }
     }
     // transpose by key tile (query tiles ascending): the kernels do not need it (the mask is symmetric,
     // so the backward walks the same lists); it is derived here for callers that want both views

@@ -68,7 +68,7 @@ struct CrossArgs {
                      // (allowed iff visible), keys = decoder positions
     int tr, e_max;   // row tiles per sample, list entries reserved per row tile
     int32_t *q_range, *c_row, *c_cnt, *q_keys;
-    uint32_t *q_sub, *bits;
+    uint32_t *q_sub;
     unsigned long long *bits_rm;
 };
 
@@ -121,11 +121,6 @@ __global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
     }
     __syncthreads();
     const int wpr = a.bn >> 5, nrb = a.bm >> 5, nsub = nrb * wpr;
-    // row-major bitmap
-    for (int w = lane; w < a.bm * wpr; w += 64) {
-        const int r = w / wpr, cw = w % wpr;
-        a.bits[(size_t)entry * a.bm * wpr + w] = ((s_row[r >> 5] >> (r & 31)) & 1u) ? s_col[cw] : 0u;
-    }
     // lane masks of the MFMA accumulator registers: sub-block (rblk, cblk), register x: bit l <=> row
     // rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(x/4) + x%4
     for (int w = lane; w < nsub * 16; w += 64) {
@@ -159,7 +154,7 @@ __global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
 struct CrossBuffers {
     int32_t *sel, *count, *q_range;  // first arena
     int32_t *c_row, *c_cnt, *q_keys;  // second arena
-    uint32_t *q_sub, *bits;
+    uint32_t *q_sub;
     unsigned long long *bits_rm;
     size_t bytes1, bytes2;
 };
@@ -186,7 +181,6 @@ CrossBuffers carve_cross(char *a1, char *a2, int B, int n_enc, int tr, int64_t e
     c.c_cnt = carve<int32_t>(a2, o2, n);
     c.q_sub = carve<uint32_t>(a2, o2, n);
     c.q_keys = carve<int32_t>(a2, o2, n * (size_t)bn);
-    c.bits = carve<uint32_t>(a2, o2, n * (size_t)bm * (bn / 32));
     c.bits_rm = carve<unsigned long long>(a2, o2, n * (size_t)(bm / 32) * (bn / 32) * 16);
     c.bytes1 = o1;
     c.bytes2 = o2;
@@ -297,13 +291,13 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
                                    level_mask, f.sel, f.count);
             }
             CrossArgs a{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 0, L->s.tr, e_fwd,
-                        f.q_range, f.c_row, f.c_cnt, f.q_keys, f.q_sub, f.bits, f.bits_rm};
+                        f.q_range, f.c_row, f.c_cnt, f.q_keys, f.q_sub, f.bits_rm};
             {
                 HdtTimer tm("hdt_cross_entries", st);
                 hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_fwd), dim3(64), 0, st, a);
             }
             CrossArgs at{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 1, T->s.tr, e_tr,
-                         t.q_range, t.c_row, t.c_cnt, t.q_keys, t.q_sub, t.bits, t.bits_rm};
+                         t.q_range, t.c_row, t.c_cnt, t.q_keys, t.q_sub, t.bits_rm};
             {
                 HdtTimer tm("hdt_cross_entries_transposed", st);
                 hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_tr), dim3(64), 0, st, at);
@@ -320,7 +314,6 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
             s.q_range = x.c->q_range;
             s.q_keys = x.c->q_keys;
             s.q_sub = x.c->q_sub;
-            s.bits = x.c->bits;
             s.bits_rm = x.c->bits_rm;
             s.q_cols = nullptr;
             s.kperm = nullptr;

@@ -24,9 +24,8 @@ __global__ __launch_bounds__(128) void k_fwd_f32(HdtSchedule s, const float *__r
     float m = -INFINITY, l = 0.f;
     const size_t row = (size_t)b * s.tr + I;
     for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
-        const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
-            if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
+            if (!hdt_pair_allowed(s.bits_rm, s.bm, s.wpr, (size_t)t, r, c)) continue;
             const int pos = s.q_keys[(size_t)t * s.bn + c];
             if (pos < 0) continue;
             const float *kj = k + kv_base + (size_t)pos * D;
@@ -71,9 +70,8 @@ __global__ __launch_bounds__(128) void k_bwd_dq_f32(HdtSchedule s, const float *
     for (int c = 0; c < D; c++) acc[c] = 0.f;
     const size_t row = (size_t)b * s.tr + I;
     for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
-        const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
-            if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
+            if (!hdt_pair_allowed(s.bits_rm, s.bm, s.wpr, (size_t)t, r, c)) continue;
             const int pos = s.q_keys[(size_t)t * s.bn + c];
             if (pos < 0) continue;
             const float *kj = k + kv_base + (size_t)pos * D;
@@ -114,9 +112,8 @@ __global__ __launch_bounds__(128) void k_bwd_dkv_f32(HdtSchedule s, const float 
     for (int e = 0; e < D; e++) ak[e] = av[e] = 0.f;
     const size_t row = (size_t)b * s.tr + I;
     for (int t = s.q_range[2 * row]; t < s.q_range[2 * row + 1]; t++) {
-        const uint32_t *bw = s.bits + ((size_t)t * s.bm + r) * s.wpr;
         for (int c = 0; c < s.bn; c++) {
-            if (!((bw[c >> 5] >> (c & 31)) & 1u)) continue;
+            if (!hdt_pair_allowed(s.bits_rm, s.bm, s.wpr, (size_t)t, r, c)) continue;
             const int i = s.q_keys[(size_t)t * s.bn + c];  // query position
             if (i < 0) continue;
             const float *qi = q + q_base + (size_t)i * D;

@@ -32,11 +32,18 @@ struct HdtSchedule {
     const int32_t *q_cols;    // [entries] windowed layouts: key window of each entry
     const int32_t *q_keys;    // [entries][bn] document position behind each key slot, -1 = none
     const uint32_t *q_sub;    // [entries] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
-    const uint32_t *bits;     // [entries][bm][wpr]   row r, word c/32, bit c%32
     // [entries][(bm/32)*(bn/32)][16] per 32x32 sub-block (r, c) = index r*(bn/32)+c: bit l of word e <=>
     // row 32r + l%32, column 32c + (l/32)*4 + 8*(e/4) + e%4 allowed: the lane mask of MFMA accumulator register e
     const unsigned long long *bits_rm;
 };
+
+// whether row r of list entry t may attend to the key in slot c (plain indexing of bits_rm)
+__host__ __device__ inline bool hdt_pair_allowed(const unsigned long long *bits_rm, int bm, int wpr, size_t t, int r, int c)
+{
+    const size_t sb = (size_t)(r >> 5) * wpr + (c >> 5), nsub = (size_t)(bm >> 5) * wpr;
+    const int l = (r & 31) + 32 * ((c >> 2) & 1), e = ((c & 31) >> 3) * 4 + (c & 3);
+    return (bits_rm[(t * nsub + sb) * 16 + e] >> l) & 1ull;
+}
 
 struct hdt_layout {
     uint32_t magic;

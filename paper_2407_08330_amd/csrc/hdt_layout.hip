@@ -384,11 +384,9 @@ struct EntryPart {
 __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int wsub, int khalf, int lane, int i, int pi,
                                                    bool rowok,
                                                    const int (&kpos)[2], const int (&kpar)[2], int bm, int bn, int edges,
-                                                   uint32_t *bits, unsigned long long *bits_rm)
+                                                   unsigned long long *bits_rm)
 {
     const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
-    const size_t words = (size_t)bm * wpr;
-    const int r = wsub * 64 + lane;
     // a disabled edge kind is a comparison against a value no key carries
     const int pi_sib = (edges & HDT_EDGE_SIBLING) && pi >= 0 ? pi : -3;  // my parent, for "same parent"
     const int pi_up = (edges & HDT_EDGE_UP) ? pi : -3;                   // my parent, for "is my parent"
@@ -409,7 +407,6 @@ __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int w
             }
             w[wd] = rowok ? out : 0u;
             cnt += __popc(w[wd]);
-            if (active && r < bm) bits[(size_t)c * words + (size_t)r * wpr + wd] = w[wd];
         }
     }
     EntryPart part;
@@ -443,6 +440,70 @@ __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int w
     return part;
 }
 
+// ---- the same evaluation with the entry's keys in LDS, lanes arranged as in the MFMA accumulator ------
+// Wave (wsub, khalf) takes row blocks 2*wsub, 2*wsub + 1 and the 32-key words of its half of the entry.
+// Inside a 32x32 sub-block lane l stands for row l%32 and the columns (l/32)*4 + 8*(e/4) + e%4, e = 0..15:
+// the wave ballot of test e IS lane mask e of the sub-block, four consecutive keys come with one 16-byte LDS
+// read, and pair count and summary are scalar operations on the ballots.  The row-major word of a row is put
+// together from the 16 results of its lane and the 16 of lane l + 32.  ek, ep: positions and parents of the
+// entry's bn keys (16-byte aligned, -1 where a slot holds no key); s_row: (position, parent) of the tile's rows,
+// position < 0 where there is no row.
+__device__ __forceinline__ EntryPart entry_bitmaps_lds(int64_t c, int wsub, int khalf, int lane, const int2 *s_row,
+                                                       const int *ek, const int *ep, int bm, int bn, int edges,
+                                                       unsigned long long *bits_rm)
+{
+    const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
+    const int hf = lane >> 5, l32 = lane & 31;
+    EntryPart part;
+    part.cnt = 0;
+    part.any = part.all = 0;
+    // rolled loops on purpose: the kernel runs once per compute unit and launch, so its instructions come from
+    // memory, and the unrolled form (28 KB of code) spent as long waiting for them as executing them
+#pragma unroll 1
+    for (int rr = 0; rr < 2; rr++) {
+        const int rblk = 2 * wsub + rr;
+        if (rblk >= nrb) continue;
+        const int2 me = s_row[rblk * 32 + l32];
+        // a row that does not exist, and a disabled edge kind, compare against a value no key carries
+        const bool rowok = me.x >= 0, has_parent = rowok && me.y >= 0;
+        const int i = rowok ? me.x : -3;
+        const int p_sib = (has_parent && (edges & HDT_EDGE_SIBLING)) ? me.y : -3;  // my parent, for "same parent"
+        const int p_up = (has_parent && (edges & HDT_EDGE_UP)) ? me.y : -3;        // my parent, for "is my parent"
+        const int i_down = (rowok && (edges & HDT_EDGE_DOWN)) ? me.x : -3;         // me, for "is my child"
+#pragma unroll 1
+        for (int cblk = 0; cblk < wpr; cblk++) {
+            if (!(khalf < 0 || (cblk * 2) / wpr == khalf)) continue;
+            unsigned long long any = 0, all = ~0ull;
+            int mine_lo = 0, mine_hi = 0, cnt = 0;  // lane e keeps mask e
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const int4 kj4 = *reinterpret_cast<const int4 *>(&ek[cblk * 32 + hf * 4 + 8 * q]);
+                const int4 kr4 = *reinterpret_cast<const int4 *>(&ep[cblk * 32 + hf * 4 + 8 * q]);
+                const int kj[4] = {kj4.x, kj4.y, kj4.z, kj4.w}, kr[4] = {kr4.x, kr4.y, kr4.z, kr4.w};
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const int e = 4 * q + j;
+                    // four compares into scalar masks, combined by scalar instructions
+                    const unsigned long long m = __ballot(kj[j] == i) | __ballot(kr[j] == p_sib) | __ballot(kj[j] == p_up) |
+                                                 __ballot(kr[j] == i_down);
+                    asm("v_writelane_b32 %0, %1, %2" : "+v"(mine_lo) : "s"((uint32_t)m), "n"(e));
+                    asm("v_writelane_b32 %0, %1, %2" : "+v"(mine_hi) : "s"((uint32_t)(m >> 32)), "n"(e));
+                    cnt += __popcll(m);
+                    any |= m;
+                    all &= m;
+                }
+            }
+            const unsigned long long mine = (unsigned long long)(uint32_t)mine_lo | ((unsigned long long)(uint32_t)mine_hi << 32);
+            const int sb = rblk * wpr + cblk;
+            if (lane < 16) bits_rm[((size_t)c * nsub + sb) * 16 + lane] = mine;
+            if (any != 0ull) part.any |= 1u << sb;
+            if (all == ~0ull) part.all |= 1u << sb;
+            part.cnt += cnt;
+        }
+    }
+    return part;
+}
+
 struct KeyListArgs {
     const int32_t *level, *parent;
     int n, bm, bn, tr, no_sort, edges;
@@ -450,14 +511,28 @@ struct KeyListArgs {
     int32_t *q_range;  // [B][tr][2]
     int32_t *c_row, *q_keys, *q_kpar, *c_cnt;
     int32_t *level_copy, *parent_copy;  // the layout's own copy of the ids (the key order is sorted from it on demand)
-    uint32_t *q_sub, *bits;
+    uint32_t *q_sub;
     unsigned long long *bits_rm;
     int32_t *counters;
     unsigned long long *report;
     uint32_t ticket;
 };
 
+// Workgroup barrier for data exchanged through LDS only: unlike __syncthreads() it does not wait for this
+// wave's global loads and stores (a store to HBM takes 2-3 us to be acknowledged).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Sets the hierarchy error flag and waits for it to be set (a returning atomic): what this thread does next,
+// a barrier in front of the workgroup's reservation, is then ordered behind it for the workgroup that reads
+// the flag after the last reservation.
+__device__ __forceinline__ void raise_error(int32_t *counters)
+{
+    const int old = atomicOr(&counters[CNT_ERR], 1);
+    asm volatile("" ::"v"(old));
+}
+
 constexpr int kListThreads = 1024, kListWaves = kListThreads / 64, kBatch = 8;
+constexpr int kLdsKeys = 2048;  // key lists up to this length stay in LDS between the packing and the bitmaps
 
 // ---- key lists: ONE kernel from level/parent to the finished entries, a workgroup per query tile ----
 // Key j is needed by the tile iff it is one of the tile's rows, the parent of one (bitmap over the
@@ -472,24 +547,43 @@ constexpr int kListThreads = 1024, kListWaves = kListThreads / 64, kBatch = 8;
 // hands out indices in document order.  The global key order is therefore not an input of this kernel.
 // The workgroup then evaluates its own entries pair by pair (bitmaps, lane masks, summaries), four waves
 // per entry.  It also validates its own rows.
+// A list of up to kLdsKeys keys is packed into LDS while the reservation (a returning device-scope atomic,
+// about 2 us) is in flight, copied to global memory from there, and evaluated from there; a longer list is
+// packed straight into global memory once the reservation is back and read again from there.
 __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
 {
     extern __shared__ uint32_t s_dyn[];  // [ceil(n/32)] parents of the tile's rows, then [2 * groups] needed positions
     __shared__ uint32_t s_rowok[4];      // valid rows of the tile
     __shared__ int2 s_row[128];          // (position, parent) of the tile's rows; position -2: no such row
     __shared__ int s_lcnt[kListWaves][kBuckets];  // needed keys per (wave, level), then their first index
-    __shared__ int s_cnt[kListWaves];
-    __shared__ uint32_t s_any[kListWaves], s_all[kListWaves];
+    __shared__ int s_cnt[2][kListWaves];  // partial results of an entry's four waves, by parity of the round
+    __shared__ uint32_t s_any[2][kListWaves], s_all[2][kListWaves];
     __shared__ int s_base, s_total;
+    __shared__ __attribute__((aligned(16))) int s_keys[kLdsKeys], s_kpar[kLdsKeys];
     const int b = blockIdx.x / a.tr, I = blockIdx.x - b * a.tr, n = a.n;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int bm = a.bm, bn = a.bn;
     const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
     const int pw = (n + 31) >> 5, ng = (n + 63) >> 6;
     uint32_t *s_par = s_dyn, *s_need = s_dyn + pw;
+    // kBatch groups of 64 positions at a time: all their loads are issued before the first is used, and those
+    // of the first batch before anything else
+    const int gpw = (ng + kListWaves - 1) / kListWaves;
+    const int g0 = min(wave * gpw, ng), g1 = min(g0 + gpw, ng);
+    int klv[kBatch], kp[kBatch];
+    auto load_batch = [&](int gb) {
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {
+            const int j = (gb + u) * 64 + lane;
+            const bool ok = gb + u < g1 && j < n;
+            klv[u] = ok ? level[j] : -1;
+            kp[u] = ok ? parent[j] : -1;
+        }
+    };
+    load_batch(g0);
     for (int w = tid; w < pw; w += kListThreads) s_par[w] = 0;
     if (tid < 4) s_rowok[tid] = 0;
-    __syncthreads();
+    lds_barrier();
     const int row0 = I * bm;
     bool check_parent = false;
     int my_parent = 0;
@@ -501,7 +595,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
             a.level_copy[(size_t)b * n + i] = l;
             a.parent_copy[(size_t)b * n + i] = p;
             if (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1))
-                atomicOr(&a.counters[CNT_ERR], 1);
+                raise_error(a.counters);
             else if (l >= 0) {
                 me = make_int2(i, p);
                 atomicOr(&s_rowok[tid >> 5], 1u << (tid & 31));
@@ -515,26 +609,13 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         s_row[tid] = me;
     }
     const int parent_level = check_parent ? level[my_parent] : 0;  // looked at once the scan is under way
-    __syncthreads();
-    const int gpw = (ng + kListWaves - 1) / kListWaves;
-    const int g0 = min(wave * gpw, ng), g1 = min(g0 + gpw, ng);
+    lds_barrier();
     auto in_tile = [&](int x) { return x >= row0 && x < row0 + bm && ((s_rowok[(x - row0) >> 5] >> ((x - row0) & 31)) & 1u); };
     auto is_par = [&](int x) { return (s_par[x >> 5] >> (x & 31)) & 1u; };
     const bool e_up = a.edges & HDT_EDGE_UP, e_sib = a.edges & HDT_EDGE_SIBLING, e_down = a.edges & HDT_EDGE_DOWN;
-    // kBatch groups of 64 positions at a time: all their loads are issued before the first is used
-    int klv[kBatch], kp[kBatch];
-    auto load_batch = [&](int gb) {
-#pragma unroll
-        for (int u = 0; u < kBatch; u++) {
-            const int j = (gb + u) * 64 + lane;
-            const bool ok = gb + u < g1 && j < n;
-            klv[u] = ok ? level[j] : -1;
-            kp[u] = ok ? parent[j] : -1;
-        }
-    };
     int lcount = 0;  // lane k: needed keys of level k in this wave's share
     for (int gb = g0; gb < g1; gb += kBatch) {
-        load_batch(gb);
+        if (gb != g0) load_batch(gb);
 #pragma unroll
         for (int u = 0; u < kBatch; u++) {
             if (gb + u >= g1) break;
@@ -554,8 +635,8 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     }
     const bool one_batch = g1 - g0 <= kBatch;  // the registers still hold the wave's whole share
     if (lane < kBuckets) s_lcnt[wave][lane] = lcount;
-    if (check_parent && parent_level < 0) atomicOr(&a.counters[CNT_ERR], 1);  // a parent must be a real position
-    __syncthreads();
+    if (check_parent && parent_level < 0) raise_error(a.counters);  // a parent must be a real position
+    lds_barrier();
     if (wave == 0) {  // first index of every (level, wave): level major, then wave
         int t = 0;
         if (lane < kBuckets) {
@@ -577,23 +658,67 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
                 run += c;
             }
         }
-        const int total = __shfl(incl, 63);
-        if (lane == 0) {
-            // this tile's slice of the per-entry arrays; the last workgroup to get here knows the final count
-            // and tells the host, which is waiting for exactly this word, while the lists and the bitmaps
-            // are still being written (no device-scope fence: it would write back the whole L2 of this XCD)
-            s_total = total;
-            int final_total;
-            s_base = reserve_entries(a.counters, (total + bn - 1) / bn, &final_total);
-            if (final_total >= 0) {
-                const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)final_total), __ATOMIC_RELEASE,
-                                   __HIP_MEMORY_SCOPE_SYSTEM);
+        if (lane == 63) s_total = incl;
+    }
+    lds_barrier();
+    const int total = s_total, n_ent = (total + bn - 1) / bn;
+    const bool in_lds = n_ent * bn <= kLdsKeys;
+    // This tile's slice of the per-entry arrays.  The last workgroup to reserve knows the final count and tells
+    // the host, which is waiting for exactly this word, while the lists and the bitmaps are still being
+    // written (no device-scope fence: it would write back the whole L2 of this XCD).
+    int reserved = 0, final_total = -1;
+    if (tid == 0) reserved = reserve_entries(a.counters, n_ent, &final_total);
+
+    // hands out the indices of this wave's needed keys, in document order inside every level
+    int mybase = lane < kBuckets ? s_lcnt[wave][lane] : 0;  // lane k: next index of level k in this wave
+    auto pack = [&](bool to_lds, int32_t *keys, int32_t *kpars, int key_fit) {
+        for (int gb = g0; gb < g1; gb += kBatch) {
+            if (!one_batch) load_batch(gb);
+#pragma unroll
+            for (int u = 0; u < kBatch; u++) {
+                if (gb + u >= g1) break;
+                const int g = gb + u;
+                const unsigned long long m = (unsigned long long)s_need[2 * g] | ((unsigned long long)s_need[2 * g + 1] << 32);
+                if (m == 0ull) continue;
+                const bool need = (m >> lane) & 1ull;
+                const int bucket = a.no_sort ? 0 : bucket_of(klv[u]);
+                int t = 0;
+                unsigned long long remaining = m;
+                while (remaining) {
+                    const int leader = __ffsll((long long)remaining) - 1;
+                    const int bk = __builtin_amdgcn_readlane(bucket, leader);
+                    const bool is_bk = need && bucket == bk;
+                    const unsigned long long mm = __ballot(is_bk);
+                    const int first = __builtin_amdgcn_readlane(mybase, bk);
+                    if (is_bk) t = first + __popcll(mm & lanemask_lt());
+                    if (lane == bk) mybase += __popcll(mm);
+                    remaining &= ~mm;
+                }
+                if (need) {
+                    if (to_lds) {
+                        s_keys[t] = g * 64 + lane;
+                        s_kpar[t] = kp[u];
+                    } else if (t < key_fit) {
+                        keys[t] = g * 64 + lane;
+                        kpars[t] = kp[u];
+                    }
+                }
             }
         }
+    };
+    if (in_lds) {  // while the reservation is in flight
+        for (int t = total + tid; t < n_ent * bn; t += kListThreads) s_keys[t] = s_kpar[t] = -1;  // tail of the last entry
+        pack(true, nullptr, nullptr, 0);
     }
-    __syncthreads();
-    const int total = s_total, n_ent = (total + bn - 1) / bn;
+    if (tid == 0) {
+        s_base = reserved;
+        if (final_total >= 0) {
+            const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)final_total), __ATOMIC_RELEASE,
+                               __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    lds_barrier();
     const int64_t base = s_base;
     const size_t row = (size_t)b * a.tr + I;
     if (tid == 0) {
@@ -606,77 +731,62 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     const int key_fit = n_fit * bn;
     for (int e = tid; e < n_fit; e += kListThreads) a.c_row[base + e] = (int32_t)row;
     int32_t *keys = a.q_keys + (size_t)base * bn, *kpars = a.q_kpar + (size_t)base * bn;
-    for (int t = total + tid; t < key_fit; t += kListThreads) keys[t] = -1;  // tail of the last entry
-    int mybase = lane < kBuckets ? s_lcnt[wave][lane] : 0;  // lane k: next index of level k in this wave
-    for (int gb = g0; gb < g1; gb += kBatch) {
-        if (!one_batch) load_batch(gb);
-#pragma unroll
-        for (int u = 0; u < kBatch; u++) {
-            if (gb + u >= g1) break;
-            const int g = gb + u;
-            const unsigned long long m = (unsigned long long)s_need[2 * g] | ((unsigned long long)s_need[2 * g + 1] << 32);
-            if (m == 0ull) continue;
-            const bool need = (m >> lane) & 1ull;
-            const int bucket = a.no_sort ? 0 : bucket_of(klv[u]);
-            int t = 0;
-            unsigned long long remaining = m;
-            while (remaining) {
-                const int leader = __ffsll((long long)remaining) - 1;
-                const int bk = __builtin_amdgcn_readlane(bucket, leader);
-                const bool is_bk = need && bucket == bk;
-                const unsigned long long mm = __ballot(is_bk);
-                const int first = __builtin_amdgcn_readlane(mybase, bk);
-                if (is_bk) t = first + __popcll(mm & lanemask_lt());
-                if (lane == bk) mybase += __popcll(mm);
-                remaining &= ~mm;
-            }
-            if (need && t < key_fit) {
-                keys[t] = g * 64 + lane;
-                kpars[t] = kp[u];
-            }
+    if (in_lds) {
+        for (int t = tid; t < key_fit; t += kListThreads) {
+            keys[t] = s_keys[t];
+            if (t < total) kpars[t] = s_kpar[t];
         }
-    }
-    // The entries of this tile, four waves each (two halves of the rows x two halves of the keys).  Their
-    // keys were written to global memory by other waves of this workgroup; the barrier orders those stores
-    // before the loads below at workgroup scope, which is all that is needed on one compute unit (the
-    // loads also bypass the vector cache).
-    __syncthreads();
-    const int wsub = wave & 1, khalf = (wave >> 1) & 1, quad = wave >> 2;
-    const int2 me = s_row[wsub * 64 + lane];
-    for (int e0 = 0; e0 < n_fit; e0 += kListWaves / 4) {
-        const int e = e0 + quad;
-        const bool active = e < n_fit;
-        int kpos[2], kparent[2];
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-            const int si = 64 * u + lane;
-            kpos[u] = -1;
-            kparent[u] = -1;
-            if (active && si < bn) {
-                const int kk = __hip_atomic_load(&keys[e * bn + si], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (kk >= 0 && kk < n) {  // a real key: its parent was written next to it
-                    kpos[u] = kk;
-                    kparent[u] = __hip_atomic_load(&kpars[e * bn + si], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-            }
-        }
-        const EntryPart part = entry_bitmaps(active, base + e, wsub, khalf, lane, me.x, me.y, me.x >= 0, kpos, kparent,
-                                             bm, bn, a.edges, a.bits, a.bits_rm);
-        __syncthreads();  // the previous round's partial results have been read
-        if (lane == 0) {
-            s_cnt[wave] = part.cnt;
-            s_any[wave] = part.any;
-            s_all[wave] = part.all;
-        }
+    } else {
+        for (int t = total + tid; t < key_fit; t += kListThreads) keys[t] = -1;
+        pack(false, keys, kpars, key_fit);
+        // The keys were written to global memory by other waves of this workgroup; the barrier orders those
+        // stores before the loads below at workgroup scope, which is all that is needed on one compute unit
+        // (the loads also bypass the vector cache).
         __syncthreads();
+    }
+    // The entries of this tile, four waves each (two halves of the rows x two halves of the keys), out of LDS:
+    // a list that did not fit is brought back four entries at a time.
+    const int wsub = wave & 1, khalf = (wave >> 1) & 1, quad = wave >> 2;
+    constexpr int kPerRound = kListWaves / 4;
+    int par = 0;
+    for (int e0 = 0; e0 < n_fit; e0 += kPerRound, par ^= 1) {
+        const int e = e0 + quad;
+        int kb = e * bn;  // the entry's first key in s_keys, s_kpar
+        if (!in_lds) {
+            lds_barrier();  // the previous round's keys have been read
+            for (int t = tid; t < kPerRound * bn; t += kListThreads) {
+                const int gi = e0 * bn + t;
+                int kk = -1, kq = -1;
+                if (gi < key_fit) kk = __hip_atomic_load(&keys[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (kk >= 0 && kk < n) kq = __hip_atomic_load(&kpars[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_keys[t] = (kk >= 0 && kk < n) ? kk : -1;
+                s_kpar[t] = kq;
+            }
+            lds_barrier();
+            kb = quad * bn;
+        }
+        const bool active = e < n_fit;
+        EntryPart part;
+        part.cnt = 0;
+        part.any = part.all = 0;
+        if (active)
+            part = entry_bitmaps_lds(base + e, wsub, khalf, lane, s_row, s_keys + kb, s_kpar + kb, bm, bn, a.edges,
+                                     a.bits_rm);
+        // the slots of this parity were last read two rounds ago, in front of the previous round's barrier
+        if (lane == 0) {
+            s_cnt[par][wave] = part.cnt;
+            s_any[par][wave] = part.any;
+            s_all[par][wave] = part.all;
+        }
+        lds_barrier();
         if (active && (wave & 3) == 0 && lane == 0) {
             int c = 0;
             uint32_t any = 0, all = 0;
 #pragma unroll
             for (int w = 0; w < 4; w++) {
-                c += s_cnt[wave + w];
-                any |= s_any[wave + w];
-                all |= s_all[wave + w];
+                c += s_cnt[par][wave + w];
+                any |= s_any[par][wave + w];
+                all |= s_all[par][wave + w];
             }
             a.c_cnt[base + e] = c;
             a.q_sub[base + e] = any | (all << 16);
@@ -694,7 +804,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
                                                       const int32_t *__restrict__ c_row,
                                                       const int32_t *__restrict__ c_col, int32_t *q_keys,
                                                       const int32_t *__restrict__ counters, int64_t capacity,
-                                                      int n, int n_slots, int bm, int bn, int tr, int edges, uint32_t *bits,
+                                                      int n, int n_slots, int bm, int bn, int tr, int edges,
                                                       unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
 {
     __shared__ int s_cnt[2];
@@ -727,7 +837,7 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
             kpar[u] = (okp && lv >= 0) ? pr : -1;
             if (wave == 0 && 64 * u + lane < bn) q_keys[(size_t)c * bn + 64 * u + lane] = kpos[u];
         }
-        const EntryPart part = entry_bitmaps(true, c, wave, -1, lane, i, pi, rowok, kpos, kpar, bm, bn, edges, bits, bits_rm);
+        const EntryPart part = entry_bitmaps(true, c, wave, -1, lane, i, pi, rowok, kpos, kpar, bm, bn, edges, bits_rm);
         __syncthreads();  // the previous candidate's partial results have been read
         if (lane == 0) {
             s_cnt[wave] = part.cnt;
@@ -831,7 +941,7 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int nchunks)
 
 struct Phase2 {
     int32_t *q_cols, *c_row, *c_cnt, *q_keys, *q_kpar;
-    uint32_t *q_sub, *bits;
+    uint32_t *q_sub;
     unsigned long long *bits_rm;
     size_t bytes;
 };
@@ -840,14 +950,13 @@ Phase2 carve_phase2(char *base, int64_t cap, int bm, int bn)
 {
     Carver c{base};
     Phase2 p;
-    const size_t n = (size_t)cap, words = (size_t)bm * (bn / 32), nsub = (size_t)(bm / 32) * (bn / 32);
+    const size_t n = (size_t)cap, nsub = (size_t)(bm / 32) * (bn / 32);
     p.q_cols = c.take<int32_t>(n);
     p.q_sub = c.take<uint32_t>(n);
     p.c_row = c.take<int32_t>(n);
     p.c_cnt = c.take<int32_t>(n);
     p.q_keys = c.take<int32_t>(n * (size_t)bn);
     p.q_kpar = c.take<int32_t>(n * (size_t)bn);
-    p.bits = c.take<uint32_t>(n * words);
     p.bits_rm = c.take<unsigned long long>(n * nsub * 16);
     p.bytes = c.off;
     return p;
@@ -1136,10 +1245,10 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 // one kernel from the ids to the finished entries; the global key order is not needed for it
                 // and is sorted from the layout's copy of the ids only when someone asks (hdt_layout_export)
                 KeyListArgs ka{d_level, d_parent, n, bm, bn, tr, no_sort, edges, cap, p.q_range, q.c_row, q.q_keys, q.q_kpar,
-                               q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits, q.bits_rm, p.counters, report,
+                               q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits_rm, p.counters, report,
                                ticket};
                 const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
-                if (lds > 48 * 1024)
+                if (lds > 32 * 1024)  // with the kernel's static arrays: beyond the 64 KB a launch gets by default
                     BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                   (int)lds));
                 HdtTimer t("hdt_layout_key_lists", st);
@@ -1149,7 +1258,7 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
                 hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(128), 0, st, d_level, d_parent, p.kperm, q.c_row,
-                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, edges, q.bits,
+                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, edges,
                                    q.bits_rm, q.c_cnt, q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
@@ -1192,7 +1301,6 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 s.q_cols = q.q_cols;
                 s.q_keys = q.q_keys;
                 s.q_sub = q.q_sub;
-                s.bits = q.bits;
                 s.bits_rm = q.bits_rm;
                 L->d_cnt = q.c_cnt;
                 L->d_row = q.c_row;
