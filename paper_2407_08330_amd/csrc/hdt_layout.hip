@@ -440,66 +440,66 @@ __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int w
     return part;
 }
 
-// ---- the same evaluation with the entry's keys in LDS, lanes arranged as in the MFMA accumulator ------
-// Wave (wsub, khalf) takes row blocks 2*wsub, 2*wsub + 1 and the 32-key words of its half of the entry.
-// Inside a 32x32 sub-block lane l stands for row l%32 and the columns (l/32)*4 + 8*(e/4) + e%4, e = 0..15:
-// the wave ballot of test e IS lane mask e of the sub-block, four consecutive keys come with one 16-byte LDS
-// read, and pair count and summary are scalar operations on the ballots.  The row-major word of a row is put
-// together from the 16 results of its lane and the 16 of lane l + 32.  ek, ep: positions and parents of the
-// entry's bn keys (16-byte aligned, -1 where a slot holds no key); s_row: (position, parent) of the tile's rows,
-// position < 0 where there is no row.
-__device__ __forceinline__ EntryPart entry_bitmaps_lds(int64_t c, int wsub, int khalf, int lane, const int2 *s_row,
-                                                       const int *ek, const int *ep, int bm, int bn, int edges,
-                                                       unsigned long long *bits_rm)
+// ---- bitmaps of a list entry by columns, one wave per 64 key slots ----------------------------------
+// Lane c stands for key slot k0 + c and builds that key's COLUMN of the tile: bit r%32 of col[r/32] <=> row r
+// may attend to it.  Rows see a key through their own parent in two ways - the key is that parent, or the
+// key has the same parent - so for both the rows are R(v) = {rows whose parent is v}, with v the key's
+// position or the key's parent; R is tabulated once per tile for the distinct parents of its rows (a
+// handful, since the tokens of a sentence share theirs).  The key itself and the key's own parent are
+// single rows.  The lane masks of the MFMA kernels need no transposition from there: mask e of sub-block
+// (rblk, cblk) is the column word of key 32*cblk + 8*(e/4) + e%4 (lanes 0..31) next to that of key
+// 32*cblk + 4 + 8*(e/4) + e%4 (lanes 32..63), so every lane stores its own words.
+struct ParentTable {
+    int n;
+    const int *v;         // [n] distinct parents of the tile's rows
+    const uint4 *rows;    // [n] the rows with that parent, 32 per word
+};
+
+__device__ __forceinline__ EntryPart entry_columns(int64_t c, int k0, int lane, const ParentTable &tab, const int *ek,
+                                                   const int *ep, int row0, int bm, int bn, int edges,
+                                                   unsigned long long *bits_rm)
 {
     const int wpr = bn >> 5, nrb = bm >> 5, nsub = nrb * wpr;
-    const int hf = lane >> 5, l32 = lane & 31;
+    const int k = k0 + lane;
+    const bool slot = k < bn;
+    const int kj = slot ? ek[k] : -1, kr = slot ? ep[k] : -1;  // -1: no key
+    const int v_up = (edges & HDT_EDGE_UP) ? kj : -1, v_sib = (edges & HDT_EDGE_SIBLING) ? kr : -1;
+    uint32_t col[4] = {0u, 0u, 0u, 0u};
+#pragma unroll 1
+    for (int t = 0; t < tab.n; t++) {
+        const int v = tab.v[t];  // >= 0
+        const bool hit = v_up == v || v_sib == v;
+        if (__ballot(hit) == 0ull) continue;
+        const uint4 r = tab.rows[t];
+        col[0] |= hit ? r.x : 0u;
+        col[1] |= hit ? r.y : 0u;
+        col[2] |= hit ? r.z : 0u;
+        col[3] |= hit ? r.w : 0u;
+    }
+    // the key itself; the key's parent (the key is that row's child).  A key or a key's parent inside the
+    // tile's range is a real position, hence a valid row.
+    const int r_self = kj - row0, r_down = (edges & HDT_EDGE_DOWN) ? kr - row0 : -1;
+    const bool has_self = kj >= 0 && r_self >= 0 && r_self < bm, has_down = kr >= 0 && r_down >= 0 && r_down < bm;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        if (has_self && (r_self >> 5) == w) col[w] |= 1u << (r_self & 31);
+        if (has_down && (r_down >> 5) == w) col[w] |= 1u << (r_down & 31);
+    }
     EntryPart part;
-    part.cnt = 0;
+    part.cnt = wave_sum(__popc(col[0]) + __popc(col[1]) + __popc(col[2]) + __popc(col[3]));
     part.any = part.all = 0;
-    // rolled loops on purpose: the kernel runs once per compute unit and launch, so its instructions come from
-    // memory, and the unrolled form (28 KB of code) spent as long waiting for them as executing them
-#pragma unroll 1
-    for (int rr = 0; rr < 2; rr++) {
-        const int rblk = 2 * wsub + rr;
-        if (rblk >= nrb) continue;
-        const int2 me = s_row[rblk * 32 + l32];
-        // a row that does not exist, and a disabled edge kind, compare against a value no key carries
-        const bool rowok = me.x >= 0, has_parent = rowok && me.y >= 0;
-        const int i = rowok ? me.x : -3;
-        const int p_sib = (has_parent && (edges & HDT_EDGE_SIBLING)) ? me.y : -3;  // my parent, for "same parent"
-        const int p_up = (has_parent && (edges & HDT_EDGE_UP)) ? me.y : -3;        // my parent, for "is my parent"
-        const int i_down = (rowok && (edges & HDT_EDGE_DOWN)) ? me.x : -3;         // me, for "is my child"
-#pragma unroll 1
-        for (int cblk = 0; cblk < wpr; cblk++) {
-            if (!(khalf < 0 || (cblk * 2) / wpr == khalf)) continue;
-            unsigned long long any = 0, all = ~0ull;
-            int mine_lo = 0, mine_hi = 0, cnt = 0;  // lane e keeps mask e
+    const int cblk = k >> 5, cc = k & 31, e = ((cc >> 3) << 2) | (cc & 3), hf = (cc >> 2) & 1;
+    uint32_t *rm32 = reinterpret_cast<uint32_t *>(bits_rm + (size_t)c * nsub * 16);
 #pragma unroll
-            for (int q = 0; q < 4; q++) {
-                const int4 kj4 = *reinterpret_cast<const int4 *>(&ek[cblk * 32 + hf * 4 + 8 * q]);
-                const int4 kr4 = *reinterpret_cast<const int4 *>(&ep[cblk * 32 + hf * 4 + 8 * q]);
-                const int kj[4] = {kj4.x, kj4.y, kj4.z, kj4.w}, kr[4] = {kr4.x, kr4.y, kr4.z, kr4.w};
-#pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    const int e = 4 * q + j;
-                    // four compares into scalar masks, combined by scalar instructions
-                    const unsigned long long m = __ballot(kj[j] == i) | __ballot(kr[j] == p_sib) | __ballot(kj[j] == p_up) |
-                                                 __ballot(kr[j] == i_down);
-                    asm("v_writelane_b32 %0, %1, %2" : "+v"(mine_lo) : "s"((uint32_t)m), "n"(e));
-                    asm("v_writelane_b32 %0, %1, %2" : "+v"(mine_hi) : "s"((uint32_t)(m >> 32)), "n"(e));
-                    cnt += __popcll(m);
-                    any |= m;
-                    all &= m;
-                }
-            }
-            const unsigned long long mine = (unsigned long long)(uint32_t)mine_lo | ((unsigned long long)(uint32_t)mine_hi << 32);
-            const int sb = rblk * wpr + cblk;
-            if (lane < 16) bits_rm[((size_t)c * nsub + sb) * 16 + lane] = mine;
-            if (any != 0ull) part.any |= 1u << sb;
-            if (all == ~0ull) part.all |= 1u << sb;
-            part.cnt += cnt;
-        }
+    for (int rblk = 0; rblk < 4; rblk++) {
+        if (rblk >= nrb) break;
+        if (slot) rm32[((size_t)(rblk * wpr + cblk) * 16 + e) * 2 + hf] = col[rblk];
+        const unsigned long long any = __ballot(col[rblk] != 0u), all = __ballot(col[rblk] == 0xffffffffu);
+        const int sb = rblk * wpr + (k0 >> 5);  // lanes 0..31: sub-block sb, lanes 32..63: sb + 1
+        if ((uint32_t)any) part.any |= 1u << sb;
+        if ((uint32_t)(any >> 32)) part.any |= 2u << sb;
+        if ((uint32_t)all == 0xffffffffu) part.all |= 1u << sb;
+        if ((uint32_t)(all >> 32) == 0xffffffffu) part.all |= 2u << sb;
     }
     return part;
 }
@@ -553,13 +553,14 @@ constexpr int kLdsKeys = 2048;  // key lists up to this length stay in LDS betwe
 __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
 {
     extern __shared__ uint32_t s_dyn[];  // [ceil(n/32)] parents of the tile's rows, then [2 * groups] needed positions
-    __shared__ uint32_t s_rowok[4];      // valid rows of the tile
     __shared__ int2 s_row[128];          // (position, parent) of the tile's rows; position -2: no such row
     __shared__ int s_lcnt[kListWaves][kBuckets];  // needed keys per (wave, level), then their first index
     __shared__ int s_cnt[2][kListWaves];  // partial results of an entry's four waves, by parity of the round
     __shared__ uint32_t s_any[2][kListWaves], s_all[2][kListWaves];
-    __shared__ int s_base, s_total;
+    __shared__ int s_base, s_total, s_wtotal[kListWaves];
     __shared__ __attribute__((aligned(16))) int s_keys[kLdsKeys], s_kpar[kLdsKeys];
+    __shared__ int s_tab_v[128], s_ntab;  // distinct parents of the tile's rows, and the rows of each
+    __shared__ uint4 s_tab_rows[128];
     const int b = blockIdx.x / a.tr, I = blockIdx.x - b * a.tr, n = a.n;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int bm = a.bm, bn = a.bn;
@@ -582,7 +583,6 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     };
     load_batch(g0);
     for (int w = tid; w < pw; w += kListThreads) s_par[w] = 0;
-    if (tid < 4) s_rowok[tid] = 0;
     lds_barrier();
     const int row0 = I * bm;
     bool check_parent = false;
@@ -598,7 +598,6 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
                 raise_error(a.counters);
             else if (l >= 0) {
                 me = make_int2(i, p);
-                atomicOr(&s_rowok[tid >> 5], 1u << (tid & 31));
                 if (p >= 0) {
                     atomicOr(&s_par[p >> 5], 1u << (p & 31));
                     check_parent = true;
@@ -610,33 +609,74 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     }
     const int parent_level = check_parent ? level[my_parent] : 0;  // looked at once the scan is under way
     lds_barrier();
-    auto in_tile = [&](int x) { return x >= row0 && x < row0 + bm && ((s_rowok[(x - row0) >> 5] >> ((x - row0) & 31)) & 1u); };
-    auto is_par = [&](int x) { return (s_par[x >> 5] >> (x & 31)) & 1u; };
+    if (wave == kListWaves - 1) {  // the table of the rows' parents (see entry_columns)
+        const int2 ra = s_row[lane], rb = s_row[64 + lane];
+        const int pa = ra.x >= 0 ? ra.y : -1, pb = rb.x >= 0 ? rb.y : -1;
+        unsigned long long rem_a = __ballot(pa >= 0), rem_b = __ballot(pb >= 0);
+        int nt = 0;
+        while (rem_a | rem_b) {
+            const int v = rem_a ? __builtin_amdgcn_readlane(pa, __ffsll((long long)rem_a) - 1)
+                                : __builtin_amdgcn_readlane(pb, __ffsll((long long)rem_b) - 1);
+            const unsigned long long ma = __ballot(pa == v), mb = __ballot(pb == v);
+            if (lane == 0) {
+                s_tab_v[nt] = v;
+                s_tab_rows[nt] = make_uint4((uint32_t)ma, (uint32_t)(ma >> 32), (uint32_t)mb, (uint32_t)(mb >> 32));
+            }
+            rem_a &= ~ma;
+            rem_b &= ~mb;
+            nt++;
+        }
+        if (lane == 0) s_ntab = nt;
+    }
+    // A key is a real position, and so is the parent of one (or the build fails on the hierarchy): for both, being
+    // a row of the tile is a matter of the range alone.  The two bitmap lookups are issued for every position,
+    // needed or not, so that the loads of a whole batch are in flight together.
+    auto in_tile = [&](int x) { return (unsigned)(x - row0) < (unsigned)bm; };
     const bool e_up = a.edges & HDT_EDGE_UP, e_sib = a.edges & HDT_EDGE_SIBLING, e_down = a.edges & HDT_EDGE_DOWN;
     int lcount = 0;  // lane k: needed keys of level k in this wave's share
+    int wtotal = 0;  // needed keys in this wave's share
     for (int gb = g0; gb < g1; gb += kBatch) {
         if (gb != g0) load_batch(gb);
+        bool need[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {  // groups past the share were loaded as pads
+            const int j = (gb + u) * 64 + lane, pj = kp[u];
+            const bool real = klv[u] >= 0 && j < n, has_parent = pj >= 0 && pj < n;
+            const int jc = real ? j : 0, pc = has_parent ? pj : 0;
+            const uint32_t wj = s_par[jc >> 5], wp = s_par[pc >> 5];
+            const bool by_self = in_tile(j) | (e_up & (bool)((wj >> (jc & 31)) & 1u));
+            const bool by_parent = has_parent & ((e_down & in_tile(pj)) | (e_sib & (bool)((wp >> (pc & 31)) & 1u)));
+            need[u] = real & (by_self | by_parent);
+        }
 #pragma unroll
         for (int u = 0; u < kBatch; u++) {
             if (gb + u >= g1) break;
-            const int j = (gb + u) * 64 + lane, pj = kp[u];
-            bool need = false;
-            if (klv[u] >= 0 && j < n) {
-                need = in_tile(j) || (e_up && is_par(j));
-                if (!need && pj >= 0 && pj < n) need = (e_down && in_tile(pj)) || (e_sib && is_par(pj));
-            }
-            const unsigned long long m = __ballot(need);
+            const unsigned long long m = __ballot(need[u]);
             if (lane == 0) {
                 s_need[2 * (gb + u)] = (uint32_t)m;
                 s_need[2 * (gb + u) + 1] = (uint32_t)(m >> 32);
             }
-            if (m != 0ull) lcount += wave_bucket_count(need, a.no_sort ? 0 : bucket_of(klv[u]));
+            wtotal += __popcll(m);
+            if (m != 0ull) lcount += wave_bucket_count(need[u], a.no_sort ? 0 : bucket_of(klv[u]));
         }
     }
     const bool one_batch = g1 - g0 <= kBatch;  // the registers still hold the wave's whole share
     if (lane < kBuckets) s_lcnt[wave][lane] = lcount;
+    if (lane == 0) s_wtotal[wave] = wtotal;
     if (check_parent && parent_level < 0) raise_error(a.counters);  // a parent must be a real position
     lds_barrier();
+    // This tile's slice of the per-entry arrays: reserved by wave 1 as soon as the length of the list is known,
+    // used once the list has been packed.  The last workgroup to reserve knows the final count and tells the
+    // host, which is waiting for exactly this word, while the lists and the bitmaps are still being written (no
+    // device-scope fence: it would write back the whole L2 of this XCD).
+    int reserved = 0, final_total = -1;
+    if (wave == 1) {
+        const int total = wave_sum(lane < kListWaves ? s_wtotal[lane] : 0);
+        if (lane == 0) {
+            s_total = total;
+            reserved = reserve_entries(a.counters, (total + bn - 1) / bn, &final_total);
+        }
+    }
     if (wave == 0) {  // first index of every (level, wave): level major, then wave
         int t = 0;
         if (lane < kBuckets) {
@@ -658,17 +698,10 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
                 run += c;
             }
         }
-        if (lane == 63) s_total = incl;
     }
     lds_barrier();
     const int total = s_total, n_ent = (total + bn - 1) / bn;
     const bool in_lds = n_ent * bn <= kLdsKeys;
-    // This tile's slice of the per-entry arrays.  The last workgroup to reserve knows the final count and tells
-    // the host, which is waiting for exactly this word, while the lists and the bitmaps are still being
-    // written (no device-scope fence: it would write back the whole L2 of this XCD).
-    int reserved = 0, final_total = -1;
-    if (tid == 0) reserved = reserve_entries(a.counters, n_ent, &final_total);
-
     // hands out the indices of this wave's needed keys, in document order inside every level
     int mybase = lane < kBuckets ? s_lcnt[wave][lane] : 0;  // lane k: next index of level k in this wave
     auto pack = [&](bool to_lds, int32_t *keys, int32_t *kpars, int key_fit) {
@@ -710,7 +743,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         for (int t = total + tid; t < n_ent * bn; t += kListThreads) s_keys[t] = s_kpar[t] = -1;  // tail of the last entry
         pack(true, nullptr, nullptr, 0);
     }
-    if (tid == 0) {
+    if (tid == 64) {
         s_base = reserved;
         if (final_total >= 0) {
             const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -744,17 +777,21 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         // (the loads also bypass the vector cache).
         __syncthreads();
     }
-    // The entries of this tile, four waves each (two halves of the rows x two halves of the keys), out of LDS:
-    // a list that did not fit is brought back four entries at a time.
-    const int wsub = wave & 1, khalf = (wave >> 1) & 1, quad = wave >> 2;
-    constexpr int kPerRound = kListWaves / 4;
+    // The entries of this tile out of LDS, one wave per 64 key slots; a list that did not fit is brought back
+    // one round of entries at a time.
+    const int wpe = (bn + 63) >> 6, per_round = kListWaves / wpe;  // waves per entry, entries per round
+    const int quad = wave / wpe, k0 = (wave - quad * wpe) * 64;
+    ParentTable tab;
+    tab.n = s_ntab;
+    tab.v = s_tab_v;
+    tab.rows = s_tab_rows;
     int par = 0;
-    for (int e0 = 0; e0 < n_fit; e0 += kPerRound, par ^= 1) {
+    for (int e0 = 0; e0 < n_fit; e0 += per_round, par ^= 1) {
         const int e = e0 + quad;
         int kb = e * bn;  // the entry's first key in s_keys, s_kpar
         if (!in_lds) {
             lds_barrier();  // the previous round's keys have been read
-            for (int t = tid; t < kPerRound * bn; t += kListThreads) {
+            for (int t = tid; t < per_round * bn; t += kListThreads) {
                 const int gi = e0 * bn + t;
                 int kk = -1, kq = -1;
                 if (gi < key_fit) kk = __hip_atomic_load(&keys[gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -769,27 +806,25 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         EntryPart part;
         part.cnt = 0;
         part.any = part.all = 0;
-        if (active)
-            part = entry_bitmaps_lds(base + e, wsub, khalf, lane, s_row, s_keys + kb, s_kpar + kb, bm, bn, a.edges,
-                                     a.bits_rm);
-        // the slots of this parity were last read two rounds ago, in front of the previous round's barrier
+        if (active) part = entry_columns(base + e, k0, lane, tab, s_keys + kb, s_kpar + kb, row0, bm, bn, a.edges, a.bits_rm);
+        if (wpe == 1) {
+            if (active && lane == 0) {
+                a.c_cnt[base + e] = part.cnt;
+                a.q_sub[base + e] = part.any | (part.all << 16);
+            }
+            continue;
+        }
+        // two waves per entry: the slots of this parity were last read two rounds ago, in front of the previous
+        // round's barrier
         if (lane == 0) {
             s_cnt[par][wave] = part.cnt;
             s_any[par][wave] = part.any;
             s_all[par][wave] = part.all;
         }
         lds_barrier();
-        if (active && (wave & 3) == 0 && lane == 0) {
-            int c = 0;
-            uint32_t any = 0, all = 0;
-#pragma unroll
-            for (int w = 0; w < 4; w++) {
-                c += s_cnt[par][wave + w];
-                any |= s_any[par][wave + w];
-                all |= s_all[par][wave + w];
-            }
-            a.c_cnt[base + e] = c;
-            a.q_sub[base + e] = any | (all << 16);
+        if (active && k0 == 0 && lane == 0) {
+            a.c_cnt[base + e] = s_cnt[par][wave] + s_cnt[par][wave + 1];
+            a.q_sub[base + e] = (s_any[par][wave] | s_any[par][wave + 1]) | ((s_all[par][wave] | s_all[par][wave + 1]) << 16);
         }
     }
 }
