@@ -516,6 +516,7 @@ struct KeyListArgs {
     int32_t *counters;
     unsigned long long *report;
     uint32_t ticket;
+    int self_reset;  // the counters are a slot that must be zero again when the build has reported
 };
 
 // Workgroup barrier for data exchanged through LDS only: unlike __syncthreads() it does not wait for this
@@ -609,25 +610,6 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     }
     const int parent_level = check_parent ? level[my_parent] : 0;  // looked at once the scan is under way
     lds_barrier();
-    if (wave == kListWaves - 1) {  // the table of the rows' parents (see entry_columns)
-        const int2 ra = s_row[lane], rb = s_row[64 + lane];
-        const int pa = ra.x >= 0 ? ra.y : -1, pb = rb.x >= 0 ? rb.y : -1;
-        unsigned long long rem_a = __ballot(pa >= 0), rem_b = __ballot(pb >= 0);
-        int nt = 0;
-        while (rem_a | rem_b) {
-            const int v = rem_a ? __builtin_amdgcn_readlane(pa, __ffsll((long long)rem_a) - 1)
-                                : __builtin_amdgcn_readlane(pb, __ffsll((long long)rem_b) - 1);
-            const unsigned long long ma = __ballot(pa == v), mb = __ballot(pb == v);
-            if (lane == 0) {
-                s_tab_v[nt] = v;
-                s_tab_rows[nt] = make_uint4((uint32_t)ma, (uint32_t)(ma >> 32), (uint32_t)mb, (uint32_t)(mb >> 32));
-            }
-            rem_a &= ~ma;
-            rem_b &= ~mb;
-            nt++;
-        }
-        if (lane == 0) s_ntab = nt;
-    }
     // A key is a real position, and so is the parent of one (or the build fails on the hierarchy): for both, being
     // a row of the tile is a matter of the range alone.  The two bitmap lookups are issued for every position,
     // needed or not, so that the loads of a whole batch are in flight together.
@@ -676,6 +658,25 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
             s_total = total;
             reserved = reserve_entries(a.counters, (total + bn - 1) / bn, &final_total);
         }
+    }
+    if (wave == 2) {  // meanwhile: the table of the rows' parents (see entry_columns)
+        const int2 ra = s_row[lane], rb = s_row[64 + lane];
+        const int pa = ra.x >= 0 ? ra.y : -1, pb = rb.x >= 0 ? rb.y : -1;
+        unsigned long long rem_a = __ballot(pa >= 0), rem_b = __ballot(pb >= 0);
+        int nt = 0;
+        while (rem_a | rem_b) {
+            const int v = rem_a ? __builtin_amdgcn_readlane(pa, __ffsll((long long)rem_a) - 1)
+                                : __builtin_amdgcn_readlane(pb, __ffsll((long long)rem_b) - 1);
+            const unsigned long long ma = __ballot(pa == v), mb = __ballot(pb == v);
+            if (lane == 0) {
+                s_tab_v[nt] = v;
+                s_tab_rows[nt] = make_uint4((uint32_t)ma, (uint32_t)(ma >> 32), (uint32_t)mb, (uint32_t)(mb >> 32));
+            }
+            rem_a &= ~ma;
+            rem_b &= ~mb;
+            nt++;
+        }
+        if (lane == 0) s_ntab = nt;
     }
     if (wave == 0) {  // first index of every (level, wave): level major, then wave
         int t = 0;
@@ -747,6 +748,11 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         s_base = reserved;
         if (final_total >= 0) {
             const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.self_reset) {  // nobody touches the counters after the last reservation: clear them for the next build
+                __hip_atomic_store(&a.counters[CNT_ERR], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(reinterpret_cast<unsigned long long *>(a.counters + CNT_CAND), 0ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
             __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)final_total), __ATOMIC_RELEASE,
                                __HIP_MEMORY_SCOPE_SYSTEM);
         }
@@ -1020,6 +1026,29 @@ unsigned long long *report_slot(uint32_t *ticket)
     return g_reports + (size_t)(g_ticket % kReportSlots) * 8;  // one 64-byte line per slot
 }
 
+// The counters of a key-list build: device memory, one 256-byte slot per build in flight (chosen by the
+// ticket, like the report word), zero whenever no build owns it: the kernel's last workgroup clears the slot
+// before it reports, so a build needs no clearing launch of its own.  Never freed.
+constexpr int kCounterDevices = 64;
+int32_t *g_counter_slots[kCounterDevices] = {};
+
+int32_t *counter_slot(int device, uint32_t ticket)
+{
+    if (device < 0 || device >= kCounterDevices) return nullptr;
+    std::lock_guard<std::mutex> lk(g_pool_mutex);
+    if (!g_counter_slots[device]) {
+        void *ptr = nullptr;
+        const size_t bytes = (size_t)kReportSlots * 64 * sizeof(int32_t);
+        if (hipMalloc(&ptr, bytes) != hipSuccess || hipMemset(ptr, 0, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            if (ptr) (void)hipFree(ptr);
+            return nullptr;
+        }
+        g_counter_slots[device] = static_cast<int32_t *>(ptr);
+    }
+    return g_counter_slots[device] + (size_t)(ticket % kReportSlots) * 64;
+}
+
 // polls the word until it carries this build's ticket; false after 10 s without it
 bool wait_for_report(const unsigned long long *slot, uint32_t ticket, unsigned long long *word)
 {
@@ -1259,7 +1288,11 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 status = hdt_fail(HDT_ERR_OOM, "hdt_build_layout: no pinned host memory for the build report");
                 goto fail;
             }
-            BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
+            // the windowed kernels count in the arena, cleared here; a key-list build counts in a slot that is
+            // already clear (if there is none, in the arena as well)
+            int32_t *slot_counters = windowed ? nullptr : counter_slot(L->device, ticket);
+            if (!slot_counters)
+                BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
             if (windowed) {
                 SortArgs sa{d_level, d_parent, n, s.n_slots, nchunks, no_sort, p.hist, p.kperm, p.slot, p.cmin,
                             p.cmax, p.counters, 1};
@@ -1280,8 +1313,8 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 // one kernel from the ids to the finished entries; the global key order is not needed for it
                 // and is sorted from the layout's copy of the ids only when someone asks (hdt_layout_export)
                 KeyListArgs ka{d_level, d_parent, n, bm, bn, tr, no_sort, edges, cap, p.q_range, q.c_row, q.q_keys, q.q_kpar,
-                               q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits_rm, p.counters, report,
-                               ticket};
+                               q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits_rm,
+                               slot_counters ? slot_counters : p.counters, report, ticket, slot_counters != nullptr};
                 const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
                 if (lds > 32 * 1024)  // with the kernel's static arrays: beyond the 64 KB a launch gets by default
                     BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1303,11 +1336,18 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
             // draining the stream, so the bitmap kernel and whatever the caller enqueues next keep the GPU busy.
             unsigned long long word = 0;
             if (!wait_for_report(report, ticket, &word)) {
-                // no word within the time limit: drain the stream and read the counters the slow way
-                int32_t cnt[4] = {0, 0, 0, 0};
+                // no word within the time limit: drain the stream and look again, then read the counters the slow way
                 BUILD_TRY(hipStreamSynchronize(st));
-                BUILD_TRY(hipMemcpy(cnt, p.counters, sizeof(cnt), hipMemcpyDeviceToHost));
-                word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);  // low word of the combined counter
+                word = __atomic_load_n(report, __ATOMIC_ACQUIRE);
+                if ((uint32_t)(word >> 40) != ticket) {
+                    if (slot_counters) {
+                        status = hdt_fail(HDT_ERR_HIP, "hdt_build_layout: the build kernel finished without its report");
+                        goto fail;
+                    }
+                    int32_t cnt[4] = {0, 0, 0, 0};
+                    BUILD_TRY(hipMemcpy(cnt, p.counters, sizeof(cnt), hipMemcpyDeviceToHost));
+                    word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);  // low word of the combined counter
+                }
             }
             if ((word >> 39) & 1u) {
                 BUILD_TRY(hipStreamSynchronize(st));  // the bitmap kernel still reads the arenas
