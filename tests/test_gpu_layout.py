@@ -96,6 +96,27 @@ def test_layout_force_dense_and_no_sort(oracle):
         compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, windowed=windowed, use_sort=False)
 
 
+@pytest.mark.parametrize("bm,bn", [(128, 64), (64, 32), (96, 128)])
+@pytest.mark.parametrize("n_children", [1500, 2999])
+def test_layout_one_parent_with_thousands_of_children(oracle, n_children, bm, bn):
+    # every tile's key list holds the root and all its children: 1501 keys still fit the kernel's on-chip copy
+    # of a list (several rounds of entries), 3000 do not (the list goes through global memory); sample 1 is an
+    # ordinary document, so both kinds of tile meet in one launch
+    n = 3072
+    level = np.full((2, n), -1, np.int32)
+    parent = np.full((2, n), -1, np.int32)
+    level[0, 0] = 0
+    level[0, 1:1 + n_children] = 1
+    parent[0, 1:1 + n_children] = 0
+    wl = inputs.make_workload(1, batch=1)
+    level[1, :wl.n_pos] = wl.level[0]
+    parent[1, :wl.n_pos] = wl.parent[0]
+    say(f"[layout] root with {n_children} children, tile {bm}x{bn}")
+    lay = _build(level, parent, tile_m=bm, tile_n=bn)
+    tiles, nnz = compare_layout(oracle, lay, level, parent, bm, bn)
+    assert nnz >= (n_children + 1) ** 2
+
+
 @pytest.mark.parametrize("log2n,n_sections", [(17, 120), (19, 500)])
 def test_layout_long_documents_need_a_large_slot_bitmap(oracle, log2n, n_sections):
     # 2^17 / 2^19 (the largest accepted) positions: the key-list kernel's bitmaps over the positions take
