@@ -2,36 +2,40 @@
 //
 // What is computed is fixed by the paper (Sec. 3.2: a position attends to parent, siblings and
 // children; App. A.1, Alg. 1: sort keys by hierarchy level, partition into blocks, process a block
-// only if its mask has a non-zero entry).  How it is computed is ours.  Four small kernels per build:
+// only if its mask has a non-zero entry).  How it is computed is ours.  Two kinds of schedule:
 //
-//  sort_count / sort_scatter (one workgroup per 1024 positions)
-//   1. key order: stable counting sort by level with wave ballots; the first kernel counts the levels
-//      of every chunk, the second turns the counts into each chunk's first slot per level and hands
-//      out the slots in document order;
-//   2. per anchor, the range of sorted slots its children occupy (integer atomic min/max, one
-//      pair of atomics per run of consecutive children);
-//  key_lists (default; one workgroup per query tile)
-//   3. the key list of the query tile: every allowed key of a row lies in one of <= 2 slot ranges
-//      (its siblings = the children of its parent, and its own children) or is one of 2 single
-//      slots (itself, its parent), so a row marks O(1) ranges in a bitmap over the key order instead
-//      of testing n keys; every marked slot is then tested exactly against the rows of the tile (for
-//      documents laid out in pre-order the ranges are already exact, for other forests they are a
-//      superset), and the surviving slots are packed, in key order, into entries of tile_n keys;
-//  candidates (windowed layouts; one wave per query tile)
-//   3'. the same marking on the granularity of key windows: the candidate windows of the query tile;
-//   4. either kernel reserves a slice of the per-tile arrays with one atomic add per workgroup and
-//      writes its entries there: these ARE the tile lists (first/last entry per query tile);
-//  tile_bitmaps (grid-stride over entries)
-//   5. every entry is evaluated exactly, pair by pair (bitmap, pair count, 32x32 sub-block summary,
-//      and for windowed layouts the positions behind its key slots), so the result never depends on
-//      step 3 being tight.  A windowed candidate without any allowed pair keeps its list entry with an
-//      all-zero summary, which every kernel skips; it is not counted as a tile and hdt_layout_export
-//      leaves it out.
+//  key lists (the default): ONE kernel, key_lists, a workgroup per query tile.  It finds the keys the
+//   tile's rows may attend to by scanning level[] / parent[] of the sample once, packs them in key order
+//   (by level, ties in document order) into entries of tile_n keys, reserves the tile's slice of the
+//   per-entry arrays with one atomic, and evaluates its entries exactly, by key columns (lane masks for
+//   the MFMA kernels, pair count, 32x32 sub-block summary).  See the comment at the kernel.
 //
-// The per-tile arrays are sized before the number of candidates is known (a heuristic, raised by
-// what earlier builds needed); the kernels check the capacity.  The candidate kernel reports the count
-// (and whether the hierarchy was valid) through one word of pinned host memory as soon as it is
-// known; the host waits for that word only, not for the stream, and repeats the build with the exact
+//  windowed (Alg. 1 as printed: the key tiles are windows of the globally sorted key order; also the
+//  dense baseline): four kernels.
+//   sort_count / sort_scatter (one workgroup per 1024 positions)
+//    1. key order: stable counting sort by level with wave ballots; the first kernel counts the levels
+//       of every chunk, the second turns the counts into each chunk's first slot per level and hands
+//       out the slots in document order;
+//    2. per anchor, the range of sorted slots its children occupy (integer atomic min/max, one
+//       pair of atomics per run of consecutive children);
+//   candidates (one wave per query tile)
+//    3. every allowed key of a row lies in one of <= 2 slot ranges (its siblings = the children of its
+//       parent, and its own children) or is one of 2 single slots (itself, its parent), so a row marks
+//       O(1) ranges in a bitmap over the key windows: the candidate windows of the query tile (exact for
+//       documents laid out in pre-order, a superset for other forests); the workgroup reserves a slice
+//       of the per-entry arrays with one atomic add and writes its candidates there;
+//   tile_bitmaps (grid-stride over candidates)
+//    4. every candidate is evaluated exactly, pair by pair (lane masks, pair count, sub-block summary,
+//       the positions behind its key slots), so the result never depends on step 3 being tight.  A
+//       candidate without any allowed pair keeps its list entry with an all-zero summary, which every
+//       kernel skips; it is not counted as a tile and hdt_layout_export leaves it out.
+//  The same two sort kernels produce the global key order of a key-list layout when hdt_layout_export
+//  asks for it.
+//
+// The per-entry arrays are sized before the number of entries is known (a heuristic, raised by what
+// earlier builds needed); the kernels check the capacity.  The kernel that reserves the entries reports
+// the count (and whether the hierarchy was valid) through one word of pinned host memory as soon as it
+// is known; the host waits for that word only, not for the stream, and repeats the build with the exact
 // size in the rare case the guess was too small.
 // Device memory comes from a small cache of earlier layouts' buffers.
 #include <limits.h>
@@ -367,15 +371,15 @@ __global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
     }
 }
 
-// ---- exact evaluation of one list entry by two or four waves ---------------------------------------
+// ---- exact evaluation of one list entry pair by pair, by two waves (windowed layouts) ---------------
 // Wave `wsub` (0 or 1) holds rows 64*wsub + lane of the query tile (position i, parent pi, rowok = a
 // real position) and evaluates them against all keys (khalf < 0) or against one half of the entry's
 // 32-key words (khalf = 0, 1); every wave holds the entry's keys, lane l the slots l and 64 + l (position
 // and parent, -1 where the slot holds no key), which are broadcast by lane index while each lane tests
-// its row against every key.  Outputs of entry c: the row-major bitmap (export, fp32 path), per 32x32
-// sub-block the 16 x 64-bit lane masks the MFMA kernels apply to their accumulator registers (wave
-// ballots), and through `part` (this wave's slot of a pair's scratch in LDS) the pair count and the
-// sub-block summary, which the caller adds up after a barrier.
+// its row against every key.  Outputs of entry c: per 32x32 sub-block the 16 x 64-bit lane masks the
+// MFMA kernels apply to their accumulator registers (wave ballots), and through `part` (this wave's slot
+// of a pair's scratch in LDS) the pair count and the sub-block summary, which the caller adds up after
+// a barrier.
 struct EntryPart {
     int cnt;
     uint32_t any, all;
@@ -546,8 +550,8 @@ constexpr int kLdsKeys = 2048;  // key lists up to this length stay in LDS betwe
 // needed keys only: every wave counts the levels in its contiguous share, the counts are turned into
 // first indices (level major, then wave), and after the workgroup has reserved its entries each wave
 // hands out indices in document order.  The global key order is therefore not an input of this kernel.
-// The workgroup then evaluates its own entries pair by pair (bitmaps, lane masks, summaries), four waves
-// per entry.  It also validates its own rows.
+// The workgroup then evaluates its own entries by key columns (entry_columns: lane masks, pair counts,
+// summaries), one wave per 64 key slots.  It also validates its own rows.
 // A list of up to kLdsKeys keys is packed into LDS while the reservation (a returning device-scope atomic,
 // about 2 us) is in flight, copied to global memory from there, and evaluated from there; a longer list is
 // packed straight into global memory once the reservation is back and read again from there.
@@ -556,7 +560,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     extern __shared__ uint32_t s_dyn[];  // [ceil(n/32)] parents of the tile's rows, then [2 * groups] needed positions
     __shared__ int2 s_row[128];          // (position, parent) of the tile's rows; position -2: no such row
     __shared__ int s_lcnt[kListWaves][kBuckets];  // needed keys per (wave, level), then their first index
-    __shared__ int s_cnt[2][kListWaves];  // partial results of an entry's four waves, by parity of the round
+    __shared__ int s_cnt[2][kListWaves];  // partial results of an entry's two waves (tile_n > 64), by parity of the round
     __shared__ uint32_t s_any[2][kListWaves], s_all[2][kListWaves];
     __shared__ int s_base, s_total, s_wtotal[kListWaves];
     __shared__ __attribute__((aligned(16))) int s_keys[kLdsKeys], s_kpar[kLdsKeys];
