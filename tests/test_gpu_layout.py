@@ -220,6 +220,33 @@ def test_layout_rejects_bad_hierarchies():
         assert e.value.name == "HDT_ERR_HIERARCHY", name
 
 
+def test_layout_many_builds_in_a_row_share_the_counter_slots(oracle):
+    # a key-list build counts in one of 64 device slots that its kernel clears before it reports: 150 builds,
+    # different inputs in turn and a rejected hierarchy now and then, must each see a clear slot
+    import paper_2407_08330_amd as hdt
+    a = inputs.make_workload(1, batch=2)
+    b = inputs.make_workload(2, batch=1)
+    bad_l = np.array([[0, 1, 2, 3, -1, -1]], np.int32)
+    bad_p = np.array([[-1, 1, 1, 2, -1, -1]], np.int32)
+    say("[layout] 150 builds in a row")
+    want = {}
+    for k in range(150):
+        wl = a if k % 2 == 0 else b
+        lay = _build(wl.level, wl.parent)
+        info = lay.info()
+        key = k % 2
+        if key not in want:
+            compare_layout(oracle, lay, wl.level, wl.parent, 128, 64)
+            want[key] = (info["n_tiles"], info["nnz"])
+        assert (info["n_tiles"], info["nnz"]) == want[key], f"build {k}"
+        lay.destroy()
+        if k % 37 == 5:
+            with pytest.raises(hdt.HdtError):
+                _build(bad_l, bad_p)
+    lay = _build(b.level, b.parent)
+    compare_layout(oracle, lay, b.level, b.parent, 128, 64)
+
+
 def test_layout_empty_inputs():
     import torch
     import paper_2407_08330_amd as hdt
