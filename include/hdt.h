@@ -90,7 +90,8 @@ typedef struct {
                                  self-attention layout, the encoder length for a cross-attention layout */
     int32_t cross;            /* 1: built by hdt_build_cross_layout                  */
     uint32_t cross_level_mask;
-    int32_t reserved_;
+    int32_t compact_rows;     /* cross-attention layout whose backward runs on compact copies of K and V: their
+                                 rows per sample; 0 otherwise (see hdt_build_cross_layout)              */
 } hdt_layout_info_t;
 
 /*
@@ -153,14 +154,19 @@ hdt_status_t hdt_build_layout(const int32_t *d_level, const int32_t *d_parent, i
  *
  * Every decoder row attends to every visible position of its sample.  The layout is then used with the
  * ordinary attention calls, whose tensors take two lengths: q, o, d_o, dq are [batch][heads][n_dec][d] and
- * lse [batch][heads][n_dec]; k, v, dk, dv are [batch][heads][n_enc][d].  K and V rows of the visible
- * positions are gathered by the attention kernels themselves (no compacted copy is made); dk and dv of
+ * lse [batch][heads][n_dec]; k, v, dk, dv are [batch][heads][n_enc][d].  In the forward, K and V rows of the
+ * visible positions are gathered by the attention kernel itself (no compacted copy is made); dk and dv of
  * invisible positions are written as zeros; a sample without visible positions gives O = 0, LSE = -inf.
  * hdt_layout_info reports n_pos = n_dec and n_kv = n_enc.  The layout holds a second schedule for the
  * backward pass (rows = encoder positions), reachable through hdt_layout_transposed.
+ * When at most a quarter of the encoder's positions are visible in every sample, the layout also holds a pair
+ * of schedules over the visible positions alone, and hdt_attn_bwd works on compact copies of K, V, dK, dV of
+ * compact_rows (hdt_layout_info) rows per sample, which it keeps in its workspace
+ * (hdt_attn_bwd_workspace_bytes grows by those four tensors): its dK/dV pass then tiles the visible rows
+ * instead of all encoder rows.  Results and arguments are the same either way.
  *
- * The build is asynchronous (kernels on `stream`, no read-back); device memory as for hdt_build_layout,
- * sized for the case that every position is visible.
+ * Kernels are enqueued on `stream`; the call waits for the first of them once (it reads the number of visible
+ * positions back); device memory as for hdt_build_layout, sized for the case that every position is visible.
  * batch == 0 gives an empty layout on which the attention calls are no-ops.
  * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes), HDT_ERR_SHAPE (a length of 0 or > 2^19, too many
  * entries), HDT_ERR_UNSUPPORTED (tile shape, other options), HDT_ERR_OOM, HDT_ERR_HIP.  On error *out is NULL.

@@ -42,7 +42,7 @@ class _Info(ctypes.Structure):
                 ("tile_n", ctypes.c_int32), ("q_tiles", ctypes.c_int32), ("k_tiles", ctypes.c_int32),
                 ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32), ("n_tiles", ctypes.c_int64),
                 ("nnz", ctypes.c_int64), ("device_bytes", ctypes.c_int64), ("n_kv", ctypes.c_int32),
-                ("cross", ctypes.c_int32), ("cross_level_mask", ctypes.c_uint32), ("reserved_", ctypes.c_int32)]
+                ("cross", ctypes.c_int32), ("cross_level_mask", ctypes.c_uint32), ("compact_rows", ctypes.c_int32)]
 
 
 def library_path() -> str:

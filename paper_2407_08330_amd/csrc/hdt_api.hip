@@ -145,6 +145,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(c
     info->n_kv = l->s.n_kv;
     info->cross = l->cross;
     info->cross_level_mask = l->cross_level_mask;
+    info->compact_rows = l->compact ? l->n_compact : 0;
     return HDT_OK;
 }
 
@@ -263,9 +264,11 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destro
 {
     if (!layout) return HDT_OK;
     if (layout->magic != HDT_LAYOUT_MAGIC) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_destroy: not a layout");
-    if (layout->transposed) {
-        hdt_layout_t *t = layout->transposed;
-        layout->transposed = nullptr;
+    hdt_layout_t *owned[3] = {layout->compact ? layout->compact->transposed : nullptr, layout->compact, layout->transposed};
+    layout->compact = layout->transposed = nullptr;
+    for (hdt_layout_t *t : owned) {
+        if (!t) continue;
+        t->transposed = nullptr;
         t->magic = 0;
         hdt_layout_release(t);
         delete t;
@@ -318,12 +321,13 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd(cons
 extern "C" __attribute__((visibility("default"))) size_t hdt_attn_bwd_workspace_bytes(const hdt_layout_t *layout, int32_t heads, int32_t head_dim,
                                                hdt_dtype_t dt)
 {
-    (void)head_dim;
-    (void)dt;
     if (!hdt_layout_ok(layout) || heads < 0) return 0;
     // D_i = sum_c dO_ic O_ic, one float per (batch, head, position)
     size_t n = (size_t)layout->s.batch * (size_t)heads * (size_t)layout->s.n_pos * sizeof(float);
-    return (n + 255) & ~(size_t)255;
+    n = (n + 255) & ~(size_t)255;
+    // a cross-attention layout with a compact pair: compact copies of K, V and of their gradients behind it
+    if (layout->compact) n += hdt_cross_compact_workspace_bytes(layout, heads, head_dim, dt == HDT_BF16 ? 2 : 4);
+    return n;
 }
 
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
@@ -355,6 +359,9 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if ((int64_t)s.batch * heads * ((int64_t)s.tr + 2 * (int64_t)s_tr.tr) > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
+    if (layout->compact)
+        return hdt_cross_bwd_compact(layout, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, dt == HDT_BF16, scale,
+                                     workspace, hs);
     if (dt == HDT_BF16)
         return hdt_launch_bwd_bf16(s, s_tr, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, (float *)workspace, hs);
     return hdt_launch_bwd_f32(s, s_tr, (const float *)q, (const float *)k, (const float *)v, (const float *)o, lse,

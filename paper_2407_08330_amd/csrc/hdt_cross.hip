@@ -9,17 +9,28 @@
 // copy of K and V is made.  The backward pass needs the transposed schedule as well: rows are the encoder
 // positions (allowed iff visible), a row tile that holds a visible position lists all decoder rows.
 //
-// Nothing is read back: the list entries of a row tile sit at a fixed stride (room for the longest possible
-// list), the unused ones are marked empty, and a tile's range covers the ones in use.
+// The list entries of a row tile sit at a fixed stride (room for the longest possible list), the unused ones
+// are marked empty, and a tile's range covers the ones in use.
+//
+// The dK/dV pass of the backward tiles the ENCODER rows, and with a few anchors visible nearly every 32-row
+// block of them holds one allowed row among 31 idle ones.  The build therefore reads the number of visible
+// positions back, and when they are at most a quarter of the encoder's positions it adds a second pair of
+// schedules in the index space of the visible positions (row = rank among them): hdt_attn_bwd then gathers
+// the visible rows of K and V into compact tensors (in its workspace), runs the ordinary backward kernels
+// on those, and scatters dK and dV back (zeros for the rows that are not visible).  The forward keeps
+// gathering straight from K and V.
 #include <string.h>
 
+#include <initializer_list>
 #include <new>
+#include <vector>
 
 #include "hdt_internal.h"
 
 namespace {
 
 constexpr int kSelThreads = 1024;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bool visible(int level, uint32_t level_mask)
 {
@@ -29,7 +40,7 @@ __device__ __forceinline__ bool visible(int level, uint32_t level_mask)
 // One workgroup per sample: the visible positions in document order (sel) and their number (count).
 __global__ __launch_bounds__(kSelThreads) void k_cross_select(const int32_t *__restrict__ level, int n_enc,
                                                                uint32_t level_mask, int32_t *__restrict__ sel,
-                                                               int32_t *__restrict__ count)
+                                                               int32_t *__restrict__ rank, int32_t *__restrict__ count)
 {
     __shared__ int s_wave[kSelThreads / 64];
     __shared__ int s_base;
@@ -46,7 +57,9 @@ __global__ __launch_bounds__(kSelThreads) void k_cross_select(const int32_t *__r
         __syncthreads();
         int before = s_base;
         for (int w = 0; w < wave; w++) before += s_wave[w];
-        if (vis) out[before + __popcll(m & ((1ull << lane) - 1ull))] = i;
+        const int mine = before + __popcll(m & ((1ull << lane) - 1ull));
+        if (vis) out[mine] = i;
+        if (i < n_enc) rank[(size_t)b * n_enc + i] = vis ? mine : -1;
         __syncthreads();
         if (tid == 0) {
             int tot = 0;
@@ -67,6 +80,8 @@ struct CrossArgs {
     int transposed;  // 0: rows = decoder positions, keys = visible encoder positions; 1: rows = encoder positions
                      // (allowed iff visible), keys = decoder positions
     int tr, e_max;   // row tiles per sample, list entries reserved per row tile
+    int compact;     // 0, or the rows per sample of the compact tensors: encoder positions are named by their rank
+                     // among the visible ones (keys of the forward schedule, rows of the transposed one)
     int32_t *q_range, *c_row, *c_cnt, *q_keys;
     uint32_t *q_sub;
     unsigned long long *bits_rm;
@@ -80,14 +95,14 @@ __global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
     const int e = blockIdx.x % a.e_max, tile = blockIdx.x / a.e_max;  // tile = b * tr + I
     const int b = tile / a.tr, I = tile % a.tr;
     const int64_t entry = blockIdx.x;
-    const int n_rows = a.transposed ? a.n_enc : a.n_dec;
+    const int n_rows = a.transposed ? (a.compact ? a.compact : a.n_enc) : a.n_dec;
     const int n_keys = a.transposed ? a.n_dec : a.count[b];
     // rows of the tile
     bool any_row = false;
     for (int h = 0; h < 2; h++) {
         const int r = h * 64 + lane, i = I * a.bm + r;
         bool ok = r < a.bm && i < n_rows;
-        if (ok && a.transposed) ok = visible(a.level[(size_t)b * a.n_enc + i], a.level_mask);
+        if (ok && a.transposed) ok = a.compact ? i < a.count[b] : visible(a.level[(size_t)b * a.n_enc + i], a.level_mask);
         const unsigned long long m = __ballot(ok);
         if (lane == 0) {
             s_row[2 * h] = (uint32_t)m;
@@ -112,7 +127,7 @@ __global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
     for (int h = 0; h < 2; h++) {
         const int c = h * 64 + lane, idx = e * a.bn + c;
         const bool ok = c < a.bn && idx < n_keys;
-        if (c < a.bn) a.q_keys[entry * a.bn + c] = ok ? (a.transposed ? idx : a.sel[(size_t)b * a.n_enc + idx]) : -1;
+        if (c < a.bn) a.q_keys[entry * a.bn + c] = ok ? ((a.transposed || a.compact) ? idx : a.sel[(size_t)b * a.n_enc + idx]) : -1;
         const unsigned long long m = __ballot(ok);
         if (lane == 0) {
             s_col[2 * h] = (uint32_t)m;
@@ -151,8 +166,57 @@ __global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
     }
 }
 
+// ---- compact copies for the backward: rows of [B][H][n][row_bytes] tensors, 16 bytes per thread ----------
+// dst[b][h][c] = src[b][h][sel[b][c]] for c < count[b], zeros for the other rows of the compact tensors
+// (they are operands of the kernels' contractions, masked but read); two tensors per launch.
+__global__ __launch_bounds__(256) void k_cross_gather(const int32_t *__restrict__ sel, const int32_t *__restrict__ count,
+                                                       int n_enc, int n_compact, int heads, int chunks,
+                                                       const u32x4 *__restrict__ src0, const u32x4 *__restrict__ src1,
+                                                       u32x4 *__restrict__ dst0, u32x4 *__restrict__ dst1, long long total)
+{
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int ch = (int)(t % chunks);
+    const long long row = t / chunks;  // (b * heads + h) * n_compact + c
+    const int c = (int)(row % n_compact);
+    const long long bh = row / n_compact;
+    const int b = (int)(bh / heads);
+    u32x4 x0 = {0u, 0u, 0u, 0u}, x1 = x0;
+    if (c < count[b]) {
+        const long long from = (bh * n_enc + sel[(size_t)b * n_enc + c]) * chunks + ch;
+        x0 = src0[from];
+        x1 = src1[from];
+    }
+    dst0[t] = x0;
+    dst1[t] = x1;
+}
+
+// dst[b][h][p] = src[b][h][rank[b][p]] for visible p, zeros otherwise; two tensors per launch
+__global__ __launch_bounds__(256) void k_cross_scatter(const int32_t *__restrict__ rank, int n_enc, int n_compact, int heads,
+                                                        int chunks, const u32x4 *__restrict__ src0,
+                                                        const u32x4 *__restrict__ src1, u32x4 *__restrict__ dst0,
+                                                        u32x4 *__restrict__ dst1, long long total)
+{
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int ch = (int)(t % chunks);
+    const long long row = t / chunks;  // (b * heads + h) * n_enc + p
+    const int pos = (int)(row % n_enc);
+    const long long bh = row / n_enc;
+    const int b = (int)(bh / heads);
+    const int r = rank[(size_t)b * n_enc + pos];
+    u32x4 x0 = {0u, 0u, 0u, 0u}, x1 = x0;
+    if (r >= 0) {
+        const long long from = (bh * n_compact + r) * chunks + ch;
+        x0 = src0[from];
+        x1 = src1[from];
+    }
+    __builtin_nontemporal_store(x0, &dst0[t]);
+    __builtin_nontemporal_store(x1, &dst1[t]);
+}
+
 struct CrossBuffers {
-    int32_t *sel, *count, *q_range;  // first arena
+    int32_t *sel, *rank, *count, *q_range;  // first arena
     int32_t *c_row, *c_cnt, *q_keys;  // second arena
     uint32_t *q_sub;
     unsigned long long *bits_rm;
@@ -173,6 +237,7 @@ CrossBuffers carve_cross(char *a1, char *a2, int B, int n_enc, int tr, int64_t e
     size_t o1 = 0, o2 = 0;
     if (with_sel) {
         c.sel = carve<int32_t>(a1, o1, (size_t)B * n_enc);
+        c.rank = carve<int32_t>(a1, o1, (size_t)B * n_enc);
         c.count = carve<int32_t>(a1, o1, (size_t)B);
     }
     c.q_range = carve<int32_t>(a1, o1, (size_t)B * tr * 2);
@@ -207,6 +272,9 @@ hdt_layout_t *new_layout(int batch, int n_rows, int n_kv, int bm, int bn)
     L->edges = 0;
     L->cross = 1;
     L->transposed = nullptr;
+    L->compact = nullptr;
+    L->cross_sel = L->cross_count = L->cross_rank = nullptr;
+    L->n_compact = 0;
     L->device_bytes = 0;
     L->device = 0;
     (void)hipGetDevice(&L->device);
@@ -223,6 +291,24 @@ hdt_layout_t *new_layout(int batch, int n_rows, int n_kv, int bm, int bn)
     s.n_slots = s.tc * bn;
     L->h_stats.assign((size_t)batch * 2, 0);
     return L;
+}
+
+// the finished arrays become the layout's schedule
+void adopt(hdt_layout_t *l, const CrossBuffers &c, int64_t n)
+{
+    HdtSchedule &s = l->s;
+    s.q_range = c.q_range;
+    s.q_keys = c.q_keys;
+    s.q_sub = c.q_sub;
+    s.bits_rm = c.bits_rm;
+    s.q_cols = nullptr;
+    s.kperm = nullptr;
+    l->d_cnt = c.c_cnt;
+    l->d_row = c.c_row;
+    l->n_entries = n;
+    l->capacity = n;
+    l->device_bytes = (int64_t)(l->arena_bytes + l->arena2_bytes);
+    if (n == 0) l->stats_ready = true;
 }
 
 }  // namespace
@@ -258,6 +344,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
     }
     L->transposed = T;
     L->cross_level_mask = T->cross_level_mask = level_mask;
+    hdt_layout_t *Lc = nullptr, *Tc = nullptr;  // the compact pair while it is being built
     hdt_status_t status = HDT_OK;
     hipStream_t st = (hipStream_t)stream;
     const int e_fwd = (n_enc + bn - 1) / bn, e_tr = (n_dec + bn - 1) / bn;
@@ -288,47 +375,91 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
             {
                 HdtTimer tm("hdt_cross_select", st);
                 hipLaunchKernelGGL(k_cross_select, dim3((unsigned)batch), dim3(kSelThreads), 0, st, d_level_enc, n_enc,
-                                   level_mask, f.sel, f.count);
+                                   level_mask, f.sel, f.rank, f.count);
             }
-            CrossArgs a{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 0, L->s.tr, e_fwd,
+            CrossArgs a{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 0, L->s.tr, e_fwd, 0,
                         f.q_range, f.c_row, f.c_cnt, f.q_keys, f.q_sub, f.bits_rm};
             {
                 HdtTimer tm("hdt_cross_entries", st);
                 hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_fwd), dim3(64), 0, st, a);
             }
-            CrossArgs at{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 1, T->s.tr, e_tr,
+            CrossArgs at{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 1, T->s.tr, e_tr, 0,
                          t.q_range, t.c_row, t.c_cnt, t.q_keys, t.q_sub, t.bits_rm};
             {
                 HdtTimer tm("hdt_cross_entries_transposed", st);
                 hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_tr), dim3(64), 0, st, at);
             }
             CROSS_TRY(hipGetLastError());
+            L->cross_sel = f.sel;
+            L->cross_rank = f.rank;
+            L->cross_count = f.count;
+            // How many positions are visible?  (The one read-back of the build: it waits for the select kernel.)
+            std::vector<int32_t> h_count((size_t)batch, 0);
+            CROSS_TRY(hipMemcpyAsync(h_count.data(), f.count, sizeof(int32_t) * batch, hipMemcpyDeviceToHost, st));
+            CROSS_TRY(hipStreamSynchronize(st));
+            int c_max = 0;
+            for (int32_t c : h_count) c_max = c > c_max ? c : c_max;
+            if (c_max > 0 && (int64_t)c_max * 4 <= n_enc) {
+                // the compact pair: decoder rows x ranks, and ranks x decoder rows
+                const int n_c = (c_max + 31) / 32 * 32;
+                Lc = new_layout(batch, n_dec, n_c, bm, bn);
+                Tc = Lc ? new_layout(batch, n_c, n_dec, bm, bn) : nullptr;
+                if (!Lc || !Tc) {
+                    status = hdt_fail(HDT_ERR_OOM, "hdt_build_cross_layout: host allocation failed");
+                    goto fail;
+                }
+                Lc->transposed = Tc;
+                Lc->cross_level_mask = Tc->cross_level_mask = level_mask;
+                const int e_fc = (n_c + bn - 1) / bn;
+                const int64_t ent_fc = (int64_t)batch * Lc->s.tr * e_fc, ent_tc = (int64_t)batch * Tc->s.tr * e_tr;
+                CrossBuffers fc = carve_cross(nullptr, nullptr, batch, n_enc, Lc->s.tr, ent_fc, bm, bn, false);
+                CrossBuffers tc = carve_cross(nullptr, nullptr, batch, n_enc, Tc->s.tr, ent_tc, bm, bn, false);
+                CROSS_TRY(hdt_pool_alloc(&Lc->arena, fc.bytes1 + 256, &Lc->arena_bytes));
+                CROSS_TRY(hdt_pool_alloc(&Lc->arena2, fc.bytes2 + 256, &Lc->arena2_bytes));
+                CROSS_TRY(hdt_pool_alloc(&Tc->arena, tc.bytes1 + 256, &Tc->arena_bytes));
+                CROSS_TRY(hdt_pool_alloc(&Tc->arena2, tc.bytes2 + 256, &Tc->arena2_bytes));
+                fc = carve_cross((char *)Lc->arena, (char *)Lc->arena2, batch, n_enc, Lc->s.tr, ent_fc, bm, bn, false);
+                tc = carve_cross((char *)Tc->arena, (char *)Tc->arena2, batch, n_enc, Tc->s.tr, ent_tc, bm, bn, false);
+                CrossArgs ac{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 0, Lc->s.tr, e_fc, n_c,
+                             fc.q_range, fc.c_row, fc.c_cnt, fc.q_keys, fc.q_sub, fc.bits_rm};
+                {
+                    HdtTimer tm("hdt_cross_entries_compact", st);
+                    hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_fc), dim3(64), 0, st, ac);
+                }
+                CrossArgs atc{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 1, Tc->s.tr, e_tr, n_c,
+                              tc.q_range, tc.c_row, tc.c_cnt, tc.q_keys, tc.q_sub, tc.bits_rm};
+                {
+                    HdtTimer tm("hdt_cross_entries_compact_transposed", st);
+                    hipLaunchKernelGGL(k_cross_entries, dim3((unsigned)ent_tc), dim3(64), 0, st, atc);
+                }
+                CROSS_TRY(hipGetLastError());
+                adopt(Lc, fc, ent_fc);
+                adopt(Tc, tc, ent_tc);
+                L->compact = Lc;
+                L->n_compact = n_c;
+                L->device_bytes += Lc->device_bytes + Tc->device_bytes;
+                Lc = Tc = nullptr;  // owned by L from here on
+            }
         }
         struct {
             hdt_layout_t *l;
             CrossBuffers *c;
             int64_t n;
         } both[2] = {{L, &f, empty ? 0 : ent_fwd}, {T, &t, empty ? 0 : ent_tr}};
-        for (auto &x : both) {
-            HdtSchedule &s = x.l->s;
-            s.q_range = x.c->q_range;
-            s.q_keys = x.c->q_keys;
-            s.q_sub = x.c->q_sub;
-            s.bits_rm = x.c->bits_rm;
-            s.q_cols = nullptr;
-            s.kperm = nullptr;
-            x.l->d_cnt = x.c->c_cnt;
-            x.l->d_row = x.c->c_row;
-            x.l->n_entries = x.n;
-            x.l->capacity = x.n;
-            x.l->device_bytes = (int64_t)(x.l->arena_bytes + x.l->arena2_bytes);
-            if (x.n == 0) x.l->stats_ready = true;
-        }
+        const int64_t compact_bytes = L->device_bytes;  // added above, if a compact pair was built
+        for (auto &x : both) adopt(x.l, *x.c, x.n);
+        L->device_bytes += compact_bytes;
         L->device_bytes += T->device_bytes;
         *out = L;
         return HDT_OK;
     }
 fail:
+    for (hdt_layout_t *x : {Tc, Lc}) {
+        if (!x) continue;
+        hdt_layout_release(x);
+        x->magic = 0;
+        delete x;
+    }
     hdt_layout_release(T);
     T->magic = 0;
     delete T;
@@ -338,4 +469,55 @@ fail:
     delete L;
     return status;
 #undef CROSS_TRY
+}
+
+// ---- backward through the compact pair ------------------------------------------------------------------
+static size_t compact_tensor_bytes(const hdt_layout_t *l, int heads, int head_dim, int elem_bytes)
+{
+    const size_t n = (size_t)l->s.batch * (size_t)heads * (size_t)l->n_compact * (size_t)head_dim * (size_t)elem_bytes;
+    return (n + 255) & ~(size_t)255;
+}
+
+size_t hdt_cross_compact_workspace_bytes(const hdt_layout_t *l, int heads, int head_dim, int elem_bytes)
+{
+    return l->compact ? 4 * compact_tensor_bytes(l, heads, head_dim, elem_bytes) : 0;
+}
+
+// Workspace: D of the decoder rows (as for every backward), then the compact K, V, dK, dV.  The visible rows of K
+// and V are gathered, the ordinary backward runs on the compact pair of schedules (dQ is written in place: its rows
+// are the decoder's), and dK, dV are scattered to the encoder's rows, zeros where a row is not visible.
+hdt_status_t hdt_cross_bwd_compact(const hdt_layout_t *l, const void *q, const void *k, const void *v, const void *o,
+                                   const float *lse, const void *d_o, void *dq, void *dk, void *dv, int heads,
+                                   int head_dim, bool bf16, float scale, void *workspace, hipStream_t st)
+{
+    const hdt_layout_t *lc = l->compact;
+    const HdtSchedule &s = lc->s, &s_tr = lc->transposed->s;
+    const int elem = bf16 ? 2 : 4, n_enc = l->s.n_kv, n_c = l->n_compact, B = l->s.batch;
+    const size_t d_bytes = ((size_t)B * heads * (size_t)l->s.n_pos * sizeof(float) + 255) & ~(size_t)255;
+    const size_t t_bytes = compact_tensor_bytes(l, heads, head_dim, elem);
+    char *w = static_cast<char *>(workspace);
+    float *delta = reinterpret_cast<float *>(w);
+    void *kc = w + d_bytes, *vc = w + d_bytes + t_bytes, *dkc = w + d_bytes + 2 * t_bytes, *dvc = w + d_bytes + 3 * t_bytes;
+    const int chunks = head_dim * elem / 16;
+    {
+        const long long total = (long long)B * heads * n_c * chunks;
+        HdtTimer tm("hdt_cross_gather", st);
+        hipLaunchKernelGGL(k_cross_gather, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, l->cross_sel, l->cross_count,
+                           n_enc, n_c, heads, chunks, (const u32x4 *)k, (const u32x4 *)v, (u32x4 *)kc, (u32x4 *)vc, total);
+    }
+    HDT_HIP_TRY(hipGetLastError());
+    hdt_status_t status =
+        bf16 ? hdt_launch_bwd_bf16(s, s_tr, q, kc, vc, o, lse, d_o, dq, dkc, dvc, heads, head_dim, scale, delta, st)
+             : hdt_launch_bwd_f32(s, s_tr, (const float *)q, (const float *)kc, (const float *)vc, (const float *)o, lse,
+                                  (const float *)d_o, (float *)dq, (float *)dkc, (float *)dvc, heads, head_dim, scale, delta,
+                                  st);
+    if (status != HDT_OK) return status;
+    {
+        const long long total = (long long)B * heads * n_enc * chunks;
+        HdtTimer tm("hdt_cross_scatter", st);
+        hipLaunchKernelGGL(k_cross_scatter, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, l->cross_rank, n_enc, n_c,
+                           heads, chunks, (const u32x4 *)dkc, (const u32x4 *)dvc, (u32x4 *)dk, (u32x4 *)dv, total);
+    }
+    HDT_HIP_TRY(hipGetLastError());
+    return HDT_OK;
 }

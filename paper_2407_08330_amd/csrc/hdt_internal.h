@@ -57,6 +57,15 @@ struct hdt_layout {
     // directed masks (edges without up/down symmetry): the schedule of the transposed mask (rows = keys,
     // list entries = the queries attending to them), owned by this layout; NULL for symmetric masks
     hdt_layout *transposed;
+    // Cross-attention layouts with few visible positions (hdt_cross.hip): a second pair of schedules in the index
+    // space of the visible positions (a position's row = its rank among them), on which the backward runs with
+    // compact copies of K and V.  `compact` schedules the dQ pass (keys = ranks), compact->transposed the
+    // dK/dV pass (rows = ranks); all owned by this layout.  NULL: no such pair.
+    hdt_layout *compact;
+    const int32_t *cross_sel;    // [batch][n_kv] visible positions in document order (device)
+    const int32_t *cross_count;  // [batch] their number (device)
+    const int32_t *cross_rank;   // [batch][n_kv] rank among the visible positions, -1 = not visible (device)
+    int32_t n_compact;           // rows per (sample, head) of the compact tensors
     int64_t capacity;    // entries the per-tile arrays can hold
     int64_t device_bytes;
     void *arena;         // key order, list pointers, scratch of the build
@@ -93,6 +102,12 @@ hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (wa
 void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
 // device buffer from the cache of destroyed layouts' buffers, or a new one; *got = its real size (hdt_layout.hip)
 hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got);
+
+// --- backward of a cross-attention layout with a compact pair (hdt_cross.hip) ---
+size_t hdt_cross_compact_workspace_bytes(const hdt_layout_t *l, int heads, int head_dim, int elem_bytes);
+hdt_status_t hdt_cross_bwd_compact(const hdt_layout_t *l, const void *q, const void *k, const void *v, const void *o,
+                                   const float *lse, const void *d_o, void *dq, void *dk, void *dv, int heads,
+                                   int head_dim, bool bf16, float scale, void *workspace, hipStream_t st);
 
 // --- per-kernel timing (hdt_api.hip) ---
 struct HdtTimer {  // brackets one kernel launch with events when timing is enabled

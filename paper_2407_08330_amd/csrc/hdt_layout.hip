@@ -1227,6 +1227,9 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     L->cross = 0;
     L->cross_level_mask = 0;
     L->transposed = nullptr;
+    L->compact = nullptr;
+    L->cross_sel = L->cross_count = L->cross_rank = nullptr;
+    L->n_compact = 0;
     L->device_bytes = 0;
     L->device = 0;
     HdtSchedule &s = L->s;

@@ -80,6 +80,11 @@ def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0,
     scale = 1.0 / np.sqrt(D)
     (q, k, v, d_o), (q_, k_, v_, do_) = _tensors(B, H, n_dec, n_enc, D, seed, dtype)
     lay = hdt.hdt_build_cross_layout(to_dev_i32(level), n_dec, level_mask, tile_m=tile[0], tile_n=tile[1])
+    # the backward runs on compact copies of K and V iff at most a quarter of the positions are visible
+    c_max = max(int(oracle.cross_select(l, level_mask).size) for l in level)
+    compact_rows = lay.info()["compact_rows"]
+    say(f"    visible at most {c_max} of {n_enc}: compact rows {compact_rows}")
+    assert (compact_rows > 0) == (0 < c_max and 4 * c_max <= n_enc) and (compact_rows == 0 or c_max <= compact_rows < c_max + 32)
     o_ = torch.full_like(q_, float("nan"))
     lse_ = torch.full((B, H, n_dec), float("nan"), dtype=torch.float32, device="cuda")
     hdt.hdt_attn_fwd(lay, q_, k_, v_, scale, o=o_, lse=lse_)
