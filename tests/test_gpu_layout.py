@@ -247,6 +247,46 @@ def test_layout_many_builds_in_a_row_share_the_counter_slots(oracle):
     compare_layout(oracle, lay, b.level, b.parent, 128, 64)
 
 
+def test_layout_builds_from_two_host_threads(oracle):
+    # two host threads build on streams of their own at the same time (the binding releases the GIL inside the
+    # call): tickets, report words, counter slots and the buffer cache are shared state of the library
+    import threading
+    import torch
+    import paper_2407_08330_amd as hdt
+    work = [inputs.make_workload(1, batch=2), inputs.make_workload(2, batch=1)]
+    want = []
+    for wl in work:
+        lay = _build(wl.level, wl.parent)
+        compare_layout(oracle, lay, wl.level, wl.parent, 128, 64)
+        info = lay.info()
+        want.append((info["n_tiles"], info["nnz"]))
+    dev = [(to_dev_i32(wl.level), to_dev_i32(wl.parent)) for wl in work]
+    errors = []
+
+    def builder(k):
+        try:
+            stream = torch.cuda.Stream()
+            for it in range(40):
+                which = (k + it) % 2
+                lay = hdt.hdt_build_layout(dev[which][0], dev[which][1], stream=stream)
+                info = lay.info()
+                if (info["n_tiles"], info["nnz"]) != want[which]:
+                    errors.append(f"thread {k} build {it}: {info['n_tiles']}, {info['nnz']} instead of {want[which]}")
+                lay.destroy()
+        except Exception as e:   # noqa: BLE001 - reported below
+            errors.append(f"thread {k}: {e!r}")
+
+    say("[layout] 2 threads x 40 builds")
+    threads = [threading.Thread(target=builder, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+        assert not t.is_alive(), "a builder thread is stuck"
+    torch.cuda.synchronize()
+    assert not errors, errors[:3]
+
+
 def test_layout_empty_inputs():
     import torch
     import paper_2407_08330_amd as hdt
