@@ -343,8 +343,11 @@ def main() -> int:
             fwd_bytes = H * (B * n_dec * (2 * row + 4) + visible * 2 * row)          # Q, O, LSE; visible K, V rows
             bwd_bytes = H * (B * n_dec * (3 * row + 8) + visible * 2 * row + B * N * 2 * row)  # Q, dO, dQ; K, V; all of dK, dV
             fwd_us = tk.get(f"hdt_fwd_bf16_d{D}")
-            bwd_us = tk.get(f"hdt_bwd_bf16_d{D}")
-            cross[name] = {"visible_positions": int(visible), "kernels_us": tk,
+            # the whole backward call: D pass and kernel, plus the copies of a compact layout
+            bwd_parts = [tk.get(k) for k in (f"hdt_bwd_delta_d{D}", f"hdt_bwd_bf16_d{D}", "hdt_cross_gather", "hdt_cross_scatter")]
+            bwd_us = sum(x for x in bwd_parts if x) if tk.get(f"hdt_bwd_bf16_d{D}") else None
+            cross[name] = {"visible_positions": int(visible), "compact_rows": int(lay_c.info()["compact_rows"]), "kernels_us": tk,
+                           "bwd_us": None if not bwd_us else round(bwd_us, 2),
                            "fwd_algorithmic_bytes": fwd_bytes, "bwd_algorithmic_bytes": bwd_bytes,
                            "fwd_gbs": None if not fwd_us else round(fwd_bytes / (fwd_us * 1e-6) / 1e9, 1),
                            "bwd_gbs": None if not bwd_us else round(bwd_bytes / (bwd_us * 1e-6) / 1e9, 1)}
