@@ -23,8 +23,10 @@
  *     only enqueue work on it; they never synchronise and never allocate.
  *   - Every function returns an hdt_status_t; nothing aborts or throws across the boundary.
  *     hdt_last_error() gives a thread-local text for the last non-OK status.
- *   - Values at pad positions and at masked pairs are never used as logits, but K/V/dO rows of
- *     a tile are multiplied by zero weights: all inputs must be finite everywhere.
+ *   - Rows of pad positions may hold anything, NaN and infinities included: no result at a real
+ *     position depends on them, and their own output rows are written as stated below.  The same
+ *     holds for the K, V rows of encoder positions a cross-attention layout does not make visible.
+ *     A masked pair contributes nothing (Sec. 3.2), whatever the two rows hold.
  */
 #ifndef HDT_H
 #define HDT_H
@@ -76,6 +78,9 @@ typedef struct {
     int32_t windowed;    /* 1: key tiles are fixed windows of the key order (Alg. 1 as printed); */
                          /* 0: every query tile gets its own packed key list (default)         */
     int32_t edges;       /* OR of HDT_EDGE_*; 0 = HDT_EDGE_ALL                                  */
+    int32_t deferred;    /* 1: hdt_build_layout does not wait for the device (see there); key lists only */
+    int32_t reserved;    /* 0 */
+    int64_t capacity;    /* list entries the layout has room for; 0 = the library chooses        */
 } hdt_layout_opts_t;
 
 typedef struct {
@@ -132,6 +137,19 @@ typedef struct {
  * layout comes from a cache of buffers of destroyed layouts (hipMalloc when the cache has nothing
  * that fits).  batch == 0 or n_pos == 0 gives an empty layout on which the attention calls are no-ops.
  *
+ * opts->deferred = 1 (key-list layouts; ignored for windowed and dense ones): the call only enqueues the
+ * build and returns without waiting for anything, so a training loop never stalls its launch queue on it.
+ * The layout can be passed to the attention calls at once (they are ordered behind the build on the same
+ * stream).  What the device finds out is looked at later: HDT_ERR_HIERARCHY (invalid ids) or HDT_ERR_SHAPE
+ * (more list entries needed than the layout has room for) is returned by hdt_layout_status, which waits
+ * for the build kernel, by hdt_layout_info / hdt_layout_sample_info / hdt_layout_export, and by every
+ * attention call made after the report has arrived; attention calls made before that run on the lists as
+ * far as they were written (always inside the layout's arrays) and their results are then meaningless.
+ * The room is opts->capacity list entries if given (also for a call that waits: HDT_ERR_SHAPE instead of a
+ * second attempt); otherwise a deferred build takes the most any document can need, batch * q_tiles *
+ * k_tiles, as far as that stays within 256 MiB (n_pos up to about 32768 for one sample), and beyond
+ * that what 256 MiB hold.  At most 1024 builds may be in flight per process.
+ *
  * Errors: HDT_ERR_INVALID_ARG (NULL, negative sizes, edges outside HDT_EDGE_ALL), HDT_ERR_SHAPE (n_pos > 2^19),
  * HDT_ERR_UNSUPPORTED (tile shape), HDT_ERR_HIERARCHY (level outside [-1, HDT_MAX_LEVELS),
  * parent outside [-1, n_pos), parent[i] == i, a pad with a parent, a parent that is a pad),
@@ -181,6 +199,13 @@ hdt_status_t hdt_build_cross_layout(const int32_t *d_level_enc, int32_t batch, i
  * owned by `layout` and dies with it. */
 hdt_status_t hdt_layout_transposed(const hdt_layout_t *layout, const hdt_layout_t **out);
 
+/* The outcome of a deferred build (opts->deferred): waits until the build kernel has reported (not for the
+ * stream), then returns HDT_OK, HDT_ERR_HIERARCHY or HDT_ERR_SHAPE as hdt_build_layout would have.
+ * *h_entries_needed (may be NULL) receives the number of list entries the schedule needs, which is what
+ * opts->capacity must be at least for the build to succeed.  On a layout built without `deferred` it returns
+ * HDT_OK at once. */
+hdt_status_t hdt_layout_status(const hdt_layout_t *layout, int64_t *h_entries_needed);
+
 /* Sizes of a layout (host struct).  n_tiles and nnz are read back from the device by the first call
  * of hdt_layout_info / hdt_layout_sample_info / hdt_layout_export on a layout, which synchronises
  * the device; later calls are host-only. */
@@ -198,9 +223,11 @@ hdt_status_t hdt_layout_sample_info(const hdt_layout_t *layout, int32_t sample, 
  *   h_q_cols   int32  [T]            windowed: key window J of each entry, ascending inside a query tile;
  *                                    otherwise the ordinal of the entry inside its query tile
  *   h_q_keys   int32  [T][tile_n]    document position behind every key slot of every entry; -1 where the
- *                                    slot holds no key (pads, slots past n_pos, the tail of a key list)
+ *                                    slot holds no key (the tail of a key list; in a windowed layout also pads,
+ *                                    slots past n_pos and keys that no row of the query tile may attend to)
  *   h_q_sub    uint32 [T]            32x32 sub-block (r, c) -> bit r*(tile_n/32)+c: bits 0..15 set iff the
- *                                    sub-block holds an allowed pair, bits 16..31 iff all its pairs are allowed
+ *                                    sub-block is computed, i.e. holds an allowed pair (force_dense: every
+ *                                    sub-block of the tile), bits 16..31 iff all its pairs are allowed
  *   h_bits     uint32 [T][tile_m][tile_n/32]  bitmap, word r*(tile_n/32)+c/32, bit c%32 <=> row r, slot c allowed
  *   h_k_colptr int32  [k_tiles + 1]  windowed layouts only: the transpose, entries of key window J
  *   h_k_rows   int32  [T]            query tile of each transposed entry, ascending inside a key window

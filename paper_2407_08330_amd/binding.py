@@ -10,15 +10,14 @@ from typing import Optional
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# HDT_LIBRARY_PATH selects another build of the same library (kernel tuning variants)
-_LIB_PATH = os.environ.get("HDT_LIBRARY_PATH") or os.path.join(_PKG, "libhdt.so")
+_LIB_PATH = os.path.join(_PKG, "libhdt.so")
 _lib = None
 
 HDT_BF16, HDT_F32 = 0, 1
 HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 
 EXPORTED_SYMBOLS = [
-    "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
+    "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_status", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
     "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
     "hdt_parents_from_levels", "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
@@ -34,7 +33,8 @@ class HdtError(RuntimeError):
 
 class _Opts(ctypes.Structure):
     _fields_ = [("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32), ("force_dense", ctypes.c_int32),
-                ("no_sort", ctypes.c_int32), ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32)]
+                ("no_sort", ctypes.c_int32), ("windowed", ctypes.c_int32), ("edges", ctypes.c_int32),
+                ("deferred", ctypes.c_int32), ("reserved", ctypes.c_int32), ("capacity", ctypes.c_int64)]
 
 
 class _Info(ctypes.Structure):
@@ -68,6 +68,8 @@ def load_library():
     lib.hdt_build_cross_layout.restype = ctypes.c_int
     lib.hdt_layout_transposed.argtypes = [vp, ctypes.POINTER(vp)]
     lib.hdt_layout_transposed.restype = ctypes.c_int
+    lib.hdt_layout_status.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.hdt_layout_status.restype = ctypes.c_int
     lib.hdt_layout_info.argtypes = [vp, ctypes.POINTER(_Info)]
     lib.hdt_layout_info.restype = ctypes.c_int
     lib.hdt_layout_sample_info.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -146,6 +148,19 @@ class Layout:
     def handle(self):
         return self._h
 
+    def status(self) -> int:
+        """Outcome of a deferred build: waits for the build kernel's report, raises HdtError if the build failed
+        (``entries_needed`` on the exception is what ``capacity`` must be at least); returns the list entries
+        the schedule needs."""
+        need = ctypes.c_int64(0)
+        st = load_library().hdt_layout_status(self._h, ctypes.byref(need))
+        if st != 0:
+            lib = load_library()
+            err = HdtError(st, lib.hdt_status_string(st).decode(), lib.hdt_last_error().decode())
+            err.entries_needed = need.value
+            raise err
+        return need.value
+
     def info(self) -> dict:
         info = _Info()
         _check(load_library().hdt_layout_info(self._h, ctypes.byref(info)))
@@ -195,8 +210,11 @@ class Layout:
 
 
 def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dense: bool = False,
-                     no_sort: bool = False, windowed: bool = False, edges: int = 0, stream=None) -> Layout:
-    """level, parent: int32 device tensors [batch][n_pos].  ``edges``: OR of HDT_EDGE_* (0 = all)."""
+                     no_sort: bool = False, windowed: bool = False, edges: int = 0, deferred: bool = False,
+                     capacity: int = 0, stream=None) -> Layout:
+    """level, parent: int32 device tensors [batch][n_pos].  ``edges``: OR of HDT_EDGE_* (0 = all).
+    ``deferred``: only enqueue the build (see hdt_build_layout in include/hdt.h); ``capacity``: list entries
+    the layout has room for (0 = the library chooses)."""
     import torch
     if level.dtype != torch.int32 or parent.dtype != torch.int32:
         raise TypeError("level and parent must be int32")
@@ -204,7 +222,8 @@ def hdt_build_layout(level, parent, tile_m: int = 0, tile_n: int = 0, force_dens
         raise ValueError("level and parent must both be [batch][n_pos]")
     if not (level.is_cuda and parent.is_cuda and level.is_contiguous() and parent.is_contiguous()):
         raise ValueError("level and parent must be contiguous device tensors")
-    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort), int(windowed), int(edges))
+    opts = _Opts(tile_m, tile_n, int(force_dense), int(no_sort), int(windowed), int(edges), int(deferred), 0,
+                 int(capacity))
     h = ctypes.c_void_p(0)
     B, N = level.shape
     _check(load_library().hdt_build_layout(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,
@@ -221,7 +240,7 @@ def hdt_build_cross_layout(level_enc, n_dec: int, level_mask: int, tile_m: int =
         raise TypeError("level_enc must be int32 [batch][n_enc]")
     if not (level_enc.is_cuda and level_enc.is_contiguous()):
         raise ValueError("level_enc must be a contiguous device tensor")
-    opts = _Opts(tile_m, tile_n, 0, 0, 0, 0)
+    opts = _Opts(tile_m, tile_n, 0, 0, 0, 0, 0, 0, 0)
     h = ctypes.c_void_p(0)
     B, n_enc = level_enc.shape
     _check(load_library().hdt_build_cross_layout(_ptr(level_enc) if B * n_enc else None, B, n_enc, int(n_dec),

@@ -149,6 +149,19 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_info(c
     return HDT_OK;
 }
 
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_status(const hdt_layout_t *layout,
+                                                                                  int64_t *entries_needed)
+{
+    if (!hdt_layout_ok(layout)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_status: NULL or invalid layout");
+    const hdt_status_t st = hdt_layout_resolve(layout, true);
+    if (entries_needed) {
+        *entries_needed = layout->entries_needed;
+        if (layout->transposed && layout->transposed->entries_needed > *entries_needed)
+            *entries_needed = layout->transposed->entries_needed;
+    }
+    return st;
+}
+
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_sample_info(const hdt_layout_t *layout, int32_t sample, int64_t *n_tiles,
                                                int64_t *nnz)
 {
@@ -222,9 +235,12 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_export
     for (int64_t t = 0; t < T; t++) {
         if (q_cols) q_cols[t] = keep_col[t];
         if (q_sub) q_sub[t] = sub[keep_entry[t]];
-        if (q_keys)
+        if (q_keys) {  // slots without a key: the device keeps the row gathered in their place, complemented
             HDT_HIP_TRY(hipMemcpy(q_keys + (size_t)t * s.bn, s.q_keys + (size_t)keep_entry[t] * s.bn,
                                   sizeof(int32_t) * s.bn, hipMemcpyDeviceToHost));
+            for (int c = 0; c < s.bn; c++)
+                if (q_keys[(size_t)t * s.bn + c] < 0) q_keys[(size_t)t * s.bn + c] = -1;
+        }
         if (bits) {  // row-major bitmaps are derived here from the lane masks the device keeps
             HDT_HIP_TRY(hipMemcpy(rm.data(), s.bits_rm + (size_t)keep_entry[t] * rm.size(),
                                   sizeof(unsigned long long) * rm.size(), hipMemcpyDeviceToHost));
@@ -293,7 +309,8 @@ static hdt_status_t check_attn_args(const char *fn, const hdt_layout_t *layout, 
     if (dt == HDT_BF16 && !((layout->s.bm == 64 && layout->s.bn == 32) || (layout->s.bm == 128 && layout->s.bn == 64)))
         return hdt_fail(HDT_ERR_UNSUPPORTED, "%s: bf16 kernels need 64x32 or 128x64 tiles, layout has %dx%d", fn,
                         layout->s.bm, layout->s.bn);
-    return HDT_OK;
+    // a deferred build that is known to have failed (a look at its report, no wait)
+    return hdt_layout_resolve(layout, false);
 }
 
 static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }

@@ -142,8 +142,16 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
     }
     const int qrow_ld = min(qrow, s.n_pos - 1);
     float lse2 = lse[(size_t)bh * s.n_pos + qrow_ld];
-    lse2 = (lse2 == -INFINITY) ? 0.f : lse2 * LOG2E;  // pad rows are masked by the bitmap anyway
-    const float Di = delta[(size_t)bh * s.n_pos + qrow_ld];
+    float Di = delta[(size_t)bh * s.n_pos + qrow_ld];
+    // A row without any key (a pad: LSE = -inf) is masked by the bitmap, but its Q, dO and D may hold anything,
+    // NaN included, which a zero weight would not remove: it takes part as a row of zeros.
+    const bool dead_row = lse2 == -INFINITY;
+    lse2 = dead_row ? 0.f : lse2 * LOG2E;
+    Di = dead_row ? 0.f : Di;
+    if (dead_row) {
+#pragma unroll
+        for (int st = 0; st < KSTEPS; st++) qf[st] = dof[st] = zero_bf16x8();
+    }
     // the compiler must finish its own loads before the hand-scheduled ones continue
     asm volatile("" ::"v"(Di), "v"(lse2));
     wg_barrier();  // every wave has read its fragments: the ring may use all stages
@@ -240,6 +248,9 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     pipe.aux1 = delta + (size_t)bh * s.n_kv;
     const RowLane rl = row_lane(lane);
     const TrLane tl = tr_lane(lane);
+    // is this lane's own row a real position?  (Requested first, looked at once the rows are in registers.)
+    const int own_row = min(I * BM + wave * 32 + (lane & 31), s.n_pos - 1);
+    const int own_flag = s.row_flag ? s.row_flag[(size_t)b * s.n_pos + own_row] : 0;
 
     // K and V rows of this wave: through the two highest ring stages, as Q and dO in the dQ pass
     constexpr uint32_t STG_K = (uint32_t)(S - 1) * 2 * P::TILE, STG_V = (uint32_t)(S - 2) * 2 * P::TILE;
@@ -253,6 +264,16 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     for (int st = 0; st < KSTEPS; st++) {
         kf[st] = read_row<ROWB>(smem + STG_K, rl, wave * 32, st);
         if (DO_DK) vf[st] = read_row<ROWB>(smem + STG_V, rl, wave * 32, st);
+    }
+    // A row that is no real position (a pad, an encoder position the decoder does not see) is masked by the
+    // bitmap, but its K and V may hold anything, NaN included, which a zero weight would not remove: it takes
+    // part as a row of zeros.
+    if (own_flag < 0) {
+#pragma unroll
+        for (int st = 0; st < KSTEPS; st++) {
+            kf[st] = zero_bf16x8();
+            if (DO_DK) vf[st] = zero_bf16x8();
+        }
     }
     wg_barrier();
     R::template prologue<S - 2, S - 1>(pipe, n);

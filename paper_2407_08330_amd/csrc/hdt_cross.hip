@@ -127,7 +127,10 @@ __global__ __launch_bounds__(64) void k_cross_entries(CrossArgs a)
     for (int h = 0; h < 2; h++) {
         const int c = h * 64 + lane, idx = e * a.bn + c;
         const bool ok = c < a.bn && idx < n_keys;
-        if (c < a.bn) a.q_keys[entry * a.bn + c] = ok ? ((a.transposed || a.compact) ? idx : a.sel[(size_t)b * a.n_enc + idx]) : -1;
+        // a slot past the last key holds ~f, f = the entry's first key: the row gathered in its place
+        const int at = ok ? idx : e * a.bn;
+        const int key = (a.transposed || a.compact) ? at : a.sel[(size_t)b * a.n_enc + at];
+        if (c < a.bn) a.q_keys[entry * a.bn + c] = ok ? key : ~key;
         const unsigned long long m = __ballot(ok);
         if (lane == 0) {
             s_col[2 * h] = (uint32_t)m;
@@ -326,7 +329,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
     if (opts) {
         if (opts->tile_m) bm = opts->tile_m;
         if (opts->tile_n) bn = opts->tile_n;
-        if (opts->force_dense || opts->no_sort || opts->windowed || opts->edges)
+        if (opts->force_dense || opts->no_sort || opts->windowed || opts->edges || opts->deferred || opts->capacity)
             return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_build_cross_layout: only the tile shape can be chosen");
     }
     if (bm < 32 || bm > 128 || bm % 32 || bn < 32 || bn > 128 || bn % 32)
@@ -448,6 +451,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
         } both[2] = {{L, &f, empty ? 0 : ent_fwd}, {T, &t, empty ? 0 : ent_tr}};
         const int64_t compact_bytes = L->device_bytes;  // added above, if a compact pair was built
         for (auto &x : both) adopt(x.l, *x.c, x.n);
+        T->s.row_flag = f.rank;  // encoder rows that are not visible (pads among them) may hold anything
         L->device_bytes += compact_bytes;
         L->device_bytes += T->device_bytes;
         *out = L;

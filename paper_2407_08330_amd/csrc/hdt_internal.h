@@ -14,7 +14,7 @@
 // Device-side view of a tile schedule, passed by value to the attention kernels.
 //
 // Every query tile (b, I) owns a contiguous run of list entries; an entry is one key tile: bn key
-// slots, each naming the document position to gather (q_keys, -1 = no key), with the bitmaps of the
+// slots, each naming the document position to gather (q_keys, negative = no key), with the bitmaps of the
 // allowed pairs.  Windowed layouts fill an entry's slots from a window of the key order kperm, the
 // default layouts with the next bn keys of the query tile's own key list; the kernels do not care.
 // In a windowed layout an entry may turn out to hold no allowed pair (only for documents that are not
@@ -30,11 +30,17 @@ struct HdtSchedule {
     const int32_t *kperm;  // [batch][n_slots] sorted slot -> position, -1 beyond n_pos (not read by the attention kernels)
     const int32_t *q_range;   // [batch][tr][2] first and one-past-last list entry of query tile (b, I)
     const int32_t *q_cols;    // [entries] windowed layouts: key window of each entry
-    const int32_t *q_keys;    // [entries][bn] document position behind each key slot, -1 = none
+    // [entries][bn] document position behind each key slot; a slot without a key (no key left, a pad, a key
+    // no row of the tile may attend to) holds ~f < 0, f being the first real row of the tile: the row the
+    // attention kernels gather in its place (see gather_row in hdt_tile.h)
+    const int32_t *q_keys;
     const uint32_t *q_sub;    // [entries] 32x32 sub-block summary (bits 0..15 any, 16..31 all)
     // [entries][(bm/32)*(bn/32)][16] per 32x32 sub-block (r, c) = index r*(bn/32)+c: bit l of word e <=>
     // row 32r + l%32, column 32c + (l/32)*4 + 8*(e/4) + e%4 allowed: the lane mask of MFMA accumulator register e
     const unsigned long long *bits_rm;
+    // [batch][n_pos] >= 0 iff the row is a real position (may attend to anything), or NULL = every row is:
+    // the level ids of a self-attention layout, the ranks of a cross-attention layout's encoder rows
+    const int32_t *row_flag;
 };
 
 // whether row r of list entry t may attend to the key in slot c (plain indexing of bits_rm)
@@ -73,7 +79,7 @@ struct hdt_layout {
     size_t arena_bytes, arena2_bytes;
     const int32_t *d_cnt;          // [entries] allowed pairs of each entry (device)
     const int32_t *d_row;          // [entries] query tile (global numbering b * tr + I) of each entry (device)
-    int64_t n_entries;             // list entries of all samples
+    mutable int64_t n_entries;     // list entries of all samples (a deferred build: once its report has been read)
     // [batch][2] = (surviving tiles, allowed pairs) per sample; read back from the device by the first
     // query that needs them (hdt_layout_stats), not by the build
     mutable std::vector<int64_t> h_stats;
@@ -84,6 +90,15 @@ struct hdt_layout {
     int32_t no_sort;
     int32_t *sort_hist, *sort_counters;
     const int32_t *level_copy, *parent_copy;
+    // A deferred build (hdt_layout_opts_t.deferred) has not looked at the device's report yet: whether the
+    // hierarchy was valid and how many list entries it needed.  hdt_layout_resolve reads it (once).
+    mutable bool pending;
+    mutable hdt_status_t build_status;     // what the report said, once it has been read
+    mutable int64_t entries_needed;        // list entries the build needed (-1: not known yet)
+    mutable char build_error[320];         // text of build_status
+    const unsigned long long *report;      // the build's word of pinned host memory
+    const unsigned long long *report_dev;  // the same word in the layout's own device memory
+    uint32_t ticket, ticket_before;        // the build's ticket; the one its report slot held when it was enqueued
 };
 
 // --- error reporting (hdt_api.hip) ---
@@ -97,6 +112,10 @@ hdt_status_t hdt_fail(hdt_status_t st, const char *fmt, ...);
     } while (0)
 
 bool hdt_layout_ok(const hdt_layout_t *l);
+// Reads the report of a deferred build: with `wait` it returns once the report is in (it waits for the build
+// kernel, not for the stream), without it only looks.  Returns the build's status as far as it is known (HDT_OK
+// while nothing is known); covers the transposed schedule a directed mask brings.  (hdt_layout.hip)
+hdt_status_t hdt_layout_resolve(const hdt_layout_t *l, bool wait);
 hdt_status_t hdt_layout_ensure_kperm(const hdt_layout_t *l);  // sorts s.kperm if the build did not (waits for the device) (hdt_layout.hip)
 hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (waits for the device) (hdt_layout.hip)
 void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)

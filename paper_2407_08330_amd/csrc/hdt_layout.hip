@@ -39,6 +39,7 @@
 // size in the rare case the guess was too small.
 // Device memory comes from a small cache of earlier layouts' buffers.
 #include <limits.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <algorithm>
@@ -121,6 +122,7 @@ struct SortArgs {
     int32_t *kperm, *slot, *cmin, *cmax;
     int32_t *counters;
     int ranges;  // also compute the slot range of every node's children (windowed layouts)
+    int32_t *level_copy;  // [B][n] or NULL: the layout's own copy of the level ids
 };
 
 // ---- sort, first half: validate, count the levels of each chunk ---------------------------------
@@ -140,6 +142,7 @@ __global__ __launch_bounds__(kThreads) void k_sort_count(SortArgs a)
             a.cmin[o + i] = INT_MAX;
             a.cmax[o + i] = -1;
         }
+        if (a.level_copy) a.level_copy[o + i] = l;
     }
     const bool bad = in && (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1));
     if (__ballot(bad) && lane == 0) atomicOr(&a.counters[CNT_ERR], 1);
@@ -383,7 +386,15 @@ __global__ __launch_bounds__(kThreads) void k_candidates(CandArgs a)
 struct EntryPart {
     int cnt;
     uint32_t any, all;
+    uint32_t col[4];  // entry_bitmaps only: key slots (32 per word) that some row of this wave may attend to
 };
+
+__device__ __forceinline__ uint32_t wave_or(uint32_t x)
+{
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) x |= (uint32_t)__shfl_xor((int)x, d);
+    return x;
+}
 
 __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int wsub, int khalf, int lane, int i, int pi,
                                                    bool rowok,
@@ -416,6 +427,8 @@ __device__ __forceinline__ EntryPart entry_bitmaps(bool active, int64_t c, int w
     EntryPart part;
     part.cnt = wave_sum(cnt);
     part.any = part.all = 0;
+#pragma unroll
+    for (int wd = 0; wd < 4; wd++) part.col[wd] = wave_or(w[wd]);
     // register-major masks of sub-block (rblk, cblk), accumulator register e: bit l <=> row
     // rblk*32 + l%32, column cblk*32 + (l/32)*4 + 8*(e/4) + e%4
 #pragma unroll
@@ -518,7 +531,8 @@ struct KeyListArgs {
     uint32_t *q_sub;
     unsigned long long *bits_rm;
     int32_t *counters;
-    unsigned long long *report;
+    unsigned long long *report;      // pinned host memory
+    unsigned long long *report_dev;  // the layout's own copy of the report
     uint32_t ticket;
     int self_reset;  // the counters are a slot that must be zero again when the build has reported
 };
@@ -565,6 +579,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     __shared__ int s_base, s_total, s_wtotal[kListWaves];
     __shared__ __attribute__((aligned(16))) int s_keys[kLdsKeys], s_kpar[kLdsKeys];
     __shared__ int s_tab_v[128], s_ntab;  // distinct parents of the tile's rows, and the rows of each
+    __shared__ int s_first;               // first real row of the tile (a position), INT_MAX if it has none
     __shared__ uint4 s_tab_rows[128];
     const int b = blockIdx.x / a.tr, I = blockIdx.x - b * a.tr, n = a.n;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -588,6 +603,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     };
     load_batch(g0);
     for (int w = tid; w < pw; w += kListThreads) s_par[w] = 0;
+    if (tid == 0) s_first = INT_MAX;
     lds_barrier();
     const int row0 = I * bm;
     bool check_parent = false;
@@ -603,6 +619,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
                 raise_error(a.counters);
             else if (l >= 0) {
                 me = make_int2(i, p);
+                atomicMin(&s_first, i);
                 if (p >= 0) {
                     atomicOr(&s_par[p >> 5], 1u << (p & 31));
                     check_parent = true;
@@ -707,6 +724,9 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
     lds_barrier();
     const int total = s_total, n_ent = (total + bn - 1) / bn;
     const bool in_lds = n_ent * bn <= kLdsKeys;
+    // Slots behind the last key name no key: they hold ~f, f = the tile's first real row (a list with a key has
+    // one), which is the row the attention kernels gather for such a slot.
+    const int no_key = ~s_first;
     // hands out the indices of this wave's needed keys, in document order inside every level
     int mybase = lane < kBuckets ? s_lcnt[wave][lane] : 0;  // lane k: next index of level k in this wave
     auto pack = [&](bool to_lds, int32_t *keys, int32_t *kpars, int key_fit) {
@@ -745,7 +765,10 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         }
     };
     if (in_lds) {  // while the reservation is in flight
-        for (int t = total + tid; t < n_ent * bn; t += kListThreads) s_keys[t] = s_kpar[t] = -1;  // tail of the last entry
+        for (int t = total + tid; t < n_ent * bn; t += kListThreads) {  // tail of the last entry
+            s_keys[t] = no_key;
+            s_kpar[t] = -1;
+        }
         pack(true, nullptr, nullptr, 0);
     }
     if (tid == 64) {
@@ -757,20 +780,24 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
                 __hip_atomic_store(reinterpret_cast<unsigned long long *>(a.counters + CNT_CAND), 0ull, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             }
-            __hip_atomic_store(a.report, report_word(a.ticket, err, (uint32_t)final_total), __ATOMIC_RELEASE,
-                               __HIP_MEMORY_SCOPE_SYSTEM);
+            const unsigned long long word = report_word(a.ticket, err, (uint32_t)final_total);
+            *a.report_dev = word;
+            __hip_atomic_store(a.report, word, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
     lds_barrier();
     const int64_t base = s_base;
     const size_t row = (size_t)b * a.tr + I;
-    if (tid == 0) {
-        a.q_range[2 * row] = (int32_t)base;
-        a.q_range[2 * row + 1] = (int32_t)(base + n_ent);
-    }
-    // entries past the capacity are not written (the host then repeats the build with larger arrays)
+    // entries past the capacity are not written, and the tile's range ends where they would begin: whoever walks
+    // the lists stays inside the arrays (the host learns of the shortfall from the report and repeats the build
+    // with larger arrays, or tells the caller of a deferred build to)
     const int64_t room = a.capacity - base;
     const int n_fit = room <= 0 ? 0 : (room < n_ent ? (int)room : n_ent);
+    if (tid == 0) {
+        const int32_t first = (int32_t)(room <= 0 ? a.capacity : base);
+        a.q_range[2 * row] = first;
+        a.q_range[2 * row + 1] = first + n_fit;
+    }
     const int key_fit = n_fit * bn;
     for (int e = tid; e < n_fit; e += kListThreads) a.c_row[base + e] = (int32_t)row;
     int32_t *keys = a.q_keys + (size_t)base * bn, *kpars = a.q_kpar + (size_t)base * bn;
@@ -780,7 +807,7 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
             if (t < total) kpars[t] = s_kpar[t];
         }
     } else {
-        for (int t = total + tid; t < key_fit; t += kListThreads) keys[t] = -1;
+        for (int t = total + tid; t < key_fit; t += kListThreads) keys[t] = no_key;
         pack(false, keys, kpars, key_fit);
         // The keys were written to global memory by other waves of this workgroup; the barrier orders those
         // stores before the loads below at workgroup scope, which is all that is needed on one compute unit
@@ -850,10 +877,11 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
                                                       const int32_t *__restrict__ c_col, int32_t *q_keys,
                                                       const int32_t *__restrict__ counters, int64_t capacity,
                                                       int n, int n_slots, int bm, int bn, int tr, int edges,
-                                                      unsigned long long *bits_rm, int32_t *c_cnt, uint32_t *c_sub)
+                                                      int force_dense, unsigned long long *bits_rm, int32_t *c_cnt,
+                                                      uint32_t *c_sub)
 {
-    __shared__ int s_cnt[2];
-    __shared__ uint32_t s_any[2], s_all[2];
+    __shared__ int s_cnt[2], s_first[2];
+    __shared__ uint32_t s_any[2], s_all[2], s_col[2][4];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t total = min((int64_t)(uint32_t)counters[CNT_CAND], capacity);  // low word of the combined counter
     for (int64_t c = blockIdx.x; c < total; c += gridDim.x) {
@@ -880,19 +908,36 @@ __global__ __launch_bounds__(128) void k_tile_bitmaps(const int32_t *__restrict_
             const int lv = level[o + pp], pr = parent[o + pp];
             kpos[u] = (okp && lv >= 0) ? kpos[u] : -1;
             kpar[u] = (okp && lv >= 0) ? pr : -1;
-            if (wave == 0 && 64 * u + lane < bn) q_keys[(size_t)c * bn + 64 * u + lane] = kpos[u];
         }
         const EntryPart part = entry_bitmaps(true, c, wave, -1, lane, i, pi, rowok, kpos, kpar, bm, bn, edges, bits_rm);
+        const unsigned long long real_rows = __ballot(rowok);
         __syncthreads();  // the previous candidate's partial results have been read
         if (lane == 0) {
             s_cnt[wave] = part.cnt;
             s_any[wave] = part.any;
             s_all[wave] = part.all;
+            s_first[wave] = real_rows ? I * bm + wave * 64 + __ffsll((long long)real_rows) - 1 : INT_MAX;
+#pragma unroll
+            for (int wd = 0; wd < 4; wd++) s_col[wave][wd] = part.col[wd];
         }
         __syncthreads();
+        if (wave == 0) {
+            // A slot keeps its key only if some row of the tile may attend to it; the others (pads, slots past the
+            // key order, keys of no concern to this tile) hold ~f, f = the tile's first real row (0 if it has
+            // none): the row the attention kernels gather in their place.
+            const int f = s_first[0] != INT_MAX ? s_first[0] : (s_first[1] != INT_MAX ? s_first[1] : 0);
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int si = 64 * u + lane;
+                const bool seen = ((s_col[0][si >> 5] | s_col[1][si >> 5]) >> (si & 31)) & 1u;
+                if (si < bn) q_keys[(size_t)c * bn + si] = seen ? kpos[u] : ~f;
+            }
+        }
         if (tid == 0) {
             c_cnt[c] = s_cnt[0] + s_cnt[1];
-            c_sub[c] = (s_any[0] | s_any[1]) | ((s_all[0] | s_all[1]) << 16);
+            // the dense baseline computes every sub-block, allowed pairs or not
+            const uint32_t any = force_dense ? (1u << ((bm >> 5) * (bn >> 5))) - 1u : (s_any[0] | s_any[1]);
+            c_sub[c] = any | ((s_all[0] | s_all[1]) << 16);
         }
     }
 }
@@ -961,6 +1006,7 @@ struct Carver {
 
 struct Phase1 {
     int32_t *kperm, *slot, *cmin, *cmax, *hist, *q_range, *counters, *level_copy, *parent_copy;
+    unsigned long long *report_copy;
     size_t zero_begin, zero_end;  // byte range that must start at zero
     size_t bytes;
 };
@@ -977,6 +1023,7 @@ Phase1 carve_phase1(char *base, int B, int n, int n_slots, int tr, int nchunks)
     p.q_range = c.take<int32_t>((size_t)B * tr * 2);
     p.level_copy = c.take<int32_t>((size_t)B * n);
     p.parent_copy = c.take<int32_t>((size_t)B * n);
+    p.report_copy = c.take<unsigned long long>(1);
     p.zero_begin = c.off;
     p.counters = c.take<int32_t>(64);
     p.zero_end = c.off;
@@ -1007,12 +1054,12 @@ Phase2 carve_phase2(char *base, int64_t cap, int bm, int bn)
     return p;
 }
 
-// ---- the build's report from the device: 64 words of pinned host memory, one per build in flight ----
-constexpr int kReportSlots = 64;
+// ---- the build's report from the device: words of pinned host memory, one per build in flight ----
+constexpr int kReportSlots = 1024;
 unsigned long long *g_reports = nullptr;  // never freed: a kernel may still write to it at exit
 uint32_t g_ticket = 0;
 
-unsigned long long *report_slot(uint32_t *ticket)
+unsigned long long *report_slot(uint32_t *ticket, uint32_t *ticket_before)
 {
     std::lock_guard<std::mutex> lk(g_pool_mutex);
     if (!g_reports) {
@@ -1027,7 +1074,13 @@ unsigned long long *report_slot(uint32_t *ticket)
     g_ticket = (g_ticket + 1) & 0xffffffu;
     if (g_ticket == 0) g_ticket = 1;
     *ticket = g_ticket;
-    return g_reports + (size_t)(g_ticket % kReportSlots) * 8;  // one 64-byte line per slot
+    unsigned long long *slot = g_reports + (size_t)(g_ticket % kReportSlots) * 8;  // one 64-byte line per slot
+    *ticket_before = (uint32_t)(__atomic_load_n(slot, __ATOMIC_ACQUIRE) >> 40);
+    if (*ticket_before == *ticket) {  // the ticket counter has wrapped around: a report of 2^24 builds ago
+        __atomic_store_n(slot, 0ull, __ATOMIC_RELEASE);
+        *ticket_before = 0;
+    }
+    return slot;
 }
 
 // The counters of a key-list build: device memory, one 256-byte slot per build in flight (chosen by the
@@ -1053,8 +1106,9 @@ int32_t *counter_slot(int device, uint32_t ticket)
     return g_counter_slots[device] + (size_t)(ticket % kReportSlots) * 64;
 }
 
-// polls the word until it carries this build's ticket; false after 10 s without it
-bool wait_for_report(const unsigned long long *slot, uint32_t ticket, unsigned long long *word)
+// polls the word until it carries this build's ticket; false after 10 s without it, or at once when the slot
+// has been taken over by a later build (it then holds neither this ticket nor the one it held before)
+bool wait_for_report(const unsigned long long *slot, uint32_t ticket, uint32_t ticket_before, unsigned long long *word)
 {
     const auto t0 = std::chrono::steady_clock::now();
     for (uint64_t spins = 0;; spins++) {
@@ -1063,12 +1117,69 @@ bool wait_for_report(const unsigned long long *slot, uint32_t ticket, unsigned l
             *word = w;
             return true;
         }
+        if ((uint32_t)(w >> 40) != ticket_before) return false;
         if ((spins & 0x3ff) == 0x3ff && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(10)) return false;
         __builtin_ia32_pause();
     }
 }
 
+const char kHierarchyText[] =
+    "level/parent arrays are not a valid hierarchy (level outside [-1, 32), parent outside [-1, n_pos), self-parent, "
+    "pad with a parent, or pad parent)";
+
 }  // namespace
+
+// What a deferred build's report says, read at most once per layout.
+static hdt_status_t resolve_one(const hdt_layout_t *L, bool wait)
+{
+    static std::mutex resolve_mutex;
+    std::lock_guard<std::mutex> lk(resolve_mutex);
+    if (L->pending) {
+        unsigned long long word = __atomic_load_n(L->report, __ATOMIC_ACQUIRE);
+        bool have = (uint32_t)(word >> 40) == L->ticket;
+        if (!have && !wait) return HDT_OK;
+        if (!have) have = wait_for_report(L->report, L->ticket, L->ticket_before, &word);
+        if (!have) {
+            // the slot has gone to a later build (or nothing came for 10 s): the copy in the layout's own memory
+            int dev = 0;
+            HDT_HIP_TRY(hipGetDevice(&dev));
+            if (dev != L->device) HDT_HIP_TRY(hipSetDevice(L->device));
+            hipError_t e = hipDeviceSynchronize();
+            if (e == hipSuccess) e = hipMemcpy(&word, L->report_dev, sizeof(word), hipMemcpyDeviceToHost);
+            if (dev != L->device) (void)hipSetDevice(dev);
+            if (e != hipSuccess) return hdt_fail(HDT_ERR_HIP, "hdt_layout_resolve: %s", hipGetErrorString(e));
+            if ((uint32_t)(word >> 40) != L->ticket)
+                return hdt_fail(HDT_ERR_HIP, "hdt_layout_resolve: the build kernel finished without its report");
+        }
+        const int64_t need = (int64_t)(word & 0xffffffffu);
+        L->entries_needed = need;
+        if ((word >> 39) & 1u) {
+            L->build_status = HDT_ERR_HIERARCHY;
+            snprintf(L->build_error, sizeof(L->build_error), "deferred hdt_build_layout: %s", kHierarchyText);
+        } else if (need > L->capacity) {
+            L->build_status = HDT_ERR_SHAPE;
+            snprintf(L->build_error, sizeof(L->build_error),
+                     "deferred hdt_build_layout: the schedule needs %lld list entries, the layout holds %lld "
+                     "(build again with opts->capacity)", (long long)need, (long long)L->capacity);
+        } else {
+            L->n_entries = need;
+        }
+        if (!((word >> 39) & 1u)) {
+            std::lock_guard<std::mutex> lk2(g_pool_mutex);
+            g_capacity_hint = need;
+        }
+        L->pending = false;
+    }
+    if (L->build_status != HDT_OK) return hdt_fail(L->build_status, "%s", L->build_error);
+    return HDT_OK;
+}
+
+hdt_status_t hdt_layout_resolve(const hdt_layout_t *L, bool wait)
+{
+    if (hdt_status_t st = resolve_one(L, wait)) return st;
+    if (L->transposed) return resolve_one(L->transposed, wait);
+    return HDT_OK;
+}
 
 hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got) { return pool_alloc(out, bytes, got); }
 
@@ -1087,6 +1198,7 @@ hdt_status_t hdt_layout_stats(const hdt_layout_t *L)
     static std::mutex stats_mutex;
     std::lock_guard<std::mutex> lk(stats_mutex);
     if (L->stats_ready) return HDT_OK;
+    if (hdt_status_t st = hdt_layout_resolve(L, true)) return st;
     const int64_t E = L->n_entries;
     std::vector<int32_t> row((size_t)E), cnt((size_t)E);
     int dev = 0;
@@ -1125,7 +1237,7 @@ hdt_status_t hdt_layout_ensure_kperm(const hdt_layout_t *L)
     if (e == hipSuccess) {
         const int B = L->s.batch, n = L->s.n_pos, nchunks = (n + kChunk - 1) / kChunk;
         SortArgs sa{L->level_copy, L->parent_copy, n, L->s.n_slots, nchunks, L->no_sort, L->sort_hist,
-                    const_cast<int32_t *>(L->s.kperm), nullptr, nullptr, nullptr, L->sort_counters, 0};
+                    const_cast<int32_t *>(L->s.kperm), nullptr, nullptr, nullptr, L->sort_counters, 0, nullptr};
         hipLaunchKernelGGL(k_sort_count, dim3((unsigned)B * nchunks), dim3(kThreads), 0, nullptr, sa);
         hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)B * nchunks), dim3(kThreads), 0, nullptr, sa);
         e = hipGetLastError();
@@ -1195,12 +1307,17 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     if (batch < 0 || n_pos < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: negative size");
     if (n_pos > (1 << 19)) return hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: n_pos %d > 2^19", n_pos);
     int bm = 128, bn = 64, force_dense = 0, no_sort = 0, windowed = 0;
+    bool deferred = false;
+    int64_t capacity_opt = 0;
     if (opts) {
         if (opts->tile_m) bm = opts->tile_m;
         if (opts->tile_n) bn = opts->tile_n;
         force_dense = opts->force_dense != 0;
         no_sort = opts->no_sort != 0;
         windowed = opts->windowed != 0 || force_dense;
+        if (opts->capacity < 0) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_build_layout: capacity = %lld", (long long)opts->capacity);
+        capacity_opt = opts->capacity;
+        deferred = opts->deferred != 0 && !windowed;  // the windowed kernels are launched from what the first reports
     }
     if (bm < 32 || bm > 128 || bm % 32 || bn < 32 || bn > 128 || bn % 32)
         return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_build_layout: tile %dx%d (each side: 32, 64, 96 or 128)", bm, bn);
@@ -1232,6 +1349,12 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     L->n_compact = 0;
     L->device_bytes = 0;
     L->device = 0;
+    L->pending = false;
+    L->build_status = HDT_OK;
+    L->entries_needed = 0;
+    L->build_error[0] = 0;
+    L->report = L->report_dev = nullptr;
+    L->ticket = L->ticket_before = 0;
     HdtSchedule &s = L->s;
     memset(&s, 0, sizeof(s));
     s.batch = batch;
@@ -1274,13 +1397,42 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
         BUILD_TRY(pool_alloc(&L->arena, p.bytes, &L->arena_bytes));
         p = carve_phase1((char *)L->arena, B, n, s.n_slots, tr, nchunks);
 
-        // capacity of the per-tile arrays: exact for the dense baseline, else a guess
-        int64_t cap = force_dense ? (int64_t)B * tr * tc : (int64_t)B * ((int64_t)tr * 8 + 64);
-        {
+        // The schedule as far as the host knows it before the device has reported.
+        auto adopt = [&](const Phase2 &q, int64_t cap) {
+            L->capacity = cap;
+            s.kperm = p.kperm;
+            L->kperm_ready = windowed != 0;
+            L->no_sort = no_sort;
+            L->sort_hist = p.hist;
+            L->sort_counters = p.counters;
+            L->level_copy = p.level_copy;
+            L->parent_copy = p.parent_copy;
+            s.q_range = p.q_range;
+            s.q_cols = q.q_cols;
+            s.q_keys = q.q_keys;
+            s.q_sub = q.q_sub;
+            s.bits_rm = q.bits_rm;
+            s.row_flag = p.level_copy;
+            L->d_cnt = q.c_cnt;
+            L->d_row = q.c_row;
+            L->force_dense = force_dense;
+            L->device_bytes = (int64_t)(L->arena_bytes + L->arena2_bytes);
+        };
+        // capacity of the per-tile arrays: exact for the dense baseline, the caller's if given, else a guess raised
+        // by what earlier builds needed.  A deferred build cannot be repeated by this call, so it takes what no
+        // document can exceed (every query tile listing every key) as far as that stays below 256 MiB.
+        const int64_t cap_bound = (int64_t)B * tr * tc;
+        int64_t cap = force_dense ? cap_bound : (int64_t)B * ((int64_t)tr * 8 + 64);
+        if (!force_dense) {
             std::lock_guard<std::mutex> lk(g_pool_mutex);
-            if (!force_dense && g_capacity_hint + g_capacity_hint / 8 > cap) cap = g_capacity_hint + g_capacity_hint / 8;
+            if (g_capacity_hint + g_capacity_hint / 8 > cap) cap = g_capacity_hint + g_capacity_hint / 8;
         }
-        cap = cap > (int64_t)B * tr * tc ? (int64_t)B * tr * tc : cap;
+        if (deferred) {
+            const int64_t per_entry = (int64_t)carve_phase2(nullptr, 1024, bm, bn).bytes / 1024 + 1;
+            cap = std::max(cap, ((int64_t)256 << 20) / per_entry);
+        }
+        if (!force_dense && capacity_opt > 0) cap = capacity_opt;
+        cap = cap > cap_bound ? cap_bound : cap;
         for (int attempt = 0; attempt < 2; attempt++) {
             if (cap >= (1LL << 31)) {
                 status = hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: %lld candidate tiles", (long long)cap);
@@ -1289,8 +1441,8 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
             Phase2 q = carve_phase2(nullptr, cap, bm, bn);
             BUILD_TRY(pool_alloc(&L->arena2, q.bytes, &L->arena2_bytes));
             q = carve_phase2((char *)L->arena2, cap, bm, bn);
-            uint32_t ticket = 0;
-            unsigned long long *report = report_slot(&ticket);
+            uint32_t ticket = 0, ticket_before = 0;
+            unsigned long long *report = report_slot(&ticket, &ticket_before);
             if (!report) {
                 status = hdt_fail(HDT_ERR_OOM, "hdt_build_layout: no pinned host memory for the build report");
                 goto fail;
@@ -1302,7 +1454,7 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 BUILD_TRY(hipMemsetAsync((char *)L->arena + p.zero_begin, 0, p.zero_end - p.zero_begin, st));
             if (windowed) {
                 SortArgs sa{d_level, d_parent, n, s.n_slots, nchunks, no_sort, p.hist, p.kperm, p.slot, p.cmin,
-                            p.cmax, p.counters, 1};
+                            p.cmax, p.counters, 1, p.level_copy};
                 {
                     HdtTimer t("hdt_layout_sort_count", st);
                     hipLaunchKernelGGL(k_sort_count, dim3((unsigned)B * nchunks), dim3(kThreads), 0, st, sa);
@@ -1321,7 +1473,8 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 // and is sorted from the layout's copy of the ids only when someone asks (hdt_layout_export)
                 KeyListArgs ka{d_level, d_parent, n, bm, bn, tr, no_sort, edges, cap, p.q_range, q.c_row, q.q_keys, q.q_kpar,
                                q.c_cnt, p.level_copy, p.parent_copy, q.q_sub, q.bits_rm,
-                               slot_counters ? slot_counters : p.counters, report, ticket, slot_counters != nullptr};
+                               slot_counters ? slot_counters : p.counters, report, p.report_copy, ticket,
+                               slot_counters != nullptr};
                 const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
                 if (lds > 32 * 1024)  // with the kernel's static arrays: beyond the 64 KB a launch gets by default
                     BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1333,35 +1486,50 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);
                 HdtTimer t("hdt_layout_tile_bitmaps", st);
                 hipLaunchKernelGGL(k_tile_bitmaps, dim3(grid), dim3(128), 0, st, d_level, d_parent, p.kperm, q.c_row,
-                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, edges,
+                                   q.q_cols, q.q_keys, p.counters, cap, n, s.n_slots, bm, bn, tr, edges, force_dense,
                                    q.bits_rm, q.c_cnt, q.q_sub);
             }
             BUILD_TRY(hipGetLastError());
+            if (deferred) {
+                // The layout goes out as it is.  What the device reports (through the same word of pinned host
+                // memory, and a copy in the layout's own memory) is read by hdt_layout_resolve, when someone asks.
+                adopt(q, cap);
+                L->n_entries = 0;
+                L->entries_needed = -1;
+                L->pending = true;
+                L->report = report;
+                L->report_dev = p.report_copy;
+                L->ticket = ticket;
+                L->ticket_before = ticket_before;
+                *out = L;
+                return HDT_OK;
+            }
             // The host needs two facts before it can hand the layout out: whether the hierarchy was valid and
             // whether the per-tile arrays were large enough.  The candidate kernel knows both before it writes
             // the lists; it stores them into pinned host memory and the host polls that word instead of
             // draining the stream, so the bitmap kernel and whatever the caller enqueues next keep the GPU busy.
             unsigned long long word = 0;
-            if (!wait_for_report(report, ticket, &word)) {
+            if (!wait_for_report(report, ticket, ticket_before, &word)) {
                 // no word within the time limit: drain the stream and look again, then read the counters the slow way
                 BUILD_TRY(hipStreamSynchronize(st));
                 word = __atomic_load_n(report, __ATOMIC_ACQUIRE);
                 if ((uint32_t)(word >> 40) != ticket) {
                     if (slot_counters) {
-                        status = hdt_fail(HDT_ERR_HIP, "hdt_build_layout: the build kernel finished without its report");
-                        goto fail;
+                        BUILD_TRY(hipMemcpy(&word, p.report_copy, sizeof(word), hipMemcpyDeviceToHost));
+                        if ((uint32_t)(word >> 40) != ticket) {
+                            status = hdt_fail(HDT_ERR_HIP, "hdt_build_layout: the build kernel finished without its report");
+                            goto fail;
+                        }
+                    } else {
+                        int32_t cnt[4] = {0, 0, 0, 0};
+                        BUILD_TRY(hipMemcpy(cnt, p.counters, sizeof(cnt), hipMemcpyDeviceToHost));
+                        word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);  // low word of the combined counter
                     }
-                    int32_t cnt[4] = {0, 0, 0, 0};
-                    BUILD_TRY(hipMemcpy(cnt, p.counters, sizeof(cnt), hipMemcpyDeviceToHost));
-                    word = report_word(ticket, cnt[CNT_ERR], (uint32_t)cnt[CNT_CAND]);  // low word of the combined counter
                 }
             }
             if ((word >> 39) & 1u) {
                 BUILD_TRY(hipStreamSynchronize(st));  // the bitmap kernel still reads the arenas
-                status = hdt_fail(HDT_ERR_HIERARCHY,
-                                  "hdt_build_layout: level/parent arrays are not a valid hierarchy (level outside "
-                                  "[-1, %d), parent outside [-1, n_pos), self-parent, pad with a parent, or pad parent)",
-                                  HDT_MAX_LEVELS);
+                status = hdt_fail(HDT_ERR_HIERARCHY, "hdt_build_layout: %s", kHierarchyText);
                 goto fail;
             }
             const int64_t need = (int64_t)(word & 0xffffffffu);
@@ -1370,28 +1538,18 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 if (!force_dense) g_capacity_hint = need;
             }
             if (need <= cap) {
-                L->capacity = cap;
+                adopt(q, cap);
                 L->n_entries = need;
-                s.kperm = p.kperm;
-                L->kperm_ready = windowed != 0;
-                L->no_sort = no_sort;
-                L->sort_hist = p.hist;
-                L->sort_counters = p.counters;
-                L->level_copy = p.level_copy;
-                L->parent_copy = p.parent_copy;
-                s.q_range = p.q_range;
-                s.q_cols = q.q_cols;
-                s.q_keys = q.q_keys;
-                s.q_sub = q.q_sub;
-                s.bits_rm = q.bits_rm;
-                L->d_cnt = q.c_cnt;
-                L->d_row = q.c_row;
-                L->force_dense = force_dense;
-                L->device_bytes = (int64_t)(L->arena_bytes + L->arena2_bytes);
+                L->entries_needed = need;
                 *out = L;
                 return HDT_OK;
             }
             BUILD_TRY(hipStreamSynchronize(st));  // the bitmap kernel still writes the arrays about to be replaced
+            if (capacity_opt > 0) {
+                status = hdt_fail(HDT_ERR_SHAPE, "hdt_build_layout: the schedule needs %lld list entries, opts->capacity is %lld",
+                                  (long long)need, (long long)capacity_opt);
+                goto fail;
+            }
             // the guess was too small: once more with the exact size
             pool_free(L->arena2, L->arena2_bytes, L->device);
             L->arena2 = nullptr;

@@ -48,6 +48,12 @@ __device__ __forceinline__ bf16x8 lds_read_tr_8(const char *p0, const char *p1)
     return __builtin_bit_cast(bf16x8, r);
 }
 
+__device__ __forceinline__ bf16x8 zero_bf16x8()
+{
+    const s16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    return __builtin_bit_cast(bf16x8, z);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16 &p, int first)

@@ -102,6 +102,11 @@ __device__ __forceinline__ void wg_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// The row to gather for a key slot.  A slot without a key holds ~f, f being a position of the same sample that
+// some row of the tile may attend to: its rows are finite whenever the tile's real rows are, so the zero weights
+// the bitmap gives the slot never meet a non-finite operand (pad rows may hold anything).
+__device__ __forceinline__ int gather_row(int slot_value) { return slot_value ^ (slot_value >> 31); }
+
 template <int D, int S_, bool AUX, typename G>
 struct Pipe {
     static constexpr int BM = G::BM, BN = G::BN, NW = G::NW;
@@ -156,14 +161,14 @@ struct Pipe {
 #pragma unroll
         for (int i = 0; i < NI; i++) {
             const int r = wave * LPW + i * RPI + lr;
-            const int pos = max(pb[r], 0);  // slots without a key: any readable row, the bitmap masks them
+            const int pos = gather_row(pb[r]);
             const uint32_t off = (uint32_t)pos * ROWB + (uint32_t)((c ^ swz(r & 7)) * 16);  // bytes
             const uint32_t dst = (uint32_t)((wave * LPW + i * RPI) * ROWB);
             dma16(a, off, smem_addr + (stage * 2 + 0) * TILE + dst);
             dma16(b, off, smem_addr + (stage * 2 + 1) * TILE + dst);
         }
         if (AUX) {
-            const int pos = max(pb[lane & (BN - 1)], 0);
+            const int pos = gather_row(pb[lane & (BN - 1)]);
             const float *src = (wave & 1) ? aux1 : aux0;
             dma4(src, (uint32_t)pos * 4u, smem_addr + DATA_BYTES + POS_BYTES + ((stage * NW + wave) * POSW) * 4);
         }

@@ -12,14 +12,15 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": 5e-2, "f32": 1e-4}
 
 
-def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0, tile=(0, 0)):
+def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0, tile=(0, 0),
+                 force_dense=False):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v, d_o), (q_, k_, v_, do_) = make_inputs(B, H, N, D, seed, dtype, n_tensors=4)
     lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), tile_m=tile[0], tile_n=tile[1],
-                               windowed=windowed, edges=edges)
+                               windowed=windowed, edges=edges, force_dense=force_dense)
     o_, lse_ = hdt.hdt_attn_fwd(lay, q_, k_, v_, scale)
     dq_ = torch.full_like(q_, float("nan"))
     dk_ = torch.full_like(q_, float("nan"))
@@ -187,3 +188,12 @@ def test_bwd_argument_errors():
     with pytest.raises(hdt.HdtError) as e:
         hdt.hdt_attn_bwd(lay, q, q.clone(), q.clone(), q.clone(), lse, q.clone(), 0.1, dq=q)
     assert e.value.name == "HDT_ERR_INVALID_ARG"
+
+
+@pytest.mark.parametrize("dtype,D,tile", [("bf16", 64, (128, 64)), ("bf16", 128, (64, 32)), ("f32", 64, (128, 64))])
+def test_bwd_dense_baseline_layout(oracle, dtype, D, tile):
+    """Backward on the dense masked-attention baseline (every tile issued and computed, mask per element)."""
+    wl = inputs.make_workload(2, batch=2)
+    level, parent = wl.level[:, :1024].copy(), wl.parent[:, :1024].copy()
+    say(f"[bwd] force_dense layout, {dtype} d={D} tile {tile}")
+    run_bwd_case(oracle, level, parent, 3, D, dtype, 4200 + D, tile=tile, force_dense=True)

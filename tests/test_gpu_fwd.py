@@ -12,14 +12,15 @@ pytestmark = pytest.mark.gpu
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
 
 
-def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0, tile=(0, 0)):
+def run_fwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=False, edges=0, tile=(0, 0),
+                 force_dense=False):
     import torch
     import paper_2407_08330_amd as hdt
     B, N = level.shape
     scale = 1.0 / np.sqrt(D) if scale is None else scale
     (q, k, v), (dq_, dk_, dv_) = make_inputs(B, H, N, D, seed, dtype)
     lay = hdt.hdt_build_layout(to_dev_i32(level), to_dev_i32(parent), tile_m=tile[0], tile_n=tile[1],
-                               windowed=windowed, edges=edges)
+                               windowed=windowed, edges=edges, force_dense=force_dense)
     o = torch.full_like(dq_, float("nan"))
     lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device="cuda")
     hdt.hdt_attn_fwd(lay, dq_, dk_, dv_, scale, o=o, lse=lse)
@@ -199,3 +200,15 @@ def test_fwd_argument_errors():
     qf = torch.zeros((1, 1, 512, 64), dtype=torch.float32, device="cuda")
     hdt.hdt_attn_fwd(lay32, qf, qf.clone(), qf.clone(), 0.1)   # fp32 path takes any tile shape
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype,D,tile", [("bf16", 64, (128, 64)), ("bf16", 128, (64, 32)), ("f32", 64, (128, 64))])
+def test_fwd_dense_baseline_layout(oracle, dtype, D, tile):
+    """The dense masked-attention baseline: every tile of the 1024 x 1024 score matrix is issued and computed,
+    the mask applied per element.  Same results as the sparse schedule."""
+    wl = inputs.make_workload(2, batch=2)
+    level, parent = wl.level[:, :1024].copy(), wl.parent[:, :1024].copy()
+    say(f"[fwd] force_dense layout, {dtype} d={D} tile {tile}")
+    lay = run_fwd_case(oracle, level, parent, 3, D, dtype, 4100 + D, tile=tile, force_dense=True)
+    info = lay.info()
+    assert info["n_tiles"] == 2 * (1024 // tile[0]) * (1024 // tile[1])

@@ -287,6 +287,80 @@ def test_layout_builds_from_two_host_threads(oracle):
     assert not errors, errors[:3]
 
 
+def test_deferred_build_matches_the_waiting_one(oracle):
+    # a deferred build only enqueues its kernel; the schedule it leaves is the same, and hdt_layout_status tells
+    # how many list entries it needed
+    import torch
+    import paper_2407_08330_amd as hdt
+    for config, tile in [(1, (128, 64)), (2, (128, 64)), (3, (64, 32))]:
+        wl = inputs.make_workload(config, batch=2 if config > 1 else None)
+        say(f"[layout] deferred build, config {config}, tile {tile}")
+        lay = _build(wl.level, wl.parent, tile_m=tile[0], tile_n=tile[1], deferred=True)
+        need = lay.status()
+        tiles, _ = compare_layout(oracle, lay, wl.level, wl.parent, tile[0], tile[1])
+        assert need == tiles
+        lay.destroy()
+    # many deferred builds in a row on one stream, looked at only at the end (the report slots are a ring)
+    wl = inputs.make_workload(1)
+    lv, pr = to_dev_i32(wl.level), to_dev_i32(wl.parent)
+    lays = [hdt.hdt_build_layout(lv, pr, deferred=True) for _ in range(40)]
+    torch.cuda.synchronize()
+    want = lays[0].info()
+    for lay in lays:
+        info = lay.info()
+        assert (info["n_tiles"], info["nnz"]) == (want["n_tiles"], want["nnz"])
+        lay.destroy()
+
+
+def test_deferred_build_reports_its_errors_later():
+    import torch
+    import paper_2407_08330_amd as hdt
+    bad_l = np.array([[0, 1, 2, 3, -1, -1] + [-1] * 122], np.int32)
+    bad_p = np.array([[-1, 1, 1, 2, -1, -1] + [-1] * 122], np.int32)   # position 1 is its own parent
+    say("[layout] deferred build of an invalid hierarchy")
+    lay = _build(bad_l, bad_p, deferred=True)          # returns without having looked
+    with pytest.raises(hdt.HdtError) as e:
+        lay.status()
+    assert e.value.name == "HDT_ERR_HIERARCHY"
+    q = torch.zeros((1, 1, 128, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(hdt.HdtError) as e:               # known by now: attention calls refuse the layout
+        hdt.hdt_attn_fwd(lay, q, q.clone(), q.clone(), 0.125)
+    assert e.value.name == "HDT_ERR_HIERARCHY"
+    with pytest.raises(hdt.HdtError):
+        lay.info()
+    lay.destroy()
+
+    # too little room: the kernels stay inside the arrays, the status says how much is needed
+    n = 3000
+    level = np.array([[0] + [1] * (n - 1) + [-1] * 72], np.int32)
+    parent = np.array([[-1] + [0] * (n - 1) + [-1] * 72], np.int32)
+    say("[layout] deferred build with too small a capacity")
+    x = torch.randn((1, 2, n + 72, 64), device="cuda").to(torch.bfloat16)
+    y, z = x.clone(), x.clone()
+    lv, pr = to_dev_i32(level), to_dev_i32(parent)
+    torch.cuda.synchronize()
+    lay = hdt.hdt_build_layout(lv, pr, deferred=True, capacity=100)
+    try:   # enqueued right behind the build: runs on the truncated lists, inside the arrays ...
+        hdt.hdt_attn_fwd(lay, x, y, z, 0.125)
+    except hdt.HdtError as err:   # ... unless the report was quicker than this host thread
+        assert err.name == "HDT_ERR_SHAPE"
+    torch.cuda.synchronize()
+    with pytest.raises(hdt.HdtError) as e:
+        lay.status()
+    assert e.value.name == "HDT_ERR_SHAPE" and e.value.entries_needed == 24 * 47
+    lay.destroy()
+    lay = _build(level, parent, deferred=True, capacity=24 * 47)
+    assert lay.status() == 24 * 47 and lay.info()["nnz"] == n * n
+    lay.destroy()
+    # the same limit on a build that waits: an error instead of a second attempt
+    with pytest.raises(hdt.HdtError) as e:
+        _build(level, parent, capacity=100)
+    assert e.value.name == "HDT_ERR_SHAPE"
+    lay = _build(level, parent, capacity=24 * 47 + 5)
+    assert lay.info()["n_tiles"] == 24 * 47
+    lay.destroy()
+
+
 def test_layout_empty_inputs():
     import torch
     import paper_2407_08330_amd as hdt
