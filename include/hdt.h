@@ -290,6 +290,22 @@ hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void 
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * hdt_attn_bwd_no_alloc -- hdt_attn_bwd for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same computation with the same arguments
+ * except the workspace, which is an array inside the library (HDT_NO_ALLOC_WORKSPACE_BYTES of device memory
+ * that every GPU the library runs on holds until the process ends).  The call allocates nothing and frees
+ * nothing.  HDT_ERR_SHAPE if hdt_attn_bwd_workspace_bytes() of the call exceeds the array (for a self-attention
+ * layout: batch * heads * n_pos > 2^21); the other errors are hdt_attn_bwd's.  All calls on one GPU share the
+ * array: calls that may overlap there (different streams, different host threads) race; calls on one stream
+ * do not.  Nothing in the array has to survive between calls and nothing in it has to start at zero.
+ */
+#define HDT_NO_ALLOC_WORKSPACE_BYTES (8u << 20)
+hdt_status_t hdt_attn_bwd_no_alloc(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
+                                   const void *o, const float *lse, const void *d_o, void *dq, void *dk, void *dv,
+                                   int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
+                                   void *stream);
+
+/*
  * Hierarchical positional encoding (Sec. 3.2 "Hierarchical Positional Encoding", Eq. pos_enc, Fig. 3):
  * every position carries one linear index p^l per hierarchy level l = 1 .. n_levels (level 0 needs none);
  *     HPE(p, c) = sum_l sin(w_k p^l) if c = 2k,  sum_l cos(w_k p^l) if c = 2k + 1,  w_k = 10000^(-2k/d_model),

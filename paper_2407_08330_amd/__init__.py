@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     HdtError,
     Layout,
     hdt_attn_bwd,
+    hdt_attn_bwd_no_alloc,
     hdt_attn_bwd_workspace_bytes,
     hdt_attn_fwd,
     hdt_build_cross_layout,

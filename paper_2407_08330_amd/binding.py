@@ -18,7 +18,7 @@ HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 
 EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_status", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
-    "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_status_string", "hdt_last_error",
+    "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_attn_bwd_no_alloc", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
     "hdt_parents_from_levels", "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
 ]
@@ -85,6 +85,8 @@ def load_library():
     lib.hdt_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp,
                                  ctypes.c_size_t, vp]
     lib.hdt_attn_bwd.restype = ctypes.c_int
+    lib.hdt_attn_bwd_no_alloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp]
+    lib.hdt_attn_bwd_no_alloc.restype = ctypes.c_int
     lib.hdt_status_string.argtypes = [ctypes.c_int]
     lib.hdt_status_string.restype = ctypes.c_char_p
     lib.hdt_last_error.argtypes = []
@@ -307,6 +309,20 @@ def hdt_attn_bwd(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq=
                                        _ptr(dq), _ptr(dk), _ptr(dv), H, D, _dtype_code(q), float(softmax_scale),
                                        _ptr(workspace), workspace.numel() * workspace.element_size(),
                                        _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def hdt_attn_bwd_no_alloc(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq, dk, dv, stream=None):
+    """hdt_attn_bwd on the library's own workspace: every tensor, outputs included, comes from the caller, and
+    neither this wrapper nor the library allocates device memory.  Returns (dq, dk, dv)."""
+    B, H, N, D = q.shape
+    _check_tensors((q, o, d_o, dq), q.shape)
+    _check_tensors((k, v, dk, dv), (B, H, layout.n_kv, D))
+    if (B, N) != (layout.batch, layout.n_pos) or any(t.dtype != q.dtype for t in (k, v, o, d_o, dq, dk, dv)):
+        raise ValueError("tensor shapes or dtypes do not match the layout")
+    _check(load_library().hdt_attn_bwd_no_alloc(layout.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                                _ptr(dq), _ptr(dk), _ptr(dv), H, D, _dtype_code(q),
+                                                float(softmax_scale), _stream_ptr(stream)))
     return dq, dk, dv
 
 

@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "hdt_internal.h"
 
 // ---------------------------------------------------------------------------- errors
@@ -345,6 +347,54 @@ extern "C" __attribute__((visibility("default"))) size_t hdt_attn_bwd_workspace_
     // a cross-attention layout with a compact pair: compact copies of K, V and of their gradients behind it
     if (layout->compact) n += hdt_cross_compact_workspace_bytes(layout, heads, head_dim, dt == HDT_BF16 ? 2 : 4);
     return n;
+}
+
+// ---- hdt_attn_bwd for callers that cannot allocate: the workspace is an array of the library's own ----
+// One copy per GPU, alive until the process ends.  In host code the array's name only stands for the symbol;
+// its address on the current device comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[HDT_NO_ALLOC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+hdt_status_t scratch_on_current_device(void **out)
+{
+    int dev = 0;
+    HDT_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hdt_fail(HDT_ERR_UNSUPPORTED, "hdt_attn_bwd_no_alloc: device %d", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HDT_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return hdt_fail(HDT_ERR_HIP, "hdt_attn_bwd_no_alloc: the scratch array has no address on device %d", dev);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HDT_OK;
+}
+}  // namespace
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd_no_alloc(
+    const hdt_layout_t *layout, const void *q, const void *k, const void *v, const void *o, const float *lse,
+    const void *d_o, void *dq, void *dk, void *dv, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float scale,
+    void *stream)
+{
+    hdt_status_t st = check_attn_args("hdt_attn_bwd_no_alloc", layout, heads, head_dim, dt, scale);
+    if (st != HDT_OK) return st;
+    if (layout->s.batch == 0 || layout->s.n_pos == 0 || heads == 0) return HDT_OK;
+    const size_t need = hdt_attn_bwd_workspace_bytes(layout, heads, head_dim, dt);
+    if (need > (size_t)HDT_NO_ALLOC_WORKSPACE_BYTES)
+        return hdt_fail(HDT_ERR_SHAPE,
+                        "hdt_attn_bwd_no_alloc: this call needs %zu bytes of workspace, the library's own array holds %zu "
+                        "(batch * heads * n_pos <= %zu for a self-attention layout); use hdt_attn_bwd",
+                        need, (size_t)HDT_NO_ALLOC_WORKSPACE_BYTES, (size_t)HDT_NO_ALLOC_WORKSPACE_BYTES / sizeof(float));
+    void *ws = nullptr;
+    st = scratch_on_current_device(&ws);
+    if (st != HDT_OK) return st;
+    return hdt_attn_bwd(layout, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, dt, scale, ws,
+                        (size_t)HDT_NO_ALLOC_WORKSPACE_BYTES, stream);
 }
 
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
