@@ -19,14 +19,21 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hdt_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# HDT_ORACLE_SANITIZE=1 (CPU test runs only): the oracle built with AddressSanitizer and
+# UndefinedBehaviorSanitizer, loaded by a python started with gcc's libasan preloaded:
+#   HDT_ORACLE_SANITIZE=1 ASAN_OPTIONS=detect_leaks=0 LD_PRELOAD=$(gcc -print-file-name=libasan.so) \
+#       python -m pytest tests -m "not gpu" --deselect tests/test_abi.py
+_SANITIZE = os.environ.get("HDT_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "liboracle_san.so" if _SANITIZE else "liboracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (fp64, no fast-math)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        flags = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=undefined"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *flags, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -15,8 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     # packed fp32 instructions are kept off on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # no NaN-quieting v_max(x, x) in front of every fmaxf: inputs are required to be finite and the
-    # kernels never produce a NaN on their own (infinities are still honoured)
+    # no NaN-quieting v_max(x, x) in front of every fmaxf: wherever a NaN can stand (rows of pad positions may
+    # hold anything) it is removed by a select before any arithmetic looks at it, and the kernels produce none
+    # on their own (infinities are still honoured)
     "-fno-honor-nans",
     "-Wno-unused-command-line-argument",
     # the direct-to-LDS loads set M0 inside their asm block and list it as clobbered
@@ -24,15 +25,14 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra_flags=(), out: str = LIB, tag: str = "") -> str:
-    """Compile every source and link the shared library.  Always recompiles.  ``out``/``tag``/
-    ``extra_flags`` build a variant (tuning experiments) next to the default library."""
+def build(verbose: bool = False) -> str:
+    """Compile every source and link the shared library.  Always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", tag + ".o"))
-        cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(_ROOT, "include"), "-I", CSRC, "-c",
+        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", CSRC, "-c",
                os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -49,17 +49,14 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB, tag: str = "") 
             print(log)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
-    return out
+    return LIB
 
 
 if __name__ == "__main__":
     import argparse
     ap = argparse.ArgumentParser()
-    ap.add_argument("--out", default=LIB)
-    ap.add_argument("--tag", default="")
-    ap.add_argument("--flag", action="append", default=[])
     ap.add_argument("-v", "--verbose", action="store_true")
     a = ap.parse_args()
-    print(build(verbose=a.verbose, extra_flags=a.flag, out=a.out, tag=a.tag))
+    print(build(verbose=a.verbose))

@@ -38,22 +38,10 @@ using namespace hdt_tile;
 
 template <int D>
 struct BwdCfg {
-#ifndef HDT_DQ_S64
-#define HDT_DQ_S64 3
-#endif
-#ifndef HDT_DKV_S64
-#define HDT_DKV_S64 2
-#endif
-#ifndef HDT_BWD_W64
-#define HDT_BWD_W64 3
-#endif
-#ifndef HDT_BWD_W128
-#define HDT_BWD_W128 2
-#endif
     // ring stages of the two roles and waves per SIMD (register budget) of the kernel
-    static constexpr int S_DQ = (D == 64) ? HDT_DQ_S64 : 2;
-    static constexpr int S_DKV = (D == 64) ? HDT_DKV_S64 : 2;
-    static constexpr int WAVES = (D == 64) ? HDT_BWD_W64 : HDT_BWD_W128;
+    static constexpr int S_DQ = (D == 64) ? 3 : 2;
+    static constexpr int S_DKV = 2;
+    static constexpr int WAVES = (D == 64) ? 3 : 2;
     // At head size 128 the dK/dV role would need 128 accumulator registers per lane on top of 64 operand
     // registers, which leaves one wave per SIMD.  It is split there into a dV role and a dK role (each
     // recomputes the scores), so that every role fits two waves per SIMD.

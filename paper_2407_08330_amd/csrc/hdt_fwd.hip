@@ -29,14 +29,8 @@ using namespace hdt_tile;
 
 template <int D>
 struct FwdCfg {
-#ifndef HDT_FWD_S64
-#define HDT_FWD_S64 2
-#endif
-#ifndef HDT_FWD_W64
-#define HDT_FWD_W64 4
-#endif
-    static constexpr int S = (D == 64) ? HDT_FWD_S64 : 2;      // ring stages (LDS at 128 x 64: 36 KB / 68 KB per workgroup)
-    static constexpr int WAVES = (D == 64) ? HDT_FWD_W64 : 2;  // waves per SIMD the register budget allows
+    static constexpr int S = 2;                      // ring stages (LDS at 128 x 64: 36 KB / 68 KB per workgroup)
+    static constexpr int WAVES = (D == 64) ? 4 : 2;  // waves per SIMD the register budget allows
 };
 
 // One key tile for one wave: its sub-blocks A0 (keys 0..31) and A1 (keys 32..63) of the tile, as selected.

@@ -61,6 +61,8 @@ def test_build_layout_argument_errors_without_gpu(lib):
         assert lib.hdt_build_layout(None, None, 0, 0, ctypes.byref(opts), None, ctypes.byref(h)) == 4  # UNSUPPORTED
     opts = _Opts(0, 0, 0, 0, 0, 8)   # an edge kind that does not exist
     assert lib.hdt_build_layout(None, None, 0, 0, ctypes.byref(opts), None, ctypes.byref(h)) == 1
+    opts = _Opts(0, 0, 0, 0, 0, 0, 0, 0, -5)   # a negative capacity
+    assert lib.hdt_build_layout(None, None, 0, 0, ctypes.byref(opts), None, ctypes.byref(h)) == 1
     assert h.value is None or h.value == 0
 
 
@@ -73,6 +75,11 @@ def test_empty_layout_and_calls_on_it_are_noops_without_gpu(lib):
         assert lib.hdt_layout_info(h, ctypes.byref(info)) == 0
         assert (info.batch, info.n_pos, info.n_tiles, info.nnz) == (batch, n_pos, 0, 0)
         assert (info.tile_m, info.tile_n) == (128, 64)
+        need = ctypes.c_int64(-7)
+        assert lib.hdt_layout_status(h, ctypes.byref(need)) == 0 and need.value == 0   # nothing deferred, nothing needed
+        assert lib.hdt_layout_status(h, None) == 0
+        assert lib.hdt_attn_bwd_no_alloc(h, None, None, None, None, None, None, None, None, None, 4, 64, 0,
+                                         ctypes.c_float(0.125), None) == 0
         # attention on an empty layout: nothing to do, pointers are not looked at
         assert lib.hdt_attn_fwd(h, None, None, None, None, None, 4, 64, 0, ctypes.c_float(0.125), None) == 0
         assert lib.hdt_attn_bwd(h, None, None, None, None, None, None, None, None, None, 4, 64, 0,
@@ -97,6 +104,7 @@ def test_invalid_layout_handles_are_refused(lib):
     info = _Info()
     assert lib.hdt_layout_info(None, ctypes.byref(info)) == 1
     assert lib.hdt_layout_info(junk, ctypes.byref(info)) == 1
+    assert lib.hdt_layout_status(junk, None) == 1 and lib.hdt_layout_status(None, None) == 1
     assert lib.hdt_attn_fwd(junk, None, None, None, None, None, 1, 64, 0, ctypes.c_float(0.1), None) == 1
     assert lib.hdt_attn_bwd_workspace_bytes(junk, 1, 64, 0) == 0
     assert lib.hdt_layout_destroy(junk) == 1
