@@ -110,8 +110,8 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
     pipe.b = v + kv_base;
     pipe.aux0 = pipe.aux1 = nullptr;
     const int qrow = I * BM + wave * 32 + qn;
-    const RowLane rl = row_lane(lane);
-    const TrLane tl = tr_lane(lane);
+    const RowLane rl = row_lane<P::CPR>(lane);
+    const TrLane tl = tr_lane<P::CPR>(lane);
 
     // Q and dO rows of this wave go through the two highest ring stages (full-row loads into LDS);
     // the B fragments are read back from there.  The ring may only take those stages over after a
@@ -234,8 +234,8 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     pipe.b = d_o + q_base;
     pipe.aux0 = lse + (size_t)bh * s.n_kv;
     pipe.aux1 = delta + (size_t)bh * s.n_kv;
-    const RowLane rl = row_lane(lane);
-    const TrLane tl = tr_lane(lane);
+    const RowLane rl = row_lane<P::CPR>(lane);
+    const TrLane tl = tr_lane<P::CPR>(lane);
     // is this lane's own row a real position?  (Requested first, looked at once the rows are in registers.)
     const int own_row = min(I * BM + wave * 32 + (lane & 31), s.n_pos - 1);
     const int own_flag = s.row_flag ? s.row_flag[(size_t)b * s.n_pos + own_row] : 0;

@@ -147,8 +147,8 @@ __global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     pipe.aux0 = pipe.aux1 = nullptr;
     // this lane's query row; rows past n_pos are computed on a clamped copy and never stored
     const int qrow = I * BM + wave * 32 + qn;
-    const RowLane rl = row_lane(lane);
-    const TrLane tl = tr_lane(lane);
+    const RowLane rl = row_lane<P::CPR>(lane);
+    const TrLane tl = tr_lane<P::CPR>(lane);
 
     // Q rows of this wave go through the ring stage the prologue leaves free (S-1): full-row loads
     // into LDS, then the B fragments (query l%32, 8 head-dim values per step) are read back
