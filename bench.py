@@ -457,7 +457,9 @@ def main() -> int:
         for name, mask in (("sec", 2), ("sec+sent", 6), ("sec+sent+tokens", 14)):
             lay_c = hdt.hdt_build_cross_layout(level, n_dec, mask)
             ws_c = torch.empty(max(16, hdt.hdt_attn_bwd_workspace_bytes(lay_c, H, D, 0)), dtype=torch.uint8, device=dev)
-            oc, lc = hdt.hdt_attn_fwd(lay_c, qd, kt, vt, scale)
+            wf_bytes = hdt.hdt_attn_fwd_workspace_bytes(lay_c, H, D, 0)   # > 0: long key lists, walked in pieces
+            ws_f = torch.empty(wf_bytes, dtype=torch.uint8, device=dev) if wf_bytes else None
+            oc, lc = hdt.hdt_attn_fwd(lay_c, qd, kt, vt, scale, workspace=ws_f)
             dqc = torch.empty_like(qd)
             hdt.hdt_attn_bwd(lay_c, qd, kt, vt, oc, lc, dod, scale, dq=dqc, dk=dkc, dv=dvc, workspace=ws_c)
             torch.cuda.synchronize()
@@ -466,7 +468,7 @@ def main() -> int:
             for _ in range(20):
                 tmp = hdt.hdt_build_cross_layout(level, n_dec, mask)
                 tmp.destroy()
-                hdt.hdt_attn_fwd(lay_c, qd, kt, vt, scale, o=oc, lse=lc)
+                hdt.hdt_attn_fwd(lay_c, qd, kt, vt, scale, o=oc, lse=lc, workspace=ws_f)
                 hdt.hdt_attn_bwd(lay_c, qd, kt, vt, oc, lc, dod, scale, dq=dqc, dk=dkc, dv=dvc, workspace=ws_c)
             torch.cuda.synchronize()
             tk = {n: round(1e3 * ms / c, 2) for n, (c, ms) in hdt.hdt_timing_read().items()}
@@ -475,12 +477,18 @@ def main() -> int:
             row = 2 * D
             fwd_bytes = H * (B * n_dec * (2 * row + 4) + visible * 2 * row)          # Q, O, LSE; visible K, V rows
             bwd_bytes = H * (B * n_dec * (3 * row + 8) + visible * 2 * row + B * N * 2 * row)  # Q, dO, dQ; K, V; all of dK, dV
+            # the whole forward call: the kernel, plus the kernel that combines the pieces of cut key lists
             fwd_us = tk.get(f"hdt_fwd_bf16_d{D}")
-            # the whole backward call: D pass and kernel, plus the copies of a compact layout
-            bwd_parts = [tk.get(k) for k in (f"hdt_bwd_delta_d{D}", f"hdt_bwd_bf16_d{D}", "hdt_cross_gather", "hdt_cross_scatter")]
+            if fwd_us and tk.get("hdt_cross_combine_fwd"):
+                fwd_us += tk["hdt_cross_combine_fwd"]
+            # the whole backward call: D pass and kernel, plus the copies of a compact layout or the sum of dQ's parts
+            bwd_parts = [tk.get(k) for k in (f"hdt_bwd_delta_d{D}", f"hdt_bwd_bf16_d{D}", "hdt_cross_gather", "hdt_cross_scatter",
+                                             "hdt_cross_sum_dq")]
             bwd_us = sum(x for x in bwd_parts if x) if tk.get(f"hdt_bwd_bf16_d{D}") else None
             cross[name] = {"visible_positions": int(visible), "compact_rows": int(lay_c.info()["compact_rows"]), "kernels_us": tk,
+                           "fwd_us": None if not fwd_us else round(fwd_us, 2),
                            "bwd_us": None if not bwd_us else round(bwd_us, 2),
+                           "forward_workspace_bytes": int(wf_bytes),
                            "fwd_algorithmic_bytes": fwd_bytes, "bwd_algorithmic_bytes": bwd_bytes,
                            "fwd_gbs": None if not fwd_us else round(fwd_bytes / (fwd_us * 1e-6) / 1e9, 1),
                            "bwd_gbs": None if not bwd_us else round(bwd_bytes / (bwd_us * 1e-6) / 1e9, 1),

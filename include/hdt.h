@@ -269,6 +269,21 @@ hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void 
                           float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
                           void *stream);
 
+/*
+ * hdt_attn_fwd_ws -- hdt_attn_fwd with a workspace.  Where a few row tiles would each walk a very long key list
+ * (a cross-attention layout with the regular tokens visible: Sec. 4.2, the widest setting of the summarisation
+ * study), the lists are cut into pieces that separate workgroups walk, each producing a partial O and LSE in the
+ * workspace, and a small kernel combines them (O = sum_p exp(LSE_p - LSE) O_p, LSE = log sum_p exp(LSE_p); a fixed
+ * order, so the result is reproducible).  Results agree with hdt_attn_fwd within the rounding of the partial O to
+ * bf16.  hdt_attn_fwd_workspace_bytes says how much room that takes for a layout, head count and head size: 0
+ * means hdt_attn_fwd_ws does what hdt_attn_fwd does (every self-attention layout, HDT_F32, short lists); with
+ * less room than that (or NULL) it also does.  `workspace`: device, 16-byte aligned, scratch only.
+ */
+size_t hdt_attn_fwd_workspace_bytes(const hdt_layout_t *layout, int32_t heads, int32_t head_dim, hdt_dtype_t dt);
+hdt_status_t hdt_attn_fwd_ws(const hdt_layout_t *layout, const void *q, const void *k, const void *v, void *o,
+                             float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bytes of device workspace hdt_attn_bwd needs (0 on bad arguments). */
 size_t hdt_attn_bwd_workspace_bytes(const hdt_layout_t *layout, int32_t heads, int32_t head_dim,
                                     hdt_dtype_t dt);

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     hdt_attn_bwd_no_alloc,
     hdt_attn_bwd_workspace_bytes,
     hdt_attn_fwd,
+    hdt_attn_fwd_workspace_bytes,
     hdt_build_cross_layout,
     hdt_build_layout,
     hdt_hpe_add,

@@ -18,7 +18,7 @@ HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 
 EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_status", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
-    "hdt_attn_fwd", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_attn_bwd_no_alloc", "hdt_status_string", "hdt_last_error",
+    "hdt_attn_fwd", "hdt_attn_fwd_ws", "hdt_attn_fwd_workspace_bytes", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_attn_bwd_no_alloc", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
     "hdt_parents_from_levels", "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
 ]
@@ -80,6 +80,10 @@ def load_library():
     lib.hdt_layout_destroy.restype = ctypes.c_int
     lib.hdt_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp]
     lib.hdt_attn_fwd.restype = ctypes.c_int
+    lib.hdt_attn_fwd_ws.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp, ctypes.c_size_t, vp]
+    lib.hdt_attn_fwd_ws.restype = ctypes.c_int
+    lib.hdt_attn_fwd_workspace_bytes.argtypes = [vp, i32, i32, ctypes.c_int]
+    lib.hdt_attn_fwd_workspace_bytes.restype = ctypes.c_size_t
     lib.hdt_attn_bwd_workspace_bytes.argtypes = [vp, i32, i32, ctypes.c_int]
     lib.hdt_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.hdt_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp,
@@ -268,9 +272,14 @@ def _check_tensors(ts, shape=None):
             raise ValueError(f"tensor shape {tuple(t.shape)} != {tuple(shape)}")
 
 
-def hdt_attn_fwd(layout: Layout, q, k, v, softmax_scale: float, o=None, lse=None, stream=None):
+def hdt_attn_fwd_workspace_bytes(layout: Layout, heads: int, head_dim: int, dtype_code: int) -> int:
+    return int(load_library().hdt_attn_fwd_workspace_bytes(layout.handle, heads, head_dim, dtype_code))
+
+
+def hdt_attn_fwd(layout: Layout, q, k, v, softmax_scale: float, o=None, lse=None, workspace=None, stream=None):
     """q: [batch][heads][n_pos][head_dim], k, v: [batch][heads][n_kv][head_dim] device tensors (bf16 or fp32;
-    n_kv = n_pos unless the layout is a cross-attention layout).  Returns (o, lse)."""
+    n_kv = n_pos unless the layout is a cross-attention layout).  ``workspace``: a uint8 device tensor for
+    hdt_attn_fwd_ws (long key lists of a cross-attention layout cut into pieces).  Returns (o, lse)."""
     import torch
     B, H, N, D = q.shape
     _check_tensors((q,), q.shape)
@@ -281,6 +290,11 @@ def hdt_attn_fwd(layout: Layout, q, k, v, softmax_scale: float, o=None, lse=None
         o = torch.empty_like(q)
     if lse is None:
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
+    if workspace is not None:
+        _check(load_library().hdt_attn_fwd_ws(layout.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), H, D,
+                                              _dtype_code(q), float(softmax_scale), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+        return o, lse
     _check(load_library().hdt_attn_fwd(layout.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), H, D,
                                        _dtype_code(q), float(softmax_scale), _stream_ptr(stream)))
     return o, lse

@@ -317,9 +317,24 @@ static hdt_status_t check_attn_args(const char *fn, const hdt_layout_t *layout, 
 
 static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 
+extern "C" __attribute__((visibility("default"))) size_t hdt_attn_fwd_workspace_bytes(const hdt_layout_t *layout, int32_t heads,
+                                                                                       int32_t head_dim, hdt_dtype_t dt)
+{
+    if (!hdt_layout_ok(layout) || heads <= 0 || dt != HDT_BF16 || (head_dim != 64 && head_dim != 128)) return 0;
+    return hdt_cross_fwd_workspace_bytes(layout, heads, head_dim);
+}
+
 extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v,
                                      void *o, float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt,
                                      float scale, void *stream)
+{
+    return hdt_attn_fwd_ws(layout, q, k, v, o, lse, heads, head_dim, dt, scale, nullptr, 0, stream);
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd_ws(const hdt_layout_t *layout, const void *q, const void *k,
+                                                                                const void *v, void *o, float *lse, int32_t heads,
+                                                                                int32_t head_dim, hdt_dtype_t dt, float scale,
+                                                                                void *workspace, size_t workspace_bytes, void *stream)
 {
     hdt_status_t st = check_attn_args("hdt_attn_fwd", layout, heads, head_dim, dt, scale);
     if (st != HDT_OK) return st;
@@ -332,6 +347,12 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd(cons
     if ((int64_t)s.batch * heads * s.tr > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_fwd: batch*heads*q_tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
+    // long key lists of a cross-attention layout, cut into pieces, when the caller brings room for the partial results
+    const size_t ws_need = dt == HDT_BF16 ? hdt_cross_fwd_workspace_bytes(layout, heads, head_dim) : 0;
+    if (ws_need > 0 && workspace != nullptr && workspace_bytes >= ws_need) {
+        if (misaligned(workspace)) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_attn_fwd_ws: the workspace must be 16-byte aligned");
+        return hdt_cross_fwd_split(layout, q, k, v, o, lse, heads, head_dim, scale, workspace, hs);
+    }
     if (dt == HDT_BF16) return hdt_launch_fwd_bf16(s, q, k, v, o, lse, heads, head_dim, scale, hs);
     return hdt_launch_fwd_f32(s, (const float *)q, (const float *)k, (const float *)v, (float *)o, lse, heads,
                               head_dim, scale, hs);
@@ -346,6 +367,8 @@ extern "C" __attribute__((visibility("default"))) size_t hdt_attn_bwd_workspace_
     n = (n + 255) & ~(size_t)255;
     // a cross-attention layout with a compact pair: compact copies of K, V and of their gradients behind it
     if (layout->compact) n += hdt_cross_compact_workspace_bytes(layout, heads, head_dim, dt == HDT_BF16 ? 2 : 4);
+    // a cross-attention layout with long key lists: the parts of dQ that the pieces of the lists produce
+    if (dt == HDT_BF16 && (head_dim == 64 || head_dim == 128)) n += hdt_cross_dq_workspace_bytes(layout, heads, head_dim);
     return n;
 }
 
@@ -429,6 +452,8 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if (layout->compact)
         return hdt_cross_bwd_compact(layout, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, dt == HDT_BF16, scale,
                                      workspace, hs);
+    if (dt == HDT_BF16 && hdt_cross_pieces(layout, heads) > 1)
+        return hdt_cross_bwd_split(layout, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, workspace, hs);
     if (dt == HDT_BF16)
         return hdt_launch_bwd_bf16(s, s_tr, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, scale, (float *)workspace, hs);
     return hdt_launch_bwd_f32(s, s_tr, (const float *)q, (const float *)k, (const float *)v, (const float *)o, lse,

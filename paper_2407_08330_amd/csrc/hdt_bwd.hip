@@ -92,7 +92,8 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
 
     const int lane = threadIdx.x & 63;
     const int qn = lane & 31;
-    const size_t base = (size_t)bh * s.n_pos * D, kv_base = (size_t)bh * s.n_kv * D;
+    const int I_own = I % s.tr_own;  // the rows this tile works on (several tiles share them when key lists are cut)
+    const size_t base = (size_t)bh * s.n_pos * D, own_base = (size_t)bh * s.n_own * D, kv_base = (size_t)bh * s.n_kv * D;
     const float scale_log2 = scale * LOG2E;
 
     const size_t row = (size_t)b * s.tr + I;
@@ -109,7 +110,7 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
     pipe.a = k + kv_base;
     pipe.b = v + kv_base;
     pipe.aux0 = pipe.aux1 = nullptr;
-    const int qrow = I * BM + wave * 32 + qn;
+    const int qrow = I_own * BM + wave * 32 + qn;
     const RowLane rl = row_lane<P::CPR>(lane);
     const TrLane tl = tr_lane<P::CPR>(lane);
 
@@ -117,8 +118,8 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
     // the B fragments are read back from there.  The ring may only take those stages over after a
     // barrier, so the prologue is issued in two pieces.
     constexpr uint32_t STG_Q = (uint32_t)(S - 1) * 2 * P::TILE, STG_DO = (uint32_t)(S - 2) * 2 * P::TILE;
-    stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, STG_Q);
-    stage_own_rows(pipe, d_o + base, I * BM, s.n_pos, D, STG_DO);
+    stage_own_rows(pipe, q + own_base, I_own * BM, s.n_own, D, STG_Q);
+    stage_own_rows(pipe, d_o + own_base, I_own * BM, s.n_own, D, STG_DO);
     R::start(pipe, n);
     R::template prologue<0, S - 2>(pipe, n);
     if (S == 2 || n == 0) wait_vmcnt<0>();  // otherwise the prologue's first wait covered the staged rows
@@ -128,9 +129,9 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
         qf[st] = read_row<ROWB>(smem + STG_Q, rl, wave * 32, st);
         dof[st] = read_row<ROWB>(smem + STG_DO, rl, wave * 32, st);
     }
-    const int qrow_ld = min(qrow, s.n_pos - 1);
-    float lse2 = lse[(size_t)bh * s.n_pos + qrow_ld];
-    float Di = delta[(size_t)bh * s.n_pos + qrow_ld];
+    const int qrow_ld = min(qrow, s.n_own - 1);
+    float lse2 = lse[(size_t)bh * s.n_own + qrow_ld];
+    float Di = delta[(size_t)bh * s.n_own + qrow_ld];
     // A row without any key (a pad: LSE = -inf) is masked by the bitmap, but its Q, dO and D may hold anything,
     // NaN included, which a zero weight would not remove: it takes part as a row of zeros.
     const bool dead_row = lse2 == -INFINITY;
@@ -237,8 +238,11 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     const RowLane rl = row_lane<P::CPR>(lane);
     const TrLane tl = tr_lane<P::CPR>(lane);
     // is this lane's own row a real position?  (Requested first, looked at once the rows are in registers.)
+    // (An unconditional load: inside a branch the compiler would wait for it on the spot.  Without flags any
+    // readable word will do, its value is not used.)
     const int own_row = min(I * BM + wave * 32 + (lane & 31), s.n_pos - 1);
-    const int own_flag = s.row_flag ? s.row_flag[(size_t)b * s.n_pos + own_row] : 0;
+    const int32_t *flag_at = s.row_flag ? s.row_flag + ((size_t)b * s.n_pos + own_row) : s.q_range;
+    int own_flag = *flag_at;
 
     // K and V rows of this wave: through the two highest ring stages, as Q and dO in the dQ pass
     constexpr uint32_t STG_K = (uint32_t)(S - 1) * 2 * P::TILE, STG_V = (uint32_t)(S - 2) * 2 * P::TILE;
@@ -256,7 +260,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     // A row that is no real position (a pad, an encoder position the decoder does not see) is masked by the
     // bitmap, but its K and V may hold anything, NaN included, which a zero weight would not remove: it takes
     // part as a row of zeros.
-    if (own_flag < 0) {
+    if (s.row_flag != nullptr && own_flag < 0) {
 #pragma unroll
         for (int st = 0; st < KSTEPS; st++) {
             kf[st] = zero_bf16x8();
@@ -397,7 +401,7 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
 {
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_delta_d64" : "hdt_bwd_delta_d128", st);
-        const long long rows = (long long)s.batch * heads * s.n_pos;
+        const long long rows = (long long)s.batch * heads * s.n_own;  // the real rows, also when key lists are cut
         const int rpb = (256 / (head_dim / 8)) * 4;
         dim3 grid((unsigned)((rows + rpb - 1) / rpb)), block(256);
         if (head_dim == 64)

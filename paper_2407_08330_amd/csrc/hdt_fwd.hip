@@ -129,7 +129,8 @@ __global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const unsigned lb = logical_block(blockIdx.x, kXcdChunk);
     if (lb >= (unsigned)s.batch * heads * s.tr) return;  // padding of the grid
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
-    const size_t base = (size_t)bh * s.n_pos * D, kv_base = (size_t)bh * s.n_kv * D;
+    const int I_own = I % s.tr_own;  // the rows this tile works on (several tiles share them when key lists are cut)
+    const size_t base = (size_t)bh * s.n_pos * D, own_base = (size_t)bh * s.n_own * D, kv_base = (size_t)bh * s.n_kv * D;
 
     const size_t row = (size_t)b * s.tr + I;
     const cptr_i32 range = as_const(s.q_range);
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     constexpr uint32_t Q_STAGE = (uint32_t)(S - 1) * 2 * P::TILE;
     bf16x8 qf[KSTEPS];
     if (n > 0) {
-        stage_own_rows(pipe, q + base, I * BM, s.n_pos, D, Q_STAGE);
+        stage_own_rows(pipe, q + own_base, I_own * BM, s.n_own, D, Q_STAGE);
         R::start(pipe, n);
         R::template prologue<0, S - 1>(pipe, n);  // its first wait covers the Q rows
 #pragma unroll

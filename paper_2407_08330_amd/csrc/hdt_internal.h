@@ -23,6 +23,11 @@
 struct HdtSchedule {
     int32_t batch, n_pos;  // n_pos: rows per sample of the row-side tensors (the ones tiled by bm)
     int32_t n_kv;          // rows per sample of the gathered tensors (= n_pos for self-attention)
+    // A schedule whose key lists are cut into several pieces (hdt_cross.hip) lists every row tile once per piece:
+    // row tile I works on the rows of tile I % tr_own of the row-side INPUT tensors, which have n_own rows per
+    // sample, and writes its (partial) results as rows of tile I of tensors with n_pos rows.  Otherwise
+    // tr_own == tr and n_own == n_pos.
+    int32_t n_own, tr_own;
     int32_t bm, bn;        // tile shape (query rows x key slots)
     int32_t tr, tc;        // tiles per sample along queries / keys
     int32_t n_slots;       // tc * bn: length of one sample's padded key order
@@ -72,6 +77,10 @@ struct hdt_layout {
     const int32_t *cross_count;  // [batch] their number (device)
     const int32_t *cross_rank;   // [batch][n_kv] rank among the visible positions, -1 = not visible (device)
     int32_t n_compact;           // rows per (sample, head) of the compact tensors
+    // Long key lists cut into 2, 4 or 8 pieces (hdt_cross.hip): the entry ranges of the row tiles of every piece,
+    // [batch][pieces * tr][2] each (device, in this layout's first arena); NULL if the lists are short
+    const int32_t *cross_split_range[3];
+    int32_t cross_entries_max;   // entries of the longest key list (host copy)
     int64_t capacity;    // entries the per-tile arrays can hold
     int64_t device_bytes;
     void *arena;         // key order, list pointers, scratch of the build
@@ -121,6 +130,16 @@ hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (wa
 void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
 // device buffer from the cache of destroyed layouts' buffers, or a new one; *got = its real size (hdt_layout.hip)
 hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got);
+
+// --- key lists of a cross-attention layout cut into pieces that separate workgroups walk (hdt_cross.hip) ---
+int hdt_cross_pieces(const hdt_layout_t *l, int heads);  // 1, 2, 4 or 8 for this many heads
+size_t hdt_cross_fwd_workspace_bytes(const hdt_layout_t *l, int heads, int head_dim);
+size_t hdt_cross_dq_workspace_bytes(const hdt_layout_t *l, int heads, int head_dim);
+hdt_status_t hdt_cross_fwd_split(const hdt_layout_t *l, const void *q, const void *k, const void *v, void *o, float *lse,
+                                 int heads, int head_dim, float scale, void *workspace, hipStream_t st);
+hdt_status_t hdt_cross_bwd_split(const hdt_layout_t *l, const void *q, const void *k, const void *v, const void *o,
+                                 const float *lse, const void *d_o, void *dq, void *dk, void *dv, int heads,
+                                 int head_dim, float scale, void *workspace, hipStream_t st);
 
 // --- backward of a cross-attention layout with a compact pair (hdt_cross.hip) ---
 size_t hdt_cross_compact_workspace_bytes(const hdt_layout_t *l, int heads, int head_dim, int elem_bytes);

@@ -1366,6 +1366,8 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     s.tr = empty ? 0 : (n_pos + bm - 1) / bm;
     s.tc = empty ? 0 : (n_pos + bn - 1) / bn;
     s.n_slots = s.tc * bn;
+    s.n_own = n_pos;
+    s.tr_own = s.tr;
     L->h_stats.assign((size_t)batch * 2, 0);
     if (empty) {
         L->stats_ready = true;

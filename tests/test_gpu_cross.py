@@ -21,6 +21,23 @@ def _encoder_levels(n_enc, seeds):
     return np.stack(lv)
 
 
+def _long_encoder_levels(n_enc, seeds, fill=1.0):
+    """Documents of sections of 3..10 sentences of 5..60 tokens that fill about `fill` of n_enc positions."""
+    lv = []
+    for s in seeds:
+        rng = np.random.default_rng(s)
+        sections, used = [], 1
+        while True:
+            sec = [int(x) for x in rng.integers(5, 61, size=int(rng.integers(3, 11)))]
+            need = 1 + sum(1 + l for l in sec)
+            if used + need > int(n_enc * fill):
+                break
+            sections.append(sec)
+            used += need
+        lv.append(inputs.document_from_sections(sections, n_enc)[0])
+    return np.stack(lv)
+
+
 def _compare_schedule(got_layout, ref, b, what):
     got = got_layout.export(b)
     assert "kperm" not in got
@@ -73,7 +90,21 @@ def _tensors(B, H, n_dec, n_enc, D, seed, dtype):
     return xs, dev
 
 
-def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0, 0), backward=True):
+def pieces_of(hdt, lay, H, D, tile_m):
+    """Into how many pieces the library cuts the key lists of this layout for H heads (from the size of the
+    forward workspace: partial O rows of D bf16 and a partial LSE per row)."""
+    need = hdt.hdt_attn_fwd_workspace_bytes(lay, H, D, 0)
+    if need == 0:
+        return 1
+    rows_per_piece = lay.batch * H * ((lay.n_pos + tile_m - 1) // tile_m) * tile_m
+    for p in (2, 4, 8):
+        rows = rows_per_piece * p
+        if need == ((rows * D * 2 + 255) // 256 + (rows * 4 + 255) // 256) * 256:
+            return p
+    raise AssertionError(f"unexpected workspace size {need}")
+
+
+def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0, 0), backward=True, want_pieces=None):
     import torch
     import paper_2407_08330_amd as hdt
     B, n_enc = level.shape
@@ -87,8 +118,21 @@ def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0,
     assert (compact_rows > 0) == (0 < c_max and 4 * c_max <= n_enc) and (compact_rows == 0 or c_max <= compact_rows < c_max + 32)
     o_ = torch.full_like(q_, float("nan"))
     lse_ = torch.full((B, H, n_dec), float("nan"), dtype=torch.float32, device="cuda")
-    hdt.hdt_attn_fwd(lay, q_, k_, v_, scale, o=o_, lse=lse_)
+    # with a workspace the forward cuts long key lists into pieces (none for short lists or fp32)
+    ws_bytes = hdt.hdt_attn_fwd_workspace_bytes(lay, H, D, 0 if dtype == "bf16" else 1)
+    pieces = pieces_of(hdt, lay, H, D, tile[0] or 128) if dtype == "bf16" else 1
+    say(f"    key lists in {pieces} piece(s), forward workspace {ws_bytes} bytes")
+    assert want_pieces is None or pieces == want_pieces
+    ws = torch.full((max(ws_bytes, 16),), 0xff, dtype=torch.uint8, device="cuda") if ws_bytes else None
+    hdt.hdt_attn_fwd(lay, q_, k_, v_, scale, o=o_, lse=lse_, workspace=ws)
     torch.cuda.synchronize()
+    if ws is not None:   # the same call without a workspace walks the whole lists: same result up to rounding
+        o1, lse1 = hdt.hdt_attn_fwd(lay, q_, k_, v_, scale)
+        torch.cuda.synchronize()
+        assert np.abs(from_dev(o1) - from_dev(o_)).max() <= 2e-2
+        fin = np.isfinite(lse1.cpu().numpy())
+        assert np.array_equal(fin, np.isfinite(lse_.cpu().numpy()))
+        assert np.abs(lse1.cpu().numpy()[fin] - lse_.cpu().numpy()[fin]).max() <= 1e-3
     o_ref, lse_ref = oracle.cross_attn_fwd(q, k, v, level, level_mask, scale)
     o_g, lse_g = from_dev(o_), lse_.cpu().numpy()
     tol_o, tol_l, tol_g = {"bf16": (2e-2, 1e-2, 5e-2), "f32": (1e-4, 1e-4, 1e-4)}[dtype]
@@ -150,6 +194,24 @@ def test_cross_attention_benchmark_documents(oracle):
         say(f"[cross] config 4 documents, n_dec=512, level_mask={level_mask}: visible "
             f"{[int(oracle.cross_select(l, level_mask).size) for l in wl.level]}")
         run_cross_case(oracle, wl.level, 512, level_mask, 4, 64, "bf16", 900 + level_mask)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_cross_attention_long_key_lists_cut_into_pieces(oracle, D):
+    # the regular tokens visible and few decoder rows: a handful of row tiles with lists of dozens of entries, which
+    # the library cuts into pieces walked by separate workgroups (forward with a workspace; dQ role of the backward)
+    level = _long_encoder_levels(5000, (43,))
+    say(f"[cross] n_enc=5000 n_dec=100, tokens visible, d={D}: 8 pieces")
+    run_cross_case(oracle, level, 100, SEC | SENT | TOK, 2, D, "bf16", 950 + D, want_pieces=8)
+    level = _long_encoder_levels(3000, (44, 45))
+    level[1, 1500:] = -1   # the second sample sees half as much: its later pieces are empty
+    say(f"[cross] n_enc=3000 n_dec=333 (a ragged last row tile), tokens visible, d={D}: 4 pieces")
+    run_cross_case(oracle, level, 333, SEC | SENT | TOK, 3, D, "bf16", 960 + D, want_pieces=4)
+    say(f"[cross] the same at 64x32 tiles")
+    run_cross_case(oracle, level, 333, SEC | SENT | TOK, 3, D, "bf16", 970 + D, tile=(64, 32))
+    # short lists, and fp32: nothing to cut
+    run_cross_case(oracle, _encoder_levels(600, (46,)), 100, SEC | SENT | TOK, 2, D, "bf16", 980 + D, want_pieces=1)
+    run_cross_case(oracle, _long_encoder_levels(3000, (47,)), 64, SEC | SENT | TOK, 1, D, "f32", 990 + D, want_pieces=1, backward=False)
 
 
 def test_cross_argument_errors():
