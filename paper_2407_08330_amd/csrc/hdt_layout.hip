@@ -550,7 +550,7 @@ __device__ __forceinline__ void raise_error(int32_t *counters)
     asm volatile("" ::"v"(old));
 }
 
-constexpr int kListThreads = 1024, kListWaves = kListThreads / 64, kBatch = 8;
+constexpr int kBatch = 8;
 constexpr int kLdsKeys = 2048;  // key lists up to this length stay in LDS between the packing and the bitmaps
 
 // ---- key lists: ONE kernel from level/parent to the finished entries, a workgroup per query tile ----
@@ -569,8 +569,13 @@ constexpr int kLdsKeys = 2048;  // key lists up to this length stay in LDS betwe
 // A list of up to kLdsKeys keys is packed into LDS while the reservation (a returning device-scope atomic,
 // about 2 us) is in flight, copied to global memory from there, and evaluated from there; a longer list is
 // packed straight into global memory once the reservation is back and read again from there.
+// The workgroup has 1024 threads, or 512 for tiles of up to 64 rows: those make twice the workgroups, and two of 512
+// threads share a compute unit where one of 1024 fills it (measured at 8192 positions x 4 samples, 64-row tiles:
+// 24 us against 28).
+template <int kListThreads>
 __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
 {
+    constexpr int kListWaves = kListThreads / 64;
     extern __shared__ uint32_t s_dyn[];  // [ceil(n/32)] parents of the tile's rows, then [2 * groups] needed positions
     __shared__ int2 s_row[128];          // (position, parent) of the tile's rows; position -2: no such row
     __shared__ int s_lcnt[kListWaves][kBuckets];  // needed keys per (wave, level), then their first index
@@ -1478,11 +1483,15 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                                slot_counters ? slot_counters : p.counters, report, p.report_copy, ticket,
                                slot_counters != nullptr};
                 const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
+                const bool small_wg = bm <= 64;
                 if (lds > 32 * 1024)  // with the kernel's static arrays: beyond the 64 KB a launch gets by default
-                    BUILD_TRY(hipFuncSetAttribute((const void *)k_key_lists, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                  (int)lds));
+                    BUILD_TRY(hipFuncSetAttribute(small_wg ? (const void *)k_key_lists<512> : (const void *)k_key_lists<1024>,
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
                 HdtTimer t("hdt_layout_key_lists", st);
-                hipLaunchKernelGGL(k_key_lists, dim3((unsigned)B * tr), dim3(kListThreads), lds, st, ka);
+                if (small_wg)
+                    hipLaunchKernelGGL(k_key_lists<512>, dim3((unsigned)B * tr), dim3(512), lds, st, ka);
+                else
+                    hipLaunchKernelGGL(k_key_lists<1024>, dim3((unsigned)B * tr), dim3(1024), lds, st, ka);
             }
             if (windowed) {
                 const unsigned grid = (unsigned)(cap < 2048 ? (cap > 0 ? cap : 1) : 2048);

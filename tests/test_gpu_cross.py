@@ -104,12 +104,21 @@ def pieces_of(hdt, lay, H, D, tile_m):
     raise AssertionError(f"unexpected workspace size {need}")
 
 
-def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0, 0), backward=True, want_pieces=None):
+def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0, 0), backward=True, want_pieces=None,
+                   poison_invisible=False):
     import torch
     import paper_2407_08330_amd as hdt
     B, n_enc = level.shape
     scale = 1.0 / np.sqrt(D)
     (q, k, v, d_o), (q_, k_, v_, do_) = _tensors(B, H, n_dec, n_enc, D, seed, dtype)
+    if poison_invisible:
+        # K, V rows of the encoder positions the decoder does not see (pads and levels outside the mask) hold NaN and
+        # infinities on the device; the oracle keeps the finite values (it never reads those rows)
+        hidden = np.stack([~np.isin(np.arange(n_enc), oracle.cross_select(l, level_mask)) for l in level])
+        junk = np.random.default_rng(seed).choice(np.array([np.nan, np.inf, -np.inf], np.float32), size=(B, H, n_enc, D))
+        w = np.broadcast_to(hidden[:, None, :, None], k.shape)
+        kd, vd = np.where(w, junk, k), np.where(w, junk[..., ::-1], v)
+        k_, v_ = (to_dev_bf16(x) if dtype == "bf16" else torch.from_numpy(np.ascontiguousarray(x)).cuda() for x in (kd, vd))
     lay = hdt.hdt_build_cross_layout(to_dev_i32(level), n_dec, level_mask, tile_m=tile[0], tile_n=tile[1])
     # the backward runs on compact copies of K and V iff at most a quarter of the positions are visible
     c_max = max(int(oracle.cross_select(l, level_mask).size) for l in level)
@@ -212,6 +221,17 @@ def test_cross_attention_long_key_lists_cut_into_pieces(oracle, D):
     # short lists, and fp32: nothing to cut
     run_cross_case(oracle, _encoder_levels(600, (46,)), 100, SEC | SENT | TOK, 2, D, "bf16", 980 + D, want_pieces=1)
     run_cross_case(oracle, _long_encoder_levels(3000, (47,)), 64, SEC | SENT | TOK, 1, D, "f32", 990 + D, want_pieces=1, backward=False)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_cross_attention_ignores_what_invisible_rows_hold(oracle, dtype):
+    # pads in front and behind, NaN / Inf in every K, V row the level mask hides: anchors only (the backward works on
+    # compact copies), and everything but [DOC] (the backward tiles the encoder rows, hidden ones among them)
+    level = _long_encoder_levels(1536, (51, 52), fill=0.8)
+    level = np.concatenate([np.full((2, 40), -1, np.int32), level[:, :-40]], axis=1)
+    for level_mask in (SEC | SENT, SEC | SENT | TOK):
+        say(f"[cross] NaN/Inf in hidden K, V rows, level_mask={level_mask}, {dtype}")
+        run_cross_case(oracle, level, 200, level_mask, 2, 64, dtype, 1000 + level_mask, poison_invisible=True)
 
 
 def test_cross_argument_errors():
