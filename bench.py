@@ -52,9 +52,10 @@ def algorithmic_bytes_per_unit(kernel: str, d: int) -> int:
 
 def mfma_flop_per_subblock(kernel: str, d: int) -> int:
     """MFMA work a kernel executes per 32x32 sub-block it does not skip: the forward two contractions
-    (S = K Q^T, O += V^T P), the backward kernel seven (the dQ role S, dP, dQ; the dK/dV role S, dP, dK, dV)."""
+    (S = K Q^T, O += V^T P), the backward kernel seven at head size 64 (the dQ role S, dP, dQ; the dK/dV role S, dP,
+    dK, dV) and eight at head size 128, where the dK/dV role is split into a dV role (S, dV) and a dK role (S, dP, dK)."""
     per_gemm = 2 * 32 * 32 * d
-    return (2 if kernel.startswith("hdt_fwd") else 7) * per_gemm
+    return (2 if kernel.startswith("hdt_fwd") else (7 if d == 64 else 8)) * per_gemm
 
 
 def kernel_source_hash() -> str:
@@ -238,7 +239,8 @@ def main() -> int:
     # Warm-up: the W steps asked for, and as many more as it takes to have the device busy for about 60 ms: after
     # an idle phase its clocks need some tens of milliseconds of work to settle, which a short run (W = 5, K = 20)
     # would otherwise spend inside its timed regions.
-    warm_steps = max(args.warmup, 300)
+    # (Not under an external profiler: --no-kernel-timing runs exactly the steps asked for.)
+    warm_steps = args.warmup if args.no_kernel_timing else max(args.warmup, 300)
     run_serial(0, warm_steps)
     torch.cuda.synchronize()
     regions = timed_regions(run_serial)
@@ -363,7 +365,7 @@ def main() -> int:
         if not name:
             continue
         us = per_kernel[name]["avg_us"]
-        gemms = 2 if phase == "fwd" else 7
+        gemms = 2 if phase == "fwd" else (7 if D == 64 else 8)
         executed = executed_subblocks * H * mfma_flop_per_subblock(name, D)
         issued = n_tiles * info["tile_m"] * info["tile_n"] * H * gemms * 2 * D
         out[phase] = {
