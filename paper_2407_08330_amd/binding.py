@@ -135,6 +135,17 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
+def _scratch(nbytes: int, device, stream):
+    """A temporary uint8 device tensor for kernels enqueued on ``stream``.  It is dropped by the caller while
+    those kernels may still be queued, so it is allocated in that stream's context: torch's allocator hands a
+    freed block out again in the order of the stream it was allocated on."""
+    import torch
+    if stream is None:
+        return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    with torch.cuda.stream(stream):
+        return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+
+
 class Layout:
     """Owns an ``hdt_layout_t``."""
 
@@ -203,6 +214,9 @@ class Layout:
         return out
 
     def destroy(self):
+        """hdt_layout_destroy: the layout's device buffers go to the library's cache, from which a later build takes
+        them without synchronising.  Call it (or drop the object) only when no attention call using the layout can
+        still be running, or when every later build is enqueued on the stream those calls were enqueued on."""
         if self._owner is None and self._h is not None and self._h.value:
             _check(load_library().hdt_layout_destroy(self._h))
         self._h = None
@@ -318,7 +332,7 @@ def hdt_attn_bwd(layout: Layout, q, k, v, o, lse, d_o, softmax_scale: float, dq=
     dv = torch.empty_like(k) if dv is None else dv
     need = hdt_attn_bwd_workspace_bytes(layout, H, D, _dtype_code(q))
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+        workspace = _scratch(need, q.device, stream)
     _check(load_library().hdt_attn_bwd(layout.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
                                        _ptr(dq), _ptr(dk), _ptr(dv), H, D, _dtype_code(q), float(softmax_scale),
                                        _ptr(workspace), workspace.numel() * workspace.element_size(),
@@ -387,7 +401,7 @@ def hdt_index_vectors(level, parent, n_levels: int, out=None, workspace=None, st
         out = torch.empty((B, N, n_levels), dtype=torch.int32, device=level.device)
     need = int(load_library().hdt_index_vectors_workspace_bytes(B, N))
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=level.device)
+        workspace = _scratch(need, level.device, stream)
     _check(load_library().hdt_index_vectors(_ptr(level) if B * N else None, _ptr(parent) if B * N else None, B, N,
                                             n_levels, _ptr(out), _ptr(workspace),
                                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
