@@ -300,6 +300,16 @@ def test_deferred_build_matches_the_waiting_one(oracle):
         tiles, _ = compare_layout(oracle, lay, wl.level, wl.parent, tile[0], tile[1])
         assert need == tiles
         lay.destroy()
+    # a directed mask brings a second schedule: both builds are deferred, the status covers both
+    rng = np.random.default_rng(5)
+    lv, pr = inputs.listops_like_tree(rng, 1024, max_depth=12)
+    edges = hdt.HDT_EDGE_SIBLING | hdt.HDT_EDGE_DOWN
+    lay = _build(lv[None], pr[None], edges=edges, deferred=True)
+    need = lay.status()
+    t_fwd, _ = compare_layout(oracle, lay, lv[None], pr[None], 128, 64, edges=edges)
+    t_tr, _ = compare_layout(oracle, lay.transposed(), lv[None], pr[None], 128, 64, edges=hdt.HDT_EDGE_SIBLING | hdt.HDT_EDGE_UP)
+    assert need == max(t_fwd, t_tr)
+    lay.destroy()
     # many deferred builds in a row on one stream, looked at only at the end (the report slots are a ring)
     wl = inputs.make_workload(1)
     lv, pr = to_dev_i32(wl.level), to_dev_i32(wl.parent)
