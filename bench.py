@@ -86,7 +86,8 @@ def main() -> int:
     ap.add_argument("--windowed", action="store_true",
                     help="key tiles = fixed windows of the level-sorted key order (Alg. 1 as printed) instead of "
                          "the default per-query-tile key lists")
-    ap.add_argument("--tile", default="", help="tile shape of the layout, 64x32 or 128x64 (default: the library's)")
+    ap.add_argument("--tile", default="", help="tile shape of the layout, 64x32 or 128x64 (default: 64x32 for a step with a backward pass, "
+                                               "else the library's 128x64)")
     ap.add_argument("--edges", type=int, default=0,
                     help="edge kinds of the mask (1 parent, 2 siblings, 4 children, OR-ed; 0 = all): the thinned "
                          "patterns of the paper's ListOps study applied to the workload's documents")
@@ -134,7 +135,12 @@ def main() -> int:
             outs.update(dq=torch.empty_like(t[0]), dk=torch.empty_like(t[0]), dv=torch.empty_like(t[0]))
         sets.append((t, outs))
     del xs
-    tile_m, tile_n = (int(x) for x in args.tile.split("x")) if args.tile else (0, 0)
+    # Tile shape: a step with a backward pass runs on 64 x 32 tiles (the backward kernel is the faster one on them,
+    # by more than their layout and forward cost), a forward-only step on the library's default (128 x 64)
+    if args.tile:
+        tile_m, tile_n = (int(x) for x in args.tile.split("x"))
+    else:
+        tile_m, tile_n = (64, 32) if do_bwd else (0, 0)
     lay_opts = dict(tile_m=tile_m, tile_n=tile_n, windowed=args.windowed, edges=args.edges)
     probe = hdt.hdt_build_layout(level, parent, **lay_opts)
     info = probe.info()
@@ -385,16 +391,17 @@ def main() -> int:
     if do_bwd and not args.no_dense and N <= 8192:
         # The dense masked-attention baseline on the same inputs: the same kernels on a layout that issues and
         # computes every tile of the N x N score matrix (force_dense), the mask applied per element.  Layout built
-        # once, outside the timed calls.
-        dense = hdt.hdt_build_layout(level, parent, tile_m=tile_m, tile_n=tile_n, force_dense=True, edges=args.edges)
+        # once, outside the timed calls, with 128 x 64 tiles: the faster shape when every tile is issued.
+        dense = hdt.hdt_build_layout(level, parent, tile_m=128, tile_n=64, force_dense=True, edges=args.edges)
         dinfo = dense.info()
+        dense_ws = torch.empty(max(hdt.hdt_attn_bwd_workspace_bytes(dense, H, D, 0), 16), dtype=torch.uint8, device=dev)
         t, outs = sets[0]
         n_rep = 3
 
         def dense_step():
             hdt.hdt_attn_fwd(dense, t[0], t[1], t[2], scale, o=outs["o"], lse=outs["lse"])
             hdt.hdt_attn_bwd(dense, t[0], t[1], t[2], outs["o"], outs["lse"], t[3], scale, dq=outs["dq"],
-                             dk=outs["dk"], dv=outs["dv"], workspace=workspace)
+                             dk=outs["dk"], dv=outs["dv"], workspace=dense_ws)
         dense_step()
         torch.cuda.synchronize()
         hdt.hdt_timing_enable(True)
@@ -412,7 +419,7 @@ def main() -> int:
         sparse_attn_ms = (phase_us["fwd"] + phase_us["bwd"]) * 1e-3
         out["dense_baseline"] = {
             "what": f"dense {N}x{N} masked attention, forward + backward, same inputs and kernels, every tile issued",
-            "n_tiles": dinfo["n_tiles"], "ms_fwd_bwd": round(dense_ms, 3),
+            "tile": f"{dinfo['tile_m']}x{dinfo['tile_n']}", "n_tiles": dinfo["n_tiles"], "ms_fwd_bwd": round(dense_ms, 3),
             "tokens_per_s": round(tokens / (dense_ms * 1e-3), 1),
             "kernels_us": {n: round(v, 1) for n, v in dk_.items()},
             "fwd_mfma_tflops": None if not f_us else round(dense_sub * H * mfma_flop_per_subblock("hdt_fwd", D) / (f_us * 1e-6) / 1e12, 1),

@@ -569,9 +569,10 @@ constexpr int kLdsKeys = 2048;  // key lists up to this length stay in LDS betwe
 // A list of up to kLdsKeys keys is packed into LDS while the reservation (a returning device-scope atomic,
 // about 2 us) is in flight, copied to global memory from there, and evaluated from there; a longer list is
 // packed straight into global memory once the reservation is back and read again from there.
-// The workgroup has 1024 threads, or 512 for tiles of up to 64 rows: those make twice the workgroups, and two of 512
-// threads share a compute unit where one of 1024 fills it (measured at 8192 positions x 4 samples, 64-row tiles:
-// 24 us against 28).
+// The workgroup has 1024 threads.  Tiles of up to 64 rows go to key_lists_pair below, two to a workgroup; where its
+// bitmaps do not fit the LDS (documents beyond 64 K positions) they come here with 512 threads: they make twice
+// the workgroups, and two of 512 threads share a compute unit where one of 1024 fills it (measured at 8192
+// positions x 4 samples, 64-row tiles: 24 us against 28).
 template <int kListThreads>
 __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
 {
@@ -867,6 +868,362 @@ __global__ __launch_bounds__(kListThreads) void k_key_lists(KeyListArgs a)
         if (active && k0 == 0 && lane == 0) {
             a.c_cnt[base + e] = s_cnt[par][wave] + s_cnt[par][wave + 1];
             a.q_sub[base + e] = (s_any[par][wave] | s_any[par][wave + 1]) | ((s_all[par][wave] | s_all[par][wave + 1]) << 16);
+        }
+    }
+}
+
+// ---- key lists of TWO neighbouring query tiles of up to 64 rows per workgroup -------------------------
+// Tiles of 64 rows make twice the query tiles, and every query tile's workgroup scans the ids of the whole
+// sample; here the tiles 2P and 2P + 1 share one workgroup of 1024 threads and one scan, which tests every
+// position against both tiles (two bitmaps of the rows' parents, two lists of needed keys); the two lists are
+// then packed, reserved (one atomic for both: the entries of tile 2P, then those of tile 2P + 1) and evaluated
+// as in key_lists, the waves working on the entries of both tiles side by side.  Same results, array by array
+// (measured at 8192 positions x 4 samples, 64 x 32 tiles: 20 us against 24; 32768 positions: 43 against 48).
+constexpr int kPairThreads = 1024, kPairWaves = kPairThreads / 64;
+
+__global__ __launch_bounds__(kPairThreads) void k_key_lists_pair(KeyListArgs a)
+{
+    constexpr int W = kPairWaves;
+    extern __shared__ uint32_t s_dyn[];  // 2 x [ceil(n/32)] parents of each tile's rows, then 2 x [2 * groups] needed positions
+    __shared__ int2 s_row[128];          // (position, parent) of the rows: tile h at [64h, 64h + 64); position -2: no such row
+    __shared__ int s_lcnt[2][W][kBuckets];
+    __shared__ int s_cnt[2][W];
+    __shared__ uint32_t s_any[2][W], s_all[2][W];
+    __shared__ int s_base[2], s_total[2], s_wtotal[2][W];
+    __shared__ __attribute__((aligned(16))) int s_keys[kLdsKeys], s_kpar[kLdsKeys];
+    __shared__ int s_tab_v[2][64], s_ntab[2];
+    __shared__ uint4 s_tab_rows[2][64];
+    __shared__ int s_first[2];
+    const int pairs = (a.tr + 1) >> 1;
+    const int b = blockIdx.x / pairs, P = blockIdx.x - b * pairs, n = a.n;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int bm = a.bm, bn = a.bn;  // bm <= 64
+    const int32_t *level = a.level + (size_t)b * n, *parent = a.parent + (size_t)b * n;
+    const int pw = (n + 31) >> 5, ng = (n + 63) >> 6;
+    uint32_t *s_par0 = s_dyn, *s_par1 = s_dyn + pw, *s_need0 = s_dyn + 2 * pw, *s_need1 = s_dyn + 2 * pw + 2 * ng;
+    const int I0 = 2 * P, I1 = 2 * P + 1;
+    const bool have1 = I1 < a.tr;  // the last pair of an odd number of tiles has one tile only
+    const int row0_0 = I0 * bm, row0_1 = I1 * bm;
+    const int bm1 = have1 ? bm : 0;
+    const int gpw = (ng + W - 1) / W;
+    const int g0 = min(wave * gpw, ng), g1 = min(g0 + gpw, ng);
+    int klv[kBatch], kp[kBatch];
+    auto load_batch = [&](int gb) {
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {
+            const int j = (gb + u) * 64 + lane;
+            const bool ok = gb + u < g1 && j < n;
+            klv[u] = ok ? level[j] : -1;
+            kp[u] = ok ? parent[j] : -1;
+        }
+    };
+    load_batch(g0);
+    for (int w = tid; w < 2 * pw; w += kPairThreads) s_dyn[w] = 0;
+    if (tid < 2) s_first[tid] = INT_MAX;
+    lds_barrier();
+    bool check_parent = false;
+    int my_parent = 0;
+    if (tid < 128) {
+        const int h = tid >> 6, r = tid & 63;
+        const int i = (h ? row0_1 : row0_0) + r;
+        int2 me = make_int2(-2, -2);
+        if (r < (h ? bm1 : bm) && i < n) {
+            const int l = level[i], p = parent[i];
+            a.level_copy[(size_t)b * n + i] = l;
+            a.parent_copy[(size_t)b * n + i] = p;
+            if (l < -1 || l >= HDT_MAX_LEVELS || p < -1 || p >= n || p == i || (l < 0 && p != -1))
+                raise_error(a.counters);
+            else if (l >= 0) {
+                me = make_int2(i, p);
+                atomicMin(&s_first[h], i);
+                if (p >= 0) {
+                    atomicOr(&(h ? s_par1 : s_par0)[p >> 5], 1u << (p & 31));
+                    check_parent = true;
+                    my_parent = p;
+                }
+            }
+        }
+        s_row[tid] = me;
+    }
+    const int parent_level = check_parent ? level[my_parent] : 0;
+    lds_barrier();
+    const bool e_up = a.edges & HDT_EDGE_UP, e_sib = a.edges & HDT_EDGE_SIBLING, e_down = a.edges & HDT_EDGE_DOWN;
+    int lcount0 = 0, lcount1 = 0, wtotal0 = 0, wtotal1 = 0;
+    for (int gb = g0; gb < g1; gb += kBatch) {
+        if (gb != g0) load_batch(gb);
+        bool need0[kBatch], need1[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {
+            const int j = (gb + u) * 64 + lane, pj = kp[u];
+            const bool real = klv[u] >= 0 && j < n, has_parent = pj >= 0 && pj < n;
+            const int jc = real ? j : 0, pc = has_parent ? pj : 0;
+            const uint32_t wj0 = s_par0[jc >> 5], wp0 = s_par0[pc >> 5], wj1 = s_par1[jc >> 5], wp1 = s_par1[pc >> 5];
+            const bool j_in0 = (unsigned)(j - row0_0) < (unsigned)bm, j_in1 = (unsigned)(j - row0_1) < (unsigned)bm1;
+            const bool p_in0 = (unsigned)(pj - row0_0) < (unsigned)bm, p_in1 = (unsigned)(pj - row0_1) < (unsigned)bm1;
+            const bool self0 = j_in0 | (e_up & (bool)((wj0 >> (jc & 31)) & 1u));
+            const bool self1 = j_in1 | (e_up & (bool)((wj1 >> (jc & 31)) & 1u));
+            const bool par0 = has_parent & ((e_down & p_in0) | (e_sib & (bool)((wp0 >> (pc & 31)) & 1u)));
+            const bool par1 = has_parent & ((e_down & p_in1) | (e_sib & (bool)((wp1 >> (pc & 31)) & 1u)));
+            need0[u] = real & (self0 | par0);
+            need1[u] = real & (self1 | par1);
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; u++) {
+            if (gb + u >= g1) break;
+            const unsigned long long m0 = __ballot(need0[u]), m1 = __ballot(need1[u]);
+            if (lane == 0) {
+                s_need0[2 * (gb + u)] = (uint32_t)m0;
+                s_need0[2 * (gb + u) + 1] = (uint32_t)(m0 >> 32);
+                s_need1[2 * (gb + u)] = (uint32_t)m1;
+                s_need1[2 * (gb + u) + 1] = (uint32_t)(m1 >> 32);
+            }
+            wtotal0 += __popcll(m0);
+            wtotal1 += __popcll(m1);
+            const int bucket = a.no_sort ? 0 : bucket_of(klv[u]);
+            if (m0 != 0ull) lcount0 += wave_bucket_count(need0[u], bucket);
+            if (m1 != 0ull) lcount1 += wave_bucket_count(need1[u], bucket);
+        }
+    }
+    const bool one_batch = g1 - g0 <= kBatch;
+    if (lane < kBuckets) {
+        s_lcnt[0][wave][lane] = lcount0;
+        s_lcnt[1][wave][lane] = lcount1;
+    }
+    if (lane == 0) {
+        s_wtotal[0][wave] = wtotal0;
+        s_wtotal[1][wave] = wtotal1;
+    }
+    if (check_parent && parent_level < 0) raise_error(a.counters);
+    lds_barrier();
+    int reserved = 0, final_total = -1;
+    if (wave == 1) {  // one reservation for both tiles
+        const int t0 = wave_sum(lane < W ? s_wtotal[0][lane] : 0), t1 = wave_sum(lane < W ? s_wtotal[1][lane] : 0);
+        if (lane == 0) {
+            s_total[0] = t0;
+            s_total[1] = t1;
+            reserved = reserve_entries(a.counters, (t0 + bn - 1) / bn + (t1 + bn - 1) / bn, &final_total);
+        }
+    }
+    if (wave == 2 || wave == 3) {  // the tables of the rows' parents, one per tile (64 rows each)
+        const int h = wave - 2;
+        const int2 ra = s_row[64 * h + lane];
+        const int pa = ra.x >= 0 ? ra.y : -1;
+        unsigned long long rem = __ballot(pa >= 0);
+        int nt = 0;
+        while (rem) {
+            const int v = __builtin_amdgcn_readlane(pa, __ffsll((long long)rem) - 1);
+            const unsigned long long ma = __ballot(pa == v);
+            if (lane == 0) {
+                s_tab_v[h][nt] = v;
+                s_tab_rows[h][nt] = make_uint4((uint32_t)ma, (uint32_t)(ma >> 32), 0u, 0u);
+            }
+            rem &= ~ma;
+            nt++;
+        }
+        if (lane == 0) s_ntab[h] = nt;
+    }
+    if (wave == 0 || wave == 4) {  // first index of every (level, wave) of a tile: level major, then wave
+        const int h = wave >> 2;
+        int t = 0;
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < W; w++) t += s_lcnt[h][w][lane];
+        }
+        int incl = t;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(incl, d);
+            if (lane >= d) incl += y;
+        }
+        int run = incl - t;
+        if (lane < kBuckets) {
+#pragma unroll
+            for (int w = 0; w < W; w++) {
+                const int c = s_lcnt[h][w][lane];
+                s_lcnt[h][w][lane] = run;
+                run += c;
+            }
+        }
+    }
+    lds_barrier();
+    const int total0 = s_total[0], total1 = s_total[1];
+    const int n_ent0 = (total0 + bn - 1) / bn, n_ent1 = (total1 + bn - 1) / bn;
+    const int koff1 = n_ent0 * bn;  // tile 1's list behind tile 0's in s_keys
+    const bool in_lds = (n_ent0 + n_ent1) * bn <= kLdsKeys;
+    const int no_key0 = ~s_first[0], no_key1 = ~s_first[1];
+    // hands out the indices of this wave's needed keys of tile h, in document order inside every level
+    auto pack = [&](int h, bool to_lds, int32_t *keys, int32_t *kpars, int key_fit) {
+        int mybase = lane < kBuckets ? s_lcnt[h][wave][lane] : 0;
+        const uint32_t *s_need = h ? s_need1 : s_need0;
+        const int koff = h ? koff1 : 0;
+        for (int gb = g0; gb < g1; gb += kBatch) {
+            if (!one_batch) load_batch(gb);
+#pragma unroll
+            for (int u = 0; u < kBatch; u++) {
+                if (gb + u >= g1) break;
+                const int g = gb + u;
+                const unsigned long long m = (unsigned long long)s_need[2 * g] | ((unsigned long long)s_need[2 * g + 1] << 32);
+                if (m == 0ull) continue;
+                const bool need = (m >> lane) & 1ull;
+                const int bucket = a.no_sort ? 0 : bucket_of(klv[u]);
+                int t = 0;
+                unsigned long long remaining = m;
+                while (remaining) {
+                    const int leader = __ffsll((long long)remaining) - 1;
+                    const int bk = __builtin_amdgcn_readlane(bucket, leader);
+                    const bool is_bk = need && bucket == bk;
+                    const unsigned long long mm = __ballot(is_bk);
+                    const int first = __builtin_amdgcn_readlane(mybase, bk);
+                    if (is_bk) t = first + __popcll(mm & lanemask_lt());
+                    if (lane == bk) mybase += __popcll(mm);
+                    remaining &= ~mm;
+                }
+                if (need) {
+                    if (to_lds) {
+                        s_keys[koff + t] = g * 64 + lane;
+                        s_kpar[koff + t] = kp[u];
+                    } else if (t < key_fit) {
+                        keys[t] = g * 64 + lane;
+                        kpars[t] = kp[u];
+                    }
+                }
+            }
+        }
+    };
+    if (in_lds) {  // while the reservation is in flight
+        for (int t = total0 + tid; t < n_ent0 * bn; t += kPairThreads) {
+            s_keys[t] = no_key0;
+            s_kpar[t] = -1;
+        }
+        for (int t = total1 + tid; t < n_ent1 * bn; t += kPairThreads) {
+            s_keys[koff1 + t] = no_key1;
+            s_kpar[koff1 + t] = -1;
+        }
+        pack(0, true, nullptr, nullptr, 0);
+        pack(1, true, nullptr, nullptr, 0);
+    }
+    if (tid == 64) {
+        s_base[0] = reserved;
+        s_base[1] = reserved + n_ent0;
+        if (final_total >= 0) {
+            const int err = __hip_atomic_load(&a.counters[CNT_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (a.self_reset) {
+                __hip_atomic_store(&a.counters[CNT_ERR], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(reinterpret_cast<unsigned long long *>(a.counters + CNT_CAND), 0ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const unsigned long long word = report_word(a.ticket, err, (uint32_t)final_total);
+            *a.report_dev = word;
+            __hip_atomic_store(a.report, word, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+    lds_barrier();
+    // per tile: its slice of the arrays, as far as it fits (see key_lists)
+    int64_t base[2];
+    int n_fit[2], key_fit[2];
+    int32_t *keys[2], *kpars[2];
+    for (int h = 0; h < 2; h++) {
+        base[h] = s_base[h];
+        const int n_ent = h ? n_ent1 : n_ent0;
+        const int64_t room = a.capacity - base[h];
+        n_fit[h] = room <= 0 ? 0 : (room < n_ent ? (int)room : n_ent);
+        key_fit[h] = n_fit[h] * bn;
+        keys[h] = a.q_keys + (size_t)(room <= 0 ? 0 : base[h]) * bn;
+        kpars[h] = a.q_kpar + (size_t)(room <= 0 ? 0 : base[h]) * bn;
+        const size_t row = (size_t)b * a.tr + (h ? I1 : I0);
+        if (h == 1 && !have1) break;
+        if (tid == 0) {
+            const int32_t first = (int32_t)(room <= 0 ? a.capacity : base[h]);
+            a.q_range[2 * row] = first;
+            a.q_range[2 * row + 1] = first + n_fit[h];
+        }
+        for (int e = tid; e < n_fit[h]; e += kPairThreads) a.c_row[base[h] + e] = (int32_t)row;
+    }
+    if (!have1) n_fit[1] = key_fit[1] = 0;
+    if (in_lds) {
+        for (int t = tid; t < key_fit[0]; t += kPairThreads) {
+            keys[0][t] = s_keys[t];
+            if (t < total0) kpars[0][t] = s_kpar[t];
+        }
+        for (int t = tid; t < key_fit[1]; t += kPairThreads) {
+            keys[1][t] = s_keys[koff1 + t];
+            if (t < total1) kpars[1][t] = s_kpar[koff1 + t];
+        }
+    } else {
+        for (int t = total0 + tid; t < key_fit[0]; t += kPairThreads) keys[0][t] = no_key0;
+        for (int t = total1 + tid; t < key_fit[1]; t += kPairThreads) keys[1][t] = no_key1;
+        pack(0, false, keys[0], kpars[0], key_fit[0]);
+        pack(1, false, keys[1], kpars[1], key_fit[1]);
+        __syncthreads();  // the keys were written by other waves of this workgroup (see key_lists)
+    }
+    // The entries of both tiles, one wave per 64 key slots.  Lists kept in LDS: the waves take the entries of both
+    // tiles in one sequence; lists that did not fit are brought back tile by tile, a round of entries at a time.
+    const int wpe = (bn + 63) >> 6, per_round = W / wpe;
+    const int quad = wave / wpe, k0 = (wave - quad * wpe) * 64;
+    ParentTable tab[2];
+    for (int h = 0; h < 2; h++) {
+        tab[h].n = s_ntab[h];
+        tab[h].v = s_tab_v[h];
+        tab[h].rows = s_tab_rows[h];
+    }
+    int par = 0;
+    auto finish = [&](bool active, int64_t c, const EntryPart &part) {  // pair count and summary of entry c
+        if (wpe == 1) {
+            if (active && lane == 0) {
+                a.c_cnt[c] = part.cnt;
+                a.q_sub[c] = part.any | (part.all << 16);
+            }
+            return;
+        }
+        if (lane == 0) {
+            s_cnt[par][wave] = part.cnt;
+            s_any[par][wave] = part.any;
+            s_all[par][wave] = part.all;
+        }
+        lds_barrier();
+        if (active && k0 == 0 && lane == 0) {
+            a.c_cnt[c] = s_cnt[par][wave] + s_cnt[par][wave + 1];
+            a.q_sub[c] = (s_any[par][wave] | s_any[par][wave + 1]) | ((s_all[par][wave] | s_all[par][wave + 1]) << 16);
+        }
+        par ^= 1;
+    };
+    if (in_lds) {
+        const int n_all = n_fit[0] + n_fit[1];
+        for (int x0 = 0; x0 < n_all; x0 += per_round) {
+            const int x = x0 + quad;
+            const bool active = x < n_all;
+            const int h = (active && x >= n_fit[0]) ? 1 : 0, e = x - (h ? n_fit[0] : 0);
+            EntryPart part;
+            part.cnt = 0;
+            part.any = part.all = 0;
+            if (active)
+                part = entry_columns(base[h] + e, k0, lane, tab[h], s_keys + (h ? koff1 : 0) + e * bn,
+                                     s_kpar + (h ? koff1 : 0) + e * bn, h ? row0_1 : row0_0, bm, bn, a.edges, a.bits_rm);
+            finish(active, base[h] + e, part);
+        }
+    } else {
+        for (int h = 0; h < 2; h++) {
+            for (int e0 = 0; e0 < n_fit[h]; e0 += per_round) {
+                const int e = e0 + quad;
+                lds_barrier();  // the previous round's keys have been read
+                for (int t = tid; t < per_round * bn; t += kPairThreads) {
+                    const int gi = e0 * bn + t;
+                    int kk = -1, kq = -1;
+                    if (gi < key_fit[h]) kk = __hip_atomic_load(&keys[h][gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (kk >= 0 && kk < n) kq = __hip_atomic_load(&kpars[h][gi], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_keys[t] = (kk >= 0 && kk < n) ? kk : -1;
+                    s_kpar[t] = kq;
+                }
+                lds_barrier();
+                const bool active = e < n_fit[h];
+                EntryPart part;
+                part.cnt = 0;
+                part.any = part.all = 0;
+                if (active)
+                    part = entry_columns(base[h] + e, k0, lane, tab[h], s_keys + quad * bn, s_kpar + quad * bn, h ? row0_1 : row0_0,
+                                         bm, bn, a.edges, a.bits_rm);
+                finish(active, base[h] + e, part);
+            }
         }
     }
 }
@@ -1484,11 +1841,16 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                                slot_counters != nullptr};
                 const size_t lds = ((size_t)(n + 31) / 32 + (size_t)2 * ((n + 63) / 64)) * sizeof(uint32_t);
                 const bool small_wg = bm <= 64;
-                if (lds > 32 * 1024)  // with the kernel's static arrays: beyond the 64 KB a launch gets by default
+                // tiles of up to 64 rows: two per workgroup, as long as the two sets of bitmaps fit the LDS beside the
+                // kernel's static arrays (documents of up to 64 K positions)
+                const bool pair = small_wg && 2 * lds <= 32 * 1024;
+                if (!pair && lds > 32 * 1024)  // with the kernel's static arrays: beyond the 64 KB a launch gets by default
                     BUILD_TRY(hipFuncSetAttribute(small_wg ? (const void *)k_key_lists<512> : (const void *)k_key_lists<1024>,
                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
                 HdtTimer t("hdt_layout_key_lists", st);
-                if (small_wg)
+                if (pair)
+                    hipLaunchKernelGGL(k_key_lists_pair, dim3((unsigned)B * ((tr + 1) / 2)), dim3(kPairThreads), 2 * lds, st, ka);
+                else if (small_wg)
                     hipLaunchKernelGGL(k_key_lists<512>, dim3((unsigned)B * tr), dim3(512), lds, st, ka);
                 else
                     hipLaunchKernelGGL(k_key_lists<1024>, dim3((unsigned)B * tr), dim3(1024), lds, st, ka);

@@ -51,10 +51,14 @@ def test_bwd_config1_hierarchy_fp32_and_bf16(oracle):
     run_bwd_case(oracle, wl.level, wl.parent, 2, 64, "bf16", 61)
 
 
-def test_bwd_config4_full(oracle):
+BOTH_TILES = pytest.mark.parametrize("tile", [(128, 64), (64, 32)], ids=["128x64", "64x32"])
+
+
+@BOTH_TILES
+def test_bwd_config4_full(oracle, tile):
     wl = inputs.make_workload(4)
-    say(f"[bwd] config 4 bf16 B={wl.batch} H={wl.heads} N={wl.n_pos} d={wl.head_dim}")
-    run_bwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(4, 50))
+    say(f"[bwd] config 4 bf16 B={wl.batch} H={wl.heads} N={wl.n_pos} d={wl.head_dim} tile {tile}")
+    run_bwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(4, 50), tile=tile)
 
 
 def test_bwd_config2_reduced(oracle):
@@ -63,10 +67,11 @@ def test_bwd_config2_reduced(oracle):
     run_bwd_case(oracle, wl.level, wl.parent, 4, 64, "bf16", inputs.sample_seed(2, 60))
 
 
-def test_bwd_config5_d128(oracle):
+@BOTH_TILES
+def test_bwd_config5_d128(oracle, tile):
     wl = inputs.make_workload(5)
-    say("[bwd] config 5 bf16 B=1 H=16 N=32768 d=128")
-    run_bwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(5, 60))
+    say(f"[bwd] config 5 bf16 B=1 H=16 N=32768 d=128 tile {tile}")
+    run_bwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(5, 60), tile=tile)
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 64), ("bf16", 128), ("f32", 64), ("f32", 128)])

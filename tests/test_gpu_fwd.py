@@ -53,17 +53,22 @@ def test_fwd_config1_shape_bf16(oracle):
     run_fwd_case(oracle, wl.level, wl.parent, 2, 64, "bf16", inputs.sample_seed(1, 51))
 
 
+BOTH_TILES = pytest.mark.parametrize("tile", [(128, 64), (64, 32)], ids=["128x64", "64x32"])
+
+
+@BOTH_TILES
 @pytest.mark.parametrize("config", [2, 3])
-def test_fwd_full_configs_bf16(oracle, config):
+def test_fwd_full_configs_bf16(oracle, config, tile):
     wl = inputs.make_workload(config)
-    say(f"[fwd] config {config} bf16 B={wl.batch} H={wl.heads} N={wl.n_pos} d={wl.head_dim}")
-    run_fwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(config, 50))
+    say(f"[fwd] config {config} bf16 B={wl.batch} H={wl.heads} N={wl.n_pos} d={wl.head_dim} tile {tile}")
+    run_fwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(config, 50), tile=tile)
 
 
-def test_fwd_config5_bf16_d128(oracle):
+@BOTH_TILES
+def test_fwd_config5_bf16_d128(oracle, tile):
     wl = inputs.make_workload(5)
-    say("[fwd] config 5 bf16 B=1 H=16 N=32768 d=128")
-    run_fwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(5, 50))
+    say(f"[fwd] config 5 bf16 B=1 H=16 N=32768 d=128 tile {tile}")
+    run_fwd_case(oracle, wl.level, wl.parent, wl.heads, wl.head_dim, "bf16", inputs.sample_seed(5, 50), tile=tile)
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 64), ("bf16", 128), ("f32", 64), ("f32", 128)])

@@ -28,6 +28,16 @@ def test_layout_matches_oracle_on_benchmark_configs(oracle, config, windowed):
     lay.destroy()
 
 
+@pytest.mark.parametrize("config", [3, 5])
+def test_layout_64x32_on_benchmark_configs(oracle, config):
+    wl = inputs.make_workload(config)
+    say(f"[layout] config {config} B={wl.batch} N={wl.n_pos} tile 64x32")
+    lay = _build(wl.level, wl.parent, tile_m=64, tile_n=32)
+    tiles, nnz = compare_layout(oracle, lay, wl.level, wl.parent, 64, 32)
+    say(f"[layout] config {config}: {tiles} tiles, nnz {nnz}")
+    lay.destroy()
+
+
 @WINDOWED
 @pytest.mark.parametrize("bm,bn", [(64, 32), (32, 32), (128, 128), (96, 64)])
 def test_layout_other_tile_shapes(oracle, bm, bn, windowed):
@@ -38,15 +48,18 @@ def test_layout_other_tile_shapes(oracle, bm, bn, windowed):
 
 
 @WINDOWED
+@pytest.mark.parametrize("bm,bn", [(128, 64), (64, 32)])
 @pytest.mark.parametrize("n", [1, 31, 100, 129, 1000, 4097])
-def test_layout_ragged_lengths(oracle, n, windowed):
+def test_layout_ragged_lengths(oracle, n, bm, bn, windowed):
+    # 64-row tiles: an odd number of query tiles at 31, 129 and 4097 (key lists of two neighbouring tiles are
+    # built by one workgroup, the last one then has a single tile)
     rng = np.random.default_rng(n)
     level, parent = inputs.tree_document([(1, 6), (0, 7), (0, 20)], rng, max_nodes=n)
     level = np.concatenate([level, np.full(n - level.shape[0], -1, np.int32)])[None]
     parent = np.concatenate([parent, np.full(n - parent.shape[0], -1, np.int32)])[None]
-    say(f"[layout] ragged n={n} real={(level >= 0).sum()} windowed={windowed}")
-    lay = _build(level, parent, windowed=windowed)
-    compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed)
+    say(f"[layout] ragged n={n} real={(level >= 0).sum()} tile {bm}x{bn} windowed={windowed}")
+    lay = _build(level, parent, tile_m=bm, tile_n=bn, windowed=windowed)
+    compare_layout(oracle, lay, level, parent, bm, bn, windowed=windowed)
 
 
 @WINDOWED
@@ -197,6 +210,11 @@ def test_layout_grows_its_arrays_when_the_first_guess_is_too_small(oracle, windo
     lay = _build(level, parent, windowed=windowed)
     tiles, nnz = compare_layout(oracle, lay, level, parent, 128, 64, windowed=windowed)
     assert nnz == n * n and tiles == 24 * 47
+    lay.destroy()
+    _build(tiny_l, tiny_p, tile_m=64, tile_n=32, windowed=windowed).destroy()
+    lay = _build(level, parent, tile_m=64, tile_n=32, windowed=windowed)   # 47 query tiles: the last on its own
+    tiles, nnz = compare_layout(oracle, lay, level, parent, 64, 32, windowed=windowed)
+    assert nnz == n * n and tiles == 47 * 94
 
 
 def test_layout_rejects_bad_hierarchies():
