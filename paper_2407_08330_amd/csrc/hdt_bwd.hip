@@ -38,10 +38,13 @@ using namespace hdt_tile;
 
 template <int D>
 struct BwdCfg {
-    // ring stages of the two roles and waves per SIMD (register budget) of the kernel
+    // ring stages of the two roles and waves per SIMD (register budget) of the kernel.  Three waves at head size
+    // 64 pay on 128 x 64 tiles only (measured, config 4: 107 us against 122 with two; on 64 x 32 tiles 101
+    // against 99 with two, whose allocation the compiler then leaves unconstrained).
     static constexpr int S_DQ = (D == 64) ? 3 : 2;
     static constexpr int S_DKV = 2;
-    static constexpr int WAVES = (D == 64) ? 3 : 2;
+    template <typename G>
+    static constexpr int WAVES = (D == 64 && G::BM == 128) ? 3 : 2;
     // At head size 128 the dK/dV role would need 128 accumulator registers per lane on top of 64 operand
     // registers, which leaves one wave per SIMD.  It is split there into a dV role and a dK role (each
     // recomputes the scores), so that every role fits two waves per SIMD.
@@ -348,7 +351,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
 }
 
 template <int D, typename G>
-__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES) void k_bwd_bf16(
+__global__ __launch_bounds__(G::THREADS, BwdCfg<D>::template WAVES<G>) void k_bwd_bf16(
     HdtSchedule s, HdtSchedule s_tr, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
     const float *__restrict__ delta, __bf16 *__restrict__ dq, __bf16 *__restrict__ dk, __bf16 *__restrict__ dv,
@@ -362,7 +365,7 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::WAVES) void k_bwd_bf16(
     // The roles tile different tensors (the same ones for self-attention): the workgroups of one tile follow each
     // other as far as both sides have that tile, the rest of the longer side comes behind them.
     constexpr unsigned R = BwdCfg<D>::SPLIT_KV ? 3u : 2u;  // roles per tile: dQ, then dK/dV or dV, dK
-    const unsigned w = logical_block(blockIdx.x, R * kXcdChunk);
+    const unsigned w = logical_block(blockIdx.x, R * G::XCD_CHUNK);
     const unsigned nq = (unsigned)s.batch * heads * s.tr, nk = (unsigned)s_tr.batch * heads * s_tr.tr;
     const unsigned common = nq < nk ? nq : nk;
     if (w >= nq + (R - 1u) * nk) return;  // padding of the grid
@@ -413,7 +416,7 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
         HdtTimer t(head_dim == 64 ? "hdt_bwd_bf16_d64" : "hdt_bwd_bf16_d128", st);
         const unsigned nq = (unsigned)s.batch * heads * s.tr, nk = (unsigned)s_tr.batch * heads * s_tr.tr;
         const unsigned roles = head_dim == 128 ? 3u : 2u;  // BwdCfg<D>::SPLIT_KV
-        dim3 grid(padded_grid(nq + (roles - 1u) * nk, roles * kXcdChunk)), block(G::THREADS);
+        dim3 grid(padded_grid(nq + (roles - 1u) * nk, roles * G::XCD_CHUNK)), block(G::THREADS);
         if (head_dim == 64)
             hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
                                (__bf16 *)dk, (__bf16 *)dv, heads, scale);

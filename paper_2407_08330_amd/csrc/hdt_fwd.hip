@@ -126,7 +126,7 @@ __global__ __launch_bounds__(G::THREADS, FwdCfg<D>::WAVES) void k_fwd_bf16(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qn = lane & 31, hf = lane >> 5;
-    const unsigned lb = logical_block(blockIdx.x, kXcdChunk);
+    const unsigned lb = logical_block(blockIdx.x, G::XCD_CHUNK);
     if (lb >= (unsigned)s.batch * heads * s.tr) return;  // padding of the grid
     const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
     const int I_own = I % s.tr_own;  // the rows this tile works on (several tiles share them when key lists are cut)
@@ -216,7 +216,7 @@ template <typename G>
 static void launch_fwd(const HdtSchedule &s, const void *q, const void *k, const void *v, void *o, float *lse,
                        int heads, int head_dim, float scale_log2, hipStream_t st)
 {
-    dim3 grid(padded_grid((unsigned)((size_t)s.batch * heads * s.tr), kXcdChunk)), block(G::THREADS);
+    dim3 grid(padded_grid((unsigned)((size_t)s.batch * heads * s.tr), G::XCD_CHUNK)), block(G::THREADS);
     if (head_dim == 64)
         hipLaunchKernelGGL((k_fwd_bf16<64, G>), grid, block, 0, st, s, (const __bf16 *)q, (const __bf16 *)k,
                            (const __bf16 *)v, (__bf16 *)o, lse, heads, scale_log2);
