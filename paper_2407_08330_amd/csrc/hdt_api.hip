@@ -362,9 +362,8 @@ extern "C" __attribute__((visibility("default"))) size_t hdt_attn_bwd_workspace_
                                                hdt_dtype_t dt)
 {
     if (!hdt_layout_ok(layout) || heads < 0) return 0;
-    // D_i = sum_c dO_ic O_ic, one float per (batch, head, position)
-    size_t n = (size_t)layout->s.batch * (size_t)heads * (size_t)layout->s.n_pos * sizeof(float);
-    n = (n + 255) & ~(size_t)255;
+    // two floats per (batch, head, position): D_i = sum_c dO_ic O_ic and LSE_i in the form the kernels start from
+    size_t n = hdt_bwd_row_scalars_bytes((size_t)layout->s.batch * (size_t)heads * (size_t)layout->s.n_pos);
     // a cross-attention layout with a compact pair: compact copies of K, V and of their gradients behind it
     if (layout->compact) n += hdt_cross_compact_workspace_bytes(layout, heads, head_dim, dt == HDT_BF16 ? 2 : 4);
     // a cross-attention layout with long key lists: the parts of dQ that the pieces of the lists produce

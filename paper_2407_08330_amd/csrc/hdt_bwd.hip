@@ -52,21 +52,29 @@ struct BwdCfg {
 };
 
 // ---------------------------------------------------------------------------------------- D
-// D_i = sum_c dO_ic O_ic for all rows of [rows][D] tensors: every lane multiplies 8 values (16 bytes of each
-// tensor), the lanes of a row are added up.  kRows rows per lane in flight.
+// For all rows of [rows][D] tensors: D_i = sum_c dO_ic O_ic (every lane multiplies 8 values, 16 bytes of each
+// tensor; the lanes of a row are added up; kRows rows per lane in flight).  What the main kernel wants of a row
+// are the two values its contractions start from, so those are what is written, side by side:
+//   .x = -D_i            dP - D        = -D + dO V^T          (accumulator of dP preset to it)
+//   .y = -LSE_i / scale  scale S - LSE = scale (-LSE / scale + Q K^T)   (accumulator of S preset to it)
+// which takes a subtraction and a multiplication per score out of both roles.  Rows without a key (LSE = -inf:
+// pads) get 0 for both: they are masked, and their dO may hold anything.
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_delta(const __bf16 *__restrict__ o, const __bf16 *__restrict__ d_o,
-                                                   float *__restrict__ delta, long long rows)
+                                                   const float *__restrict__ lse, float inv_scale,
+                                                   float2 *__restrict__ row_scalars, long long rows)
 {
     constexpr int CPR = D / 8, RPB = 256 / CPR, kRows = 4;
     const int lr = threadIdx.x / CPR, c = threadIdx.x % CPR;
     const long long r0 = (long long)blockIdx.x * (RPB * kRows) + lr;
     bf16x8 a[kRows], b[kRows];
+    float l[kRows];
 #pragma unroll
     for (int u = 0; u < kRows; u++) {
         const long long r = min(r0 + (long long)u * RPB, rows - 1);
         a[u] = *reinterpret_cast<const bf16x8 *>(o + (size_t)r * D + c * 8);
         b[u] = *reinterpret_cast<const bf16x8 *>(d_o + (size_t)r * D + c * 8);
+        l[u] = c == 0 ? lse[r] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < kRows; u++) {
@@ -76,7 +84,10 @@ __global__ __launch_bounds__(256) void k_bwd_delta(const __bf16 *__restrict__ o,
 #pragma unroll
         for (int m = 1; m < CPR; m <<= 1) part += __shfl_xor(part, m);
         const long long r = r0 + (long long)u * RPB;
-        if (c == 0 && r < rows) delta[r] = part;
+        if (c == 0 && r < rows) {
+            const bool dead = l[u] == -INFINITY;
+            row_scalars[r] = dead ? make_float2(0.f, 0.f) : make_float2(-part, -l[u] * inv_scale);
+        }
     }
 }
 
@@ -85,8 +96,8 @@ template <int D, typename G>
 __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const __bf16 *__restrict__ q,
                                          const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
                                          const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
-                                         const float *__restrict__ delta, __bf16 *__restrict__ dq, int wave, int I, int bh,
-                                         int b, float scale)
+                                         const float2 *__restrict__ row_scalars, __bf16 *__restrict__ dq, int wave,
+                                         int I, int bh, int b, float scale)
 {
     using P = Pipe<D, BwdCfg<D>::S_DQ, false, G>;
     using R = Ring<P>;
@@ -133,19 +144,18 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
         dof[st] = read_row<ROWB>(smem + STG_DO, rl, wave * 32, st);
     }
     const int qrow_ld = min(qrow, s.n_own - 1);
-    float lse2 = lse[(size_t)bh * s.n_own + qrow_ld];
-    float Di = delta[(size_t)bh * s.n_own + qrow_ld];
-    // A row without any key (a pad: LSE = -inf) is masked by the bitmap, but its Q, dO and D may hold anything,
+    const float lse_i = lse[(size_t)bh * s.n_own + qrow_ld];
+    const float2 init = row_scalars[(size_t)bh * s.n_own + qrow_ld];  // 0, 0 for a row without a key
+    const float dp_init = init.x, s_init = init.y;                    // -D_i, -LSE_i / scale
+    // A row without any key (a pad: LSE = -inf) is masked by the bitmap, but its Q and dO may hold anything,
     // NaN included, which a zero weight would not remove: it takes part as a row of zeros.
-    const bool dead_row = lse2 == -INFINITY;
-    lse2 = dead_row ? 0.f : lse2 * LOG2E;
-    Di = dead_row ? 0.f : Di;
+    const bool dead_row = lse_i == -INFINITY;
     if (dead_row) {
 #pragma unroll
         for (int st = 0; st < KSTEPS; st++) qf[st] = dof[st] = zero_bf16x8();
     }
     // the compiler must finish its own loads before the hand-scheduled ones continue
-    asm volatile("" ::"v"(Di), "v"(lse2));
+    asm volatile("" ::"v"(dp_init), "v"(s_init), "v"(lse_i));
     wg_barrier();  // every wave has read its fragments: the ring may use all stages
     R::template prologue<S - 2, S - 1>(pipe, n);
 
@@ -171,19 +181,22 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
         for (int kb = 0; kb < KB; kb++) {
             const int sb = wave * KB + kb;
             if (!((sub >> sb) & 1u)) continue;
-            f32x16 sacc, dpacc;
+            f32x16 sacc, dpacc;  // every element of a lane belongs to the lane's query
 #pragma unroll
-            for (int e = 0; e < 16; e++) sacc[e] = dpacc[e] = 0.f;
-#pragma unroll
-            for (int st = 0; st < KSTEPS; st++) {
-                sacc = mfma_32x32x16(read_row<ROWB>(sK, rl, kb * 32, st), qf[st], sacc);     // S^T  = K Q^T
-                dpacc = mfma_32x32x16(read_row<ROWB>(sV, rl, kb * 32, st), dof[st], dpacc);  // dP^T = V dO^T
+            for (int e = 0; e < 16; e++) {
+                sacc[e] = s_init;
+                dpacc[e] = dp_init;
             }
 #pragma unroll
-            for (int e = 0; e < 16; e++) sacc[e] = fast_exp2(fmaf(sacc[e], scale_log2, -lse2));  // P^T
+            for (int st = 0; st < KSTEPS; st++) {
+                sacc = mfma_32x32x16(read_row<ROWB>(sK, rl, kb * 32, st), qf[st], sacc);     // K Q^T - LSE / scale
+                dpacc = mfma_32x32x16(read_row<ROWB>(sV, rl, kb * 32, st), dof[st], dpacc);  // dP^T - D = V dO^T - D
+            }
+#pragma unroll
+            for (int e = 0; e < 16; e++) sacc[e] = fast_exp2(sacc[e] * scale_log2);  // P^T
             if (!((sub >> (16 + sb)) & 1u)) apply_mask(sacc, s.bits_rm + ((size_t)bidx * G::NSUB + sb) * 16, 0.f);
 #pragma unroll
-            for (int e = 0; e < 16; e++) sacc[e] *= dpacc[e] - Di;  // dS^T
+            for (int e = 0; e < 16; e++) sacc[e] *= dpacc[e];  // dS^T
             // dQ^T += K^T dS^T
             const bf16x8 b0 = pack_bf16x8(sacc, 0), b1 = pack_bf16x8(sacc, 8);
 #pragma unroll
@@ -208,9 +221,9 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
 template <int D, typename G, int WHICH>
 __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const __bf16 *__restrict__ q,
                                           const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
-                                          const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
-                                          const float *__restrict__ delta, __bf16 *__restrict__ dk,
-                                          __bf16 *__restrict__ dv, int wave, int I, int bh, int b, float scale)
+                                          const __bf16 *__restrict__ d_o, const float2 *__restrict__ row_scalars,
+                                          __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int wave, int I, int bh,
+                                          int b, float scale)
 {
     using P = Pipe<D, BwdCfg<D>::S_DKV, true, G>;
     using R = Ring<P>;
@@ -236,8 +249,8 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
     pipe.keys = s.q_keys + (size_t)t0 * BN;
     pipe.a = q + q_base;
     pipe.b = d_o + q_base;
-    pipe.aux0 = lse + (size_t)bh * s.n_kv;
-    pipe.aux1 = delta + (size_t)bh * s.n_kv;
+    pipe.aux0 = reinterpret_cast<const float *>(row_scalars + (size_t)bh * s.n_kv) + 1;  // -LSE / scale of a position
+    pipe.aux1 = reinterpret_cast<const float *>(row_scalars + (size_t)bh * s.n_kv);      // -D
     const RowLane rl = row_lane<P::CPR>(lane);
     const TrLane tl = tr_lane<P::CPR>(lane);
     // is this lane's own row a real position?  (Requested first, looked at once the rows are in registers.)
@@ -290,38 +303,41 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
         wg_barrier();
         R::advance(pipe, i, n);
         const char *sQ = pipe.tile_a(i % S), *sDO = pipe.tile_b(i % S);
-        const float *sLse = pipe.aux_buf(i % S, 0), *sDelta = pipe.aux_buf(i % S, 1);
+        const float *sInitS = pipe.aux_buf(i % S, 0), *sInitDP = pipe.aux_buf(i % S, 1);  // -LSE / scale, -D
 
 #pragma unroll
         for (int kb = 0; kb < KB; kb++) {  // 32 query slots
             const int sb = wave * KB + kb;
             if (!((sub >> sb) & 1u)) continue;
+            // element gq * 4 + e of a lane belongs to the query in slot kb * 32 + hf * 4 + gq * 8 + e
             f32x16 sacc, dpacc;
 #pragma unroll
-            for (int e = 0; e < 16; e++) sacc[e] = dpacc[e] = 0.f;
+            for (int gq = 0; gq < 4; gq++) {
+                const float4 l4 = *reinterpret_cast<const float4 *>(&sInitS[kb * 32 + hf * 4 + gq * 8]);
+                sacc[gq * 4 + 0] = l4.x;
+                sacc[gq * 4 + 1] = l4.y;
+                sacc[gq * 4 + 2] = l4.z;
+                sacc[gq * 4 + 3] = l4.w;
+                if (DO_DK) {
+                    const float4 d4 = *reinterpret_cast<const float4 *>(&sInitDP[kb * 32 + hf * 4 + gq * 8]);
+                    dpacc[gq * 4 + 0] = d4.x;
+                    dpacc[gq * 4 + 1] = d4.y;
+                    dpacc[gq * 4 + 2] = d4.z;
+                    dpacc[gq * 4 + 3] = d4.w;
+                }
+            }
 #pragma unroll
             for (int st = 0; st < KSTEPS; st++) {
-                sacc = mfma_32x32x16(read_row<ROWB>(sQ, rl, kb * 32, st), kf[st], sacc);     // S  = Q K^T
-                if (DO_DK) dpacc = mfma_32x32x16(read_row<ROWB>(sDO, rl, kb * 32, st), vf[st], dpacc);  // dP = dO V^T
+                sacc = mfma_32x32x16(read_row<ROWB>(sQ, rl, kb * 32, st), kf[st], sacc);     // Q K^T - LSE / scale
+                if (DO_DK) dpacc = mfma_32x32x16(read_row<ROWB>(sDO, rl, kb * 32, st), vf[st], dpacc);  // dO V^T - D
             }
             f32x16 pacc;
 #pragma unroll
-            for (int gq = 0; gq < 4; gq++) {
-                const float4 l4 = *reinterpret_cast<const float4 *>(&sLse[kb * 32 + hf * 4 + gq * 8]);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-#pragma unroll
-                for (int e = 0; e < 4; e++)  // a pad query has LSE = -inf -> +inf here, removed by its mask
-                    pacc[gq * 4 + e] = fast_exp2(fmaf(sacc[gq * 4 + e], scale_log2, -lv[e] * LOG2E));
-            }
+            for (int e = 0; e < 16; e++) pacc[e] = fast_exp2(sacc[e] * scale_log2);  // P
             if (!((sub >> (16 + sb)) & 1u)) apply_mask(pacc, s.bits_rm + ((size_t)bidx * G::NSUB + sb) * 16, 0.f);
             if (DO_DK) {
 #pragma unroll
-                for (int gq = 0; gq < 4; gq++) {
-                    const float4 d4 = *reinterpret_cast<const float4 *>(&sDelta[kb * 32 + hf * 4 + gq * 8]);
-                    const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; e++) sacc[gq * 4 + e] = pacc[gq * 4 + e] * (dpacc[gq * 4 + e] - dl[e]);  // dS
-                }
+                for (int e = 0; e < 16; e++) sacc[e] = pacc[e] * dpacc[e];  // dS
                 const bf16x8 s0 = pack_bf16x8(sacc, 0), s1 = pack_bf16x8(sacc, 8);
 #pragma unroll
                 for (int j = 0; j < DBLK; j++) {
@@ -354,8 +370,8 @@ template <int D, typename G>
 __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::template WAVES<G>) void k_bwd_bf16(
     HdtSchedule s, HdtSchedule s_tr, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse, const __bf16 *__restrict__ d_o,
-    const float *__restrict__ delta, __bf16 *__restrict__ dq, __bf16 *__restrict__ dk, __bf16 *__restrict__ dv,
-    int heads, float scale)
+    const float2 *__restrict__ row_scalars, __bf16 *__restrict__ dq, __bf16 *__restrict__ dk,
+    __bf16 *__restrict__ dv, int heads, float scale)
 {
     using PQ = Pipe<D, BwdCfg<D>::S_DQ, false, G>;
     using PK = Pipe<D, BwdCfg<D>::S_DKV, true, G>;
@@ -383,15 +399,15 @@ __global__ __launch_bounds__(G::THREADS, BwdCfg<D>::template WAVES<G>) void k_bw
     }
     if (role == 0u) {
         const int I = lb % s.tr, bh = lb / s.tr, b = bh / heads;
-        dq_role<D, G>(smem, s, q, k, v, lse, d_o, delta, dq, wave, I, bh, b, scale);
+        dq_role<D, G>(smem, s, q, k, v, lse, d_o, row_scalars, dq, wave, I, bh, b, scale);
     } else {
         const int I = lb % s_tr.tr, bh = lb / s_tr.tr, b = bh / heads;
         if (!BwdCfg<D>::SPLIT_KV)
-            dkv_role<D, G, 0>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
+            dkv_role<D, G, 0>(smem, s_tr, q, k, v, d_o, row_scalars, dk, dv, wave, I, bh, b, scale);
         else if (role == 1u)
-            dkv_role<D, G, 1>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
+            dkv_role<D, G, 1>(smem, s_tr, q, k, v, d_o, row_scalars, dk, dv, wave, I, bh, b, scale);
         else
-            dkv_role<D, G, 2>(smem, s_tr, q, k, v, lse, d_o, delta, dk, dv, wave, I, bh, b, scale);
+            dkv_role<D, G, 2>(smem, s_tr, q, k, v, d_o, row_scalars, dk, dv, wave, I, bh, b, scale);
     }
 }
 
@@ -402,15 +418,17 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
                        const __bf16 *O, const float *lse, const __bf16 *DO, void *dq, void *dk, void *dv, int heads,
                        int head_dim, float scale, float *delta, hipStream_t st)
 {
+    // the rows' two scalars (-D, -LSE / scale), see hdt_bwd_row_scalars_bytes for the room they take
+    const long long rows = (long long)s.batch * heads * s.n_own;  // the real rows, also when key lists are cut
+    float2 *row_scalars = reinterpret_cast<float2 *>(delta);
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_delta_d64" : "hdt_bwd_delta_d128", st);
-        const long long rows = (long long)s.batch * heads * s.n_own;  // the real rows, also when key lists are cut
         const int rpb = (256 / (head_dim / 8)) * 4;
         dim3 grid((unsigned)((rows + rpb - 1) / rpb)), block(256);
         if (head_dim == 64)
-            hipLaunchKernelGGL(k_bwd_delta<64>, grid, block, 0, st, O, DO, delta, rows);
+            hipLaunchKernelGGL(k_bwd_delta<64>, grid, block, 0, st, O, DO, lse, 1.f / scale, row_scalars, rows);
         else
-            hipLaunchKernelGGL(k_bwd_delta<128>, grid, block, 0, st, O, DO, delta, rows);
+            hipLaunchKernelGGL(k_bwd_delta<128>, grid, block, 0, st, O, DO, lse, 1.f / scale, row_scalars, rows);
     }
     {
         HdtTimer t(head_dim == 64 ? "hdt_bwd_bf16_d64" : "hdt_bwd_bf16_d128", st);
@@ -418,11 +436,11 @@ static void launch_bwd(const HdtSchedule &s, const HdtSchedule &s_tr, const __bf
         const unsigned roles = head_dim == 128 ? 3u : 2u;  // BwdCfg<D>::SPLIT_KV
         dim3 grid(padded_grid(nq + (roles - 1u) * nk, roles * G::XCD_CHUNK)), block(G::THREADS);
         if (head_dim == 64)
-            hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
-                               (__bf16 *)dk, (__bf16 *)dv, heads, scale);
+            hipLaunchKernelGGL((k_bwd_bf16<64, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, row_scalars,
+                               (__bf16 *)dq, (__bf16 *)dk, (__bf16 *)dv, heads, scale);
         else
-            hipLaunchKernelGGL((k_bwd_bf16<128, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, delta, (__bf16 *)dq,
-                               (__bf16 *)dk, (__bf16 *)dv, heads, scale);
+            hipLaunchKernelGGL((k_bwd_bf16<128, G>), grid, block, 0, st, s, s_tr, Q, K, V, lse, DO, row_scalars,
+                               (__bf16 *)dq, (__bf16 *)dk, (__bf16 *)dv, heads, scale);
     }
 }
 

@@ -620,7 +620,7 @@ hdt_status_t hdt_cross_bwd_compact(const hdt_layout_t *l, const void *q, const v
     const hdt_layout_t *lc = l->compact;
     const HdtSchedule &s = lc->s, &s_tr = lc->transposed->s;
     const int elem = bf16 ? 2 : 4, n_enc = l->s.n_kv, n_c = l->n_compact, B = l->s.batch;
-    const size_t d_bytes = ((size_t)B * heads * (size_t)l->s.n_pos * sizeof(float) + 255) & ~(size_t)255;
+    const size_t d_bytes = hdt_bwd_row_scalars_bytes((size_t)B * heads * (size_t)l->s.n_pos);
     const size_t t_bytes = compact_tensor_bytes(l, heads, head_dim, elem);
     char *w = static_cast<char *>(workspace);
     float *delta = reinterpret_cast<float *>(w);
@@ -725,7 +725,7 @@ hdt_status_t hdt_cross_bwd_split(const hdt_layout_t *l, const void *q, const voi
 {
     const int pieces = hdt_cross_pieces(l, heads);
     const HdtSchedule s = split_schedule(l, pieces);
-    const size_t d_bytes = align256((size_t)l->s.batch * heads * (size_t)l->s.n_pos * sizeof(float));
+    const size_t d_bytes = hdt_bwd_row_scalars_bytes((size_t)l->s.batch * heads * (size_t)l->s.n_pos);
     char *w = static_cast<char *>(workspace);
     float *delta = reinterpret_cast<float *>(w);
     void *dq_part = w + d_bytes;

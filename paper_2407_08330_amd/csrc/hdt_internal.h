@@ -161,7 +161,9 @@ hdt_status_t hdt_launch_fwd_bf16(const HdtSchedule &s, const void *q, const void
 hdt_status_t hdt_launch_fwd_f32(const HdtSchedule &s, const float *q, const float *k, const float *v, float *o,
                                 float *lse, int heads, int head_dim, float scale, hipStream_t st);
 // backward launchers: `s` schedules the dQ pass, `s_transposed` (the transposed mask's schedule; the same as `s` for
-// symmetric masks) the dK/dV pass
+// symmetric masks) the dK/dV pass.  `delta`: room for the rows' scalars, hdt_bwd_row_scalars_bytes(batch * heads * n_pos)
+// (two floats per row for the bf16 kernels: -D and -LSE / scale side by side; the fp32 kernels keep D in the first half).
+inline size_t hdt_bwd_row_scalars_bytes(size_t rows) { return (2 * rows * sizeof(float) + 255) & ~(size_t)255; }
 hdt_status_t hdt_launch_bwd_bf16(const HdtSchedule &s, const HdtSchedule &s_transposed, const void *q, const void *k, const void *v,
                                  const void *o, const float *lse, const void *d_o, void *dq, void *dk,
                                  void *dv, int heads, int head_dim, float scale, float *ws_delta,

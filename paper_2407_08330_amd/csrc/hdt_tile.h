@@ -146,7 +146,8 @@ struct Pipe {
     int wave, lane;
     const int32_t *keys;       // key positions of this row tile's entries: [n][BN]
     const __bf16 *a, *b;       // the two gathered tensors, already offset to this (sample, head)
-    const float *aux0, *aux1;  // per-position floats gathered with the rows (AUX only), same offset
+    const float *aux0, *aux1;  // per-position floats gathered with the rows (AUX only): the two halves of an array
+                               // of float pairs, hence 8 bytes from one position to the next
 
     __device__ __forceinline__ const char *tile_a(int stage) const { return smem + (stage * 2 + 0) * TILE; }
     __device__ __forceinline__ const char *tile_b(int stage) const { return smem + (stage * 2 + 1) * TILE; }
@@ -184,7 +185,7 @@ struct Pipe {
         if (AUX) {
             const int pos = gather_row(pb[lane & (BN - 1)]);
             const float *src = (wave & 1) ? aux1 : aux0;
-            dma4(src, (uint32_t)pos * 4u, smem_addr + DATA_BYTES + POS_BYTES + ((stage * NW + wave) * POSW) * 4);
+            dma4(src, (uint32_t)pos * 8u, smem_addr + DATA_BYTES + POS_BYTES + ((stage * NW + wave) * POSW) * 4);
         }
     }
 };
