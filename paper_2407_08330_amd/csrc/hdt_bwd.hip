@@ -187,11 +187,15 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
                 sacc[e] = s_init;
                 dpacc[e] = dp_init;
             }
+            // (a wave at its contractions goes before the waves of this SIMD that are at their exponentials: the
+            // kernel is 3 % faster with the priorities than with the round-robin order)
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int st = 0; st < KSTEPS; st++) {
                 sacc = mfma_32x32x16(read_row<ROWB>(sK, rl, kb * 32, st), qf[st], sacc);     // K Q^T - LSE / scale
                 dpacc = mfma_32x32x16(read_row<ROWB>(sV, rl, kb * 32, st), dof[st], dpacc);  // dP^T - D = V dO^T - D
             }
+            __builtin_amdgcn_s_setprio(0);
 #pragma unroll
             for (int e = 0; e < 16; e++) sacc[e] = fast_exp2(sacc[e] * scale_log2);  // P^T
             if (!((sub >> (16 + sb)) & 1u)) apply_mask(sacc, s.bits_rm + ((size_t)bidx * G::NSUB + sb) * 16, 0.f);
@@ -199,11 +203,13 @@ __device__ __forceinline__ void dq_role(char *smem, const HdtSchedule &s, const 
             for (int e = 0; e < 16; e++) sacc[e] *= dpacc[e];  // dS^T
             // dQ^T += K^T dS^T
             const bf16x8 b0 = pack_bf16x8(sacc, 0), b1 = pack_bf16x8(sacc, 8);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int j = 0; j < DBLK; j++) {
                 dqacc[j] = mfma_32x32x16(read_tr<ROWB>(sK, tl, kb * 32, j), b0, dqacc[j]);
                 dqacc[j] = mfma_32x32x16(read_tr<ROWB>(sK, tl, kb * 32 + 16, j), b1, dqacc[j]);
             }
+            __builtin_amdgcn_s_setprio(0);
         }
     }
 
@@ -326,11 +332,13 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
                     dpacc[gq * 4 + 3] = d4.w;
                 }
             }
+            __builtin_amdgcn_s_setprio(1);  // as in the dQ role
 #pragma unroll
             for (int st = 0; st < KSTEPS; st++) {
                 sacc = mfma_32x32x16(read_row<ROWB>(sQ, rl, kb * 32, st), kf[st], sacc);     // Q K^T - LSE / scale
                 if (DO_DK) dpacc = mfma_32x32x16(read_row<ROWB>(sDO, rl, kb * 32, st), vf[st], dpacc);  // dO V^T - D
             }
+            __builtin_amdgcn_s_setprio(0);
             f32x16 pacc;
 #pragma unroll
             for (int e = 0; e < 16; e++) pacc[e] = fast_exp2(sacc[e] * scale_log2);  // P
@@ -339,6 +347,7 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
 #pragma unroll
                 for (int e = 0; e < 16; e++) sacc[e] = pacc[e] * dpacc[e];  // dS
                 const bf16x8 s0 = pack_bf16x8(sacc, 0), s1 = pack_bf16x8(sacc, 8);
+                __builtin_amdgcn_s_setprio(1);
 #pragma unroll
                 for (int j = 0; j < DBLK; j++) {
                     dkacc[j] = mfma_32x32x16(read_tr<ROWB>(sQ, tl, kb * 32, j), s0, dkacc[j]);  // dK^T += Q^T dS
@@ -347,12 +356,14 @@ __device__ __forceinline__ void dkv_role(char *smem, const HdtSchedule &s, const
             }
             if (DO_DV) {
                 const bf16x8 p0 = pack_bf16x8(pacc, 0), p1 = pack_bf16x8(pacc, 8);
+                __builtin_amdgcn_s_setprio(1);
 #pragma unroll
                 for (int j = 0; j < DBLK; j++) {
                     dvacc[j] = mfma_32x32x16(read_tr<ROWB>(sDO, tl, kb * 32, j), p0, dvacc[j]);  // dV^T += dO^T P
                     dvacc[j] = mfma_32x32x16(read_tr<ROWB>(sDO, tl, kb * 32 + 16, j), p1, dvacc[j]);
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
         }
     }
 
