@@ -37,16 +37,16 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
 def algorithmic_bytes_per_unit(kernel: str, d: int) -> int:
-    """Compulsory HBM bytes per (position, head) of one launch of `kernel` (bf16 tensors, fp32 LSE/D):
-    forward reads Q,K,V and writes O,LSE; the D pass reads O,dO and writes D; the backward kernel reads
-    Q,K,V,dO,LSE,D and writes dQ,dK,dV."""
+    """Compulsory HBM bytes per (position, head) of one launch of `kernel` (bf16 tensors, fp32 row scalars):
+    forward reads Q,K,V and writes O,LSE; the D pass reads O,dO,LSE and writes the pair (-D, -LSE/scale); the
+    backward kernel reads Q,K,V,dO,LSE and that pair and writes dQ,dK,dV."""
     row = 2 * d
     if kernel.startswith("hdt_fwd"):
         return 4 * row + 4
     if kernel.startswith("hdt_bwd_delta"):
-        return 2 * row + 4
+        return 2 * row + 12
     if kernel.startswith("hdt_bwd_bf16"):
-        return 7 * row + 8
+        return 7 * row + 12
     raise KeyError(kernel)
 
 
