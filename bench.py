@@ -356,9 +356,12 @@ def main() -> int:
                 rec = json.load(f)
             if rec.get("kernel_source_hash") != kernel_source_hash():
                 traffic_note = "profiles/hbm_traffic.json was measured on other kernel sources: not reported"
+            elif args.tile or args.windowed or args.edges:
+                traffic_note = "the counter run on record is of this workload's default options: not reported"
             else:
                 traffic = rec.get(f"config{args.config}", {}).get(dom)
-                traffic_note = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on these kernel sources (profiles/)"
+                if traffic is not None:
+                    traffic_note = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on these kernel sources (profiles/)"
         except (OSError, ValueError):
             pass
         out["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,

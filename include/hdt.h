@@ -262,8 +262,9 @@ hdt_status_t hdt_release_cached_memory(void);
  *            of each row; -inf on pad rows
  *   head_dim 64 or 128;  softmax_scale > 0 (the paper uses 1/sqrt(head_dim))
  *
- * HDT_BF16 needs a layout with tiles 128 x 64 or 64 x 32; HDT_F32 takes any layout.  batch and n_pos come from
- * the layout.  Errors: INVALID_ARG, UNSUPPORTED (head_dim, dtype, tile shape), HDT_ERR_HIP (launch).
+ * HDT_BF16 needs a layout with tiles 128 x 64 or 64 x 32 (the backward pass is the faster one on 64 x 32 tiles,
+ * by more than their build costs; a layout used for the forward only is best left at the default); HDT_F32 takes
+ * any layout.  batch and n_pos come from the layout.  Errors: INVALID_ARG, UNSUPPORTED (head_dim, dtype, tile shape), HDT_ERR_HIP (launch).
  */
 hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v, void *o,
                           float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
@@ -310,7 +311,7 @@ hdt_status_t hdt_attn_bwd(const hdt_layout_t *layout, const void *q, const void 
  * except the workspace, which is an array inside the library (HDT_NO_ALLOC_WORKSPACE_BYTES of device memory
  * that every GPU the library runs on holds until the process ends).  The call allocates nothing and frees
  * nothing.  HDT_ERR_SHAPE if hdt_attn_bwd_workspace_bytes() of the call exceeds the array (for a self-attention
- * layout: batch * heads * n_pos > 2^21); the other errors are hdt_attn_bwd's.  All calls on one GPU share the
+ * layout: batch * heads * n_pos > 2^20, two floats each); the other errors are hdt_attn_bwd's.  All calls on one GPU share the
  * array: calls that may overlap there (different streams, different host threads) race; calls on one stream
  * do not.  Nothing in the array has to survive between calls and nothing in it has to start at zero.
  */

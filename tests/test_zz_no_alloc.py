@@ -45,8 +45,8 @@ def test_no_alloc_backward_twice_the_second_call_smaller(oracle):
 def test_no_alloc_backward_refuses_what_does_not_fit():
     import torch
     import paper_2407_08330_amd as hdt
-    # batch * heads * n_pos floats of workspace: 2^21 + 128 of them do not fit the 8 MiB array
-    n, heads = 2048, 1025
+    # two floats of workspace per (batch, head, position): 2^20 + 2048 of them do not fit the 8 MiB array
+    n, heads = 2048, 513
     level = np.full((1, n), 1, np.int32)
     level[0, 0] = 0
     parent = np.zeros((1, n), np.int32)
