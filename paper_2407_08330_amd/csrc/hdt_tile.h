@@ -58,16 +58,18 @@ __device__ __forceinline__ cptr_u32 as_const(const uint32_t *p) { return (cptr_u
 // (which gather largely the same rows) share an L2, while every XCD still gets an even mix of the samples: with
 // whole (sample, head) ranges per XCD, one long document made two XCDs finish well after the others.  The chunk
 // is counted in rows: with 32 tiles of 64 rows the forward took 48.8 us at 8192 positions x 4 samples x 12
-// heads, with 64 of them 46.4, as with 32 tiles of 128 rows.  The grid is padded to a multiple of 8 chunks;
-// padding workgroups get an index >= n_items and leave at once.
+// heads, with 64 of them 46.4, as with 32 tiles of 128 rows.  Every round of 8 chunks starts one XCD further: a
+// sample of 8192 positions is two chunks, and the first halves of documents that end in pads are the heavier
+// ones, which would otherwise all go to the even XCDs (7 % more work there).  The grid is padded to a multiple
+// of 8 chunks; padding workgroups get an index >= n_items and leave at once.
 __host__ __device__ __forceinline__ unsigned padded_grid(unsigned n_items, unsigned chunk)
 {
     return (n_items + 8u * chunk - 1u) / (8u * chunk) * (8u * chunk);
 }
 __device__ __forceinline__ unsigned logical_block(unsigned bid, unsigned chunk)
 {
-    const unsigned x = bid & 7u, k = bid >> 3;
-    return ((k / chunk) * 8u + x) * chunk + k % chunk;
+    const unsigned x = bid & 7u, k = bid >> 3, round = k / chunk;
+    return (round * 8u + ((x + round) & 7u)) * chunk + k % chunk;
 }
 
 // Chunk swizzle of row r of a tile whose rows hold CPR chunks of 16 bytes.  The LDS has 64 banks of 4 bytes
