@@ -39,7 +39,7 @@ def test_layout_64x32_on_benchmark_configs(oracle, config):
 
 
 @WINDOWED
-@pytest.mark.parametrize("bm,bn", [(64, 32), (32, 32), (128, 128), (96, 64)])
+@pytest.mark.parametrize("bm,bn", [(64, 32), (32, 32), (128, 128), (96, 64), (64, 64), (64, 128), (32, 96)])
 def test_layout_other_tile_shapes(oracle, bm, bn, windowed):
     wl = inputs.make_workload(2, batch=2)
     say(f"[layout] tile {bm}x{bn} windowed={windowed}")
@@ -109,7 +109,7 @@ def test_layout_force_dense_and_no_sort(oracle):
         compare_layout(oracle, lay, wl.level, wl.parent, 128, 64, windowed=windowed, use_sort=False)
 
 
-@pytest.mark.parametrize("bm,bn", [(128, 64), (64, 32), (96, 128)])
+@pytest.mark.parametrize("bm,bn", [(128, 64), (64, 32), (96, 128), (64, 128), (32, 64)])
 @pytest.mark.parametrize("n_children", [1500, 2999])
 def test_layout_one_parent_with_thousands_of_children(oracle, n_children, bm, bn):
     # every tile's key list holds the root and all its children: 1501 keys still fit the kernel's on-chip copy
