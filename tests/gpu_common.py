@@ -33,6 +33,21 @@ def from_dev(t):
     return t.float().cpu().numpy()
 
 
+class GuardedWorkspace:
+    """A device workspace of exactly `nbytes` bytes with a patterned guard behind it: `view` is what a call gets,
+    `check()` says whether the call stayed inside it."""
+
+    def __init__(self, nbytes, guard=4096):
+        import torch
+        self.nbytes = max(int(nbytes), 16)
+        self.buf = torch.full((self.nbytes + guard,), 0x5A, dtype=torch.uint8, device="cuda")
+        self.view = self.buf[:self.nbytes]
+
+    def check(self):
+        tail = self.buf[self.nbytes:]
+        assert bool((tail == 0x5A).all()), "the call wrote behind the workspace it was given"
+
+
 def make_inputs(B, H, N, D, seed, dtype, n_tensors=3):
     """Seeded N(0,1) tensors; for bf16 they are rounded first so that both sides see the same values."""
     xs = inputs.make_qkv(B, H, N, D, seed, n_tensors)

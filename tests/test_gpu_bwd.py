@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2407_08330_amd import inputs
-from gpu_common import from_dev, make_inputs, say, to_dev_i32
+from gpu_common import GuardedWorkspace, from_dev, make_inputs, say, to_dev_i32
 
 pytestmark = pytest.mark.gpu
 
@@ -25,8 +25,11 @@ def run_bwd_case(oracle, level, parent, H, D, dtype, seed, scale=None, windowed=
     dq_ = torch.full_like(q_, float("nan"))
     dk_ = torch.full_like(q_, float("nan"))
     dv_ = torch.full_like(q_, float("nan"))
-    hdt.hdt_attn_bwd(lay, q_, k_, v_, o_, lse_, do_, scale, dq=dq_, dk=dk_, dv=dv_)
+    # exactly the workspace the library asks for, with a guard behind it
+    ws = GuardedWorkspace(hdt.hdt_attn_bwd_workspace_bytes(lay, H, D, 0 if dtype == "bf16" else 1))
+    hdt.hdt_attn_bwd(lay, q_, k_, v_, o_, lse_, do_, scale, dq=dq_, dk=dk_, dv=dv_, workspace=ws.view)
     torch.cuda.synchronize()
+    ws.check()
     with oracle.edges(edges or oracle.EDGE_ALL):
         ref = oracle.attn_bwd(q, k, v, d_o, level, parent, scale)
     pad = np.broadcast_to((level < 0)[:, None, :, None], q.shape)

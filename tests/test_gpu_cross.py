@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2407_08330_amd import inputs
-from gpu_common import from_dev, say, to_dev_bf16, to_dev_i32
+from gpu_common import GuardedWorkspace, from_dev, say, to_dev_bf16, to_dev_i32
 
 pytestmark = pytest.mark.gpu
 
@@ -132,9 +132,12 @@ def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0,
     pieces = pieces_of(hdt, lay, H, D, tile[0] or 128) if dtype == "bf16" else 1
     say(f"    key lists in {pieces} piece(s), forward workspace {ws_bytes} bytes")
     assert want_pieces is None or pieces == want_pieces
-    ws = torch.full((max(ws_bytes, 16),), 0xff, dtype=torch.uint8, device="cuda") if ws_bytes else None
+    gws = GuardedWorkspace(ws_bytes) if ws_bytes else None   # exactly what the library asks for, a guard behind it
+    ws = gws.view if gws else None
     hdt.hdt_attn_fwd(lay, q_, k_, v_, scale, o=o_, lse=lse_, workspace=ws)
     torch.cuda.synchronize()
+    if gws:
+        gws.check()
     if ws is not None:   # the same call without a workspace walks the whole lists: same result up to rounding
         o1, lse1 = hdt.hdt_attn_fwd(lay, q_, k_, v_, scale)
         torch.cuda.synchronize()
@@ -157,8 +160,10 @@ def run_cross_case(oracle, level, n_dec, level_mask, H, D, dtype, seed, tile=(0,
     dq_ = torch.full_like(q_, float("nan"))
     dk_ = torch.full_like(k_, float("nan"))
     dv_ = torch.full_like(k_, float("nan"))
-    hdt.hdt_attn_bwd(lay, q_, k_, v_, o_, lse_, do_, scale, dq=dq_, dk=dk_, dv=dv_)
+    bws = GuardedWorkspace(hdt.hdt_attn_bwd_workspace_bytes(lay, H, D, 0 if dtype == "bf16" else 1))
+    hdt.hdt_attn_bwd(lay, q_, k_, v_, o_, lse_, do_, scale, dq=dq_, dk=dk_, dv=dv_, workspace=bws.view)
     torch.cuda.synchronize()
+    bws.check()
     ref = oracle.cross_attn_bwd(q, k, v, d_o, level, level_mask, scale)
     for name, g_dev, g_ref in zip(("dq", "dk", "dv"), (dq_, dk_, dv_), ref):
         g = from_dev(g_dev)
