@@ -340,7 +340,7 @@ def test_deferred_build_matches_the_waiting_one(oracle):
         lay.destroy()
 
 
-def test_deferred_build_reports_its_errors_later():
+def test_deferred_build_reports_its_errors_later(oracle):
     import torch
     import paper_2407_08330_amd as hdt
     bad_l = np.array([[0, 1, 2, 3, -1, -1] + [-1] * 122], np.int32)
@@ -386,6 +386,22 @@ def test_deferred_build_reports_its_errors_later():
     assert e.value.name == "HDT_ERR_SHAPE"
     lay = _build(level, parent, capacity=24 * 47 + 5)
     assert lay.info()["n_tiles"] == 24 * 47
+    lay.destroy()
+    # 64 x 32 tiles (two query tiles per workgroup share one reservation): 47 tiles with rows x 94 entries
+    for capacity in (100, 94 + 50, 47 * 94 - 1):
+        lay = hdt.hdt_build_layout(lv, pr, tile_m=64, tile_n=32, deferred=True, capacity=capacity)
+        try:
+            hdt.hdt_attn_fwd(lay, x, y, z, 0.125)
+        except hdt.HdtError as err:
+            assert err.name == "HDT_ERR_SHAPE"
+        torch.cuda.synchronize()
+        with pytest.raises(hdt.HdtError) as e:
+            lay.status()
+        assert e.value.name == "HDT_ERR_SHAPE" and e.value.entries_needed == 47 * 94
+        lay.destroy()
+    lay = _build(level, parent, tile_m=64, tile_n=32, deferred=True, capacity=47 * 94)
+    assert lay.status() == 47 * 94 and lay.info()["nnz"] == n * n
+    compare_layout(oracle, lay, level, parent, 64, 32)
     lay.destroy()
 
 
