@@ -337,8 +337,23 @@ def main() -> int:
     copy_ms = [c_ev[i].elapsed_time(c_ev[i + 1]) for i in range(10)]
     copy_gbs = 2 * (256 << 20) / (pct(copy_ms, 50) * 1e-3) / 1e9
     del src, dst
+    # practical MFMA peak: the library's measuring kernel (nothing but bf16 32x32x16 contraction instructions, four
+    # waves on every SIMD of the chip), event-timed on this stream; launches of ~0.5 ms each
+    sink = torch.zeros(16, dtype=torch.float32, device=dev)
+    m_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+    flop = hdt.hdt_probe_mfma_bf16(1024, 2000, sink)   # warm-up (clocks settle under the load)
+    for i in range(6):
+        m_ev[i].record()
+        flop = hdt.hdt_probe_mfma_bf16(1024, 2000, sink)
+    m_ev[6].record()
+    torch.cuda.synchronize()
+    mfma_ms = [m_ev[i].elapsed_time(m_ev[i + 1]) for i in range(6)]
+    mfma_tflops = flop / (pct(mfma_ms, 50) * 1e-3) / 1e12
     out["practical_peak"] = {"hbm_copy_gbs": round(copy_gbs, 1),
-                             "what": "median of 10 device copies of 256 MiB, bytes read + bytes written over time"}
+                             "what": "median of 10 device copies of 256 MiB, bytes read + bytes written over time",
+                             "mfma_bf16_tflops": round(mfma_tflops, 1),
+                             "mfma_what": "median of 6 launches of the library's MFMA-only kernel (1024 workgroups x 4 "
+                                          "waves x 64 000 instructions v_mfma_f32_32x32x16_bf16)"}
 
     units = B * H * N
     attn = {n: kv for n, kv in per_kernel.items() if not n.startswith("hdt_layout")}
@@ -385,6 +400,7 @@ def main() -> int:
             # count exactly; profiles/ holds the cross-check against SQ_INSTS_VALU_MFMA_MOPS_BF16)
             "executed_mfma_tflops": round(executed / (us * 1e-6) / 1e12, 2),
             "mfma_frac": round(executed / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "mfma_frac_of_practical_peak": round(executed / (us * 1e-6) / 1e12 / mfma_tflops, 4),
             # every sub-block of every issued tile, skipped or not
             "whole_tile_tflops_incl_skipped_subblocks": round(issued / (us * 1e-6) / 1e12, 2),
             "hbm_gbs_algorithmic": round(algorithmic_bytes_per_unit(name, D) * units / (us * 1e-6) / 1e9, 1),

@@ -369,6 +369,16 @@ hdt_status_t hdt_timing_enable(int32_t enable);
 hdt_status_t hdt_timing_reset(void);
 int32_t hdt_timing_read(const char **h_names, int64_t *h_launches, double *h_total_ms, int32_t capacity);
 
+/*
+ * A measuring stick for benchmarks (no part of the attention path): enqueues a kernel of `workgroups`
+ * workgroups of four waves that does nothing but `iters` x 32 bf16 contraction instructions per wave (the
+ * 32 x 32 x 16 form the attention kernels use, four independent accumulator chains), and returns in *h_flop the
+ * floating-point operations that launch performs.  Timed by the caller (events on `stream`), it gives the MFMA
+ * rate the chip sustains at the clock it holds under that load.  d_sink: device, 4 bytes, never written.
+ * Errors: INVALID_ARG, HDT_ERR_HIP.
+ */
+hdt_status_t hdt_probe_mfma_bf16(int32_t workgroups, int32_t iters, float *d_sink, double *h_flop, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     hdt_hpe_table,
     hdt_index_vectors,
     hdt_parents_from_levels,
+    hdt_probe_mfma_bf16,
     hdt_release_cached_memory,
     hdt_timing_enable,
     hdt_timing_read,

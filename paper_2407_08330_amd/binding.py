@@ -19,7 +19,7 @@ HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 EXPORTED_SYMBOLS = [
     "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_status", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
     "hdt_attn_fwd", "hdt_attn_fwd_ws", "hdt_attn_fwd_workspace_bytes", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_attn_bwd_no_alloc", "hdt_status_string", "hdt_last_error",
-    "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_release_cached_memory",
+    "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_probe_mfma_bf16", "hdt_release_cached_memory",
     "hdt_parents_from_levels", "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
 ]
 
@@ -102,6 +102,8 @@ def load_library():
     lib.hdt_timing_read.argtypes = [ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i64),
                                     ctypes.POINTER(ctypes.c_double), i32]
     lib.hdt_timing_read.restype = i32
+    lib.hdt_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.hdt_probe_mfma_bf16.restype = ctypes.c_int
     lib.hdt_release_cached_memory.argtypes = []
     lib.hdt_release_cached_memory.restype = ctypes.c_int
     lib.hdt_parents_from_levels.argtypes = [vp, i32, i32, vp, vp]
@@ -374,6 +376,14 @@ def hdt_timing_read() -> dict:
     ms = (ctypes.c_double * cap)()
     n = load_library().hdt_timing_read(names, launches, ms, cap)
     return {names[i].decode(): (int(launches[i]), float(ms[i])) for i in range(min(n, cap))}
+
+
+def hdt_probe_mfma_bf16(workgroups: int, iters: int, sink, stream=None) -> float:
+    """Enqueues the MFMA measuring kernel (see hdt.h); returns the floating-point operations of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(load_library().hdt_probe_mfma_bf16(int(workgroups), int(iters), _ptr(sink), ctypes.byref(flop),
+                                              _stream_ptr(stream)))
+    return float(flop.value)
 
 
 def hdt_parents_from_levels(level, out=None, stream=None):

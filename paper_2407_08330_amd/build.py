@@ -9,7 +9,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
 CSRC = os.path.join(_PKG, "csrc")
 LIB = os.path.join(_PKG, "libhdt.so")
-SOURCES = ["hdt_api.hip", "hdt_layout.hip", "hdt_f32.hip", "hdt_fwd.hip", "hdt_bwd.hip", "hdt_hpe.hip", "hdt_cross.hip"]
+SOURCES = ["hdt_api.hip", "hdt_layout.hip", "hdt_f32.hip", "hdt_fwd.hip", "hdt_bwd.hip", "hdt_hpe.hip", "hdt_cross.hip", "hdt_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -115,6 +115,9 @@ def test_timing_calls_without_gpu(lib):
     assert lib.hdt_timing_reset() == 0
     assert lib.hdt_timing_read(None, None, None, 0) == 0
     assert lib.hdt_release_cached_memory() == 0
+    flop = ctypes.c_double(-1.0)
+    assert lib.hdt_status_string(lib.hdt_probe_mfma_bf16(0, 10, None, ctypes.byref(flop), None)).decode() == "HDT_ERR_INVALID_ARG"
+    assert lib.hdt_status_string(lib.hdt_probe_mfma_bf16(4, 10, None, None, None)).decode() == "HDT_ERR_INVALID_ARG"
 
 
 def test_hpe_argument_errors_without_gpu(lib):
