@@ -185,7 +185,9 @@ def main() -> int:
     def run_pipelined(k0, k1):
         """The same steps with the layouts built on a second stream, two steps ahead (a build depends only on
         the ids).  Every step still does its own build; the main stream waits for a layout's event before the
-        forward that uses it, and a layout is destroyed only after the attention calls that use it have finished."""
+        forward that uses it.  A layout is destroyed once the attention calls that use it have finished (the host
+        waits for an event recorded behind them, three steps late), which is what hdt_layout_destroy_completed is
+        for: the library then has nothing to order when a later build takes the buffers."""
         n = k1 - k0
         if n <= 0:
             return
@@ -216,11 +218,11 @@ def main() -> int:
             while len(live) > 3:
                 old_lay, old_done = live.popleft()
                 old_done.synchronize()
-                old_lay.destroy()
+                old_lay.destroy(completed=True)
         while live:
             old_lay, old_done = live.popleft()
             old_done.synchronize()
-            old_lay.destroy()
+            old_lay.destroy(completed=True)
 
     def timed_regions(run):
         """R regions of exactly K steps, each between two device synchronisations; ms per step of each."""

@@ -241,11 +241,18 @@ hdt_status_t hdt_layout_export(const hdt_layout_t *layout, int32_t sample, int32
                                uint32_t *h_bits, int32_t *h_k_colptr, int32_t *h_k_rows, int32_t *h_k_tile,
                                int64_t tile_capacity);
 
-/* Destroys the layout.  NULL is accepted.  Its device buffers go to a cache (at most 16 buffers /
- * 1 GiB per process) that later hdt_build_layout calls draw from, without synchronising.  A later
- * build may therefore overwrite them: either no attention call using this layout is still running,
- * or every such call was enqueued on the stream the later builds use. */
+/* Destroys the layout.  NULL is accepted, and the call does not wait: attention calls that use the layout may
+ * still be queued or running.  Its device buffers go to a cache (at most 16 buffers / 1 GiB per process) that
+ * later hdt_build_layout calls draw from; a build that takes them orders itself behind everything enqueued so far
+ * on the streams this layout was built and used on (an event per other stream, nothing for its own stream, no
+ * host wait).  The streams of those calls must still exist then, or the build waits for the device instead. */
 hdt_status_t hdt_layout_destroy(hdt_layout_t *layout);
+
+/* The same for a caller that has waited for the layout's build and for every call that used it (an event of its
+ * own, a stream or device synchronisation): the buffers go to the cache with nothing left to wait for.  What the
+ * plain call costs when layouts are built on one stream and used on another is an event recorded on the stream
+ * of the attention calls, a few microseconds of that stream's time per destroyed layout. */
+hdt_status_t hdt_layout_destroy_completed(hdt_layout_t *layout);
 
 /* Returns the cached device buffers to the driver (hipFree). */
 hdt_status_t hdt_release_cached_memory(void);

@@ -17,7 +17,7 @@ HDT_BF16, HDT_F32 = 0, 1
 HDT_EDGE_UP, HDT_EDGE_SIBLING, HDT_EDGE_DOWN, HDT_EDGE_ALL = 1, 2, 4, 7
 
 EXPORTED_SYMBOLS = [
-    "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_status", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy",
+    "hdt_build_layout", "hdt_build_cross_layout", "hdt_layout_transposed", "hdt_layout_status", "hdt_layout_info", "hdt_layout_sample_info", "hdt_layout_export", "hdt_layout_destroy", "hdt_layout_destroy_completed",
     "hdt_attn_fwd", "hdt_attn_fwd_ws", "hdt_attn_fwd_workspace_bytes", "hdt_attn_bwd_workspace_bytes", "hdt_attn_bwd", "hdt_attn_bwd_no_alloc", "hdt_status_string", "hdt_last_error",
     "hdt_timing_enable", "hdt_timing_reset", "hdt_timing_read", "hdt_probe_mfma_bf16", "hdt_release_cached_memory",
     "hdt_parents_from_levels", "hdt_index_vectors_workspace_bytes", "hdt_index_vectors", "hdt_hpe_table", "hdt_hpe_add",
@@ -78,6 +78,8 @@ def load_library():
     lib.hdt_layout_export.restype = ctypes.c_int
     lib.hdt_layout_destroy.argtypes = [vp]
     lib.hdt_layout_destroy.restype = ctypes.c_int
+    lib.hdt_layout_destroy_completed.argtypes = [vp]
+    lib.hdt_layout_destroy_completed.restype = ctypes.c_int
     lib.hdt_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp]
     lib.hdt_attn_fwd.restype = ctypes.c_int
     lib.hdt_attn_fwd_ws.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, ctypes.c_int, f32, vp, ctypes.c_size_t, vp]
@@ -215,12 +217,13 @@ class Layout:
                 out[key] = out[key][:T]
         return out
 
-    def destroy(self):
-        """hdt_layout_destroy: the layout's device buffers go to the library's cache, from which a later build takes
-        them without synchronising.  Call it (or drop the object) only when no attention call using the layout can
-        still be running, or when every later build is enqueued on the stream those calls were enqueued on."""
+    def destroy(self, completed: bool = False):
+        """hdt_layout_destroy: the layout's device buffers go to the library's cache, and the build that takes them
+        later runs behind the calls that used the layout (no host wait; the calls may still be queued).
+        ``completed=True`` (hdt_layout_destroy_completed): the caller has waited for all of them already."""
         if self._owner is None and self._h is not None and self._h.value:
-            _check(load_library().hdt_layout_destroy(self._h))
+            lib = load_library()
+            _check((lib.hdt_layout_destroy_completed if completed else lib.hdt_layout_destroy)(self._h))
         self._h = None
         self._owner = None
 

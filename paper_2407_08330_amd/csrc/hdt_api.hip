@@ -278,23 +278,35 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_transp
     return HDT_OK;
 }
 
-extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destroy(hdt_layout_t *layout)
+static hdt_status_t destroy_layout(hdt_layout_t *layout, bool completed)
 {
     if (!layout) return HDT_OK;
     if (layout->magic != HDT_LAYOUT_MAGIC) return hdt_fail(HDT_ERR_INVALID_ARG, "hdt_layout_destroy: not a layout");
+    // the build and every attention call went through this handle: its streams cover the layouts it owns
+    const HdtUsers users = completed ? HdtUsers() : hdt_users_at_release(hdt_layout_streams(layout));
     hdt_layout_t *owned[3] = {layout->compact ? layout->compact->transposed : nullptr, layout->compact, layout->transposed};
     layout->compact = layout->transposed = nullptr;
     for (hdt_layout_t *t : owned) {
         if (!t) continue;
         t->transposed = nullptr;
         t->magic = 0;
-        hdt_layout_release(t);
+        hdt_layout_release(t, users);
         delete t;
     }
     layout->magic = 0;
-    hdt_layout_release(layout);
+    hdt_layout_release(layout, users);
     delete layout;
     return HDT_OK;
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destroy(hdt_layout_t *layout)
+{
+    return destroy_layout(layout, false);
+}
+
+extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_layout_destroy_completed(hdt_layout_t *layout)
+{
+    return destroy_layout(layout, true);
 }
 
 // ---------------------------------------------------------------------------- attention
@@ -347,6 +359,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_fwd_ws(c
     if ((int64_t)s.batch * heads * s.tr > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_fwd: batch*heads*q_tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
+    hdt_layout_note_stream(layout, hs);  // whoever gets this layout's buffers later waits for this stream
     // long key lists of a cross-attention layout, cut into pieces, when the caller brings room for the partial results
     const size_t ws_need = dt == HDT_BF16 ? hdt_cross_fwd_workspace_bytes(layout, heads, head_dim) : 0;
     if (ws_need > 0 && workspace != nullptr && workspace_bytes >= ws_need) {
@@ -448,6 +461,7 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_attn_bwd(cons
     if ((int64_t)s.batch * heads * ((int64_t)s.tr + 2 * (int64_t)s_tr.tr) > 0x7ffff000LL)
         return hdt_fail(HDT_ERR_SHAPE, "hdt_attn_bwd: batch*heads*tiles exceeds the grid limit");
     hipStream_t hs = (hipStream_t)stream;
+    hdt_layout_note_stream(layout, hs);
     if (layout->compact)
         return hdt_cross_bwd_compact(layout, q, k, v, o, lse, d_o, dq, dk, dv, heads, head_dim, dt == HDT_BF16, scale,
                                      workspace, hs);

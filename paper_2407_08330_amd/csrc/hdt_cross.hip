@@ -463,6 +463,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
     hdt_layout_t *Lc = nullptr, *Tc = nullptr;  // the compact pair while it is being built
     hdt_status_t status = HDT_OK;
     hipStream_t st = (hipStream_t)stream;
+    L->streams.add(st);
+    hdt_note_build_stream(st);
+    HdtUsers build_only;  // what the buffers of a failed build have been touched by
+    build_only.lazy.add(st);
     const int e_fwd = (n_enc + bn - 1) / bn, e_tr = (n_dec + bn - 1) / bn;
     const int64_t ent_fwd = (int64_t)batch * L->s.tr * e_fwd, ent_tr = (int64_t)batch * T->s.tr * e_tr;
     if (ent_fwd >= (1LL << 31) || ent_tr >= (1LL << 31)) {
@@ -481,10 +485,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
     {
         CrossBuffers f = carve_cross(nullptr, nullptr, batch, n_enc, L->s.tr, ent_fwd, bm, bn, true);
         CrossBuffers t = carve_cross(nullptr, nullptr, batch, n_enc, T->s.tr, ent_tr, bm, bn, false);
-        CROSS_TRY(hdt_pool_alloc(&L->arena, f.bytes1 + 256, &L->arena_bytes));
-        CROSS_TRY(hdt_pool_alloc(&L->arena2, f.bytes2 + 256, &L->arena2_bytes));
-        CROSS_TRY(hdt_pool_alloc(&T->arena, t.bytes1 + 256, &T->arena_bytes));
-        CROSS_TRY(hdt_pool_alloc(&T->arena2, t.bytes2 + 256, &T->arena2_bytes));
+        CROSS_TRY(hdt_pool_alloc(&L->arena, f.bytes1 + 256, &L->arena_bytes, st));
+        CROSS_TRY(hdt_pool_alloc(&L->arena2, f.bytes2 + 256, &L->arena2_bytes, st));
+        CROSS_TRY(hdt_pool_alloc(&T->arena, t.bytes1 + 256, &T->arena_bytes, st));
+        CROSS_TRY(hdt_pool_alloc(&T->arena2, t.bytes2 + 256, &T->arena2_bytes, st));
         f = carve_cross((char *)L->arena, (char *)L->arena2, batch, n_enc, L->s.tr, ent_fwd, bm, bn, true);
         t = carve_cross((char *)T->arena, (char *)T->arena2, batch, n_enc, T->s.tr, ent_tr, bm, bn, false);
         if (!empty) {
@@ -540,10 +544,10 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
                 const int64_t ent_fc = (int64_t)batch * Lc->s.tr * e_fc, ent_tc = (int64_t)batch * Tc->s.tr * e_tr;
                 CrossBuffers fc = carve_cross(nullptr, nullptr, batch, n_enc, Lc->s.tr, ent_fc, bm, bn, false);
                 CrossBuffers tc = carve_cross(nullptr, nullptr, batch, n_enc, Tc->s.tr, ent_tc, bm, bn, false);
-                CROSS_TRY(hdt_pool_alloc(&Lc->arena, fc.bytes1 + 256, &Lc->arena_bytes));
-                CROSS_TRY(hdt_pool_alloc(&Lc->arena2, fc.bytes2 + 256, &Lc->arena2_bytes));
-                CROSS_TRY(hdt_pool_alloc(&Tc->arena, tc.bytes1 + 256, &Tc->arena_bytes));
-                CROSS_TRY(hdt_pool_alloc(&Tc->arena2, tc.bytes2 + 256, &Tc->arena2_bytes));
+                CROSS_TRY(hdt_pool_alloc(&Lc->arena, fc.bytes1 + 256, &Lc->arena_bytes, st));
+                CROSS_TRY(hdt_pool_alloc(&Lc->arena2, fc.bytes2 + 256, &Lc->arena2_bytes, st));
+                CROSS_TRY(hdt_pool_alloc(&Tc->arena, tc.bytes1 + 256, &Tc->arena_bytes, st));
+                CROSS_TRY(hdt_pool_alloc(&Tc->arena2, tc.bytes2 + 256, &Tc->arena2_bytes, st));
                 fc = carve_cross((char *)Lc->arena, (char *)Lc->arena2, batch, n_enc, Lc->s.tr, ent_fc, bm, bn, false);
                 tc = carve_cross((char *)Tc->arena, (char *)Tc->arena2, batch, n_enc, Tc->s.tr, ent_tc, bm, bn, false);
                 CrossArgs ac{d_level_enc, f.sel, f.count, level_mask, n_enc, n_dec, bm, bn, 0, Lc->s.tr, e_fc, n_c,
@@ -583,15 +587,15 @@ extern "C" __attribute__((visibility("default"))) hdt_status_t hdt_build_cross_l
 fail:
     for (hdt_layout_t *x : {Tc, Lc}) {
         if (!x) continue;
-        hdt_layout_release(x);
+        hdt_layout_release(x, build_only);
         x->magic = 0;
         delete x;
     }
-    hdt_layout_release(T);
+    hdt_layout_release(T, build_only);
     T->magic = 0;
     delete T;
     L->transposed = nullptr;
-    hdt_layout_release(L);
+    hdt_layout_release(L, build_only);
     L->magic = 0;
     delete L;
     return status;

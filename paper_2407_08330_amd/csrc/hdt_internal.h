@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <memory>
 #include <stdint.h>
 
 #include <string>
@@ -56,8 +57,27 @@ __host__ __device__ inline bool hdt_pair_allowed(const unsigned long long *bits_
     return (bits_rm[(t * nsub + sb) * 16 + e] >> l) & 1ull;
 }
 
+// The streams on which work that touches a layout's buffers has been enqueued (its build, the attention calls):
+// what a later owner of those buffers orders itself after.
+struct HdtStreams {
+    static constexpr int kMax = 4;
+    hipStream_t s[kMax] = {};
+    int n = 0;
+    bool more = false;  // more than kMax streams: the later owner waits for the whole device instead
+    void add(hipStream_t x)
+    {
+        for (int i = 0; i < n; i++)
+            if (s[i] == x) return;
+        if (n < kMax)
+            s[n++] = x;
+        else
+            more = true;
+    }
+};
+
 struct hdt_layout {
     uint32_t magic;
+    mutable HdtStreams streams;  // of the handle the caller holds; the layouts it owns are used through it
     HdtSchedule s;       // pointers into the arenas
     int32_t device;      // device the buffers live on
     int32_t force_dense; // every candidate counts as a tile, empty or not
@@ -127,9 +147,30 @@ bool hdt_layout_ok(const hdt_layout_t *l);
 hdt_status_t hdt_layout_resolve(const hdt_layout_t *l, bool wait);
 hdt_status_t hdt_layout_ensure_kperm(const hdt_layout_t *l);  // sorts s.kperm if the build did not (waits for the device) (hdt_layout.hip)
 hdt_status_t hdt_layout_stats(const hdt_layout_t *l);  // fills h_stats once (waits for the device) (hdt_layout.hip)
-void hdt_layout_release(hdt_layout_t *l);  // hands the device buffers back to the cache (hdt_layout.hip)
+// What the next owner of a released buffer has to wait for.  A stream on which layouts are also built is only
+// remembered (`lazy`): the next build is most likely enqueued there too and needs nothing; should it come on another
+// stream, an event recorded then covers the work in question (and whatever was enqueued since).  For any other
+// stream an event is recorded at the release, so that a build on a second stream waits for exactly the calls that
+// used the buffer and not for the ones enqueued later.
+struct HdtFence {
+    hipEvent_t ev;
+    hipStream_t stream;
+    ~HdtFence();  // returns the event to a free list (hdt_layout.hip)
+};
+struct HdtUsers {
+    HdtStreams lazy;
+    std::vector<std::shared_ptr<HdtFence>> fences;
+    bool whole_device = false;
+};
+HdtUsers hdt_users_at_release(const HdtStreams &streams);  // records the events
+void hdt_note_build_stream(hipStream_t st);                  // a layout build is being enqueued on `st`
+// hands the device buffers back to the cache (hdt_layout.hip)
+void hdt_layout_release(hdt_layout_t *l, const HdtUsers &users);
+void hdt_layout_note_stream(const hdt_layout_t *l, hipStream_t st);  // an attention call is about to use `l` on `st`
+HdtStreams hdt_layout_streams(const hdt_layout_t *l);
 // device buffer from the cache of destroyed layouts' buffers, or a new one; *got = its real size (hdt_layout.hip)
-hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got);
+// `next_user`: the stream on which the buffer's new owner enqueues its work
+hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got, hipStream_t next_user);
 
 // --- key lists of a cross-attention layout cut into pieces that separate workgroups walk (hdt_cross.hip) ---
 int hdt_cross_pieces(const hdt_layout_t *l, int heads);  // 1, 2, 4 or 8 for this many heads

@@ -1309,6 +1309,7 @@ struct CachedBlock {
     void *ptr;
     size_t bytes;
     int device;
+    HdtUsers users;  // work that may still read or write the block
 };
 std::mutex g_pool_mutex;
 std::vector<CachedBlock> g_pool;
@@ -1316,10 +1317,62 @@ constexpr size_t kPoolMaxBlocks = 16;
 constexpr size_t kPoolMaxBytes = (size_t)1 << 30;
 int64_t g_capacity_hint = 0;  // candidates the last build needed
 
-hipError_t pool_alloc(void **out, size_t bytes, size_t *got)
+// Events for the fences: a free list, the events carry no timing.  The list and its mutex are never destroyed:
+// fences held by the cache return their events when the process ends, in an order nobody controls.
+std::mutex &g_event_mutex = *new std::mutex();
+std::vector<hipEvent_t> &g_free_events = *new std::vector<hipEvent_t>();
+hipStream_t g_last_build_stream = nullptr;  // where the most recent layout build was enqueued (under g_event_mutex)
+
+hipError_t take_fence_event(hipEvent_t *ev)
+{
+    {
+        std::lock_guard<std::mutex> lk(g_event_mutex);
+        if (!g_free_events.empty()) {
+            *ev = g_free_events.back();
+            g_free_events.pop_back();
+            return hipSuccess;
+        }
+    }
+    return hipEventCreateWithFlags(ev, hipEventDisableTiming);
+}
+
+// Whatever is enqueued on `next` from here on runs after the work the users of a block had enqueued: the fences
+// recorded at the release, and for the remembered streams an event recorded now (that covers more work than
+// needed, never less); nothing at all for `next` itself (stream order), and no host wait.
+hipError_t order_after(const HdtUsers &users, hipStream_t next)
+{
+    if (users.whole_device) return hipDeviceSynchronize();
+    for (auto &f : users.fences) {
+        if (f->stream == next) continue;
+        const hipError_t e = hipStreamWaitEvent(next, f->ev, 0);
+        if (e != hipSuccess) return e;
+    }
+    for (int i = 0; i < users.lazy.n; i++) {
+        if (users.lazy.s[i] == next) continue;
+        hipEvent_t ev;
+        hipError_t e = take_fence_event(&ev);
+        if (e != hipSuccess) return e;
+        e = hipEventRecord(ev, users.lazy.s[i]);
+        if (e == hipSuccess) e = hipStreamWaitEvent(next, ev, 0);
+        {
+            std::lock_guard<std::mutex> lk(g_event_mutex);
+            g_free_events.push_back(ev);  // a later record on it does not disturb the wait already enqueued
+        }
+        if (e != hipSuccess) {  // e.g. the caller has destroyed that stream since: wait for everything instead
+            (void)hipGetLastError();
+            e = hipDeviceSynchronize();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+hipError_t pool_alloc(void **out, size_t bytes, size_t *got, hipStream_t next_user)
 {
     int dev = 0;
     (void)hipGetDevice(&dev);
+    HdtUsers users;
+    bool found = false;
     {
         std::lock_guard<std::mutex> lk(g_pool_mutex);
         int best = -1;
@@ -1330,15 +1383,25 @@ hipError_t pool_alloc(void **out, size_t bytes, size_t *got)
         if (best >= 0) {
             *out = g_pool[best].ptr;
             *got = g_pool[best].bytes;
+            users = std::move(g_pool[best].users);
             g_pool.erase(g_pool.begin() + best);
-            return hipSuccess;
+            found = true;
         }
+    }
+    if (found) {
+        const hipError_t e = order_after(users, next_user);
+        if (e != hipSuccess) {  // the block goes back as it was
+            std::lock_guard<std::mutex> lk(g_pool_mutex);
+            g_pool.push_back({*out, *got, dev, std::move(users)});
+            *out = nullptr;
+        }
+        return e;
     }
     *got = bytes;
     return hipMalloc(out, bytes);
 }
 
-void pool_free(void *ptr, size_t bytes, int device)
+void pool_free(void *ptr, size_t bytes, int device, const HdtUsers &users)
 {
     if (!ptr) return;
     {
@@ -1346,11 +1409,11 @@ void pool_free(void *ptr, size_t bytes, int device)
         size_t held = 0;
         for (auto &b : g_pool) held += b.bytes;
         if (g_pool.size() < kPoolMaxBlocks && held + bytes <= kPoolMaxBytes) {
-            g_pool.push_back({ptr, bytes, device});
+            g_pool.push_back({ptr, bytes, device, users});
             return;
         }
     }
-    (void)hipFree(ptr);
+    (void)hipFree(ptr);  // waits for the device
 }
 
 // carve buffers (each rounded up to 256 bytes) out of an arena
@@ -1543,13 +1606,78 @@ hdt_status_t hdt_layout_resolve(const hdt_layout_t *L, bool wait)
     return HDT_OK;
 }
 
-hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got) { return pool_alloc(out, bytes, got); }
-
-void hdt_layout_release(hdt_layout_t *L)
+hipError_t hdt_pool_alloc(void **out, size_t bytes, size_t *got, hipStream_t next_user)
 {
-    pool_free(L->arena, L->arena_bytes, L->device);
-    pool_free(L->arena2, L->arena2_bytes, L->device);
+    return pool_alloc(out, bytes, got, next_user);
+}
+
+void hdt_layout_release(hdt_layout_t *L, const HdtUsers &users)
+{
+    pool_free(L->arena, L->arena_bytes, L->device, users);
+    pool_free(L->arena2, L->arena2_bytes, L->device, users);
     L->arena = L->arena2 = nullptr;
+}
+
+HdtFence::~HdtFence()
+{
+    std::lock_guard<std::mutex> lk(g_event_mutex);
+    g_free_events.push_back(ev);
+}
+
+HdtUsers hdt_users_at_release(const HdtStreams &streams)
+{
+    HdtUsers u;
+    if (streams.more) {
+        u.whole_device = true;
+        return u;
+    }
+    hipStream_t builds;
+    {
+        std::lock_guard<std::mutex> lk(g_event_mutex);
+        builds = g_last_build_stream;
+    }
+    for (int i = 0; i < streams.n; i++) {
+        if (streams.s[i] == builds) {
+            u.lazy.add(streams.s[i]);
+            continue;
+        }
+        hipEvent_t ev;
+        if (take_fence_event(&ev) != hipSuccess || hipEventRecord(ev, streams.s[i]) != hipSuccess) {
+            (void)hipGetLastError();
+            u.whole_device = true;  // the next owner waits for the device instead
+            return u;
+        }
+        u.fences.push_back(std::shared_ptr<HdtFence>(new HdtFence{ev, streams.s[i]}));
+    }
+    return u;
+}
+
+// a buffer that only a build on `st` has touched
+static HdtUsers only_stream(hipStream_t st)
+{
+    HdtUsers u;
+    u.lazy.add(st);
+    return u;
+}
+
+void hdt_note_build_stream(hipStream_t st)
+{
+    std::lock_guard<std::mutex> lk(g_event_mutex);
+    g_last_build_stream = st;
+}
+
+static std::mutex g_streams_mutex;  // attention calls on one layout may come from several host threads
+
+void hdt_layout_note_stream(const hdt_layout_t *L, hipStream_t st)
+{
+    std::lock_guard<std::mutex> lk(g_streams_mutex);
+    L->streams.add(st);
+}
+
+HdtStreams hdt_layout_streams(const hdt_layout_t *L)
+{
+    std::lock_guard<std::mutex> lk(g_streams_mutex);
+    return L->streams;
 }
 
 // Surviving tiles and allowed pairs per sample, summed on the host from the query tile and the pair
@@ -1742,6 +1870,8 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     }
 
     hipStream_t st = (hipStream_t)stream;
+    L->streams.add(st);
+    hdt_note_build_stream(st);
     const int B = batch, n = n_pos, tr = s.tr, tc = s.tc, wc = (tc + 31) / 32;
     hdt_status_t status = HDT_OK;
     (void)hipGetDevice(&L->device);
@@ -1758,7 +1888,7 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
     {
         const int nchunks = (n + kChunk - 1) / kChunk, groups = (tr + kWaves - 1) / kWaves;
         Phase1 p = carve_phase1(nullptr, B, n, s.n_slots, tr, nchunks);
-        BUILD_TRY(pool_alloc(&L->arena, p.bytes, &L->arena_bytes));
+        BUILD_TRY(pool_alloc(&L->arena, p.bytes, &L->arena_bytes, st));
         p = carve_phase1((char *)L->arena, B, n, s.n_slots, tr, nchunks);
 
         // The schedule as far as the host knows it before the device has reported.
@@ -1803,7 +1933,7 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 goto fail;
             }
             Phase2 q = carve_phase2(nullptr, cap, bm, bn);
-            BUILD_TRY(pool_alloc(&L->arena2, q.bytes, &L->arena2_bytes));
+            BUILD_TRY(pool_alloc(&L->arena2, q.bytes, &L->arena2_bytes, st));
             q = carve_phase2((char *)L->arena2, cap, bm, bn);
             uint32_t ticket = 0, ticket_before = 0;
             unsigned long long *report = report_slot(&ticket, &ticket_before);
@@ -1924,14 +2054,14 @@ static hdt_status_t build_one(const int32_t *d_level, const int32_t *d_parent, i
                 goto fail;
             }
             // the guess was too small: once more with the exact size
-            pool_free(L->arena2, L->arena2_bytes, L->device);
+            pool_free(L->arena2, L->arena2_bytes, L->device, only_stream(st));
             L->arena2 = nullptr;
             cap = need;
         }
         status = hdt_fail(HDT_ERR_HIP, "hdt_build_layout: candidate count changed between two passes");
     }
 fail:
-    hdt_layout_release(L);
+    hdt_layout_release(L, only_stream((hipStream_t)stream));
     L->magic = 0;
     delete L;
     return status;

@@ -95,7 +95,7 @@ def test_empty_layout_and_calls_on_it_are_noops_without_gpu(lib):
             assert lib.hdt_layout_sample_info(h, 0, ctypes.byref(a), ctypes.byref(b)) == 0 and a.value == 0
             assert lib.hdt_layout_sample_info(h, batch, ctypes.byref(a), ctypes.byref(b)) == 2
         assert lib.hdt_layout_destroy(h) == 0
-    assert lib.hdt_layout_destroy(None) == 0
+    assert lib.hdt_layout_destroy(None) == 0 and lib.hdt_layout_destroy_completed(None) == 0
 
 
 def test_invalid_layout_handles_are_refused(lib):
@@ -107,7 +107,7 @@ def test_invalid_layout_handles_are_refused(lib):
     assert lib.hdt_layout_status(junk, None) == 1 and lib.hdt_layout_status(None, None) == 1
     assert lib.hdt_attn_fwd(junk, None, None, None, None, None, 1, 64, 0, ctypes.c_float(0.1), None) == 1
     assert lib.hdt_attn_bwd_workspace_bytes(junk, 1, 64, 0) == 0
-    assert lib.hdt_layout_destroy(junk) == 1
+    assert lib.hdt_layout_destroy(junk) == 1 and lib.hdt_layout_destroy_completed(junk) == 1
 
 
 def test_timing_calls_without_gpu(lib):

@@ -217,3 +217,39 @@ def test_fwd_dense_baseline_layout(oracle, dtype, D, tile):
     lay = run_fwd_case(oracle, level, parent, 3, D, dtype, 4100 + D, tile=tile, force_dense=True)
     info = lay.info()
     assert info["n_tiles"] == 2 * (1024 // tile[0]) * (1024 // tile[1])
+
+
+def test_buffers_of_a_destroyed_layout_wait_for_the_calls_that_use_them():
+    """A forward call sits on stream A behind a long filler when its layout is destroyed and a build on stream B
+    takes the layout's buffers from the cache: the build has to run after the forward call (the library orders it
+    with an event), so the call's result is that of an undisturbed run, bit for bit."""
+    import torch
+    import paper_2407_08330_amd as hdt
+    wl = inputs.make_workload(2, batch=4)
+    H, D, N = 4, 64, wl.n_pos
+    lv = [to_dev_i32(wl.level[i:i + 2]) for i in (0, 2)]
+    pr = [to_dev_i32(wl.parent[i:i + 2]) for i in (0, 2)]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(31)
+    q, k, v = (torch.randn((2, H, N, D), device="cuda", generator=g).to(torch.bfloat16) for _ in range(3))
+    lay = hdt.hdt_build_layout(lv[0], pr[0])
+    want_o, want_lse = hdt.hdt_attn_fwd(lay, q, k, v, 0.125)
+    torch.cuda.synchronize()
+    lay.destroy()
+    hdt.hdt_release_cached_memory()          # the cache then holds nothing but what this test puts there
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    a = torch.randn((4096, 4096), device="cuda")
+    o = torch.full_like(q, float("nan"))
+    lse = torch.full((2, H, N), float("nan"), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    say("[fwd] layout destroyed with its forward call still queued; its buffers reused by a build on another stream")
+    lay = hdt.hdt_build_layout(lv[0], pr[0], stream=sa)
+    with torch.cuda.stream(sa):
+        for _ in range(40):                  # some tens of milliseconds in front of the forward call
+            a = a @ a * 1e-3
+    hdt.hdt_attn_fwd(lay, q, k, v, 0.125, o=o, lse=lse, stream=sa)
+    lay.destroy()
+    other = hdt.hdt_build_layout(lv[1], pr[1], stream=sb)   # other documents, the same sizes: the cached buffers fit
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), want_o.view(torch.int16)) and torch.equal(lse, want_lse)
+    other.destroy()
