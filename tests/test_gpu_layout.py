@@ -130,16 +130,17 @@ def test_layout_one_parent_with_thousands_of_children(oracle, n_children, bm, bn
     assert nnz >= (n_children + 1) ** 2
 
 
-@pytest.mark.parametrize("log2n,n_sections", [(17, 120), (19, 500)])
-def test_layout_long_documents_need_a_large_slot_bitmap(oracle, log2n, n_sections):
+@pytest.mark.parametrize("log2n,n_sections,bm,bn", [(17, 120, 128, 64), (19, 500, 128, 64), (17, 120, 64, 32)])
+def test_layout_long_documents_need_a_large_slot_bitmap(oracle, log2n, n_sections, bm, bn):
     # 2^17 / 2^19 (the largest accepted) positions: the key-list kernel's bitmaps over the positions take
-    # 32 KB / 128 KB of LDS
+    # 32 KB / 128 KB of LDS; with 64-row tiles two such sets no longer fit one workgroup, and every tile gets a
+    # workgroup of its own (512 threads)
     rng = np.random.default_rng(77)
     n = 1 << log2n
     secs = [[int(rng.integers(5, 61)) for _ in range(int(rng.integers(5, 41)))] for _ in range(n_sections)]
     level, parent = inputs.document_from_sections(secs, n)
-    say(f"[layout] n = {n}, real = {(level >= 0).sum()}")
-    lay = _build(level[None], parent[None])
+    say(f"[layout] n = {n}, real = {(level >= 0).sum()}, tile {bm}x{bn}")
+    lay = _build(level[None], parent[None], tile_m=bm, tile_n=bn)
     got = lay.export(0)
     ref_kperm = oracle.kperm(level)
     np.testing.assert_array_equal(got["kperm"], ref_kperm)
@@ -147,8 +148,8 @@ def test_layout_long_documents_need_a_large_slot_bitmap(oracle, log2n, n_section
     rowptr = got["q_rowptr"]
     slot = np.empty(n, np.int64)
     slot[ref_kperm] = np.arange(n)
-    for I in rng.choice(n // 128, size=12, replace=False).tolist() + [0]:
-        rows = np.arange(I * 128, (I + 1) * 128)
+    for I in rng.choice(n // bm, size=12, replace=False).tolist() + [0]:
+        rows = np.arange(I * bm, (I + 1) * bm)
         keys = got["q_keys"][rowptr[I]:rowptr[I + 1]].reshape(-1)
         real = keys[keys >= 0]
         assert (keys[len(real):] == -1).all() and (np.diff(slot[real]) > 0).all()
@@ -166,8 +167,8 @@ def test_layout_long_documents_need_a_large_slot_bitmap(oracle, log2n, n_section
         assert set(real.tolist()) == want, f"query tile {I}"
         bits = got["bits"][rowptr[I]:rowptr[I + 1]]
         for e in range(bits.shape[0]):
-            for c in range(64):
-                j = keys[e * 64 + c]
+            for c in range(bn):
+                j = keys[e * bn + c]
                 col = (bits[e, :, c // 32] >> np.uint32(c % 32)) & 1
                 exp = [oracle.allowed(level, parent, int(i), int(j)) if j >= 0 else 0 for i in rows]
                 np.testing.assert_array_equal(col, np.array(exp, np.uint32))
