@@ -270,8 +270,8 @@ hdt_status_t hdt_release_cached_memory(void);
  *   head_dim 64 or 128;  softmax_scale > 0 (the paper uses 1/sqrt(head_dim))
  *
  * HDT_BF16 needs a layout with tiles 128 x 64 or 64 x 32 (the backward pass is the faster one on 64 x 32 tiles,
- * by more than their build costs; a layout used for the forward only is best left at the default); HDT_F32 takes
- * any layout.  batch and n_pos come from the layout.  Errors: INVALID_ARG, UNSUPPORTED (head_dim, dtype, tile shape), HDT_ERR_HIP (launch).
+ * by more than their build costs, and so is the forward at head size 128; a layout used for the forward only at
+ * head size 64 is best left at the default); HDT_F32 takes any layout.  batch and n_pos come from the layout.  Errors: INVALID_ARG, UNSUPPORTED (head_dim, dtype, tile shape), HDT_ERR_HIP (launch).
  */
 hdt_status_t hdt_attn_fwd(const hdt_layout_t *layout, const void *q, const void *k, const void *v, void *o,
                           float *lse, int32_t heads, int32_t head_dim, hdt_dtype_t dt, float softmax_scale,
